@@ -1,0 +1,212 @@
+"""Synthetic workloads shaped like the paper's LLM runs (evaluation setup:
+Qwen3 / Llama-3.1 models on ShareGPT and WildChat-1M prompts).  Neither the
+datasets nor any weights are used: the capture path is data-oblivious, so
+seeded ~N(0,1) bf16 activations of the same shapes, ragged length mixes and
+paged-cache structure stand in for them.
+
+A workload is a list of steps; a step is a list of ObserveCall descriptors in
+the order the hooks would fire.  Both the HIP path's driver and the CPU
+oracle's driver consume these descriptors; nothing here gathers, converts or
+packs anything.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Callable, Dict, List, Optional
+
+import numpy as np
+import torch
+
+from . import prng
+
+# dtype / policy codes are plain numbers in both the C ABI and the oracle.
+DT_NONE, DT_BF16, DT_FP16, DT_FP32, DT_FP8 = 0, 1, 2, 3, 4
+SUM_L2, SUM_MEAN, SUM_ABSMAX = 1, 2, 4
+POLICY_BLOCK, POLICY_DROP_NEWEST = 0, 1
+
+REQ_FIELDS = ("req_id", "row_base", "tok_start", "tok_count", "tok_step")
+
+
+def make_reqs(rows) -> np.ndarray:
+    """rows: iterable of (req_id, row_base, tok_start, tok_count, tok_step)."""
+    a = np.asarray(list(rows), dtype=np.uint32).reshape(-1, 5)
+    return np.ascontiguousarray(a)
+
+
+@dataclass
+class PagedSpec:
+    block_size: int
+    n_heads: int
+    head_dim: int
+    heads_sel: List[int]
+    block_table: torch.Tensor          # int32 [n_seqs, max_blocks], workload device
+
+
+@dataclass
+class ObserveCall:
+    point_id: int
+    step_id: int
+    tensor: torch.Tensor               # dense: [T, E] (row stride may exceed E); paged: [blocks, slots, heads, dim]
+    reqs: np.ndarray                   # uint32 [n_reqs, 5], see REQ_FIELDS
+    out_dtype: int = DT_BF16
+    summary_mask: int = 0
+    keep_mask: Optional[np.ndarray] = None    # uint8 [n_reqs]
+    row_index: Optional[np.ndarray] = None    # int32, request-major explicit rows
+    paged: Optional[PagedSpec] = None
+
+
+@dataclass
+class Workload:
+    name: str
+    device_ring_bytes: int
+    host_ring_bytes: int
+    policy_mode: int
+    sample_k: int
+    n_steps: int
+    step_calls: Callable[[int], List[ObserveCall]]
+    max_reqs: int = 256
+    notes: Dict[str, object] = field(default_factory=dict)
+
+    def steps(self):
+        for s in range(self.n_steps):
+            yield s, self.step_calls(s)
+
+
+def _pool(seed_tags, n_slots, shape, device):
+    """n_slots independent bf16 tensors of one shape."""
+    n = int(np.prod(shape))
+    return [prng.randn_bf16(prng.sub_seed(*seed_tags, s), n, device).view(*shape)
+            for s in range(n_slots)]
+
+
+# --------------------------------------------------------------------------
+# config 1: tiny
+# --------------------------------------------------------------------------
+def tiny_lengths(step: int, n_reqs: int = 4, lo: int = 1, hi: int = 17,
+                 cap: int = 64) -> np.ndarray:
+    """Ragged lengths uniform in [lo, hi]; while the total exceeds `cap` the
+    currently longest request (lowest index on ties) loses one token."""
+    lens = prng.randint(prng.sub_seed(1, 7, step), n_reqs, lo, hi)
+    while lens.sum() > cap:
+        lens[int(np.argmax(lens))] -= 1
+    return lens
+
+
+def config1_tiny(device="cpu", n_points=8, n_steps=16, hidden=256,
+                 device_ring_bytes=1 << 20, host_ring_bytes=4 << 20) -> Workload:
+    pools = [_pool((1, p), 4, (64, hidden), device) for p in range(n_points)]
+
+    def step_calls(step):
+        lens = tiny_lengths(step)
+        base = np.concatenate([[0], np.cumsum(lens)[:-1]])
+        reqs = make_reqs((1000 + r, int(base[r]), int(lens[r]) - 1, 1, 1)
+                         for r in range(len(lens)))
+        return [ObserveCall(point_id=p, step_id=step, tensor=pools[p][step % 4],
+                            reqs=reqs, out_dtype=DT_BF16) for p in range(n_points)]
+
+    return Workload("tiny", device_ring_bytes, host_ring_bytes, POLICY_BLOCK, 1,
+                    n_steps, step_calls, max_reqs=64)
+
+
+# --------------------------------------------------------------------------
+# config 2 / 5: decode, one row per request at every layer
+# --------------------------------------------------------------------------
+def _decode(name, tag, device, hidden, n_points, n_reqs, n_steps, summary_mask,
+            device_ring_bytes, host_ring_bytes, policy_mode, sample_k) -> Workload:
+    pools = [_pool((tag, p), 4, (n_reqs, hidden), device) for p in range(n_points)]
+
+    def step_calls(step):
+        reqs = make_reqs((5000 + r, r, 0, 1, 1) for r in range(n_reqs))
+        return [ObserveCall(point_id=p, step_id=step, tensor=pools[p][step % 4],
+                            reqs=reqs, out_dtype=DT_BF16, summary_mask=summary_mask)
+                for p in range(n_points)]
+
+    return Workload(name, device_ring_bytes, host_ring_bytes, policy_mode, sample_k,
+                    n_steps, step_calls, max_reqs=max(64, n_reqs))
+
+
+def config2_decode8b(device="cpu", n_points=32, n_reqs=64, n_steps=256, hidden=4096,
+                     device_ring_bytes=256 << 20, host_ring_bytes=2 << 30) -> Workload:
+    return _decode("decode8b", 2, device, hidden, n_points, n_reqs, n_steps,
+                   SUM_L2 | SUM_ABSMAX, device_ring_bytes, host_ring_bytes,
+                   POLICY_BLOCK, 1)
+
+
+def config5_saturation(device="cpu", n_points=80, n_reqs=256, n_steps=200, hidden=8192,
+                       sample_k=1, device_ring_bytes=4 << 30,
+                       host_ring_bytes=16 << 30) -> Workload:
+    return _decode("saturation70b", 5, device, hidden, n_points, n_reqs, n_steps, 0,
+                   device_ring_bytes, host_ring_bytes, POLICY_DROP_NEWEST, sample_k)
+
+
+# --------------------------------------------------------------------------
+# config 3: ragged prefill, every 4th token, fp8 downcast
+# --------------------------------------------------------------------------
+def config3_prefill(device="cpu", n_reqs=32, len_lo=128, len_hi=2048, n_steps=8,
+                    hidden=4096, inter=14336, n_resid=8, n_mlp=2, tok_step=4,
+                    out_dtype=DT_FP8, device_ring_bytes=512 << 20,
+                    host_ring_bytes=4 << 30) -> Workload:
+    t_max = n_reqs * len_hi
+    resid = [prng.randn_bf16(prng.sub_seed(3, 0, p), t_max * hidden, device).view(t_max, hidden)
+             for p in range(n_resid)]
+    mlp = [prng.randn_bf16(prng.sub_seed(3, 1, p), t_max * inter, device).view(t_max, inter)
+           for p in range(n_mlp)]
+
+    def step_calls(step):
+        lens = prng.randint(prng.sub_seed(3, 9, step), n_reqs, len_lo, len_hi)
+        base = np.concatenate([[0], np.cumsum(lens)[:-1]])
+        reqs = make_reqs((7000 + 100 * step + r, int(base[r]), 0,
+                          -(-int(lens[r]) // tok_step), tok_step) for r in range(n_reqs))
+        calls = []
+        # hook order inside a layer stack: residual points interleaved with the MLP ones
+        mlp_after = {max(0, n_resid // 2 - 1): 0, n_resid - 1: 1} if n_mlp == 2 else \
+                    {i: i for i in range(n_mlp)}
+        for p in range(n_resid):
+            calls.append(ObserveCall(point_id=p, step_id=step, tensor=resid[p], reqs=reqs,
+                                     out_dtype=out_dtype))
+            if p in mlp_after and mlp_after[p] < n_mlp:
+                m = mlp_after[p]
+                calls.append(ObserveCall(point_id=100 + m, step_id=step, tensor=mlp[m],
+                                         reqs=reqs, out_dtype=out_dtype))
+        return calls
+
+    return Workload("prefill_ragged", device_ring_bytes, host_ring_bytes,
+                    POLICY_DROP_NEWEST, 1, n_steps, step_calls, max_reqs=max(64, n_reqs))
+
+
+# --------------------------------------------------------------------------
+# config 4: paged KV-cache slices
+# --------------------------------------------------------------------------
+def config4_paged_kv(device="cpu", n_layers_cap=4, n_blocks=65536, block_size=16,
+                     n_heads=8, head_dim=128, n_reqs=128, ctx_lo=512, ctx_hi=8192,
+                     reqs_per_step=16, n_steps=128, heads_sel=(1, 5),
+                     device_ring_bytes=2 << 30, host_ring_bytes=8 << 30) -> Workload:
+    ctx0 = prng.randint(prng.sub_seed(4, 1), n_reqs, ctx_lo, ctx_hi)
+    need = -(-(ctx0 + n_steps) // block_size)            # blocks per request
+    max_blocks = int(-(-(ctx_hi + n_steps) // block_size))
+    assert int(need.sum()) <= n_blocks, "context mix does not fit the physical block pool"
+    perm = prng.permutation(prng.sub_seed(4, 2), n_blocks)
+    table = np.full((n_reqs, max_blocks), -1, dtype=np.int32)
+    cur = 0
+    for r in range(n_reqs):
+        table[r, :need[r]] = perm[cur:cur + need[r]]
+        cur += int(need[r])
+    # unused entries point at a valid block so that no selection can leave the cache
+    table[table < 0] = 0
+    block_table = torch.from_numpy(table).to(device)
+    shape = (n_blocks, block_size, n_heads, head_dim)
+    n = int(np.prod(shape))
+    caches = [[prng.randn_bf16(prng.sub_seed(4, 3, l, kv), n, device).view(*shape)
+               for kv in range(2)] for l in range(n_layers_cap)]
+    spec = PagedSpec(block_size, n_heads, head_dim, list(heads_sel), block_table)
+
+    def step_calls(step):
+        chosen = np.sort(prng.permutation(prng.sub_seed(4, 5, step), n_reqs)[:reqs_per_step])
+        reqs = make_reqs((9000 + int(r), int(r), 0, int(ctx0[r]) + step, 1) for r in chosen)
+        return [ObserveCall(point_id=2 * l + kv, step_id=step, tensor=caches[l][kv],
+                            reqs=reqs, out_dtype=DT_BF16, paged=spec)
+                for l in range(n_layers_cap) for kv in range(2)]
+
+    return Workload("paged_kv", device_ring_bytes, host_ring_bytes, POLICY_BLOCK, 1,
+                    n_steps, step_calls, max_reqs=max(64, reqs_per_step),
+                    notes={"ctx0": ctx0, "layers": [0, 10, 21, 31][:n_layers_cap]})
