@@ -1,0 +1,279 @@
+/*
+ * dmi.h -- C ABI of the capture-and-stage library for model-internal
+ * observability on AMD Instinct MI355X (gfx950).
+ *
+ * The library is the Ring^2 staging mechanism of the DMI-Lib paper (section 4.2)
+ * together with the first stage of its data exporter (section 4.3) and the
+ * policy manager's bandwidth controls (section 4.4), for one GPU:
+ *
+ *   producer   dmi_observe / dmi_observe_paged launch one HIP kernel on the
+ *              caller's stream.  The kernel gathers the selected rows of the
+ *              observed tensor, optionally downcasts them and reduces them to
+ *              per-row summaries, and packs them behind a 64-byte descriptor
+ *              into a byte ring in device memory.  The observed tensor is never
+ *              modified and never retained (section 4.1).
+ *   consumer   dmi_drain moves committed bytes into a pinned host ring;
+ *              dmi_poll_host exposes whole records there; dmi_release_host
+ *              gives the space back.
+ *   policy     completeness (block), record-granular best effort (drop newest,
+ *              counted), 1-in-k step sampling, per-point enable (hook filtering).
+ *
+ * Record layout in both rings (little endian, every pad byte zero; all sections
+ * are padded to 64 bytes, so ring capacities and record sizes are multiples of 64
+ * and a stream byte b lives at offset b mod capacity):
+ *
+ *   header 64 B : 0 u32 magic 0x32494D44 | 4 u16 version 1 | 6 u16 header_bytes 64
+ *                 8 u64 seq | 16 u64 step_id | 24 u32 point_id
+ *                 28 u8 src_dtype | 29 u8 out_dtype | 30 u8 summary_mask
+ *                 31 u8 flags (DMI_REC_PAGED | DMI_REC_MASKED | DMI_REC_INDEXED)
+ *                 32 u32 n_reqs | 36 u32 n_rows | 40 u32 row_elems | 44 u32 rank_tag
+ *                 48 u64 record_bytes | 56 u64 payload_bytes
+ *   req table   : n_reqs x { u32 req_id, u32 tok_start, u32 tok_step, u32 n_rows_r }
+ *   payload     : n_rows x row_elems x sizeof(out_dtype), request-major, tokens
+ *                 ascending, tightly packed (absent if out_dtype is DMI_DTYPE_NONE)
+ *   summaries   : for each set bit of summary_mask in ascending order
+ *                 (L2, mean, absmax): f32[n_rows]
+ *
+ * Conventions.  Pointers are marked [host] or [device].  The library owns both
+ * rings; the caller owns every tensor, block table, mask and index list and
+ * keeps them valid until the launched kernel has run on its stream.  No call
+ * synchronises the caller's stream.  All observes of one ring must execute on
+ * the GPU in call order (one stream, or streams chained by events).  One
+ * producer thread per ring; dmi_drain / dmi_poll_host / dmi_release_host /
+ * dmi_get_stats may be called from another thread.  Every function returns
+ * DMI_OK (0), a positive informational code, or a negative error; after an
+ * error dmi_last_error() gives a message (thread local).  Nothing throws.
+ */
+#ifndef DMI_H
+#define DMI_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dmi_ring dmi_ring_t;   /* opaque, library-owned */
+typedef int32_t dmi_status_t;
+
+enum {
+    DMI_OK = 0,
+    DMI_SAMPLED_OUT = 1,        /* step not selected by 1-in-k sampling: nothing captured */
+    DMI_POINT_DISABLED = 2,     /* point switched off: nothing captured */
+    DMI_ERR_INVALID_ARG = -1,
+    DMI_ERR_NOMEM = -2,
+    DMI_ERR_TOO_LARGE = -3,     /* the record can never fit the device ring */
+    DMI_ERR_HIP = -4,           /* a HIP call failed (also: no GPU present) */
+    DMI_ERR_AGAIN = -5,         /* would block: no room and nothing more can be drained */
+    DMI_ERR_CLOSED = -6
+};
+
+enum { DMI_DTYPE_NONE = 0, DMI_DTYPE_BF16 = 1, DMI_DTYPE_FP16 = 2, DMI_DTYPE_FP32 = 3,
+       DMI_DTYPE_FP8_E4M3FN = 4 };
+enum { DMI_SUM_L2 = 1, DMI_SUM_MEAN = 2, DMI_SUM_ABSMAX = 4 };
+enum { DMI_REC_PAGED = 1, DMI_REC_MASKED = 2, DMI_REC_INDEXED = 4 };
+enum { DMI_POLICY_BLOCK = 0, DMI_POLICY_DROP_NEWEST = 1 };
+
+/* ring flags */
+enum {
+    DMI_DRAIN_COPY_ENGINE = 1,  /* drain with hipMemcpyAsync on a side stream (default) */
+    DMI_DRAIN_KERNEL = 2,       /* drain with a copy kernel writing pinned host memory */
+    DMI_BG_THREAD = 4           /* the library runs its own drain thread (section 4.3) */
+};
+/* dmi_drain flags */
+enum {
+    DMI_DRAIN_NONBLOCK = 1,     /* issue the copies and return without waiting for them */
+    DMI_DRAIN_FLUSH = 2         /* first wait until every observe issued so far has committed */
+};
+
+#define DMI_MAGIC 0x32494D44u
+#define DMI_HEADER_BYTES 64u
+#define DMI_MAX_HEADS_SEL 8u
+#define DMI_MAX_POINTS 4096u
+
+/*
+ * Ring creation (paper section 4.2: bounded staging, allocated once).
+ *   device_ring_bytes, host_ring_bytes: capacities, multiples of 64, >= 4096.
+ *   device_id: HIP device ordinal.   flags: ring flags above (0 = copy engine).
+ *   max_reqs_per_observe: upper bound on n_reqs of any observe (0 = 1024, at most 4096:
+ *             the per-request prefix sums live in LDS).
+ *   rank_tag: written into every header (section 4.5: records carry the
+ *             producer's parallel coordinates).
+ *   bg_min_bytes / bg_timeout_us: the background drain thread issues a copy
+ *             once this many committed bytes are waiting or the oldest has
+ *             waited this long (section 4.3: byte-count and timeout thresholds);
+ *             0 = 1 MiB / 200 us.
+ *   block_timeout_ms: how long a blocking call waits for room before returning
+ *             DMI_ERR_AGAIN (0 = 2000 ms).
+ * Returns DMI_ERR_HIP if the device or a HIP allocation is not available,
+ * DMI_ERR_INVALID_ARG for bad sizes.  *out is written only on success.
+ */
+typedef struct {
+    uint64_t device_ring_bytes;
+    uint64_t host_ring_bytes;
+    int32_t device_id;
+    uint32_t flags;
+    uint32_t max_reqs_per_observe;
+    uint32_t rank_tag;
+    uint64_t bg_min_bytes;
+    uint32_t bg_timeout_us;
+    uint32_t block_timeout_ms;
+} dmi_ring_config_t;
+
+dmi_status_t dmi_ring_create(const dmi_ring_config_t *cfg /*[host]*/, dmi_ring_t **out /*[host]*/);
+
+/* Stops the drain thread, waits for the library's own streams, frees both
+ * rings.  Undrained data is discarded.  The caller must have synchronised the
+ * streams it passed to dmi_observe. */
+dmi_status_t dmi_ring_destroy(dmi_ring_t *ring);
+
+/* Observed tensor: a row-major matrix [shape[0], shape[1]] of `dtype`
+ * (BF16 / FP16 / FP32), stride in elements, stride[1] == 1.  Any 2-byte (4 for
+ * FP32) aligned base and any shape are accepted; 16-byte aligned bases and row
+ * pitches with shape[1]*sizeof(dtype) % 16 == 0 take the vectorised kernel. */
+typedef struct {
+    const void *data;           /* [device] */
+    uint32_t dtype;
+    int64_t shape[2];
+    int64_t stride[2];
+} dmi_tensor_t;
+
+/* One request's token range.  Dense tensors: the j-th selected row (j < tok_count)
+ * is tensor row  row_base + tok_start + j*tok_step.  Paged caches: row_base is the
+ * request's row in the block table and tok_start + j*tok_step a logical token
+ * position.  req_id, tok_start and tok_step are copied into the record's request
+ * table (the metadata the paper keeps in its TensorMetaFIFO, section 4.2). */
+typedef struct {
+    uint32_t req_id, row_base, tok_start, tok_count, tok_step;
+} dmi_req_sel_t;
+
+/* Ragged per-request row selection.
+ *   reqs          [host]   n_reqs entries, copied during the call.
+ *   keep_mask_dev [device] optional, n_reqs bytes, read when the kernel runs:
+ *                 request r is captured iff keep_mask_dev[r] != 0 (the paper's
+ *                 batch-aligned keep/drop vector, section 4.4; it changes data,
+ *                 not launch topology).
+ *   row_index_dev [device] optional (dense only): explicit tensor row for every
+ *                 listed row, request-major, sum(tok_count) int32 entries; masked-out
+ *                 requests still occupy their entries.  tok_start/tok_step are then
+ *                 metadata only. */
+typedef struct {
+    uint32_t n_reqs;
+    const dmi_req_sel_t *reqs;
+    const uint8_t *keep_mask_dev;
+    const int32_t *row_index_dev;
+} dmi_selection_t;
+
+/* What is stored per row.  out_dtype: NONE (summaries only), the source dtype
+ * (raw copy), or, from a BF16 source, FP16 or FP8_E4M3FN (round to nearest even;
+ * FP8 saturates to +-448, NaN stays NaN).  summary_mask: DMI_SUM_* bits, fp32
+ * reductions over the source row. */
+typedef struct {
+    uint32_t out_dtype;
+    uint32_t summary_mask;
+} dmi_transform_t;
+
+/*
+ * Capture one tensor (paper section 4.2 step 1-2, section 4.4 gather-compact).
+ * Launches one kernel on hip_stream [hipStream_t, 0 = null stream] and returns.
+ * Policy: disabled point -> DMI_POINT_DISABLED; step_id % sample_k != sample_phase
+ * -> DMI_SAMPLED_OUT; record larger than the device ring -> DMI_ERR_TOO_LARGE;
+ * DMI_POLICY_BLOCK with no room -> drains, waiting on the host up to
+ * block_timeout_ms, then DMI_ERR_AGAIN; DMI_POLICY_DROP_NEWEST never waits: the
+ * kernel discards the record if it does not fit when it runs, and counts it.
+ * A sequence number is consumed only when a kernel is launched.
+ */
+dmi_status_t dmi_observe(dmi_ring_t *ring, uint32_t point_id, const dmi_tensor_t *tensor /*[host]*/,
+                         const dmi_selection_t *sel /*[host]*/, const dmi_transform_t *xf /*[host]*/,
+                         uint64_t step_id, void *hip_stream);
+
+/* Paged KV cache: element (block b, slot s, head h, dim d) is at
+ * base + b*block_stride + s*slot_stride + h*head_stride + d (strides in elements).
+ * block_table_dev [device] int32 [n_seqs][block_table_stride]: physical block of
+ * logical block t / block_size of a sequence.  A captured row is the
+ * concatenation of head_dim elements of each selected head, in heads_sel order. */
+typedef struct {
+    const void *base;           /* [device] */
+    uint32_t dtype;
+    int64_t block_stride, slot_stride, head_stride;
+    uint32_t block_size, n_heads, head_dim;
+    uint32_t n_blocks;          /* physical blocks in the cache (bounds for table entries) */
+    uint32_t n_seqs;            /* rows of the block table */
+    const int32_t *block_table_dev;
+    int64_t block_table_stride;
+    uint32_t n_heads_sel;
+    uint32_t heads_sel[DMI_MAX_HEADS_SEL];
+} dmi_paged_kv_t;
+
+/* As dmi_observe, for slices of a paged KV cache (the paper lists KV-cache
+ * slices among the observable states, section 1; the block-table walk is this
+ * build's).  sel->row_index_dev must be NULL. */
+dmi_status_t dmi_observe_paged(dmi_ring_t *ring, uint32_t point_id, const dmi_paged_kv_t *kv /*[host]*/,
+                               const dmi_selection_t *sel /*[host]*/, const dmi_transform_t *xf /*[host]*/,
+                               uint64_t step_id, void *hip_stream);
+
+/* Move committed bytes from the device ring to the host ring (section 4.3, drain
+ * stage).  Copies what is committed and fits the host ring's free space, then
+ * lets the device reuse the drained span.  *bytes_moved [host, optional] = bytes
+ * whose copy this call issued.  With DMI_DRAIN_FLUSH returns DMI_ERR_AGAIN if
+ * the host ring filled up before everything was moved (release and call again)
+ * or the observes did not commit within block_timeout_ms. */
+dmi_status_t dmi_drain(dmi_ring_t *ring, uint32_t flags, uint64_t *bytes_moved);
+
+/* A whole record in the host ring: [p0, p0+n0) then, iff it straddles the end of
+ * the ring, [p1, p1+n1).  Valid until released. */
+typedef struct {
+    const void *p0;             /* [host, pinned] */
+    uint64_t n0;
+    const void *p1;
+    uint64_t n1;
+    uint64_t seq;
+} dmi_record_view_t;
+
+/* Return up to max complete, not yet polled records in sequence order. */
+dmi_status_t dmi_poll_host(dmi_ring_t *ring, dmi_record_view_t *out /*[host]*/, uint32_t max,
+                           uint32_t *n /*[host]*/);
+
+/* Give back every polled record with seq <= upto_seq_inclusive. */
+dmi_status_t dmi_release_host(dmi_ring_t *ring, uint64_t upto_seq_inclusive);
+
+/* Backpressure policy (section 4.4), effective from the next dmi_observe. */
+typedef struct {
+    uint32_t mode;              /* DMI_POLICY_* */
+    uint32_t sample_k;          /* >= 1 */
+    uint32_t sample_phase;      /* < sample_k */
+} dmi_policy_t;
+dmi_status_t dmi_set_policy(dmi_ring_t *ring, const dmi_policy_t *policy /*[host]*/);
+
+/* Hook filtering (section 4.4): a disabled point launches nothing. */
+dmi_status_t dmi_point_enable(dmi_ring_t *ring, uint32_t point_id, int enabled);
+
+typedef struct {
+    uint64_t observed_calls, launched_records;
+    uint64_t captured_records, captured_rows, captured_bytes;   /* committed on the device */
+    uint64_t dropped_records, dropped_rows, dropped_bytes;      /* discarded by drop-newest */
+    uint64_t sampled_out_calls, sampled_out_rows, disabled_calls;
+    uint64_t drained_bytes, released_bytes, drain_batches;
+    uint64_t block_wait_ns;
+    uint64_t dev_ring_high_water, host_ring_high_water;
+} dmi_stats_t;
+/* Device-side counters reflect kernels that have finished. */
+dmi_status_t dmi_get_stats(dmi_ring_t *ring, dmi_stats_t *out /*[host]*/);
+/* Records of one point discarded by drop-newest (synchronises the library's
+ * own control stream only). */
+dmi_status_t dmi_get_point_drops(dmi_ring_t *ring, uint32_t point_id, uint64_t *n /*[host]*/);
+
+/* Test hook: fill both rings with one byte value (synchronous).  Lets a test see
+ * that every byte of every record, pads included, is written by the capture. */
+dmi_status_t dmi_debug_fill_rings(dmi_ring_t *ring, uint8_t value);
+
+/* Pure host helpers (no GPU needed). */
+uint64_t dmi_record_bytes(uint32_t n_reqs, uint64_t n_rows, uint32_t row_elems, uint32_t out_dtype,
+                          uint32_t summary_mask);
+const char *dmi_last_error(void);
+const char *dmi_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DMI_H */

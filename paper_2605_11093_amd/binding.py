@@ -1,0 +1,307 @@
+"""ctypes binding of include/dmi.h: same names, argument marshalling only.
+
+Every step of the capture-and-stage path runs inside libdmi.so.  There is no
+fallback: if the library is missing or no GPU is present the calls raise.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SO = os.path.join(_HERE, "libdmi.so")
+_lib = None
+
+OK, SAMPLED_OUT, POINT_DISABLED = 0, 1, 2
+ERR_INVALID_ARG, ERR_NOMEM, ERR_TOO_LARGE, ERR_HIP, ERR_AGAIN, ERR_CLOSED = -1, -2, -3, -4, -5, -6
+DT_NONE, DT_BF16, DT_FP16, DT_FP32, DT_FP8 = 0, 1, 2, 3, 4
+SUM_L2, SUM_MEAN, SUM_ABSMAX = 1, 2, 4
+POLICY_BLOCK, POLICY_DROP_NEWEST = 0, 1
+DRAIN_COPY_ENGINE, DRAIN_KERNEL, BG_THREAD = 1, 2, 4
+DRAIN_NONBLOCK, DRAIN_FLUSH = 1, 2
+
+
+class DmiError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"dmi error {code}: {msg}")
+        self.code = code
+
+
+class RingConfig(C.Structure):
+    _fields_ = [("device_ring_bytes", C.c_uint64), ("host_ring_bytes", C.c_uint64),
+                ("device_id", C.c_int32), ("flags", C.c_uint32),
+                ("max_reqs_per_observe", C.c_uint32), ("rank_tag", C.c_uint32),
+                ("bg_min_bytes", C.c_uint64), ("bg_timeout_us", C.c_uint32),
+                ("block_timeout_ms", C.c_uint32)]
+
+
+class Tensor(C.Structure):
+    _fields_ = [("data", C.c_void_p), ("dtype", C.c_uint32), ("shape", C.c_int64 * 2),
+                ("stride", C.c_int64 * 2)]
+
+
+class ReqSel(C.Structure):
+    _fields_ = [(n, C.c_uint32) for n in ("req_id", "row_base", "tok_start", "tok_count", "tok_step")]
+
+
+class Selection(C.Structure):
+    _fields_ = [("n_reqs", C.c_uint32), ("reqs", C.c_void_p), ("keep_mask_dev", C.c_void_p),
+                ("row_index_dev", C.c_void_p)]
+
+
+class Transform(C.Structure):
+    _fields_ = [("out_dtype", C.c_uint32), ("summary_mask", C.c_uint32)]
+
+
+class PagedKV(C.Structure):
+    _fields_ = [("base", C.c_void_p), ("dtype", C.c_uint32), ("block_stride", C.c_int64),
+                ("slot_stride", C.c_int64), ("head_stride", C.c_int64),
+                ("block_size", C.c_uint32), ("n_heads", C.c_uint32), ("head_dim", C.c_uint32),
+                ("n_blocks", C.c_uint32), ("n_seqs", C.c_uint32),
+                ("block_table_dev", C.c_void_p), ("block_table_stride", C.c_int64),
+                ("n_heads_sel", C.c_uint32), ("heads_sel", C.c_uint32 * 8)]
+
+
+class RecordViewC(C.Structure):
+    _fields_ = [("p0", C.c_void_p), ("n0", C.c_uint64), ("p1", C.c_void_p), ("n1", C.c_uint64),
+                ("seq", C.c_uint64)]
+
+
+class Policy(C.Structure):
+    _fields_ = [("mode", C.c_uint32), ("sample_k", C.c_uint32), ("sample_phase", C.c_uint32)]
+
+
+_STAT_FIELDS = ("observed_calls", "launched_records", "captured_records", "captured_rows",
+                "captured_bytes", "dropped_records", "dropped_rows", "dropped_bytes",
+                "sampled_out_calls", "sampled_out_rows", "disabled_calls", "drained_bytes",
+                "released_bytes", "drain_batches", "block_wait_ns", "dev_ring_high_water",
+                "host_ring_high_water")
+
+
+class StatsC(C.Structure):
+    _fields_ = [(n, C.c_uint64) for n in _STAT_FIELDS]
+
+
+@dataclass
+class Stats:
+    observed_calls: int = 0
+    launched_records: int = 0
+    captured_records: int = 0
+    captured_rows: int = 0
+    captured_bytes: int = 0
+    dropped_records: int = 0
+    dropped_rows: int = 0
+    dropped_bytes: int = 0
+    sampled_out_calls: int = 0
+    sampled_out_rows: int = 0
+    disabled_calls: int = 0
+    drained_bytes: int = 0
+    released_bytes: int = 0
+    drain_batches: int = 0
+    block_wait_ns: int = 0
+    dev_ring_high_water: int = 0
+    host_ring_high_water: int = 0
+
+
+@dataclass
+class RecordView:
+    seq: int
+    p0: int
+    n0: int
+    p1: int
+    n1: int
+
+    @property
+    def nbytes(self) -> int:
+        return self.n0 + self.n1
+
+    def bytes(self) -> np.ndarray:
+        """Copy of the record's bytes (valid only until the record is released)."""
+        out = np.empty(self.n0 + self.n1, dtype=np.uint8)
+        C.memmove(out.ctypes.data, self.p0, self.n0)
+        if self.n1:
+            C.memmove(out.ctypes.data + self.n0, self.p1, self.n1)
+        return out
+
+
+def library_path() -> str:
+    return _SO
+
+
+def lib():
+    """Load libdmi.so; raises if it has not been built (no fallback path exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_SO):
+        raise ImportError(f"{_SO} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
+    L = C.CDLL(_SO)
+    P = C.POINTER
+    L.dmi_last_error.restype = C.c_char_p
+    L.dmi_version.restype = C.c_char_p
+    L.dmi_record_bytes.restype = C.c_uint64
+    L.dmi_record_bytes.argtypes = [C.c_uint32, C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32]
+    L.dmi_ring_create.argtypes = [P(RingConfig), P(C.c_void_p)]
+    L.dmi_ring_destroy.argtypes = [C.c_void_p]
+    L.dmi_observe.argtypes = [C.c_void_p, C.c_uint32, P(Tensor), P(Selection), P(Transform),
+                              C.c_uint64, C.c_void_p]
+    L.dmi_observe_paged.argtypes = [C.c_void_p, C.c_uint32, P(PagedKV), P(Selection), P(Transform),
+                                    C.c_uint64, C.c_void_p]
+    L.dmi_drain.argtypes = [C.c_void_p, C.c_uint32, P(C.c_uint64)]
+    L.dmi_poll_host.argtypes = [C.c_void_p, P(RecordViewC), C.c_uint32, P(C.c_uint32)]
+    L.dmi_release_host.argtypes = [C.c_void_p, C.c_uint64]
+    L.dmi_set_policy.argtypes = [C.c_void_p, P(Policy)]
+    L.dmi_point_enable.argtypes = [C.c_void_p, C.c_uint32, C.c_int]
+    L.dmi_get_stats.argtypes = [C.c_void_p, P(StatsC)]
+    L.dmi_get_point_drops.argtypes = [C.c_void_p, C.c_uint32, P(C.c_uint64)]
+    L.dmi_debug_fill_rings.argtypes = [C.c_void_p, C.c_uint8]
+    for name in ("dmi_ring_create", "dmi_ring_destroy", "dmi_observe", "dmi_observe_paged", "dmi_drain",
+                 "dmi_poll_host", "dmi_release_host", "dmi_set_policy", "dmi_point_enable",
+                 "dmi_get_stats", "dmi_get_point_drops", "dmi_debug_fill_rings"):
+        getattr(L, name).restype = C.c_int32
+    _lib = L
+    return L
+
+
+def version() -> str:
+    return lib().dmi_version().decode()
+
+
+def record_bytes(n_reqs: int, n_rows: int, row_elems: int, out_dtype: int, summary_mask: int) -> int:
+    return int(lib().dmi_record_bytes(n_reqs, n_rows, row_elems, out_dtype, summary_mask))
+
+
+def _check(code: int, allow: Sequence[int] = ()) -> int:
+    if code < 0 and code not in allow:
+        raise DmiError(code, lib().dmi_last_error().decode())
+    return code
+
+
+_TORCH_DT = None
+
+
+def _torch_dtype_code(t) -> int:
+    global _TORCH_DT
+    if _TORCH_DT is None:
+        import torch
+        _TORCH_DT = {torch.bfloat16: DT_BF16, torch.float16: DT_FP16, torch.float32: DT_FP32}
+    return _TORCH_DT[t.dtype]
+
+
+def _reqs_buffer(reqs):
+    a = np.ascontiguousarray(np.asarray(reqs, dtype=np.uint32).reshape(-1, 5))
+    return a
+
+
+class Ring:
+    """Thin object wrapper: one method per C entry point."""
+
+    def __init__(self, device_ring_bytes: int, host_ring_bytes: int, *, device_id: int = 0,
+                 flags: int = 0, max_reqs_per_observe: int = 0, rank_tag: int = 0,
+                 bg_min_bytes: int = 0, bg_timeout_us: int = 0, block_timeout_ms: int = 0):
+        cfg = RingConfig(device_ring_bytes, host_ring_bytes, device_id, flags, max_reqs_per_observe,
+                         rank_tag, bg_min_bytes, bg_timeout_us, block_timeout_ms)
+        h = C.c_void_p()
+        _check(lib().dmi_ring_create(C.byref(cfg), C.byref(h)))
+        self._h = h
+        self._views = (RecordViewC * 256)()
+
+    # -- lifetime --------------------------------------------------------
+    def destroy(self):
+        if self._h:
+            _check(lib().dmi_ring_destroy(self._h))
+            self._h = None
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.destroy()
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    # -- producer --------------------------------------------------------
+    def observe(self, point_id: int, data_ptr: int, dtype: int, shape, stride, reqs, *,
+                step_id: int, stream: int = 0, out_dtype: int = DT_BF16, summary_mask: int = 0,
+                keep_mask_dev: int = 0, row_index_dev: int = 0, allow: Sequence[int] = ()) -> int:
+        ra = _reqs_buffer(reqs)
+        t = Tensor(data_ptr, dtype, (C.c_int64 * 2)(*shape), (C.c_int64 * 2)(*stride))
+        sel = Selection(ra.shape[0], ra.ctypes.data, keep_mask_dev or None, row_index_dev or None)
+        xf = Transform(out_dtype, summary_mask)
+        return _check(lib().dmi_observe(self._h, point_id, C.byref(t), C.byref(sel), C.byref(xf),
+                                        step_id, stream or None), allow)
+
+    def observe_tensor(self, point_id: int, tensor, reqs, *, step_id: int, stream: int = 0,
+                       out_dtype: Optional[int] = None, summary_mask: int = 0, keep_mask=None,
+                       row_index=None, allow: Sequence[int] = ()) -> int:
+        """Convenience for torch tensors on the GPU (device memory and streams only)."""
+        dt = _torch_dtype_code(tensor)
+        return self.observe(point_id, tensor.data_ptr(), dt, tuple(tensor.shape),
+                            tuple(tensor.stride()), reqs, step_id=step_id, stream=stream,
+                            out_dtype=dt if out_dtype is None else out_dtype,
+                            summary_mask=summary_mask,
+                            keep_mask_dev=0 if keep_mask is None else keep_mask.data_ptr(),
+                            row_index_dev=0 if row_index is None else row_index.data_ptr(),
+                            allow=allow)
+
+    def observe_paged(self, point_id: int, cache, block_table, reqs, *, block_size: int,
+                      n_heads: int, head_dim: int, heads_sel: Sequence[int], step_id: int,
+                      stream: int = 0, out_dtype: Optional[int] = None, summary_mask: int = 0,
+                      keep_mask=None, allow: Sequence[int] = ()) -> int:
+        """cache: torch tensor [blocks, slots, heads, dim]; block_table: int32 [n_seqs, max_blocks]."""
+        dt = _torch_dtype_code(cache)
+        ra = _reqs_buffer(reqs)
+        kv = PagedKV(cache.data_ptr(), dt, cache.stride(0), cache.stride(1), cache.stride(2),
+                     block_size, n_heads, head_dim, cache.shape[0], block_table.shape[0],
+                     block_table.data_ptr(), block_table.stride(0), len(heads_sel),
+                     (C.c_uint32 * 8)(*heads_sel))
+        sel = Selection(ra.shape[0], ra.ctypes.data,
+                        None if keep_mask is None else keep_mask.data_ptr(), None)
+        xf = Transform(dt if out_dtype is None else out_dtype, summary_mask)
+        return _check(lib().dmi_observe_paged(self._h, point_id, C.byref(kv), C.byref(sel),
+                                              C.byref(xf), step_id, stream or None), allow)
+
+    # -- consumer --------------------------------------------------------
+    def drain(self, flags: int = 0, allow: Sequence[int] = ()) -> int:
+        moved = C.c_uint64()
+        code = _check(lib().dmi_drain(self._h, flags, C.byref(moved)), allow)
+        self.last_drain_status = code
+        return int(moved.value)
+
+    def poll_host(self, max_records: int = 256) -> List[RecordView]:
+        n = C.c_uint32()
+        m = min(max_records, len(self._views))
+        _check(lib().dmi_poll_host(self._h, self._views, m, C.byref(n)))
+        return [RecordView(v.seq, v.p0 or 0, v.n0, v.p1 or 0, v.n1) for v in self._views[: n.value]]
+
+    def release_host(self, upto_seq: int):
+        _check(lib().dmi_release_host(self._h, upto_seq))
+
+    # -- policy / stats --------------------------------------------------
+    def set_policy(self, mode: int, sample_k: int = 1, sample_phase: int = 0):
+        p = Policy(mode, sample_k, sample_phase)
+        _check(lib().dmi_set_policy(self._h, C.byref(p)))
+
+    def point_enable(self, point_id: int, enabled: bool):
+        _check(lib().dmi_point_enable(self._h, point_id, int(enabled)))
+
+    def get_stats(self) -> Stats:
+        s = StatsC()
+        _check(lib().dmi_get_stats(self._h, C.byref(s)))
+        return Stats(**{n: int(getattr(s, n)) for n in _STAT_FIELDS})
+
+    def get_point_drops(self, point_id: int) -> int:
+        n = C.c_uint64()
+        _check(lib().dmi_get_point_drops(self._h, point_id, C.byref(n)))
+        return int(n.value)
+
+    def debug_fill_rings(self, value: int):
+        _check(lib().dmi_debug_fill_rings(self._h, value))

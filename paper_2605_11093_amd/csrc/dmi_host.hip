@@ -1,0 +1,754 @@
+// Host runtime of the capture-and-stage library: ring ownership, policy gate and
+// admission (paper section 4.4), kernel launches for dmi_observe (section 4.2), the
+// drain stage and pinned host ring (section 4.3), and the C ABI of include/dmi.h.
+#include "dmi.h"
+#include "dmi_internal.h"
+
+#include <atomic>
+#include <chrono>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <deque>
+#include <mutex>
+#include <new>
+#include <string>
+#include <thread>
+#include <vector>
+
+using namespace dmi;
+
+namespace {
+
+thread_local std::string g_err;
+
+dmi_status_t fail(dmi_status_t code, const char *fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+    return code;
+}
+
+#define HIP_TRY(expr)                                                                     \
+    do {                                                                                  \
+        hipError_t e_ = (expr);                                                           \
+        if (e_ != hipSuccess)                                                             \
+            return fail(DMI_ERR_HIP, "%s failed: %s", #expr, hipGetErrorString(e_));      \
+    } while (0)
+
+uint64_t now_ns()
+{
+    return (uint64_t)std::chrono::duration_cast<std::chrono::nanoseconds>(
+               std::chrono::steady_clock::now().time_since_epoch()).count();
+}
+
+inline uint64_t pad64(uint64_t n) { return (n + 63u) & ~63ull; }
+
+uint32_t dtype_size(uint32_t dt)
+{
+    switch (dt) {
+    case DMI_DTYPE_BF16: case DMI_DTYPE_FP16: return 2;
+    case DMI_DTYPE_FP32: return 4;
+    case DMI_DTYPE_FP8_E4M3FN: return 1;
+    default: return 0;
+    }
+}
+
+bool transform_ok(uint32_t src, uint32_t out)
+{
+    if (src != DMI_DTYPE_BF16 && src != DMI_DTYPE_FP16 && src != DMI_DTYPE_FP32) return false;
+    if (out == DMI_DTYPE_NONE || out == src) return true;
+    return src == DMI_DTYPE_BF16 && (out == DMI_DTYPE_FP16 || out == DMI_DTYPE_FP8_E4M3FN);
+}
+
+constexpr uint32_t kSlabSlots = 64;
+constexpr uint32_t kSelCache = 4;
+
+struct SelCache {
+    bool valid = false;
+    hipStream_t stream = nullptr;
+    uint32_t slot = 0;
+    std::vector<uint32_t> words;
+};
+
+struct Pending {
+    hipEvent_t ev;
+    uint64_t upto;
+};
+
+}  // namespace
+
+struct dmi_ring {
+    dmi_ring_config_t cfg{};
+    int dev = 0;
+    uint8_t *dev_ring = nullptr;
+    uint64_t dev_cap = 0;
+    uint8_t *host_ring = nullptr, *host_ring_dev = nullptr;
+    uint64_t host_cap = 0;
+    DevCtrl *dctrl = nullptr;
+    HostCtrl *hctrl = nullptr, *hctrl_dev = nullptr;
+    uint32_t *slab = nullptr;
+    uint32_t slab_slot_words = 0, next_slab = 0, max_reqs = 0;
+    SelCache cache[kSelCache];
+    uint32_t cache_rr = 0;
+    hipStream_t drain_stream = nullptr;
+    uint32_t block_timeout_ms = 2000;
+
+    // policy (set by the producer thread or between steps)
+    std::atomic<uint32_t> mode{DMI_POLICY_BLOCK}, sample_k{1}, sample_phase{0};
+    std::vector<uint8_t> point_off;
+
+    // producer side
+    std::atomic<uint64_t> next_seq{0};
+    std::deque<std::pair<uint64_t, uint64_t>> inflight;    // (seq, upper bound of record bytes)
+    uint64_t inflight_sum = 0;
+
+    // drain / host ring state
+    std::mutex mu;
+    uint64_t drain_issued = 0;
+    std::atomic<uint64_t> drain_done{0};
+    std::deque<Pending> pending;
+    std::vector<hipEvent_t> ev_pool;
+    uint64_t poll_cursor = 0, released = 0;
+    std::deque<std::pair<uint64_t, uint64_t>> polled;      // (seq, end offset)
+
+    // statistics kept on the host
+    std::atomic<uint64_t> observed_calls{0}, sampled_out_calls{0}, sampled_out_rows{0}, disabled_calls{0},
+        drained_bytes{0}, released_bytes{0}, drain_batches{0}, block_wait_ns{0}, dev_high{0}, host_high{0};
+
+    std::thread bg;
+    std::atomic<bool> stop{false};
+};
+
+namespace {
+
+void atomic_max(std::atomic<uint64_t> &a, uint64_t v)
+{
+    uint64_t cur = a.load(std::memory_order_relaxed);
+    while (cur < v && !a.compare_exchange_weak(cur, v, std::memory_order_relaxed)) {}
+}
+
+uint64_t read_committed(const dmi_ring *r)
+{
+    uint64_t c = r->hctrl->committed;
+    std::atomic_thread_fence(std::memory_order_acquire);
+    return c;
+}
+
+// Retire finished copies.  Caller holds r->mu.
+dmi_status_t reap(dmi_ring *r, bool wait)
+{
+    while (!r->pending.empty()) {
+        Pending &p = r->pending.front();
+        hipError_t e = wait ? hipEventSynchronize(p.ev) : hipEventQuery(p.ev);
+        if (e == hipErrorNotReady) break;
+        if (e != hipSuccess) return fail(DMI_ERR_HIP, "drain event: %s", hipGetErrorString(e));
+        r->drain_done.store(p.upto, std::memory_order_release);
+        r->ev_pool.push_back(p.ev);
+        r->pending.pop_front();
+    }
+    return DMI_OK;
+}
+
+// Issue copies for what is committed and fits the host ring.  Caller holds r->mu.
+dmi_status_t drain_locked(dmi_ring *r, bool wait, uint64_t *moved)
+{
+    if (moved) *moved = 0;
+    dmi_status_t st = reap(r, false);
+    if (st != DMI_OK) return st;
+    const uint64_t committed = read_committed(r);
+    atomic_max(r->dev_high, committed - r->drain_done.load(std::memory_order_relaxed));
+    const uint64_t avail = committed - r->drain_issued;
+    const uint64_t host_free = r->host_cap - (r->drain_issued - r->released);
+    const uint64_t n = avail < host_free ? avail : host_free;
+    if (n > 0) {
+        const uint64_t from = r->drain_issued;
+        if (r->cfg.flags & DMI_DRAIN_KERNEL) {
+            uint64_t units = n / 16u;
+            uint32_t grid = (uint32_t)((units + kThreads - 1) / kThreads);
+            if (grid > 128u) grid = 128u;
+            HIP_TRY(launch_drain_kernel(r->dev_ring, r->dev_cap, r->host_ring_dev, r->host_cap, from, n,
+                                        r->dctrl, grid, r->drain_stream));
+        } else {
+            uint64_t off = from, left = n;
+            while (left) {
+                const uint64_t s = off % r->dev_cap, d = off % r->host_cap;
+                uint64_t len = left;
+                if (len > r->dev_cap - s) len = r->dev_cap - s;
+                if (len > r->host_cap - d) len = r->host_cap - d;
+                HIP_TRY(hipMemcpyAsync(r->host_ring + d, r->dev_ring + s, len, hipMemcpyDeviceToHost,
+                                       r->drain_stream));
+                off += len;
+                left -= len;
+            }
+            // the device may reuse the span only after the copies before it have run
+            HIP_TRY(launch_set_tail(r->dctrl, from + n, r->drain_stream));
+        }
+        hipEvent_t ev;
+        if (r->ev_pool.empty()) HIP_TRY(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
+        else { ev = r->ev_pool.back(); r->ev_pool.pop_back(); }
+        HIP_TRY(hipEventRecord(ev, r->drain_stream));
+        r->pending.push_back({ev, from + n});
+        r->drain_issued = from + n;
+        r->drained_bytes += n;
+        r->drain_batches += 1;
+        atomic_max(r->host_high, r->drain_issued - r->released);
+        if (moved) *moved = n;
+    }
+    if (wait) return reap(r, true);
+    return DMI_OK;
+}
+
+// Pop launches the device has finished; returns an upper bound of the device head
+// once everything launched so far has run.
+uint64_t head_upper_bound(dmi_ring *r)
+{
+    const uint64_t done = r->hctrl->last_seq_plus1;
+    std::atomic_thread_fence(std::memory_order_acquire);
+    const uint64_t committed = r->hctrl->committed;
+    while (!r->inflight.empty() && r->inflight.front().first < done) {
+        r->inflight_sum -= r->inflight.front().second;
+        r->inflight.pop_front();
+    }
+    return committed + r->inflight_sum;
+}
+
+// Completeness policy: wait on the host until a record of `ub` bytes is sure to fit.
+dmi_status_t wait_for_room(dmi_ring *r, uint64_t ub)
+{
+    uint64_t t0 = 0;
+    for (;;) {
+        const uint64_t head_ub = head_upper_bound(r);
+        const uint64_t tail = r->drain_done.load(std::memory_order_acquire);
+        if (head_ub - tail + ub <= r->dev_cap) break;
+        if (!t0) t0 = now_ns();
+        uint64_t moved = 0;
+        {
+            std::lock_guard<std::mutex> lk(r->mu);
+            dmi_status_t st = drain_locked(r, true, &moved);
+            if (st != DMI_OK) return st;
+        }
+        if (moved == 0) {
+            if (now_ns() - t0 > (uint64_t)r->block_timeout_ms * 1000000ull) {
+                r->block_wait_ns += now_ns() - t0;
+                return fail(DMI_ERR_AGAIN, "no room in the device ring after %u ms (host ring full or "
+                                           "observes not finishing)", r->block_timeout_ms);
+            }
+            std::this_thread::sleep_for(std::chrono::microseconds(20));
+        }
+    }
+    if (t0) r->block_wait_ns += now_ns() - t0;
+    return DMI_OK;
+}
+
+// Put the request table where the kernel can read it from L2: a slab of slots in
+// device memory, refilled only when the selection differs from recent ones (all
+// hook points of a step share their selection).
+dmi_status_t stage_selection(dmi_ring *r, const dmi_selection_t *sel, hipStream_t s, uint32_t *slot_out)
+{
+    const uint32_t n = sel->n_reqs;
+    std::vector<uint32_t> words((size_t)n * 5u);
+    for (uint32_t i = 0; i < n; i++) {
+        const dmi_req_sel_t &q = sel->reqs[i];
+        words[4u * i + 0] = q.req_id;
+        words[4u * i + 1] = q.tok_start;
+        words[4u * i + 2] = q.tok_step;
+        words[4u * i + 3] = q.tok_count;
+        words[4u * n + i] = q.row_base;
+    }
+    for (auto &c : r->cache) {
+        if (c.valid && c.stream == s && c.words == words) { *slot_out = c.slot; return DMI_OK; }
+    }
+    const uint32_t slot = r->next_slab++ % kSlabSlots;
+    for (auto &c : r->cache) if (c.valid && c.slot == slot) c.valid = false;
+    if (n) HIP_TRY(launch_upload(r->slab + (size_t)slot * r->slab_slot_words, words.data(), n * 5u, s));
+    SelCache &c = r->cache[r->cache_rr++ % kSelCache];
+    c.valid = true; c.stream = s; c.slot = slot; c.words.swap(words);
+    *slot_out = slot;
+    return DMI_OK;
+}
+
+struct Geometry {
+    uint32_t src_dtype, row_elems, n_seg, seg_elems;
+    bool vec16;
+};
+
+dmi_status_t observe_common(dmi_ring *r, uint32_t point_id, const dmi_selection_t *sel,
+                            const dmi_transform_t *xf, uint64_t step_id, void *hip_stream,
+                            const Geometry &geo, CaptureArgs &a)
+{
+    hipStream_t s = (hipStream_t)hip_stream;
+    const uint32_t es_in = dtype_size(geo.src_dtype);
+    uint64_t listed = 0;
+    for (uint32_t i = 0; i < sel->n_reqs; i++) listed += sel->reqs[i].tok_count;
+    const uint32_t unit_elems = geo.vec16 ? 16u / es_in : 1u;
+    const uint64_t upr = geo.row_elems / unit_elems;
+    if (listed > 0xFFFFFFFFull || listed * upr > 0xFFFFFFFFull)
+        return fail(DMI_ERR_TOO_LARGE, "selection of %llu rows x %llu units exceeds one record",
+                    (unsigned long long)listed, (unsigned long long)upr);
+    const uint64_t ub = dmi_record_bytes(sel->n_reqs, listed, geo.row_elems, xf->out_dtype, xf->summary_mask);
+    if (ub > r->dev_cap)
+        return fail(DMI_ERR_TOO_LARGE, "record of %llu bytes exceeds the device ring (%llu)",
+                    (unsigned long long)ub, (unsigned long long)r->dev_cap);
+
+    const uint32_t mode = r->mode.load(std::memory_order_relaxed);
+    if (mode == DMI_POLICY_BLOCK) {
+        dmi_status_t st = wait_for_room(r, ub);
+        if (st != DMI_OK) return st;
+    } else {
+        head_upper_bound(r);    // keeps the in-flight list short
+    }
+
+    uint32_t slot = 0;
+    dmi_status_t st = stage_selection(r, sel, s, &slot);
+    if (st != DMI_OK) return st;
+
+    const uint64_t seq = r->next_seq.load(std::memory_order_relaxed);
+    const bool index_mode = sel->row_index_dev != nullptr;
+    const bool tab_lds = sel->n_reqs <= kLdsTableMax;
+    a.n_seg = geo.n_seg;
+    a.seg_units = geo.seg_elems / unit_elems;
+    a.req_table = reinterpret_cast<const uint4 *>(r->slab + (size_t)slot * r->slab_slot_words);
+    a.row_base = r->slab + (size_t)slot * r->slab_slot_words + 4u * (size_t)sel->n_reqs;
+    a.keep_mask = sel->keep_mask_dev;
+    a.row_index = sel->row_index_dev;
+    a.n_reqs = sel->n_reqs;
+    a.src_dtype = geo.src_dtype;
+    a.out_dtype = xf->out_dtype;
+    a.summary_mask = xf->summary_mask;
+    a.rec_flags = (a.paged ? DMI_REC_PAGED : 0u) | (sel->keep_mask_dev ? DMI_REC_MASKED : 0u) |
+                  (index_mode ? DMI_REC_INDEXED : 0u);
+    a.row_elems = geo.row_elems;
+    a.units_per_row = (uint32_t)upr;
+    a.rows_per_wg = upr <= 128u ? 4u : 1u;
+    a.point_id = point_id;
+    a.rank_tag = r->cfg.rank_tag;
+    a.seq = seq;
+    a.step_id = step_id;
+    a.ring = r->dev_ring;
+    a.cap = r->dev_cap;
+    a.ctrl = r->dctrl;
+    a.hctrl = r->hctrl_dev;
+    a.slot = (uint32_t)(seq % kLaunchSlots);
+    a.drop_newest = mode == DMI_POLICY_DROP_NEWEST ? 1u : 0u;
+    a.table_in_lds = tab_lds ? 1u : 0u;
+    a.lds_bytes = capture_lds_bytes(sel->n_reqs, index_mode, tab_lds);
+
+    uint64_t groups;
+    if (xf->summary_mask) groups = (listed + a.rows_per_wg - 1u) / a.rows_per_wg;
+    else groups = (listed * upr + kThreads - 1u) / kThreads;
+    uint32_t grid = groups < 1u ? 1u : groups > kMaxGrid ? kMaxGrid : (uint32_t)groups;
+
+    hipError_t e = launch_capture(a, grid, geo.vec16, s);
+    if (e != hipSuccess) return fail(DMI_ERR_HIP, "capture launch failed: %s", hipGetErrorString(e));
+    r->next_seq.store(seq + 1, std::memory_order_release);
+    r->inflight.emplace_back(seq, ub);
+    r->inflight_sum += ub;
+    return DMI_OK;
+}
+
+// Common front gate: argument checks shared by both observes, hook filtering, sampling.
+// Returns DMI_OK to proceed, a positive code to stop without error.
+dmi_status_t gate(dmi_ring *r, uint32_t point_id, const dmi_selection_t *sel, const dmi_transform_t *xf,
+                  uint64_t step_id, uint32_t src_dtype)
+{
+    if (!r) return fail(DMI_ERR_INVALID_ARG, "ring is NULL");
+    if (!sel || !xf) return fail(DMI_ERR_INVALID_ARG, "selection / transform is NULL");
+    if (point_id >= DMI_MAX_POINTS) return fail(DMI_ERR_INVALID_ARG, "point_id %u >= %u", point_id, DMI_MAX_POINTS);
+    if (sel->n_reqs > r->max_reqs)
+        return fail(DMI_ERR_INVALID_ARG, "n_reqs %u exceeds max_reqs_per_observe %u", sel->n_reqs, r->max_reqs);
+    if (sel->n_reqs && !sel->reqs) return fail(DMI_ERR_INVALID_ARG, "reqs is NULL");
+    if (!transform_ok(src_dtype, xf->out_dtype))
+        return fail(DMI_ERR_INVALID_ARG, "unsupported dtype pair %u -> %u", src_dtype, xf->out_dtype);
+    if (xf->summary_mask & ~7u) return fail(DMI_ERR_INVALID_ARG, "bad summary_mask %u", xf->summary_mask);
+    r->observed_calls++;
+    if (r->point_off[point_id]) { r->disabled_calls++; return DMI_POINT_DISABLED; }
+    const uint32_t k = r->sample_k.load(std::memory_order_relaxed);
+    if (step_id % k != r->sample_phase.load(std::memory_order_relaxed)) {
+        uint64_t listed = 0;
+        for (uint32_t i = 0; i < sel->n_reqs; i++) listed += sel->reqs[i].tok_count;
+        r->sampled_out_calls++;
+        r->sampled_out_rows += listed;
+        return DMI_SAMPLED_OUT;
+    }
+    return DMI_OK;
+}
+
+void bg_loop(dmi_ring *r)
+{
+    (void)hipSetDevice(r->dev);
+    const uint64_t min_bytes = r->cfg.bg_min_bytes ? r->cfg.bg_min_bytes : (1u << 20);
+    const uint64_t timeout_ns = (uint64_t)(r->cfg.bg_timeout_us ? r->cfg.bg_timeout_us : 200u) * 1000ull;
+    uint64_t waiting_since = 0;
+    while (!r->stop.load(std::memory_order_acquire)) {
+        uint64_t pending_bytes;
+        {
+            std::lock_guard<std::mutex> lk(r->mu);
+            pending_bytes = read_committed(r) - r->drain_issued;
+        }
+        const uint64_t t = now_ns();
+        if (pending_bytes == 0) waiting_since = 0;
+        else if (!waiting_since) waiting_since = t;
+        if (pending_bytes >= min_bytes || (pending_bytes && t - waiting_since >= timeout_ns)) {
+            std::lock_guard<std::mutex> lk(r->mu);
+            uint64_t moved = 0;
+            (void)drain_locked(r, true, &moved);
+            waiting_since = 0;
+            if (moved) continue;
+        }
+        std::this_thread::sleep_for(std::chrono::microseconds(20));
+    }
+}
+
+void free_ring(dmi_ring *r)
+{
+    if (!r) return;
+    if (r->drain_stream) { (void)hipStreamSynchronize(r->drain_stream); (void)hipStreamDestroy(r->drain_stream); }
+    for (auto &p : r->pending) (void)hipEventDestroy(p.ev);
+    for (auto ev : r->ev_pool) (void)hipEventDestroy(ev);
+    if (r->dev_ring) (void)hipFree(r->dev_ring);
+    if (r->dctrl) (void)hipFree(r->dctrl);
+    if (r->slab) (void)hipFree(r->slab);
+    if (r->host_ring) (void)hipHostFree(r->host_ring);
+    if (r->hctrl) (void)hipHostFree(r->hctrl);
+    delete r;
+}
+
+}  // namespace
+
+// =========================================================================== C ABI
+extern "C" {
+
+const char *dmi_last_error(void) { return g_err.c_str(); }
+const char *dmi_version(void) { return "dmi-ring 0.1 (gfx950)"; }
+
+uint64_t dmi_record_bytes(uint32_t n_reqs, uint64_t n_rows, uint32_t row_elems, uint32_t out_dtype,
+                          uint32_t summary_mask)
+{
+    uint64_t b = DMI_HEADER_BYTES;
+    b += pad64((uint64_t)n_reqs * 16u);
+    b += pad64(n_rows * row_elems * dtype_size(out_dtype));
+    b += (uint64_t)__builtin_popcount(summary_mask & 7u) * pad64(n_rows * 4u);
+    return b;
+}
+
+dmi_status_t dmi_ring_create(const dmi_ring_config_t *cfg, dmi_ring_t **out)
+{
+    if (!cfg || !out) return fail(DMI_ERR_INVALID_ARG, "cfg / out is NULL");
+    if (cfg->device_ring_bytes < 4096 || cfg->host_ring_bytes < 4096 || cfg->device_ring_bytes % 64 ||
+        cfg->host_ring_bytes % 64)
+        return fail(DMI_ERR_INVALID_ARG, "ring sizes must be multiples of 64 and at least 4096");
+    if ((cfg->flags & DMI_DRAIN_COPY_ENGINE) && (cfg->flags & DMI_DRAIN_KERNEL))
+        return fail(DMI_ERR_INVALID_ARG, "choose one drain mode");
+    const uint32_t max_reqs = cfg->max_reqs_per_observe ? cfg->max_reqs_per_observe : 1024u;
+    if (max_reqs > 4096u) return fail(DMI_ERR_INVALID_ARG, "max_reqs_per_observe > 4096");
+    int n_dev = 0;
+    hipError_t e = hipGetDeviceCount(&n_dev);
+    if (e != hipSuccess || n_dev <= 0)
+        return fail(DMI_ERR_HIP, "no HIP device available (%s)", hipGetErrorString(e));
+    if (cfg->device_id < 0 || cfg->device_id >= n_dev) return fail(DMI_ERR_INVALID_ARG, "bad device_id");
+    HIP_TRY(hipSetDevice(cfg->device_id));
+
+    dmi_ring *r = new (std::nothrow) dmi_ring;
+    if (!r) return fail(DMI_ERR_NOMEM, "out of host memory");
+    r->cfg = *cfg;
+    r->dev = cfg->device_id;
+    r->dev_cap = cfg->device_ring_bytes;
+    r->host_cap = cfg->host_ring_bytes;
+    r->max_reqs = max_reqs;
+    r->block_timeout_ms = cfg->block_timeout_ms ? cfg->block_timeout_ms : 2000u;
+    r->point_off.assign(DMI_MAX_POINTS, 0);
+    r->slab_slot_words = (max_reqs * 5u + 63u) & ~63u;
+
+    auto bail = [&](hipError_t err, const char *what) {
+        fail(DMI_ERR_HIP, "%s failed: %s", what, hipGetErrorString(err));
+        free_ring(r);
+        return DMI_ERR_HIP;
+    };
+    if ((e = hipMalloc((void **)&r->dev_ring, r->dev_cap)) != hipSuccess) return bail(e, "hipMalloc(device ring)");
+    if ((e = hipMalloc((void **)&r->dctrl, sizeof(DevCtrl))) != hipSuccess) return bail(e, "hipMalloc(ctrl)");
+    if ((e = hipMalloc((void **)&r->slab, (size_t)kSlabSlots * r->slab_slot_words * 4u)) != hipSuccess)
+        return bail(e, "hipMalloc(selection slab)");
+    if ((e = hipHostMalloc((void **)&r->host_ring, r->host_cap, hipHostMallocMapped)) != hipSuccess)
+        return bail(e, "hipHostMalloc(host ring)");
+    if ((e = hipHostGetDevicePointer((void **)&r->host_ring_dev, r->host_ring, 0)) != hipSuccess)
+        return bail(e, "hipHostGetDevicePointer(host ring)");
+    if ((e = hipHostMalloc((void **)&r->hctrl, sizeof(HostCtrl), hipHostMallocMapped | hipHostMallocCoherent)) !=
+        hipSuccess)
+        return bail(e, "hipHostMalloc(ctrl)");
+    if ((e = hipHostGetDevicePointer((void **)&r->hctrl_dev, r->hctrl, 0)) != hipSuccess)
+        return bail(e, "hipHostGetDevicePointer(ctrl)");
+    memset((void *)r->hctrl, 0, sizeof(HostCtrl));
+    {
+        DevCtrl *init = new (std::nothrow) DevCtrl;
+        if (!init) { free_ring(r); return fail(DMI_ERR_NOMEM, "out of host memory"); }
+        memset(init, 0, sizeof *init);
+        for (auto &t : init->tail_seen) t = kUnset;
+        e = hipMemcpy(r->dctrl, init, sizeof *init, hipMemcpyHostToDevice);
+        delete init;
+        if (e != hipSuccess) return bail(e, "hipMemcpy(ctrl)");
+    }
+    if ((e = hipStreamCreateWithFlags(&r->drain_stream, hipStreamNonBlocking)) != hipSuccess)
+        return bail(e, "hipStreamCreate");
+    if ((e = hipDeviceSynchronize()) != hipSuccess) return bail(e, "hipDeviceSynchronize");
+    if (cfg->flags & DMI_BG_THREAD) r->bg = std::thread(bg_loop, r);
+    *out = r;
+    return DMI_OK;
+}
+
+dmi_status_t dmi_ring_destroy(dmi_ring_t *r)
+{
+    if (!r) return fail(DMI_ERR_INVALID_ARG, "ring is NULL");
+    (void)hipSetDevice(r->dev);
+    r->stop.store(true, std::memory_order_release);
+    if (r->bg.joinable()) r->bg.join();
+    free_ring(r);
+    return DMI_OK;
+}
+
+dmi_status_t dmi_observe(dmi_ring_t *r, uint32_t point_id, const dmi_tensor_t *t, const dmi_selection_t *sel,
+                         const dmi_transform_t *xf, uint64_t step_id, void *hip_stream)
+{
+    if (!t) return fail(DMI_ERR_INVALID_ARG, "tensor is NULL");
+    dmi_status_t g = gate(r, point_id, sel, xf, step_id, t->dtype);
+    if (g != DMI_OK) return g;
+    const uint32_t es = dtype_size(t->dtype);
+    const int64_t T = t->shape[0], E = t->shape[1];
+    if (T < 0 || E < 1 || E > 0x7FFFFFFF) return fail(DMI_ERR_INVALID_ARG, "bad tensor shape");
+    if ((E > 1 && t->stride[1] != 1) || t->stride[0] < 0) return fail(DMI_ERR_INVALID_ARG, "bad tensor stride");
+    if (!t->data && T > 0) return fail(DMI_ERR_INVALID_ARG, "tensor data is NULL");
+    if ((uintptr_t)t->data % es) return fail(DMI_ERR_INVALID_ARG, "tensor data is not element aligned");
+    if (!sel->row_index_dev) {
+        for (uint32_t i = 0; i < sel->n_reqs; i++) {
+            const dmi_req_sel_t &q = sel->reqs[i];
+            if (!q.tok_count) continue;
+            const uint64_t last = (uint64_t)q.row_base + q.tok_start + (uint64_t)(q.tok_count - 1u) * q.tok_step;
+            if (last >= (uint64_t)T)
+                return fail(DMI_ERR_INVALID_ARG, "request %u selects row %llu of a %lld-row tensor", i,
+                            (unsigned long long)last, (long long)T);
+        }
+    }
+    (void)hipSetDevice(r->dev);
+    Geometry geo;
+    geo.src_dtype = t->dtype;
+    geo.row_elems = (uint32_t)E;
+    geo.n_seg = 1;
+    geo.seg_elems = (uint32_t)E;
+    geo.vec16 = (uintptr_t)t->data % 16 == 0 && ((uint64_t)t->stride[0] * es) % 16 == 0 && ((uint64_t)E * es) % 16 == 0;
+    CaptureArgs a;
+    memset(&a, 0, sizeof a);
+    a.src = (const uint8_t *)t->data;
+    a.row_stride_b = t->stride[0] * (int64_t)es;
+    a.n_src_rows = T;
+    a.paged = 0;
+    a.block_size = 1;
+    return observe_common(r, point_id, sel, xf, step_id, hip_stream, geo, a);
+}
+
+dmi_status_t dmi_observe_paged(dmi_ring_t *r, uint32_t point_id, const dmi_paged_kv_t *kv,
+                               const dmi_selection_t *sel, const dmi_transform_t *xf, uint64_t step_id,
+                               void *hip_stream)
+{
+    if (!kv) return fail(DMI_ERR_INVALID_ARG, "kv is NULL");
+    dmi_status_t g = gate(r, point_id, sel, xf, step_id, kv->dtype);
+    if (g != DMI_OK) return g;
+    const uint32_t es = dtype_size(kv->dtype);
+    if (sel->row_index_dev) return fail(DMI_ERR_INVALID_ARG, "row_index_dev is not valid for paged captures");
+    if (!kv->base || !kv->block_table_dev) return fail(DMI_ERR_INVALID_ARG, "kv base / block table is NULL");
+    if (!kv->block_size || !kv->head_dim || !kv->n_heads || !kv->n_blocks || !kv->n_seqs)
+        return fail(DMI_ERR_INVALID_ARG, "kv geometry has a zero field");
+    if (kv->n_heads_sel < 1 || kv->n_heads_sel > DMI_MAX_HEADS_SEL)
+        return fail(DMI_ERR_INVALID_ARG, "n_heads_sel must be 1..%u", DMI_MAX_HEADS_SEL);
+    for (uint32_t i = 0; i < kv->n_heads_sel; i++)
+        if (kv->heads_sel[i] >= kv->n_heads) return fail(DMI_ERR_INVALID_ARG, "selected head out of range");
+    if (kv->block_stride < 0 || kv->slot_stride < 0 || kv->head_stride < 0 || kv->block_table_stride < 1)
+        return fail(DMI_ERR_INVALID_ARG, "negative kv stride");
+    if ((uintptr_t)kv->base % es) return fail(DMI_ERR_INVALID_ARG, "kv base is not element aligned");
+    if ((uint64_t)kv->n_heads_sel * kv->head_dim > 0x7FFFFFFFull) return fail(DMI_ERR_INVALID_ARG, "row too long");
+    for (uint32_t i = 0; i < sel->n_reqs; i++) {
+        const dmi_req_sel_t &q = sel->reqs[i];
+        if (q.row_base >= kv->n_seqs) return fail(DMI_ERR_INVALID_ARG, "request %u: block-table row out of range", i);
+        if (!q.tok_count) continue;
+        const uint64_t last = (uint64_t)q.tok_start + (uint64_t)(q.tok_count - 1u) * q.tok_step;
+        if (last > 0x7FFFFFFFull || last / kv->block_size >= (uint64_t)kv->block_table_stride)
+            return fail(DMI_ERR_INVALID_ARG, "request %u: token %llu is beyond the block table", i,
+                        (unsigned long long)last);
+    }
+    (void)hipSetDevice(r->dev);
+    Geometry geo;
+    geo.src_dtype = kv->dtype;
+    geo.n_seg = kv->n_heads_sel;
+    geo.seg_elems = kv->head_dim;
+    geo.row_elems = kv->n_heads_sel * kv->head_dim;
+    geo.vec16 = (uintptr_t)kv->base % 16 == 0 && ((uint64_t)kv->block_stride * es) % 16 == 0 &&
+                ((uint64_t)kv->slot_stride * es) % 16 == 0 && ((uint64_t)kv->head_stride * es) % 16 == 0 &&
+                ((uint64_t)kv->head_dim * es) % 16 == 0;
+    CaptureArgs a;
+    memset(&a, 0, sizeof a);
+    a.src = (const uint8_t *)kv->base;
+    a.n_src_rows = kv->n_blocks;
+    a.block_stride_b = kv->block_stride * (int64_t)es;
+    a.slot_stride_b = kv->slot_stride * (int64_t)es;
+    a.head_stride_b = kv->head_stride * (int64_t)es;
+    a.block_table = kv->block_table_dev;
+    a.bt_stride = kv->block_table_stride;
+    a.block_size = kv->block_size;
+    for (uint32_t i = 0; i < kv->n_heads_sel; i++) a.heads_sel[i] = kv->heads_sel[i];
+    a.paged = 1;
+    return observe_common(r, point_id, sel, xf, step_id, hip_stream, geo, a);
+}
+
+dmi_status_t dmi_drain(dmi_ring_t *r, uint32_t flags, uint64_t *bytes_moved)
+{
+    if (!r) return fail(DMI_ERR_INVALID_ARG, "ring is NULL");
+    (void)hipSetDevice(r->dev);
+    if (bytes_moved) *bytes_moved = 0;
+    const bool wait = !(flags & DMI_DRAIN_NONBLOCK);
+    if (!(flags & DMI_DRAIN_FLUSH)) {
+        std::lock_guard<std::mutex> lk(r->mu);
+        return drain_locked(r, wait, bytes_moved);
+    }
+    // flush: everything issued so far must commit, then move all of it
+    const uint64_t want_seq = r->next_seq.load(std::memory_order_acquire);
+    const uint64_t t0 = now_ns();
+    uint64_t total = 0;
+    for (;;) {
+        const uint64_t done = r->hctrl->last_seq_plus1;
+        std::atomic_thread_fence(std::memory_order_acquire);
+        uint64_t moved = 0, left;
+        {
+            std::lock_guard<std::mutex> lk(r->mu);
+            dmi_status_t st = drain_locked(r, true, &moved);
+            if (st != DMI_OK) return st;
+            left = read_committed(r) - r->drain_issued;
+        }
+        total += moved;
+        if (bytes_moved) *bytes_moved = total;
+        if (done >= want_seq && left == 0) return DMI_OK;
+        if (done >= want_seq && moved == 0)
+            return fail(DMI_ERR_AGAIN, "host ring is full: release records and drain again");
+        if (moved == 0) {
+            if (now_ns() - t0 > (uint64_t)r->block_timeout_ms * 1000000ull)
+                return fail(DMI_ERR_AGAIN, "observes did not commit within %u ms", r->block_timeout_ms);
+            std::this_thread::sleep_for(std::chrono::microseconds(20));
+        }
+    }
+}
+
+dmi_status_t dmi_poll_host(dmi_ring_t *r, dmi_record_view_t *out, uint32_t max, uint32_t *n)
+{
+    if (!r || !n || (max && !out)) return fail(DMI_ERR_INVALID_ARG, "NULL argument");
+    *n = 0;
+    std::lock_guard<std::mutex> lk(r->mu);
+    dmi_status_t st = reap(r, false);
+    if (st != DMI_OK) return st;
+    const uint64_t done = r->drain_done.load(std::memory_order_acquire);
+    while (*n < max && r->poll_cursor + DMI_HEADER_BYTES <= done) {
+        const uint64_t off = r->poll_cursor % r->host_cap;
+        const uint8_t *h = r->host_ring + off;      // capacities and records are multiples of 64
+        uint32_t magic;
+        uint64_t seq, rb;
+        memcpy(&magic, h, 4);
+        memcpy(&seq, h + 8, 8);
+        memcpy(&rb, h + 48, 8);
+        if (magic != DMI_MAGIC || rb < DMI_HEADER_BYTES || rb % 64 || rb > r->dev_cap)
+            return fail(DMI_ERR_CLOSED, "corrupt record header at stream offset %llu",
+                        (unsigned long long)r->poll_cursor);
+        if (r->poll_cursor + rb > done) break;
+        dmi_record_view_t &v = out[*n];
+        v.p0 = h;
+        v.n0 = rb < r->host_cap - off ? rb : r->host_cap - off;
+        v.n1 = rb - v.n0;
+        v.p1 = v.n1 ? r->host_ring : nullptr;
+        v.seq = seq;
+        r->polled.emplace_back(seq, r->poll_cursor + rb);
+        r->poll_cursor += rb;
+        ++*n;
+    }
+    return DMI_OK;
+}
+
+dmi_status_t dmi_release_host(dmi_ring_t *r, uint64_t upto)
+{
+    if (!r) return fail(DMI_ERR_INVALID_ARG, "ring is NULL");
+    std::lock_guard<std::mutex> lk(r->mu);
+    while (!r->polled.empty() && r->polled.front().first <= upto) {
+        r->released_bytes += r->polled.front().second - r->released;
+        r->released = r->polled.front().second;
+        r->polled.pop_front();
+    }
+    return DMI_OK;
+}
+
+dmi_status_t dmi_set_policy(dmi_ring_t *r, const dmi_policy_t *p)
+{
+    if (!r || !p) return fail(DMI_ERR_INVALID_ARG, "NULL argument");
+    if (p->mode > DMI_POLICY_DROP_NEWEST || p->sample_k < 1 || p->sample_phase >= p->sample_k)
+        return fail(DMI_ERR_INVALID_ARG, "bad policy");
+    r->mode.store(p->mode);
+    r->sample_k.store(p->sample_k);
+    r->sample_phase.store(p->sample_phase);
+    return DMI_OK;
+}
+
+dmi_status_t dmi_point_enable(dmi_ring_t *r, uint32_t point_id, int enabled)
+{
+    if (!r || point_id >= DMI_MAX_POINTS) return fail(DMI_ERR_INVALID_ARG, "bad ring / point_id");
+    r->point_off[point_id] = enabled ? 0 : 1;
+    return DMI_OK;
+}
+
+dmi_status_t dmi_get_stats(dmi_ring_t *r, dmi_stats_t *o)
+{
+    if (!r || !o) return fail(DMI_ERR_INVALID_ARG, "NULL argument");
+    memset(o, 0, sizeof *o);
+    o->observed_calls = r->observed_calls;
+    o->launched_records = r->next_seq.load();
+    (void)r->hctrl->last_seq_plus1;
+    std::atomic_thread_fence(std::memory_order_acquire);
+    o->captured_records = r->hctrl->captured_records;
+    o->captured_rows = r->hctrl->captured_rows;
+    o->captured_bytes = r->hctrl->captured_bytes;
+    o->dropped_records = r->hctrl->dropped_records;
+    o->dropped_rows = r->hctrl->dropped_rows;
+    o->dropped_bytes = r->hctrl->dropped_bytes;
+    o->sampled_out_calls = r->sampled_out_calls;
+    o->sampled_out_rows = r->sampled_out_rows;
+    o->disabled_calls = r->disabled_calls;
+    o->drained_bytes = r->drained_bytes;
+    o->released_bytes = r->released_bytes;
+    o->drain_batches = r->drain_batches;
+    o->block_wait_ns = r->block_wait_ns;
+    o->dev_ring_high_water = r->dev_high;
+    o->host_ring_high_water = r->host_high;
+    return DMI_OK;
+}
+
+dmi_status_t dmi_get_point_drops(dmi_ring_t *r, uint32_t point_id, uint64_t *n)
+{
+    if (!r || !n || point_id >= DMI_MAX_POINTS) return fail(DMI_ERR_INVALID_ARG, "bad argument");
+    (void)hipSetDevice(r->dev);
+    uint32_t v = 0;
+    std::lock_guard<std::mutex> lk(r->mu);
+    HIP_TRY(hipMemcpyAsync(&v, &r->dctrl->point_drops[point_id], 4, hipMemcpyDeviceToHost, r->drain_stream));
+    HIP_TRY(hipStreamSynchronize(r->drain_stream));
+    *n = v;
+    return DMI_OK;
+}
+
+dmi_status_t dmi_debug_fill_rings(dmi_ring_t *r, uint8_t value)
+{
+    if (!r) return fail(DMI_ERR_INVALID_ARG, "ring is NULL");
+    (void)hipSetDevice(r->dev);
+    std::lock_guard<std::mutex> lk(r->mu);
+    HIP_TRY(hipMemsetAsync(r->dev_ring, value, r->dev_cap, r->drain_stream));
+    HIP_TRY(hipStreamSynchronize(r->drain_stream));
+    memset(r->host_ring, value, r->host_cap);
+    return DMI_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,84 @@
+// Internal interface between the host runtime (dmi_host.hip) and the device code
+// (dmi_kernels.hip).  Not part of the public ABI.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace dmi {
+
+constexpr uint32_t kThreads = 256;          // 4 wavefronts of 64 lanes per workgroup
+constexpr uint32_t kLaunchSlots = 64;       // per-launch control slots (done counter, tail consensus)
+constexpr uint32_t kMaxGrid = 2048;         // 256 CUs x 8 resident workgroups
+constexpr uint32_t kLdsTableMax = 1024;     // request tables up to this size are cached in LDS
+constexpr uint64_t kUnset = ~0ull;
+
+// Control block in device memory.  `head` and `tail` are logical stream offsets.
+struct DevCtrl {
+    uint64_t head;                  // next free stream byte (== committed: launches serialise)
+    uint64_t tail;                  // stream bytes below this have been drained
+    uint64_t captured_records, captured_rows, captured_bytes;
+    uint64_t dropped_records, dropped_rows, dropped_bytes;
+    uint64_t bad_rows;              // rows whose device-side index left the tensor (stored as zeros)
+    uint64_t tail_seen[kLaunchSlots];   // one tail value agreed by all workgroups of a launch
+    uint32_t done[kLaunchSlots];        // workgroups of a launch that have finished
+    uint32_t drain_done;                // same, for the drain kernel
+    uint32_t pad_;
+    uint32_t point_drops[4096];
+};
+
+// Control block in pinned host memory, written by the last workgroup of every
+// capture kernel, polled by the host (the role of the paper's CPU-side meta ring).
+struct HostCtrl {
+    volatile uint64_t committed;    // == DevCtrl::head after the launch
+    volatile uint64_t last_seq_plus1;   // launches with seq < this have finished
+    volatile uint64_t captured_records, captured_rows, captured_bytes;
+    volatile uint64_t dropped_records, dropped_rows, dropped_bytes;
+    volatile uint64_t bad_rows;
+};
+
+struct CaptureArgs {
+    // source
+    const uint8_t *src;
+    int64_t row_stride_b;           // dense: bytes between rows
+    int64_t n_src_rows;             // dense: rows in the tensor; paged: physical blocks
+    int64_t block_stride_b, slot_stride_b, head_stride_b;
+    const int32_t *block_table;
+    int64_t bt_stride;
+    uint32_t block_size;
+    uint32_t n_seg;                 // segments per row (1, or selected heads)
+    uint32_t seg_units;             // units per segment
+    uint32_t heads_sel[8];
+    // selection (device slab)
+    const uint4 *req_table;         // {req_id, tok_start, tok_step, tok_count}
+    const uint32_t *row_base;
+    const uint8_t *keep_mask;
+    const int32_t *row_index;
+    uint32_t n_reqs;
+    uint32_t paged;
+    // transform / record
+    uint32_t src_dtype, out_dtype, summary_mask, rec_flags;
+    uint32_t row_elems;
+    uint32_t units_per_row;
+    uint32_t rows_per_wg;           // summary kernels: 1 (a workgroup per row) or 4 (a wavefront per row)
+    uint32_t point_id, rank_tag;
+    uint64_t seq, step_id;
+    // ring
+    uint8_t *ring;
+    uint64_t cap;
+    DevCtrl *ctrl;
+    HostCtrl *hctrl;
+    uint32_t slot;
+    uint32_t drop_newest;
+    uint32_t table_in_lds;
+    uint32_t lds_bytes;
+};
+
+// Launchers (dmi_kernels.hip).  All return the launch's hipError_t.
+hipError_t launch_capture(const CaptureArgs &a, uint32_t grid, bool vec16, hipStream_t s);
+hipError_t launch_upload(uint32_t *dst, const uint32_t *words, uint32_t n_words, hipStream_t s);
+hipError_t launch_set_tail(DevCtrl *ctrl, uint64_t tail, hipStream_t s);
+hipError_t launch_drain_kernel(const uint8_t *ring, uint64_t cap, uint8_t *host_ring, uint64_t host_cap,
+                               uint64_t from, uint64_t nbytes, DevCtrl *ctrl, uint32_t grid, hipStream_t s);
+uint32_t capture_lds_bytes(uint32_t n_reqs, bool index_mode, bool table_in_lds);
+
+}  // namespace dmi

@@ -1,0 +1,664 @@
+// Device code of the capture-and-stage path for gfx950 (MI355X).
+//
+// capture_kernel is the producer of the paper's Ring^2 (section 4.2, steps 1-2;
+// section 5 "Device-to-device kernel"; section 4.4 gather-compact): it copies the
+// selected rows of one observed tensor into the device byte ring and publishes the
+// record.  The paper's kernel (1-64 blocks, grid-stride 16-byte copies, last block
+// publishes) is prior art for other hardware; here
+//   * every workgroup rebuilds the per-request prefix sums in LDS with wavefront
+//     shuffle scans, so row -> (request, token) needs no pre-pass launch;
+//   * rows are read with 16-byte vector loads and written with non-temporal
+//     16-byte stores (the ring is not read again by the GPU, so it should not
+//     displace the model's working set from the 4 MB per-XCD L2);
+//   * downcasts and fp32 row summaries happen in the same pass, summaries by
+//     wavefront shuffles (no matrix cores: nothing here is a contraction);
+//   * the record's place in the ring comes from a device-resident head that the
+//     last-finishing workgroup advances; under drop-newest all workgroups agree on
+//     one tail value through a compare-and-swap, with no spinning;
+//   * the last workgroup then writes the commit word into pinned host memory.
+#include "dmi_internal.h"
+
+#include <hip/hip_fp16.h>
+
+#include <cstring>
+
+namespace dmi {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+enum OutMode { OUT_RAW = 0, OUT_FP16 = 1, OUT_FP8 = 2, OUT_NONE = 3 };
+
+// ---------------------------------------------------------------- atomics
+__device__ __forceinline__ uint64_t ld_agent(const uint64_t *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_agent(uint64_t *p, uint64_t v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// ---------------------------------------------------------------- wavefront helpers
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v, uint32_t lane)
+{
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        uint32_t t = __shfl_up(v, d, 64);
+        if (lane >= (uint32_t)d) v += t;
+    }
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v = fmaxf(v, __shfl_xor(v, d, 64));
+    return v;
+}
+
+// ---------------------------------------------------------------- conversions
+// bf16 -> fp8 E4M3FN (OCP: bias 7, max 448, no inf, S.1111.111 NaN), round to
+// nearest even, saturating.  Integer arithmetic on the bf16 bit pattern.
+__device__ __forceinline__ uint32_t bf16_to_fp8(uint32_t b)
+{
+    const uint32_t sign = (b >> 8) & 0x80u;
+    const uint32_t a = b & 0x7FFFu;
+    const uint32_t e = a >> 7;
+    uint32_t code;
+    if (e >= 121u) {
+        // normal in fp8 (|x| >= 2^-6): rebias 127 -> 7, drop 4 mantissa bits with RNE
+        const uint32_t x = a - (120u << 7);
+        code = (x + 7u + ((x >> 4) & 1u)) >> 4;
+        code = code > 0x7Eu ? 0x7Eu : code;
+    } else {
+        // fp8 subnormal: |x| / 2^-9 = (128 + m) >> (125 - e), RNE; vanishes for shifts > 8
+        const uint32_t sh = 125u - e;
+        const uint32_t s = sh > 9u ? 9u : sh;
+        const uint32_t v = 128u + (a & 0x7Fu);
+        code = (v + (1u << (s - 1u)) - 1u + ((v >> s) & 1u)) >> s;
+    }
+    if (a > 0x7F80u) code = 0x7Fu;
+    return sign | code;
+}
+
+// bf16 -> fp16: exact widening to f32, then the hardware's round-to-nearest-even
+// convert (overflow to inf, gradual underflow); NaN -> sign | 0x7E00.
+__device__ __forceinline__ uint32_t bf16_to_fp16(uint32_t b)
+{
+    const float f = __uint_as_float(b << 16);
+    uint32_t h = (uint32_t)__half_as_ushort(__float2half_rn(f));
+    if ((b & 0x7FFFu) > 0x7F80u) h = ((b >> 15) << 15) | 0x7E00u;
+    return h;
+}
+
+__device__ __forceinline__ float widen16(uint32_t bits, uint32_t src_dtype)
+{
+    return src_dtype == 1u ? __uint_as_float(bits << 16)
+                           : __half2float(__ushort_as_half((unsigned short)bits));
+}
+
+// ---------------------------------------------------------------- units
+// A unit is what one lane moves per access: 16 source bytes on the vector path,
+// one element on the element path.
+template <int NB> struct UnitT;
+template <> struct UnitT<16> { typedef u32x4 T; };
+template <> struct UnitT<8>  { typedef u32x2 T; };
+template <> struct UnitT<4>  { typedef uint32_t T; };
+template <> struct UnitT<2>  { typedef uint16_t T; };
+template <> struct UnitT<1>  { typedef uint8_t T; };
+
+struct RingW {
+    uint8_t *ring;
+    uint64_t cap;
+    uint64_t base;      // physical offset of the record's first byte
+};
+
+template <typename T>
+__device__ __forceinline__ void ring_store(const RingW &w, uint64_t off, T v)
+{
+    uint64_t p = w.base + off;
+    if (p >= w.cap) p -= w.cap;
+    __builtin_nontemporal_store(v, reinterpret_cast<T *>(w.ring + p));
+}
+
+struct Accum {
+    float ss, s, am;
+};
+
+__device__ __forceinline__ void accum1(Accum &a, float x)
+{
+    a.ss = fmaf(x, x, a.ss);
+    a.s += x;
+    a.am = fmaxf(a.am, fabsf(x));
+}
+
+// Convert one source unit and store it; optionally accumulate the row summaries.
+template <int ES_IN, int VEC, int OUT, bool SUMM>
+__device__ __forceinline__ void emit_unit(const RingW &w, uint64_t out_off,
+                                          typename UnitT<ES_IN * VEC>::T v, uint32_t src_dtype,
+                                          Accum &acc)
+{
+    if constexpr (ES_IN == 2 && VEC == 8) {
+        uint32_t wd[4] = {v.x, v.y, v.z, v.w};
+        if constexpr (SUMM) {
+#pragma unroll
+            for (int k = 0; k < 4; k++) {
+                accum1(acc, widen16(wd[k] & 0xFFFFu, src_dtype));
+                accum1(acc, widen16(wd[k] >> 16, src_dtype));
+            }
+        }
+        if constexpr (OUT == OUT_RAW) {
+            ring_store<u32x4>(w, out_off, v);
+        } else if constexpr (OUT == OUT_FP16) {
+            u32x4 o;
+            uint32_t ow[4];
+#pragma unroll
+            for (int k = 0; k < 4; k++)
+                ow[k] = bf16_to_fp16(wd[k] & 0xFFFFu) | (bf16_to_fp16(wd[k] >> 16) << 16);
+            o.x = ow[0]; o.y = ow[1]; o.z = ow[2]; o.w = ow[3];
+            ring_store<u32x4>(w, out_off, o);
+        } else if constexpr (OUT == OUT_FP8) {
+            uint32_t c[8];
+#pragma unroll
+            for (int k = 0; k < 4; k++) {
+                c[2 * k] = bf16_to_fp8(wd[k] & 0xFFFFu);
+                c[2 * k + 1] = bf16_to_fp8(wd[k] >> 16);
+            }
+            u32x2 o;
+            o.x = c[0] | (c[1] << 8) | (c[2] << 16) | (c[3] << 24);
+            o.y = c[4] | (c[5] << 8) | (c[6] << 16) | (c[7] << 24);
+            ring_store<u32x2>(w, out_off, o);
+        }
+    } else if constexpr (ES_IN == 4 && VEC == 4) {
+        if constexpr (SUMM) {
+            accum1(acc, __uint_as_float(v.x));
+            accum1(acc, __uint_as_float(v.y));
+            accum1(acc, __uint_as_float(v.z));
+            accum1(acc, __uint_as_float(v.w));
+        }
+        if constexpr (OUT == OUT_RAW) ring_store<u32x4>(w, out_off, v);
+    } else if constexpr (ES_IN == 2) {      // one 2-byte element
+        const uint32_t b = v;
+        if constexpr (SUMM) accum1(acc, widen16(b, src_dtype));
+        if constexpr (OUT == OUT_RAW) ring_store<uint16_t>(w, out_off, (uint16_t)b);
+        else if constexpr (OUT == OUT_FP16) ring_store<uint16_t>(w, out_off, (uint16_t)bf16_to_fp16(b));
+        else if constexpr (OUT == OUT_FP8) ring_store<uint8_t>(w, out_off, (uint8_t)bf16_to_fp8(b));
+    } else {                                // one 4-byte element
+        if constexpr (SUMM) accum1(acc, __uint_as_float(v));
+        if constexpr (OUT == OUT_RAW) ring_store<uint32_t>(w, out_off, v);
+    }
+}
+
+template <int ES_IN, int VEC, int OUT>
+__host__ __device__ constexpr uint32_t out_unit_bytes()
+{
+    return OUT == OUT_NONE ? 0u : OUT == OUT_FP8 ? (uint32_t)VEC : (uint32_t)(ES_IN * VEC);
+}
+
+// ---------------------------------------------------------------- LDS layout
+struct LdsMap {
+    uint32_t hdr, heads, red, bcast, pref, btot, pref_all, btot_all, tab, rb, total_words;
+};
+
+__host__ __device__ inline LdsMap lds_map(uint32_t n_reqs, bool index_mode, bool table_in_lds)
+{
+    LdsMap m;
+    const uint32_t nb = (n_reqs + 63u) / 64u;
+    uint32_t p = 0;
+    m.hdr = p; p += 16;
+    m.heads = p; p += 8;
+    m.red = p; p += 12;
+    m.bcast = p; p += 8;           // head lo/hi, tail lo/hi, spare
+    m.pref = p; p += n_reqs + 1;
+    m.btot = p; p += nb + 1;
+    m.pref_all = p; m.btot_all = p;
+    if (index_mode) { p += n_reqs + 1; m.btot_all = p; p += nb + 1; }
+    p = (p + 3u) & ~3u;
+    m.tab = p; m.rb = p;
+    if (table_in_lds) { p += 4 * n_reqs; m.rb = p; p += n_reqs; }
+    m.total_words = p;
+    return m;
+}
+
+uint32_t capture_lds_bytes(uint32_t n_reqs, bool index_mode, bool table_in_lds)
+{
+    return lds_map(n_reqs, index_mode, table_in_lds).total_words * 4u;
+}
+
+// Where one output row comes from.
+struct RowRef {
+    const uint8_t *base;    // dense: first byte of the row; paged: first byte of the slot
+    bool ok;
+};
+
+// ---------------------------------------------------------------- capture kernel
+template <int ES_IN, int VEC, int OUT, bool SUMM>
+__global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
+    constexpr uint32_t NB_IN = ES_IN * VEC;
+    constexpr uint32_t NB_OUT = out_unit_bytes<ES_IN, VEC, OUT>();
+    typedef typename UnitT<NB_IN>::T unit_t;
+
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const uint32_t n_reqs = a.n_reqs;
+    const bool index_mode = a.row_index != nullptr;
+    const LdsMap m = lds_map(n_reqs, index_mode, a.table_in_lds != 0);
+    uint32_t *pref = lds + m.pref, *btot = lds + m.btot;
+    uint32_t *pref_all = lds + m.pref_all, *btot_all = lds + m.btot_all;
+    uint4 *ltab = reinterpret_cast<uint4 *>(lds + m.tab);
+    uint32_t *lrb = lds + m.rb;
+    const uint32_t nb = (n_reqs + 63u) / 64u;
+
+    // -- control words: one lane fetches the head (and, under drop-newest, the tail the
+    //    whole launch agrees on) while the others start on the request table
+    if (tid == 0) {
+        const uint64_t h = ld_agent(&a.ctrl->head);
+        uint64_t t = 0;
+        if (a.drop_newest) {
+            // every workgroup proposes the tail it read; the first proposal wins and all use it
+            t = ld_agent(&a.ctrl->tail);
+            uint64_t expected = kUnset;
+            if (!__hip_atomic_compare_exchange_strong(&a.ctrl->tail_seen[a.slot], &expected, t,
+                                                      __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                                      __HIP_MEMORY_SCOPE_AGENT))
+                t = expected;
+        }
+        const uint64_t base = h % a.cap;
+        lds[m.bcast + 4] = (uint32_t)base;
+        lds[m.bcast + 5] = (uint32_t)(base >> 32);
+        lds[m.bcast + 0] = (uint32_t)h;
+        lds[m.bcast + 1] = (uint32_t)(h >> 32);
+        lds[m.bcast + 2] = (uint32_t)t;
+        lds[m.bcast + 3] = (uint32_t)(t >> 32);
+    }
+    if (tid < 8) lds[m.heads + tid] = a.heads_sel[tid];
+
+    // -- per-request kept row counts -> exclusive prefix sums (wavefront shuffle scans)
+    for (uint32_t b = wave; b < nb; b += kThreads / 64u) {
+        const uint32_t r = b * 64u + lane;
+        uint32_t cnt = 0, cnt_all = 0;
+        if (r < n_reqs) {
+            uint4 e = a.req_table[r];
+            cnt_all = e.w;
+            const bool keep = a.keep_mask ? a.keep_mask[r] != 0 : true;
+            cnt = keep ? cnt_all : 0u;
+            if (a.table_in_lds) {
+                e.w = cnt;
+                ltab[r] = e;
+                lrb[r] = a.row_base[r];
+            }
+        }
+        const uint32_t inc = wave_incl_scan(cnt, lane);
+        if (r < n_reqs) pref[r] = inc - cnt;
+        if (lane == 63u) btot[b] = inc;
+        if (index_mode) {
+            const uint32_t inc_all = wave_incl_scan(cnt_all, lane);
+            if (r < n_reqs) pref_all[r] = inc_all - cnt_all;
+            if (lane == 63u) btot_all[b] = inc_all;
+        }
+    }
+    __syncthreads();
+    if (wave == 0) {
+        uint32_t carry = 0, carry_all = 0;
+        for (uint32_t b0 = 0; b0 < nb; b0 += 64u) {
+            const uint32_t b = b0 + lane;
+            const uint32_t v = b < nb ? btot[b] : 0u;
+            const uint32_t inc = wave_incl_scan(v, lane);
+            if (b < nb) btot[b] = carry + inc - v;
+            carry += __shfl(inc, 63, 64);
+            if (index_mode) {
+                const uint32_t va = b < nb ? btot_all[b] : 0u;
+                const uint32_t ia = wave_incl_scan(va, lane);
+                if (b < nb) btot_all[b] = carry_all + ia - va;
+                carry_all += __shfl(ia, 63, 64);
+            }
+        }
+        if (lane == 0) {
+            btot[nb] = carry;
+            if (index_mode) btot_all[nb] = carry_all;
+        }
+    }
+    __syncthreads();
+    for (uint32_t r = tid; r < n_reqs; r += kThreads) {
+        pref[r] += btot[r >> 6];
+        if (index_mode) pref_all[r] += btot_all[r >> 6];
+    }
+    if (tid == 0) {
+        pref[n_reqs] = btot[nb];
+        if (index_mode) pref_all[n_reqs] = btot_all[nb];
+    }
+    __syncthreads();
+
+    // -- record geometry
+    const uint32_t n_rows = pref[n_reqs];
+    const uint32_t es_out = OUT == OUT_NONE ? 0u : OUT == OUT_FP8 ? 1u : (uint32_t)ES_IN;
+    const uint64_t table_bytes = ((uint64_t)n_reqs * 16u + 63u) & ~63ull;
+    const uint64_t payload_bytes = (uint64_t)n_rows * a.row_elems * es_out;
+    const uint64_t off_payload = 64u + table_bytes;
+    const uint64_t off_sum = off_payload + ((payload_bytes + 63u) & ~63ull);
+    const uint64_t sum_arr = ((uint64_t)n_rows * 4u + 63u) & ~63ull;
+    const uint32_t n_sum = __popc(a.summary_mask & 7u);
+    const uint64_t record_bytes = off_sum + (uint64_t)n_sum * sum_arr;
+
+    const uint64_t head = (uint64_t)lds[m.bcast + 0] | ((uint64_t)lds[m.bcast + 1] << 32);
+    bool dropped = false;
+    if (a.drop_newest) {
+        const uint64_t tail = (uint64_t)lds[m.bcast + 2] | ((uint64_t)lds[m.bcast + 3] << 32);
+        dropped = head - tail + record_bytes > a.cap;
+    }
+
+    RingW w;
+    w.ring = a.ring;
+    w.cap = a.cap;
+    w.base = (uint64_t)lds[m.bcast + 4] | ((uint64_t)lds[m.bcast + 5] << 32);
+
+    // row g -> request r (largest r with pref[r] <= g; requests with no rows are skipped
+    // because their successor shares the same prefix) -> source location
+    auto locate = [&](uint32_t g) -> RowRef {
+        uint32_t lo = 0, hi = n_reqs;
+        while (hi - lo > 1u) {
+            const uint32_t mid = (lo + hi) >> 1;
+            if (pref[mid] <= g) lo = mid; else hi = mid;
+        }
+        const uint32_t r = lo, j = g - pref[r];
+        uint4 e;
+        uint32_t rbase;
+        if (a.table_in_lds) { e = ltab[r]; rbase = lrb[r]; }
+        else { e = a.req_table[r]; rbase = a.row_base[r]; }
+        RowRef ref;
+        if (!a.paged) {
+            int64_t row;
+            if (index_mode) row = (int64_t)a.row_index[pref_all[r] + j];
+            else row = (int64_t)rbase + (int64_t)e.y + (int64_t)j * (int64_t)e.z;
+            ref.ok = row >= 0 && row < a.n_src_rows;
+            ref.base = a.src + (ref.ok ? row : 0) * a.row_stride_b;
+        } else {
+            const uint32_t t = e.y + j * e.z;               // host keeps token positions below 2^31
+            const uint32_t lb = t / a.block_size;
+            const uint32_t slot = t - lb * a.block_size;
+            const int64_t blk = (int64_t)a.block_table[(int64_t)rbase * a.bt_stride + (int64_t)lb];
+            ref.ok = blk >= 0 && blk < a.n_src_rows;
+            ref.base = a.src + (ref.ok ? blk : 0) * a.block_stride_b + (int64_t)slot * a.slot_stride_b;
+        }
+        return ref;
+    };
+    auto unit_ptr = [&](const RowRef &ref, uint32_t c) -> const uint8_t * {
+        if (!a.paged) return ref.base + (uint64_t)c * NB_IN;
+        const uint32_t seg = c / a.seg_units;
+        const uint32_t cc = c - seg * a.seg_units;
+        return ref.base + (int64_t)lds[m.heads + seg] * a.head_stride_b + (uint64_t)cc * NB_IN;
+    };
+    auto load_unit = [&](const RowRef &ref, uint32_t c) -> unit_t {
+        unit_t v = {};
+        if (ref.ok) v = *reinterpret_cast<const unit_t *>(unit_ptr(ref, c));
+        return v;
+    };
+
+    if (!dropped) {
+        // ---- header, request table and all pad bytes: workgroup 0
+        if (blockIdx.x == 0) {
+            if (tid == 0) {
+                uint32_t *h = lds + m.hdr;
+                h[0] = 0x32494D44u;
+                h[1] = 1u | (64u << 16);
+                h[2] = (uint32_t)a.seq;          h[3] = (uint32_t)(a.seq >> 32);
+                h[4] = (uint32_t)a.step_id;      h[5] = (uint32_t)(a.step_id >> 32);
+                h[6] = a.point_id;
+                h[7] = a.src_dtype | (a.out_dtype << 8) | (a.summary_mask << 16) | (a.rec_flags << 24);
+                h[8] = n_reqs;  h[9] = n_rows;  h[10] = a.row_elems;  h[11] = a.rank_tag;
+                h[12] = (uint32_t)record_bytes;  h[13] = (uint32_t)(record_bytes >> 32);
+                h[14] = (uint32_t)payload_bytes; h[15] = (uint32_t)(payload_bytes >> 32);
+            }
+            __syncthreads();
+            if (tid < 4) {
+                const uint32_t *h = lds + m.hdr + 4 * tid;
+                u32x4 v = {h[0], h[1], h[2], h[3]};
+                ring_store<u32x4>(w, 16u * tid, v);
+            }
+            const uint32_t tab_slots = (uint32_t)(table_bytes / 16u);
+            for (uint32_t r = tid; r < tab_slots; r += kThreads) {
+                u32x4 v = {0u, 0u, 0u, 0u};
+                if (r < n_reqs) {
+                    uint4 e;
+                    if (a.table_in_lds) e = ltab[r];
+                    else { e = a.req_table[r]; e.w = pref[r + 1] - pref[r]; }
+                    v.x = e.x; v.y = e.y; v.z = e.z; v.w = e.w;
+                }
+                ring_store<u32x4>(w, 64u + 16ull * r, v);
+            }
+            {
+                const uint32_t pad = (uint32_t)(off_sum - off_payload - payload_bytes);
+                if (tid < pad) ring_store<uint8_t>(w, off_payload + payload_bytes + tid, (uint8_t)0);
+                const uint32_t spad = (uint32_t)(sum_arr - (uint64_t)n_rows * 4u) / 4u;
+                for (uint32_t k = tid; k < n_sum * spad; k += kThreads) {
+                    const uint32_t arr = k / spad, i = k - arr * spad;
+                    ring_store<uint32_t>(w, off_sum + arr * sum_arr + (uint64_t)n_rows * 4u + 4ull * i, 0u);
+                }
+            }
+        }
+
+        if constexpr (!SUMM) {
+            // ---- flat copy: the n_rows x units_per_row units are dealt to lanes in order, so
+            //      stores are fully coalesced whatever the row length; 4 loads in flight per lane
+            if constexpr (OUT != OUT_NONE) {
+                constexpr uint32_t U = 4;
+                const uint64_t total = (uint64_t)n_rows * a.units_per_row;
+                Accum dummy = {0.f, 0.f, 0.f};
+                for (uint64_t t0 = (uint64_t)blockIdx.x * U * kThreads; t0 < total;
+                     t0 += (uint64_t)gridDim.x * U * kThreads) {
+                    unit_t v[U];
+                    bool live[U];
+#pragma unroll
+                    for (uint32_t k = 0; k < U; k++) {
+                        const uint64_t u = t0 + (uint64_t)k * kThreads + tid;
+                        live[k] = u < total;
+                        v[k] = unit_t{};
+                        if (live[k]) {
+                            const uint32_t u32 = (uint32_t)u;       // host keeps total below 2^32
+                            const uint32_t g = u32 / a.units_per_row;
+                            const uint32_t c = u32 - g * a.units_per_row;
+                            const RowRef ref = locate(g);
+                            if (!ref.ok && c == 0)
+                                atomicAdd((unsigned long long *)&a.ctrl->bad_rows, 1ull);
+                            v[k] = load_unit(ref, c);
+                        }
+                    }
+#pragma unroll
+                    for (uint32_t k = 0; k < U; k++) {
+                        const uint64_t u = t0 + (uint64_t)k * kThreads + tid;
+                        if (live[k])
+                            emit_unit<ES_IN, VEC, OUT, false>(w, off_payload + u * NB_OUT, v[k],
+                                                              a.src_dtype, dummy);
+                    }
+                }
+            }
+        } else {
+            // ---- row-wise pass with summaries: a workgroup (or a wavefront) per row
+            const uint32_t rpw = a.rows_per_wg;
+            const uint32_t gsz = kThreads / rpw;            // lanes per row: 256 or 64
+            const uint32_t sub = tid / gsz, l = tid - sub * gsz;
+            float *red = reinterpret_cast<float *>(lds + m.red);
+            for (uint64_t g0 = (uint64_t)blockIdx.x * rpw; g0 < n_rows; g0 += (uint64_t)gridDim.x * rpw) {
+                const uint32_t g = (uint32_t)(g0 + sub);
+                const bool active = g0 + sub < n_rows;
+                Accum acc = {0.f, 0.f, 0.f};
+                if (active) {
+                    const RowRef ref = locate(g);
+                    if (!ref.ok && l == 0) atomicAdd((unsigned long long *)&a.ctrl->bad_rows, 1ull);
+                    const uint64_t row_off = off_payload + (uint64_t)g * a.units_per_row * NB_OUT;
+                    for (uint32_t c = l; c < a.units_per_row; c += gsz) {
+                        const unit_t v = load_unit(ref, c);
+                        emit_unit<ES_IN, VEC, OUT, true>(w, row_off + (uint64_t)c * NB_OUT, v,
+                                                         a.src_dtype, acc);
+                    }
+                }
+                acc.ss = wave_sum(acc.ss);
+                acc.s = wave_sum(acc.s);
+                acc.am = wave_max(acc.am);
+                if (rpw == 1u) {
+                    __syncthreads();        // previous iteration's readers are done with red[]
+                    if (lane == 0) { red[wave] = acc.ss; red[4 + wave] = acc.s; red[8 + wave] = acc.am; }
+                    __syncthreads();
+                    acc.ss = (red[0] + red[1]) + (red[2] + red[3]);
+                    acc.s = (red[4] + red[5]) + (red[6] + red[7]);
+                    acc.am = fmaxf(fmaxf(red[8], red[9]), fmaxf(red[10], red[11]));
+                }
+                if (active && l == 0) {
+                    uint64_t o = off_sum + (uint64_t)g * 4u;
+                    if (a.summary_mask & 1u) { ring_store<float>(w, o, sqrtf(acc.ss)); o += sum_arr; }
+                    if (a.summary_mask & 2u) { ring_store<float>(w, o, acc.s / (float)a.row_elems); o += sum_arr; }
+                    if (a.summary_mask & 4u) { ring_store<float>(w, o, acc.am); }
+                }
+            }
+        }
+    }
+
+    // ---- retire: the last workgroup to finish advances the head and publishes the record
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) {
+        const uint32_t prev = __hip_atomic_fetch_add(&a.ctrl->done[a.slot], 1u, __ATOMIC_ACQ_REL,
+                                                     __HIP_MEMORY_SCOPE_AGENT);
+        if (prev == gridDim.x - 1u) {
+            DevCtrl *c = a.ctrl;
+            const uint64_t new_head = dropped ? head : head + record_bytes;
+            if (dropped) {
+                c->dropped_records += 1;
+                c->dropped_rows += n_rows;
+                c->dropped_bytes += record_bytes;
+                if (a.point_id < 4096u) c->point_drops[a.point_id] += 1;
+            } else {
+                c->captured_records += 1;
+                c->captured_rows += n_rows;
+                c->captured_bytes += record_bytes;
+            }
+            __hip_atomic_store(&c->done[a.slot], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            st_agent(&c->tail_seen[a.slot], kUnset);
+            st_agent(&c->head, new_head);
+            HostCtrl *h = a.hctrl;
+            h->captured_records = c->captured_records;
+            h->captured_rows = c->captured_rows;
+            h->captured_bytes = c->captured_bytes;
+            h->dropped_records = c->dropped_records;
+            h->dropped_rows = c->dropped_rows;
+            h->dropped_bytes = c->dropped_bytes;
+            h->bad_rows = __hip_atomic_load(&c->bad_rows, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __threadfence_system();
+            __hip_atomic_store(const_cast<uint64_t *>(&h->committed), new_head, __ATOMIC_RELEASE,
+                               __HIP_MEMORY_SCOPE_SYSTEM);
+            __hip_atomic_store(const_cast<uint64_t *>(&h->last_seq_plus1), a.seq + 1u, __ATOMIC_RELEASE,
+                               __HIP_MEMORY_SCOPE_SYSTEM);
+        }
+    }
+}
+
+// ---------------------------------------------------------------- small kernels
+struct UploadChunk {
+    uint32_t w[896];
+};
+
+__global__ void __launch_bounds__(kThreads) upload_kernel(uint32_t *dst, const UploadChunk c, uint32_t n)
+{
+    for (uint32_t i = threadIdx.x; i < n; i += kThreads) dst[i] = c.w[i];
+}
+
+__global__ void set_tail_kernel(DevCtrl *ctrl, uint64_t tail)
+{
+    st_agent(&ctrl->tail, tail);
+}
+
+// Drain by kernel: 16-byte loads from the device ring, 16-byte stores into the pinned
+// host ring (posted PCIe writes), then the tail is advanced by the last workgroup.
+__global__ void __launch_bounds__(kThreads) drain_kernel(const uint8_t *ring, uint64_t cap, uint8_t *host,
+                                                         uint64_t host_cap, uint64_t from, uint64_t nbytes,
+                                                         DevCtrl *ctrl)
+{
+    const uint64_t n_units = nbytes / 16u;
+    const uint64_t s0 = from % cap, d0 = from % host_cap;
+    for (uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x; i < n_units;
+         i += (uint64_t)gridDim.x * kThreads) {
+        uint64_t s = s0 + i * 16u, d = d0 + i * 16u;
+        if (s >= cap) s -= cap;
+        if (d >= host_cap) d -= host_cap;
+        const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(ring + s));
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(host + d));
+    }
+    __threadfence_system();
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const uint32_t prev = __hip_atomic_fetch_add(&ctrl->drain_done, 1u, __ATOMIC_ACQ_REL,
+                                                     __HIP_MEMORY_SCOPE_AGENT);
+        if (prev == gridDim.x - 1u) {
+            __hip_atomic_store(&ctrl->drain_done, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            st_agent(&ctrl->tail, from + nbytes);
+        }
+    }
+}
+
+// ---------------------------------------------------------------- launchers
+template <int ES_IN, int VEC, int OUT>
+static hipError_t launch_t(const CaptureArgs &a, uint32_t grid, hipStream_t s)
+{
+    if (a.summary_mask)
+        hipLaunchKernelGGL((capture_kernel<ES_IN, VEC, OUT, true>), dim3(grid), dim3(kThreads), a.lds_bytes, s, a);
+    else
+        hipLaunchKernelGGL((capture_kernel<ES_IN, VEC, OUT, false>), dim3(grid), dim3(kThreads), a.lds_bytes, s, a);
+    return hipGetLastError();
+}
+
+template <int ES_IN, int VEC>
+static hipError_t launch_o(const CaptureArgs &a, uint32_t grid, hipStream_t s)
+{
+    const bool raw = a.out_dtype == a.src_dtype;
+    if (a.out_dtype == 0) return launch_t<ES_IN, VEC, OUT_NONE>(a, grid, s);
+    if (raw) return launch_t<ES_IN, VEC, OUT_RAW>(a, grid, s);
+    if constexpr (ES_IN == 2) {
+        if (a.out_dtype == 2) return launch_t<ES_IN, VEC, OUT_FP16>(a, grid, s);
+        if (a.out_dtype == 4) return launch_t<ES_IN, VEC, OUT_FP8>(a, grid, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_capture(const CaptureArgs &a, uint32_t grid, bool vec16, hipStream_t s)
+{
+    if (grid == 0 || grid > kMaxGrid) return hipErrorInvalidValue;
+    const bool four = a.src_dtype == 3;
+    if (four) return vec16 ? launch_o<4, 4>(a, grid, s) : launch_o<4, 1>(a, grid, s);
+    return vec16 ? launch_o<2, 8>(a, grid, s) : launch_o<2, 1>(a, grid, s);
+}
+
+hipError_t launch_upload(uint32_t *dst, const uint32_t *words, uint32_t n_words, hipStream_t s)
+{
+    for (uint32_t o = 0; o < n_words; o += 896u) {
+        UploadChunk c;
+        const uint32_t n = n_words - o < 896u ? n_words - o : 896u;
+        std::memcpy(c.w, words + o, n * 4u);
+        hipLaunchKernelGGL(upload_kernel, dim3(1), dim3(kThreads), 0, s, dst + o, c, n);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+hipError_t launch_set_tail(DevCtrl *ctrl, uint64_t tail, hipStream_t s)
+{
+    hipLaunchKernelGGL(set_tail_kernel, dim3(1), dim3(1), 0, s, ctrl, tail);
+    return hipGetLastError();
+}
+
+hipError_t launch_drain_kernel(const uint8_t *ring, uint64_t cap, uint8_t *host_ring, uint64_t host_cap,
+                               uint64_t from, uint64_t nbytes, DevCtrl *ctrl, uint32_t grid, hipStream_t s)
+{
+    hipLaunchKernelGGL(drain_kernel, dim3(grid), dim3(kThreads), 0, s, ring, cap, host_ring, host_cap, from,
+                       nbytes, ctrl);
+    return hipGetLastError();
+}
+
+}  // namespace dmi

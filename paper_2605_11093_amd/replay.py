@@ -1,0 +1,119 @@
+"""Feed a synthetic workload (workloads.configs) through the C ABI.
+
+Argument marshalling and scheduling only: which observe is called when, when the
+ring is drained, polled and released.  PyTorch supplies device memory and the
+stream handle.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Callable, List, Optional
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+@dataclass
+class GpuRun:
+    stats: B.Stats = None
+    records: List[tuple] = field(default_factory=list)     # (seq, bytes) when collecting
+    n_records: int = 0
+    n_bytes: int = 0
+
+    @property
+    def stream(self) -> np.ndarray:
+        return (np.concatenate([b for _, b in self.records]) if self.records
+                else np.zeros(0, np.uint8))
+
+
+def observe_call(ring: B.Ring, call, stream_handle: int, keep_alive: list, allow=()) -> int:
+    dev = call.tensor.device
+    km = ri = None
+    if call.keep_mask is not None:
+        km = torch.from_numpy(np.ascontiguousarray(call.keep_mask, dtype=np.uint8)).to(dev)
+        keep_alive.append(km)
+    if call.row_index is not None:
+        ri = torch.from_numpy(np.ascontiguousarray(call.row_index, dtype=np.int32)).to(dev)
+        keep_alive.append(ri)
+    if call.paged is None:
+        return ring.observe_tensor(call.point_id, call.tensor, call.reqs, step_id=call.step_id,
+                                   stream=stream_handle, out_dtype=call.out_dtype,
+                                   summary_mask=call.summary_mask, keep_mask=km, row_index=ri,
+                                   allow=allow)
+    p = call.paged
+    return ring.observe_paged(call.point_id, call.tensor, p.block_table, call.reqs,
+                              block_size=p.block_size, n_heads=p.n_heads, head_dim=p.head_dim,
+                              heads_sel=p.heads_sel, step_id=call.step_id, stream=stream_handle,
+                              out_dtype=call.out_dtype, summary_mask=call.summary_mask,
+                              keep_mask=km, allow=allow)
+
+
+def consume(ring: B.Ring, run: GpuRun, collect: bool, release: bool,
+            on_record: Optional[Callable] = None):
+    """Poll every complete record, hand it on, release it."""
+    while True:
+        views = ring.poll_host()
+        if not views:
+            return
+        for v in views:
+            run.n_records += 1
+            run.n_bytes += v.nbytes
+            if collect:
+                run.records.append((v.seq, v.bytes()))
+            if on_record is not None:
+                on_record(v)
+        if release:
+            ring.release_host(views[-1].seq)
+        else:
+            return
+
+
+def run_workload_gpu(wl, *, drain_every: int = 1, release: bool = True, collect: bool = True,
+                     flags: int = 0, device_ring_bytes=None, host_ring_bytes=None,
+                     max_steps=None, lockstep: bool = True, on_record=None,
+                     block_timeout_ms: int = 0, poison: Optional[int] = None,
+                     ring: Optional[B.Ring] = None) -> GpuRun:
+    """Lockstep schedule (the one the oracle's model follows): a step's observes,
+    then every `drain_every` steps a flush-drain followed by poll + release.
+    With lockstep=False the drain after a step moves only what has committed by
+    then, without waiting for the step's kernels."""
+    own = ring is None
+    if own:
+        ring = B.Ring(device_ring_bytes or wl.device_ring_bytes, host_ring_bytes or wl.host_ring_bytes,
+                      flags=flags, max_reqs_per_observe=wl.max_reqs, block_timeout_ms=block_timeout_ms)
+        ring.set_policy(wl.policy_mode, wl.sample_k, 0)
+    if poison is not None:
+        ring.debug_fill_rings(poison)
+    run = GpuRun()
+    s = torch.cuda.current_stream()
+    keep_alive: list = []
+    try:
+        for step, calls in wl.steps():
+            if max_steps is not None and step >= max_steps:
+                break
+            for c in calls:
+                rc = observe_call(ring, c, s.cuda_stream, keep_alive, allow=(B.ERR_AGAIN,))
+                if rc == B.ERR_AGAIN:
+                    # completeness policy, host ring full: consume, then try once more
+                    consume(ring, run, collect, release, on_record)
+                    observe_call(ring, c, s.cuda_stream, keep_alive)
+            if (step + 1) % drain_every == 0:
+                ring.drain(B.DRAIN_FLUSH if lockstep else 0, allow=(B.ERR_AGAIN,))
+                consume(ring, run, collect, release, on_record)
+                keep_alive.clear() if lockstep else None
+        # tail: everything still in flight
+        for _ in range(1 << 20):
+            ring.drain(B.DRAIN_FLUSH, allow=(B.ERR_AGAIN,))
+            before = run.n_records
+            consume(ring, run, collect, release, on_record)
+            if ring.last_drain_status == B.OK or run.n_records == before:
+                break
+        s.synchronize()
+        run.stats = ring.get_stats()
+    finally:
+        if own:
+            s.synchronize()
+            ring.destroy()
+    return run

@@ -1,0 +1,53 @@
+"""Comparison helpers for the parity tests (oracle side only: the decoder used
+here is the oracle's independent one)."""
+import numpy as np
+
+from oracle.decode import decode_record, record_offsets
+
+L2_RTOL = 1e-3          # spec tolerance for the fp32 summaries
+MEAN_RTOL, MEAN_ATOL_SCALE = 1e-3, 1e-5
+
+
+def compare_record(got: np.ndarray, ref: np.ndarray, what=""):
+    """Bit-exact on header, request table, payload and pads; summaries: absmax
+    exact, L2 within rel 1e-3, mean within 1e-3*|ref| + 1e-5*mean|x| where
+    mean|x| is bounded by L2/sqrt(E) (pure relative error on a mean is ill-posed
+    when the sum cancels)."""
+    assert got.size == ref.size, f"{what}: size {got.size} != {ref.size}"
+    g, r = decode_record(got), decode_record(ref)
+    if not r.summary_mask:
+        assert np.array_equal(got, ref), f"{what}: bytes differ at {np.flatnonzero(got != ref)[:8]}"
+        return
+    n_sum = bin(r.summary_mask).count("1")
+    sum_bytes = n_sum * ((r.n_rows * 4 + 63) // 64 * 64)
+    head = r.record_bytes - sum_bytes
+    assert np.array_equal(got[:head], ref[:head]), \
+        f"{what}: non-summary bytes differ at {np.flatnonzero(got[:head] != ref[:head])[:8]}"
+    if 4 in r.summaries:
+        a, b = g.summaries[4], r.summaries[4]
+        nan = np.isnan(b)
+        assert np.array_equal(a[~nan], b[~nan]), f"{what}: absmax differs"
+    l2_ref = None
+    if 1 in r.summaries:
+        a, b = g.summaries[1].astype(np.float64), r.summaries[1].astype(np.float64)
+        l2_ref = b
+        fin = np.isfinite(b)
+        assert np.array_equal(np.isnan(a), np.isnan(b)), f"{what}: L2 NaN pattern differs"
+        assert np.all(np.abs(a[fin] - b[fin]) <= L2_RTOL * np.abs(b[fin])), f"{what}: L2 out of tolerance"
+        inf = np.isinf(b)
+        assert np.array_equal(a[inf], b[inf]), f"{what}: L2 inf differs"
+    if 2 in r.summaries:
+        a, b = g.summaries[2].astype(np.float64), r.summaries[2].astype(np.float64)
+        fin = np.isfinite(b)
+        assert np.array_equal(np.isnan(a), np.isnan(b)), f"{what}: mean NaN pattern differs"
+        scale = (l2_ref[fin] / np.sqrt(r.row_elems)) if l2_ref is not None else np.abs(b[fin]) + 1.0
+        tol = MEAN_RTOL * np.abs(b[fin]) + MEAN_ATOL_SCALE * scale
+        assert np.all(np.abs(a[fin] - b[fin]) <= tol), f"{what}: mean out of tolerance"
+
+
+def compare_streams(got: np.ndarray, ref: np.ndarray):
+    assert got.size == ref.size, f"stream size {got.size} != {ref.size}"
+    go, ro = record_offsets(got), record_offsets(ref)
+    assert [(s, o, n) for s, o, n in go] == [(s, o, n) for s, o, n in ro], "record boundaries differ"
+    for seq, off, n in ro:
+        compare_record(got[off:off + n], ref[off:off + n], what=f"seq {seq}")
