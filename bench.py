@@ -1,0 +1,376 @@
+#!/usr/bin/env python3
+"""Benchmark of the capture-and-stage path on one MI355X.
+
+A step is one pass of the whole hot path over one decode step of the
+Llama-3-8B-shaped workload (config 2): 32 observes (policy gate, admission,
+row-count scan and slot reservation, gather + pack + L2/absmax summaries,
+header and commit), the drain into the pinned host ring, host poll and release.
+Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+
+Also measured in the same run: the capture kernel alone (HIP events on the
+launch stream) against the HBM roofline, the drain against the box's own pinned
+D2H rate, the other workload shapes' kernels, step-time overhead against a
+synthetic bf16 weight-streaming step, and the CPU oracle on this machine's host
+cores (a reported baseline, not the target).
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import json
+import os
+import statistics
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0           # MI355X published HBM3E bandwidth
+SEED_NOTE = "synthetic (seeded ~N(0,1) bf16, shapes of the paper's LLM workloads)"
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=256)
+    ap.add_argument("--warmup", type=int, default=16)
+    ap.add_argument("--skip-cpu-baseline", action="store_true")
+    ap.add_argument("--skip-overhead", action="store_true")
+    ap.add_argument("--skip-extra", action="store_true")
+    ap.add_argument("--only-capture", action="store_true",
+                    help="run just the capture-kernel timing loop (for rocprofv3)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build is a one-GPU path (each rank runs a private ring with no "
+            "cross-GPU traffic); run with --gpus 1")
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2605_11093_amd as dmi
+    from paper_2605_11093_amd import binding as B
+    from workloads import configs
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    dmi.lib()
+    bench_lib = C.CDLL(os.path.join(ROOT, "paper_2605_11093_amd", "libdmi_bench.so"))
+    bench_lib.dmi_bench_sleep.argtypes = [C.c_void_p, C.c_uint32]
+    bench_lib.dmi_bench_stream_gemv.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p]
+    stream = torch.cuda.current_stream()
+    sh = stream.cuda_stream
+
+    def ev_pair():
+        return torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    # ------------------------------------------------------------------ workload (config 2)
+    wl = configs.config2_decode8b(device=dev, n_steps=args.steps + args.warmup)
+    n_points, n_reqs, hidden = 32, 64, 4096
+    rec_bytes = dmi.record_bytes(n_reqs, n_reqs, hidden, B.DT_BF16, 5)
+    step_bytes = rec_bytes * n_points
+    calls0 = [wl.step_calls(s) for s in range(4)]          # the pool has 4 slots per point
+
+    def prepared(ring):
+        return [[dmi.PreparedObserve(ring, c.point_id, c.tensor, c.reqs, out_dtype=c.out_dtype,
+                                     summary_mask=c.summary_mask) for c in calls0[slot]]
+                for slot in range(4)]
+
+    def consume(ring):
+        n = 0
+        while True:
+            v = ring.poll_host()
+            if not v:
+                return n
+            n += len(v)
+            ring.release_host(v[-1].seq)
+
+    def settle(ring):
+        stream.synchronize()
+        for _ in range(100000):
+            ring.drain(B.DRAIN_FLUSH, allow=(B.ERR_AGAIN,))
+            consume(ring)
+            if ring.last_drain_status == B.OK:
+                return
+        raise RuntimeError("ring did not settle")
+
+    def observe_checked(po, step):
+        rc = po(step, sh)
+        if rc < 0:
+            raise dmi.DmiError(rc, dmi.lib().dmi_last_error().decode())
+
+    # ------------------------------------------------------------------ capture kernel alone
+    def time_capture_kernel(ring, pos, n_launch, reps=5):
+        """n_launch observes queued behind a sleeping stream so that they run back to
+        back; HIP events on the same stream bracket them."""
+        best = None
+        for _ in range(reps):
+            settle(ring)
+            e0, e1 = ev_pair()
+            bench_lib.dmi_bench_sleep(sh, 400 + 12 * n_launch)
+            e0.record(stream)
+            for i in range(n_launch):
+                observe_checked(pos[i % len(pos)], 10_000 + i)
+            e1.record(stream)
+            e1.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / n_launch
+            best = us if best is None else min(best, us)
+        settle(ring)
+        return best
+
+    ring = B.Ring(wl.device_ring_bytes, wl.host_ring_bytes, max_reqs_per_observe=256, block_timeout_ms=2000)
+    ring.set_policy(B.POLICY_BLOCK)
+    pos = prepared(ring)
+    flat = [po for slot in pos for po in slot]
+    for i in range(64):
+        observe_checked(flat[i % len(flat)], i)
+    settle(ring)
+    cap_us = time_capture_kernel(ring, flat, 256)
+    alg_bytes = rec_bytes + n_reqs * hidden * 2 + n_reqs * 20     # written + rows read + table read
+    log(f"capture kernel (config 2 record, {alg_bytes} algorithmic bytes): {cap_us:.2f} us/launch "
+        f"= {alg_bytes / cap_us / 1e3:.1f} GB/s")
+    if args.only_capture:
+        ring.destroy()
+        return
+
+    # ------------------------------------------------------------------ whole path, timed
+    def run_steps(first, count):
+        for s in range(first, first + count):
+            for po in pos[s % 4]:
+                observe_checked(po, s)
+            ring.drain(B.DRAIN_NONBLOCK)
+            consume(ring)
+
+    run_steps(0, args.warmup)
+    settle(ring)
+    st0 = ring.get_stats()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run_steps(args.warmup, args.steps)
+    settle(ring)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    st1 = ring.get_stats()
+    moved = st1.released_bytes - st0.released_bytes
+    assert moved == step_bytes * args.steps, (moved, step_bytes * args.steps)
+    assert st1.dropped_records == 0
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = moved / (t1 - t0) / 1e9
+    log(f"whole path: {ms_per_step:.3f} ms/step, {value:.2f} GB/s captured to pinned host")
+    ring.destroy()
+
+    extra = {}
+    # ------------------------------------------------------------------ probes: HBM copy, pinned D2H
+    a = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    b = torch.empty_like(a)
+    hp = torch.empty(1 << 30, dtype=torch.uint8, pin_memory=True)
+    best = 1e9
+    for _ in range(5):
+        e0, e1 = ev_pair()
+        e0.record(stream)
+        b.copy_(a)
+        e1.record(stream)
+        e1.synchronize()
+        best = min(best, e0.elapsed_time(e1))
+    d2d = 2 * (1 << 30) / best / 1e6
+    best = 1e9
+    for _ in range(10):
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        hp.copy_(a, non_blocking=True)
+        torch.cuda.synchronize()
+        best = min(best, time.perf_counter() - t)
+    d2h_peak = (1 << 30) / best / 1e9
+    del b, hp
+    log(f"probes: device copy {d2d:.0f} GB/s (read+write), pinned D2H {d2h_peak:.1f} GB/s")
+    extra["hbm_copy_probe_GBs"] = round(d2d, 1)
+    extra["pinned_d2h_peak_GBs"] = round(d2h_peak, 2)
+
+    # ------------------------------------------------------------------ drain alone, both engines
+    drain = {}
+    for name, fl in (("copy_engine", B.DRAIN_COPY_ENGINE), ("kernel", B.DRAIN_KERNEL)):
+        r2 = B.Ring(wl.device_ring_bytes, wl.host_ring_bytes, flags=fl, max_reqs_per_observe=256)
+        p2 = [po for slot in prepared(r2) for po in slot]
+        rates = []
+        for rep in range(4):
+            for i in range(384):                                  # 202 MB committed, nothing drained
+                observe_checked(p2[i % len(p2)], i)
+            stream.synchronize()
+            t = time.perf_counter()
+            n = r2.drain(B.DRAIN_FLUSH)
+            dt = time.perf_counter() - t
+            rates.append(n / dt / 1e9)
+            while r2.poll_host():
+                pass
+            v = r2.get_stats()
+            r2.release_host(v.launched_records)
+        drain[name] = round(max(rates[1:]), 2)
+        r2.destroy()
+    log(f"drain alone: {drain} GB/s")
+    extra["drain_GBs"] = drain
+    extra["drain_frac_of_d2h_peak"] = {k: round(v / d2h_peak, 3) for k, v in drain.items()}
+
+    # ------------------------------------------------------------------ other workload shapes' kernels
+    if not args.skip_extra:
+        kernels = {}
+
+        def time_shape(name, make_call, alg, n_launch, ring_bytes):
+            # drop-newest: no admission waits on the host (the ring is sized to hold every launch)
+            r3 = B.Ring(ring_bytes, 1 << 26, max_reqs_per_observe=256)
+            r3.set_policy(B.POLICY_DROP_NEWEST)
+            po = make_call(r3)
+            for i in range(3):
+                observe_checked(po, i)
+            stream.synchronize()
+            best = 1e9
+            for rep in range(3):
+                r3.destroy()
+                r3 = B.Ring(ring_bytes, 1 << 26, max_reqs_per_observe=256)
+                r3.set_policy(B.POLICY_DROP_NEWEST)
+                po = make_call(r3)
+                e0, e1 = ev_pair()
+                bench_lib.dmi_bench_sleep(sh, 300 + 10 * n_launch)
+                e0.record(stream)
+                for i in range(n_launch):
+                    observe_checked(po, i)
+                e1.record(stream)
+                e1.synchronize()
+                best = min(best, e0.elapsed_time(e1) * 1e3 / n_launch)
+                assert r3.get_stats().dropped_records == 0
+            r3.destroy()
+            kernels[name] = {"us_per_launch": round(best, 2), "algorithmic_bytes": alg,
+                             "GBs": round(alg / best / 1e3, 1), "frac_hbm_peak": round(alg / best / 1e3 / HBM_PEAK_GBS, 4)}
+            log(f"kernel {name}: {kernels[name]}")
+
+        # config 3: ragged prefill, every 4th token, bf16 -> fp8
+        w3 = configs.config3_prefill(device=dev, n_steps=1, n_resid=1, n_mlp=1)
+        c_res, c_mlp = [c for c in w3.step_calls(0) if c.point_id < 100][0], [c for c in w3.step_calls(0) if c.point_id >= 100][0]
+        rows3 = int(c_res.reqs[:, 3].sum())
+        for nm, c, E in (("config3_resid_fp8", c_res, 4096), ("config3_mlp_fp8", c_mlp, 14336)):
+            alg = rows3 * E * 3 + 32 * 36 + 64
+            rb = dmi.record_bytes(32, rows3, E, B.DT_FP8, 0)
+            time_shape(nm, lambda r, c=c: dmi.PreparedObserve(r, c.point_id, c.tensor, c.reqs, out_dtype=B.DT_FP8),
+                       alg, 8, rb * 8 + (1 << 20))
+        del w3, c_res, c_mlp
+        torch.cuda.empty_cache()
+        # config 4: paged KV slices (one layer's K cache, 2 GiB)
+        w4 = configs.config4_paged_kv(device=dev, n_layers_cap=1, n_steps=1)
+        c4 = w4.step_calls(0)[0]
+        rows4 = int(c4.reqs[:, 3].sum())
+        alg = rows4 * 256 * 4 + rows4 // 16 * 4 + 16 * 36 + 64
+        rb = dmi.record_bytes(16, rows4, 256, B.DT_BF16, 0)
+        time_shape("config4_paged_kv", lambda r: dmi.PreparedObserve(r, c4.point_id, c4.tensor, c4.reqs, paged=c4.paged),
+                   alg, 8, rb * 8 + (1 << 20))
+        del w4, c4
+        torch.cuda.empty_cache()
+        # config 5: 70B-shaped decode rows
+        w5 = configs.config5_saturation(device=dev, n_points=1, n_steps=1)
+        c5 = w5.step_calls(0)[0]
+        alg = 256 * 8192 * 4 + 256 * 36 + 64
+        rb = dmi.record_bytes(256, 256, 8192, B.DT_BF16, 0)
+        time_shape("config5_decode70b", lambda r: dmi.PreparedObserve(r, c5.point_id, c5.tensor, c5.reqs),
+                   alg, 64, rb * 64 + (1 << 20))
+        del w5, c5
+        torch.cuda.empty_cache()
+        extra["kernels"] = kernels
+
+    # ------------------------------------------------------------------ step-time overhead
+    if not args.skip_overhead:
+        n_w = 436 * 1000 * 1000 // 2 // 8 * 8                  # one Llama-3-8B layer of bf16 weights
+        weights = [torch.empty(n_w, dtype=torch.bfloat16, device=dev).normal_() for _ in range(n_points)]
+        xvec = torch.randn(4096, device=dev).to(torch.bfloat16)
+        acc = torch.zeros(4096, dtype=torch.float32, device=dev)
+        r4 = B.Ring(wl.device_ring_bytes, wl.host_ring_bytes, flags=B.BG_THREAD, max_reqs_per_observe=256)
+        p4 = prepared(r4)
+
+        def model_steps(first, count, capture):
+            for s in range(first, first + count):
+                for l in range(n_points):
+                    bench_lib.dmi_bench_stream_gemv(weights[l].data_ptr(), n_w, xvec.data_ptr(), acc.data_ptr(), sh)
+                    if capture:
+                        observe_checked(p4[s % 4][l], s)
+                if capture:
+                    consume(r4)
+
+        per_step = {False: [], True: []}
+        model_steps(0, 5, True)
+        stream.synchronize()
+        for rep in range(5):
+            for capture in (False, True):
+                torch.cuda.synchronize()
+                t = time.perf_counter()
+                model_steps(100 + rep * 20, 20, capture)
+                stream.synchronize()
+                if capture:      # "including the tail of the offload path"
+                    while r4.get_stats().drained_bytes < r4.get_stats().captured_bytes:
+                        time.sleep(0.00005)
+                    consume(r4)
+                per_step[capture].append((time.perf_counter() - t) * 1e3 / 20)
+        base, with_cap = statistics.median(per_step[False]), statistics.median(per_step[True])
+        st = r4.get_stats()
+        r4.destroy()
+        extra["overhead"] = {"no_capture_ms_per_step": round(base, 4), "capture_ms_per_step": round(with_cap, 4),
+                             "overhead_pct": round((with_cap - base) / base * 100, 3),
+                             "interfering_workload": "32 x 436 MB bf16 weight-streaming GEMV per step",
+                             "filler_GBs": round(n_points * n_w * 2 / base / 1e6, 1),
+                             "captured_GBs_during": round(step_bytes / with_cap / 1e6, 2),
+                             "dropped_records": st.dropped_records,
+                             "paper_context": "0.4-6.8 % offline, ~6 % online on H100 (other hardware, real models)"}
+        log(f"overhead: {extra['overhead']}")
+        del weights
+
+    # ------------------------------------------------------------------ CPU oracle baseline
+    cpu = None
+    if not args.skip_cpu_baseline:
+        import oracle
+        from oracle.replay import CpuView
+        oracle.build()
+        view = CpuView()
+        n_sample_steps = 96
+        t = time.perf_counter()
+        nbytes = 0
+        seq = 0
+        for s in range(n_sample_steps):
+            for c in calls0[s % 4]:
+                rec = oracle.build_record(view.tensor(c.tensor), c.reqs, seq=seq, step_id=s, point_id=c.point_id,
+                                          out_dtype=c.out_dtype, summary_mask=c.summary_mask)
+                nbytes += rec.size
+                seq += 1
+            if time.perf_counter() - t > 25.0:
+                n_sample_steps = s + 1
+                break
+        dt = time.perf_counter() - t
+        cpu = {"value": round(nbytes / dt / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+               "sample": f"record building for the first {n_sample_steps} steps ({seq} records, "
+                         f"{nbytes / 1e6:.0f} MB) of the same workload"}
+        log(f"cpu oracle: {cpu}")
+
+    cap_gbs = alg_bytes / cap_us / 1e3
+    out = {
+        "metric": "sustained captured GB/s to pinned host + % step-time overhead vs no-capture",
+        "value": round(value, 3), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": SEED_NOTE,
+        "config": {"workload": "config 2: Llama-3-8B-shaped decode, hidden 4096 bf16, 32 observation points, "
+                               "64 requests x 1 row, raw bf16 + L2 + absmax per row, device ring 256 MiB, "
+                               "host ring 2 GiB, policy block",
+                   "bytes_per_step": step_bytes, "drain": "copy engine, issued by the producer thread each step"},
+        "roofline": {"bound": "hbm", "kernel": "capture_kernel<bf16, vec16, raw, summaries> (config 2 record)",
+                     "achieved": round(cap_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(cap_gbs / HBM_PEAK_GBS, 4), "us_per_launch": round(cap_us, 3),
+                     "algorithmic_bytes_per_launch": alg_bytes, "traffic": None},
+        "cpu_baseline": cpu,
+    }
+    out.update(extra)
+    if "overhead" in extra:
+        out["overhead_pct"] = extra["overhead"]["overhead_pct"]
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -256,8 +256,12 @@ typedef struct {
     uint64_t drained_bytes, released_bytes, drain_batches;
     uint64_t block_wait_ns;
     uint64_t dev_ring_high_water, host_ring_high_water;
+    uint64_t bad_rows;          /* rows whose row_index_dev / block-table entry left the source:
+                                   stored as zeros (read from the device, synchronises the library's
+                                   own stream only) */
 } dmi_stats_t;
-/* Device-side counters reflect kernels that have finished. */
+/* Device-side counters (captured_*, dropped_*) cover the launches whose completion the
+ * library has observed: after dmi_drain(DMI_DRAIN_FLUSH) that is all of them. */
 dmi_status_t dmi_get_stats(dmi_ring_t *ring, dmi_stats_t *out /*[host]*/);
 /* Records of one point discarded by drop-newest (synchronises the library's
  * own control stream only). */

@@ -79,7 +79,7 @@ _STAT_FIELDS = ("observed_calls", "launched_records", "captured_records", "captu
                 "captured_bytes", "dropped_records", "dropped_rows", "dropped_bytes",
                 "sampled_out_calls", "sampled_out_rows", "disabled_calls", "drained_bytes",
                 "released_bytes", "drain_batches", "block_wait_ns", "dev_ring_high_water",
-                "host_ring_high_water")
+                "host_ring_high_water", "bad_rows")
 
 
 class StatsC(C.Structure):
@@ -105,6 +105,7 @@ class Stats:
     block_wait_ns: int = 0
     dev_ring_high_water: int = 0
     host_ring_high_water: int = 0
+    bad_rows: int = 0
 
 
 @dataclass
@@ -195,6 +196,38 @@ def _torch_dtype_code(t) -> int:
 def _reqs_buffer(reqs):
     a = np.ascontiguousarray(np.asarray(reqs, dtype=np.uint32).reshape(-1, 5))
     return a
+
+
+class PreparedObserve:
+    """The argument structs of one dmi_observe / dmi_observe_paged call, built once so
+    that a per-step loop pays only the foreign call itself.  Calling it returns the
+    raw status code."""
+
+    def __init__(self, ring: "Ring", point_id: int, tensor, reqs, *, out_dtype: Optional[int] = None,
+                 summary_mask: int = 0, keep_mask=None, row_index=None, paged=None):
+        dt = _torch_dtype_code(tensor)
+        self._keep = (tensor, keep_mask, row_index, paged)
+        self._ra = _reqs_buffer(reqs)
+        self._sel = Selection(self._ra.shape[0], self._ra.ctypes.data,
+                              None if keep_mask is None else keep_mask.data_ptr(),
+                              None if row_index is None else row_index.data_ptr())
+        self._xf = Transform(dt if out_dtype is None else out_dtype, summary_mask)
+        self._h, self._point = ring._h, point_id
+        if paged is None:
+            self._src = Tensor(tensor.data_ptr(), dt, (C.c_int64 * 2)(*tensor.shape),
+                               (C.c_int64 * 2)(*tensor.stride()))
+            self._fn = lib().dmi_observe
+        else:
+            bt = paged.block_table
+            self._src = PagedKV(tensor.data_ptr(), dt, tensor.stride(0), tensor.stride(1), tensor.stride(2),
+                                paged.block_size, paged.n_heads, paged.head_dim, tensor.shape[0], bt.shape[0],
+                                bt.data_ptr(), bt.stride(0), len(paged.heads_sel),
+                                (C.c_uint32 * 8)(*paged.heads_sel))
+            self._fn = lib().dmi_observe_paged
+        self._a = (C.byref(self._src), C.byref(self._sel), C.byref(self._xf))
+
+    def __call__(self, step_id: int, stream: int) -> int:
+        return self._fn(self._h, self._point, self._a[0], self._a[1], self._a[2], step_id, stream)
 
 
 class Ring:

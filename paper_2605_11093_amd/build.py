@@ -16,6 +16,20 @@ def hipcc() -> str:
     return shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
 
 
+BENCH_SO = os.path.join(HERE, "libdmi_bench.so")
+BENCH_SRC = os.path.join(HERE, "csrc", "bench_kernels.hip")
+
+
+def build_bench() -> str:
+    """Harness-side kernels for bench.py (sleep, streaming GEMV)."""
+    cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+           "-I", os.path.join(ROOT, "include"),
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           BENCH_SRC, "-o", BENCH_SO]
+    subprocess.check_call(cmd)
+    return BENCH_SO
+
+
 def build(force: bool = True) -> str:
     if not force and os.path.exists(SO):
         newest = max(os.path.getmtime(p) for p in SOURCES + HEADERS)
@@ -31,3 +45,4 @@ def build(force: bool = True) -> str:
 
 if __name__ == "__main__":
     print(build())
+    print(build_bench())

@@ -70,6 +70,7 @@ constexpr uint32_t kSelCache = 4;
 
 struct SelCache {
     bool valid = false;
+    bool paged = false;
     hipStream_t stream = nullptr;
     uint32_t slot = 0;
     std::vector<uint32_t> words;
@@ -78,6 +79,12 @@ struct SelCache {
 struct Pending {
     hipEvent_t ev;
     uint64_t upto;
+};
+
+struct Probe {
+    hipEvent_t ev_user;     // recorded on the producer's stream behind the launches
+    hipEvent_t ev_done;     // recorded on the control stream behind the slot fetch
+    uint64_t covers;        // every launch with seq < covers was enqueued before ev_user
 };
 
 }  // namespace
@@ -90,7 +97,8 @@ struct dmi_ring {
     uint8_t *host_ring = nullptr, *host_ring_dev = nullptr;
     uint64_t host_cap = 0;
     DevCtrl *dctrl = nullptr;
-    HostCtrl *hctrl = nullptr, *hctrl_dev = nullptr;
+    CommitSlot *hslots = nullptr, *hslots_dev = nullptr;   // pinned mirror of DevCtrl::slots
+    hipStream_t ctl_stream = nullptr;                      // fetches commit slots
     uint32_t *slab = nullptr;
     uint32_t slab_slot_words = 0, next_slab = 0, max_reqs = 0;
     SelCache cache[kSelCache];
@@ -103,9 +111,20 @@ struct dmi_ring {
     std::vector<uint8_t> point_off;
 
     // producer side
-    std::atomic<uint64_t> next_seq{0};
+    std::atomic<uint64_t> next_seq{0};                     // launches issued so far
+    std::atomic<void *> last_stream{nullptr};
     std::deque<std::pair<uint64_t, uint64_t>> inflight;    // (seq, upper bound of record bytes)
     uint64_t inflight_sum = 0;
+    uint64_t unprobed_launches = 0, unprobed_bytes = 0, probe_bytes = 4u << 20;
+
+    // commit discovery: events recorded behind launches ("probes"), queried in order
+    std::mutex pmu;
+    std::deque<Probe> probes;
+    std::vector<hipEvent_t> probe_pool;
+    uint64_t probed_upto = 0;                              // launches with seq < this have a probe behind them
+    std::atomic<uint64_t> confirmed{0};                    // launches with seq < this have finished
+    std::atomic<uint64_t> committed{0};                    // device head after launch confirmed-1
+    uint64_t snap[6] = {0, 0, 0, 0, 0, 0};                 // counters of the last confirmed slot
 
     // drain / host ring state
     std::mutex mu;
@@ -132,12 +151,56 @@ void atomic_max(std::atomic<uint64_t> &a, uint64_t v)
     while (cur < v && !a.compare_exchange_weak(cur, v, std::memory_order_relaxed)) {}
 }
 
-uint64_t read_committed(const dmi_ring *r)
+// Record an event behind everything launched so far (no-op if that is already covered)
+// and, behind it on the control stream, the fetch of the newest launch's commit slot.
+dmi_status_t record_probe(dmi_ring *r)
 {
-    uint64_t c = r->hctrl->committed;
-    std::atomic_thread_fence(std::memory_order_acquire);
-    return c;
+    std::lock_guard<std::mutex> lk(r->pmu);
+    const uint64_t launched = r->next_seq.load(std::memory_order_acquire);
+    if (launched <= r->probed_upto) return DMI_OK;
+    hipEvent_t ev[2];
+    for (int i = 0; i < 2; i++) {
+        if (r->probe_pool.empty()) HIP_TRY(hipEventCreateWithFlags(&ev[i], hipEventDisableTiming));
+        else { ev[i] = r->probe_pool.back(); r->probe_pool.pop_back(); }
+    }
+    const uint32_t slot = (uint32_t)((launched - 1u) % kCommitSlots);
+    HIP_TRY(hipEventRecord(ev[0], (hipStream_t)r->last_stream.load(std::memory_order_acquire)));
+    HIP_TRY(hipStreamWaitEvent(r->ctl_stream, ev[0], 0));
+    HIP_TRY(launch_fetch_slot(&r->dctrl->slots[slot], r->hslots_dev + slot, r->ctl_stream));
+    HIP_TRY(hipEventRecord(ev[1], r->ctl_stream));
+    r->probes.push_back({ev[0], ev[1], launched});
+    r->probed_upto = launched;
+    return DMI_OK;
 }
+
+// Take note of finished probes: the slot of the newest launch they cover says where the
+// device head stands.  With block=true waits for the oldest outstanding probe.
+dmi_status_t advance_commits(dmi_ring *r, bool block)
+{
+    std::lock_guard<std::mutex> lk(r->pmu);
+    while (!r->probes.empty()) {
+        Probe &p = r->probes.front();
+        hipError_t e = block ? hipEventSynchronize(p.ev_done) : hipEventQuery(p.ev_done);
+        block = false;
+        if (e == hipErrorNotReady) break;
+        if (e != hipSuccess) return fail(DMI_ERR_HIP, "commit event: %s", hipGetErrorString(e));
+        const volatile CommitSlot &sl = r->hslots[(p.covers - 1u) % kCommitSlots];
+        std::atomic_thread_fence(std::memory_order_acquire);
+        if (sl.seq_plus1 != p.covers)
+            return fail(DMI_ERR_CLOSED, "commit slot of launch %llu holds %llu",
+                        (unsigned long long)(p.covers - 1u), (unsigned long long)sl.seq_plus1);
+        r->snap[0] = sl.captured_records; r->snap[1] = sl.captured_rows; r->snap[2] = sl.captured_bytes;
+        r->snap[3] = sl.dropped_records;  r->snap[4] = sl.dropped_rows;  r->snap[5] = sl.dropped_bytes;
+        r->committed.store(sl.head, std::memory_order_release);
+        r->confirmed.store(p.covers, std::memory_order_release);
+        r->probe_pool.push_back(p.ev_user);
+        r->probe_pool.push_back(p.ev_done);
+        r->probes.pop_front();
+    }
+    return DMI_OK;
+}
+
+uint64_t read_committed(const dmi_ring *r) { return r->committed.load(std::memory_order_acquire); }
 
 // Retire finished copies.  Caller holds r->mu.
 dmi_status_t reap(dmi_ring *r, bool wait)
@@ -171,8 +234,8 @@ dmi_status_t drain_locked(dmi_ring *r, bool wait, uint64_t *moved)
             uint64_t units = n / 16u;
             uint32_t grid = (uint32_t)((units + kThreads - 1) / kThreads);
             if (grid > 128u) grid = 128u;
-            HIP_TRY(launch_drain_kernel(r->dev_ring, r->dev_cap, r->host_ring_dev, r->host_cap, from, n,
-                                        r->dctrl, grid, r->drain_stream));
+            HIP_TRY(launch_drain_kernel(r->dev_ring, r->dev_cap, r->host_ring_dev, r->host_cap, from, n, grid,
+                                        r->drain_stream));
         } else {
             uint64_t off = from, left = n;
             while (left) {
@@ -185,9 +248,9 @@ dmi_status_t drain_locked(dmi_ring *r, bool wait, uint64_t *moved)
                 off += len;
                 left -= len;
             }
-            // the device may reuse the span only after the copies before it have run
-            HIP_TRY(launch_set_tail(r->dctrl, from + n, r->drain_stream));
         }
+        // the device may reuse the span only after the copies before this have run
+        HIP_TRY(launch_set_tail(r->dctrl, from + n, r->drain_stream));
         hipEvent_t ev;
         if (r->ev_pool.empty()) HIP_TRY(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
         else { ev = r->ev_pool.back(); r->ev_pool.pop_back(); }
@@ -203,13 +266,12 @@ dmi_status_t drain_locked(dmi_ring *r, bool wait, uint64_t *moved)
     return DMI_OK;
 }
 
-// Pop launches the device has finished; returns an upper bound of the device head
-// once everything launched so far has run.
+// Pop launches known to have finished; returns an upper bound of the device head once
+// everything launched so far has run.  Producer thread only.
 uint64_t head_upper_bound(dmi_ring *r)
 {
-    const uint64_t done = r->hctrl->last_seq_plus1;
-    std::atomic_thread_fence(std::memory_order_acquire);
-    const uint64_t committed = r->hctrl->committed;
+    const uint64_t done = r->confirmed.load(std::memory_order_acquire);
+    const uint64_t committed = r->committed.load(std::memory_order_acquire);
     while (!r->inflight.empty() && r->inflight.front().first < done) {
         r->inflight_sum -= r->inflight.front().second;
         r->inflight.pop_front();
@@ -217,11 +279,14 @@ uint64_t head_upper_bound(dmi_ring *r)
     return committed + r->inflight_sum;
 }
 
-// Completeness policy: wait on the host until a record of `ub` bytes is sure to fit.
+// Completeness policy: wait on the host until a record of `ub` bytes is sure to fit
+// (the paper's flush before the forward step, section 4.4).  Never a device-side wait.
 dmi_status_t wait_for_room(dmi_ring *r, uint64_t ub)
 {
     uint64_t t0 = 0;
     for (;;) {
+        dmi_status_t st = advance_commits(r, false);
+        if (st != DMI_OK) return st;
         const uint64_t head_ub = head_upper_bound(r);
         const uint64_t tail = r->drain_done.load(std::memory_order_acquire);
         if (head_ub - tail + ub <= r->dev_cap) break;
@@ -229,17 +294,18 @@ dmi_status_t wait_for_room(dmi_ring *r, uint64_t ub)
         uint64_t moved = 0;
         {
             std::lock_guard<std::mutex> lk(r->mu);
-            dmi_status_t st = drain_locked(r, true, &moved);
+            st = drain_locked(r, true, &moved);
             if (st != DMI_OK) return st;
         }
-        if (moved == 0) {
-            if (now_ns() - t0 > (uint64_t)r->block_timeout_ms * 1000000ull) {
-                r->block_wait_ns += now_ns() - t0;
-                return fail(DMI_ERR_AGAIN, "no room in the device ring after %u ms (host ring full or "
-                                           "observes not finishing)", r->block_timeout_ms);
-            }
-            std::this_thread::sleep_for(std::chrono::microseconds(20));
+        if (moved) continue;
+        st = record_probe(r);       // make sure the launches we wait for will report
+        if (st != DMI_OK) return st;
+        if (now_ns() - t0 > (uint64_t)r->block_timeout_ms * 1000000ull) {
+            r->block_wait_ns += now_ns() - t0;
+            return fail(DMI_ERR_AGAIN, "no room in the device ring after %u ms (host ring full or "
+                                       "observes not finishing)", r->block_timeout_ms);
         }
+        std::this_thread::sleep_for(std::chrono::microseconds(10));
     }
     if (t0) r->block_wait_ns += now_ns() - t0;
     return DMI_OK;
@@ -248,7 +314,8 @@ dmi_status_t wait_for_room(dmi_ring *r, uint64_t ub)
 // Put the request table where the kernel can read it from L2: a slab of slots in
 // device memory, refilled only when the selection differs from recent ones (all
 // hook points of a step share their selection).
-dmi_status_t stage_selection(dmi_ring *r, const dmi_selection_t *sel, hipStream_t s, uint32_t *slot_out)
+dmi_status_t stage_selection(dmi_ring *r, const dmi_selection_t *sel, bool paged, hipStream_t s,
+                             uint32_t *slot_out)
 {
     const uint32_t n = sel->n_reqs;
     std::vector<uint32_t> words((size_t)n * 5u);
@@ -258,16 +325,18 @@ dmi_status_t stage_selection(dmi_ring *r, const dmi_selection_t *sel, hipStream_
         words[4u * i + 1] = q.tok_start;
         words[4u * i + 2] = q.tok_step;
         words[4u * i + 3] = q.tok_count;
-        words[4u * n + i] = q.row_base;
+        // first source row of the request (dense; the caller has checked that it fits 32 bits),
+        // or its row of the block table (paged)
+        words[4u * n + i] = paged ? q.row_base : q.row_base + q.tok_start;
     }
     for (auto &c : r->cache) {
-        if (c.valid && c.stream == s && c.words == words) { *slot_out = c.slot; return DMI_OK; }
+        if (c.valid && c.stream == s && c.paged == paged && c.words == words) { *slot_out = c.slot; return DMI_OK; }
     }
     const uint32_t slot = r->next_slab++ % kSlabSlots;
     for (auto &c : r->cache) if (c.valid && c.slot == slot) c.valid = false;
     if (n) HIP_TRY(launch_upload(r->slab + (size_t)slot * r->slab_slot_words, words.data(), n * 5u, s));
     SelCache &c = r->cache[r->cache_rr++ % kSelCache];
-    c.valid = true; c.stream = s; c.slot = slot; c.words.swap(words);
+    c.valid = true; c.paged = paged; c.stream = s; c.slot = slot; c.words.swap(words);
     *slot_out = slot;
     return DMI_OK;
 }
@@ -296,24 +365,36 @@ dmi_status_t observe_common(dmi_ring *r, uint32_t point_id, const dmi_selection_
                     (unsigned long long)ub, (unsigned long long)r->dev_cap);
 
     const uint32_t mode = r->mode.load(std::memory_order_relaxed);
+    r->last_stream.store(hip_stream, std::memory_order_release);
     if (mode == DMI_POLICY_BLOCK) {
         dmi_status_t st = wait_for_room(r, ub);
         if (st != DMI_OK) return st;
     } else {
+        dmi_status_t st = advance_commits(r, false);
+        if (st != DMI_OK) return st;
         head_upper_bound(r);    // keeps the in-flight list short
+    }
+    // a launch's host slot is reused kCommitSlots launches later: keep fewer than that unconfirmed
+    while (r->next_seq.load(std::memory_order_relaxed) - r->confirmed.load(std::memory_order_acquire) >=
+           kCommitSlots - 1u) {
+        dmi_status_t st = record_probe(r);
+        if (st == DMI_OK) st = advance_commits(r, true);
+        if (st != DMI_OK) return st;
     }
 
     uint32_t slot = 0;
-    dmi_status_t st = stage_selection(r, sel, s, &slot);
+    dmi_status_t st = stage_selection(r, sel, a.paged != 0, s, &slot);
     if (st != DMI_OK) return st;
 
     const uint64_t seq = r->next_seq.load(std::memory_order_relaxed);
     const bool index_mode = sel->row_index_dev != nullptr;
-    const bool tab_lds = sel->n_reqs <= kLdsTableMax;
+    bool simple = sel->keep_mask_dev == nullptr;
+    for (uint32_t i = 0; simple && i < sel->n_reqs; i++) simple = sel->reqs[i].tok_count == 1u;
+    const bool tab_lds = !simple && sel->n_reqs <= kLdsTableMax;
     a.n_seg = geo.n_seg;
     a.seg_units = geo.seg_elems / unit_elems;
     a.req_table = reinterpret_cast<const uint4 *>(r->slab + (size_t)slot * r->slab_slot_words);
-    a.row_base = r->slab + (size_t)slot * r->slab_slot_words + 4u * (size_t)sel->n_reqs;
+    a.row0 = r->slab + (size_t)slot * r->slab_slot_words + 4u * (size_t)sel->n_reqs;
     a.keep_mask = sel->keep_mask_dev;
     a.row_index = sel->row_index_dev;
     a.n_reqs = sel->n_reqs;
@@ -332,11 +413,13 @@ dmi_status_t observe_common(dmi_ring *r, uint32_t point_id, const dmi_selection_
     a.ring = r->dev_ring;
     a.cap = r->dev_cap;
     a.ctrl = r->dctrl;
-    a.hctrl = r->hctrl_dev;
-    a.slot = (uint32_t)(seq % kLaunchSlots);
+    a.cslot = &r->dctrl->slots[seq % kCommitSlots];
+    a.tail_floor = r->drain_done.load(std::memory_order_acquire);
+    a.simple = simple ? 1u : 0u;
+    a.upr_shift = (upr & (upr - 1u)) == 0 ? (uint32_t)__builtin_ctzll(upr) : 32u;
     a.drop_newest = mode == DMI_POLICY_DROP_NEWEST ? 1u : 0u;
     a.table_in_lds = tab_lds ? 1u : 0u;
-    a.lds_bytes = capture_lds_bytes(sel->n_reqs, index_mode, tab_lds);
+    a.lds_bytes = capture_lds_bytes(simple ? 0u : sel->n_reqs, index_mode, tab_lds);
 
     uint64_t groups;
     if (xf->summary_mask) groups = (listed + a.rows_per_wg - 1u) / a.rows_per_wg;
@@ -348,6 +431,13 @@ dmi_status_t observe_common(dmi_ring *r, uint32_t point_id, const dmi_selection_
     r->next_seq.store(seq + 1, std::memory_order_release);
     r->inflight.emplace_back(seq, ub);
     r->inflight_sum += ub;
+    r->unprobed_launches += 1;
+    r->unprobed_bytes += ub;
+    if (r->unprobed_launches >= 16u || r->unprobed_bytes >= r->probe_bytes) {
+        r->unprobed_launches = 0;
+        r->unprobed_bytes = 0;
+        return record_probe(r);
+    }
     return DMI_OK;
 }
 
@@ -385,6 +475,13 @@ void bg_loop(dmi_ring *r)
     const uint64_t timeout_ns = (uint64_t)(r->cfg.bg_timeout_us ? r->cfg.bg_timeout_us : 200u) * 1000ull;
     uint64_t waiting_since = 0;
     while (!r->stop.load(std::memory_order_acquire)) {
+        bool idle_probes;
+        {
+            std::lock_guard<std::mutex> lk(r->pmu);
+            idle_probes = r->probes.empty();
+        }
+        if (idle_probes) (void)record_probe(r);     // covers launches the producer left unprobed
+        (void)advance_commits(r, false);
         uint64_t pending_bytes;
         {
             std::lock_guard<std::mutex> lk(r->mu);
@@ -408,13 +505,16 @@ void free_ring(dmi_ring *r)
 {
     if (!r) return;
     if (r->drain_stream) { (void)hipStreamSynchronize(r->drain_stream); (void)hipStreamDestroy(r->drain_stream); }
+    if (r->ctl_stream) { (void)hipStreamSynchronize(r->ctl_stream); (void)hipStreamDestroy(r->ctl_stream); }
     for (auto &p : r->pending) (void)hipEventDestroy(p.ev);
     for (auto ev : r->ev_pool) (void)hipEventDestroy(ev);
+    for (auto &p : r->probes) { (void)hipEventDestroy(p.ev_user); (void)hipEventDestroy(p.ev_done); }
+    for (auto ev : r->probe_pool) (void)hipEventDestroy(ev);
     if (r->dev_ring) (void)hipFree(r->dev_ring);
     if (r->dctrl) (void)hipFree(r->dctrl);
     if (r->slab) (void)hipFree(r->slab);
     if (r->host_ring) (void)hipHostFree(r->host_ring);
-    if (r->hctrl) (void)hipHostFree(r->hctrl);
+    if (r->hslots) (void)hipHostFree((void *)r->hslots);
     delete r;
 }
 
@@ -477,22 +577,23 @@ dmi_status_t dmi_ring_create(const dmi_ring_config_t *cfg, dmi_ring_t **out)
         return bail(e, "hipHostMalloc(host ring)");
     if ((e = hipHostGetDevicePointer((void **)&r->host_ring_dev, r->host_ring, 0)) != hipSuccess)
         return bail(e, "hipHostGetDevicePointer(host ring)");
-    if ((e = hipHostMalloc((void **)&r->hctrl, sizeof(HostCtrl), hipHostMallocMapped | hipHostMallocCoherent)) !=
-        hipSuccess)
-        return bail(e, "hipHostMalloc(ctrl)");
-    if ((e = hipHostGetDevicePointer((void **)&r->hctrl_dev, r->hctrl, 0)) != hipSuccess)
-        return bail(e, "hipHostGetDevicePointer(ctrl)");
-    memset((void *)r->hctrl, 0, sizeof(HostCtrl));
+    if ((e = hipHostMalloc((void **)&r->hslots, sizeof(CommitSlot) * kCommitSlots,
+                           hipHostMallocMapped | hipHostMallocCoherent)) != hipSuccess)
+        return bail(e, "hipHostMalloc(commit slots)");
+    if ((e = hipHostGetDevicePointer((void **)&r->hslots_dev, (void *)r->hslots, 0)) != hipSuccess)
+        return bail(e, "hipHostGetDevicePointer(commit slots)");
+    memset((void *)r->hslots, 0, sizeof(CommitSlot) * kCommitSlots);
     {
         DevCtrl *init = new (std::nothrow) DevCtrl;
         if (!init) { free_ring(r); return fail(DMI_ERR_NOMEM, "out of host memory"); }
         memset(init, 0, sizeof *init);
-        for (auto &t : init->tail_seen) t = kUnset;
         e = hipMemcpy(r->dctrl, init, sizeof *init, hipMemcpyHostToDevice);
         delete init;
         if (e != hipSuccess) return bail(e, "hipMemcpy(ctrl)");
     }
     if ((e = hipStreamCreateWithFlags(&r->drain_stream, hipStreamNonBlocking)) != hipSuccess)
+        return bail(e, "hipStreamCreate");
+    if ((e = hipStreamCreateWithFlags(&r->ctl_stream, hipStreamNonBlocking)) != hipSuccess)
         return bail(e, "hipStreamCreate");
     if ((e = hipDeviceSynchronize()) != hipSuccess) return bail(e, "hipDeviceSynchronize");
     if (cfg->flags & DMI_BG_THREAD) r->bg = std::thread(bg_loop, r);
@@ -518,7 +619,7 @@ dmi_status_t dmi_observe(dmi_ring_t *r, uint32_t point_id, const dmi_tensor_t *t
     if (g != DMI_OK) return g;
     const uint32_t es = dtype_size(t->dtype);
     const int64_t T = t->shape[0], E = t->shape[1];
-    if (T < 0 || E < 1 || E > 0x7FFFFFFF) return fail(DMI_ERR_INVALID_ARG, "bad tensor shape");
+    if (T < 0 || T > 0xFFFFFFFFll || E < 1 || E > 0x7FFFFFFF) return fail(DMI_ERR_INVALID_ARG, "bad tensor shape");
     if ((E > 1 && t->stride[1] != 1) || t->stride[0] < 0) return fail(DMI_ERR_INVALID_ARG, "bad tensor stride");
     if (!t->data && T > 0) return fail(DMI_ERR_INVALID_ARG, "tensor data is NULL");
     if ((uintptr_t)t->data % es) return fail(DMI_ERR_INVALID_ARG, "tensor data is not element aligned");
@@ -608,21 +709,30 @@ dmi_status_t dmi_drain(dmi_ring_t *r, uint32_t flags, uint64_t *bytes_moved)
     (void)hipSetDevice(r->dev);
     if (bytes_moved) *bytes_moved = 0;
     const bool wait = !(flags & DMI_DRAIN_NONBLOCK);
+    dmi_status_t st;
     if (!(flags & DMI_DRAIN_FLUSH)) {
+        bool idle_probes;
+        {
+            std::lock_guard<std::mutex> lk(r->pmu);
+            idle_probes = r->probes.empty();
+        }
+        if (idle_probes && (st = record_probe(r)) != DMI_OK) return st;
+        if ((st = advance_commits(r, false)) != DMI_OK) return st;
         std::lock_guard<std::mutex> lk(r->mu);
         return drain_locked(r, wait, bytes_moved);
     }
-    // flush: everything issued so far must commit, then move all of it
+    // flush: everything issued so far must finish, then all of it is moved
     const uint64_t want_seq = r->next_seq.load(std::memory_order_acquire);
+    if ((st = record_probe(r)) != DMI_OK) return st;
     const uint64_t t0 = now_ns();
     uint64_t total = 0;
     for (;;) {
-        const uint64_t done = r->hctrl->last_seq_plus1;
-        std::atomic_thread_fence(std::memory_order_acquire);
+        if ((st = advance_commits(r, false)) != DMI_OK) return st;
+        const uint64_t done = r->confirmed.load(std::memory_order_acquire);
         uint64_t moved = 0, left;
         {
             std::lock_guard<std::mutex> lk(r->mu);
-            dmi_status_t st = drain_locked(r, true, &moved);
+            st = drain_locked(r, true, &moved);
             if (st != DMI_OK) return st;
             left = read_committed(r) - r->drain_issued;
         }
@@ -633,8 +743,8 @@ dmi_status_t dmi_drain(dmi_ring_t *r, uint32_t flags, uint64_t *bytes_moved)
             return fail(DMI_ERR_AGAIN, "host ring is full: release records and drain again");
         if (moved == 0) {
             if (now_ns() - t0 > (uint64_t)r->block_timeout_ms * 1000000ull)
-                return fail(DMI_ERR_AGAIN, "observes did not commit within %u ms", r->block_timeout_ms);
-            std::this_thread::sleep_for(std::chrono::microseconds(20));
+                return fail(DMI_ERR_AGAIN, "observes did not finish within %u ms", r->block_timeout_ms);
+            std::this_thread::sleep_for(std::chrono::microseconds(10));
         }
     }
 }
@@ -708,14 +818,17 @@ dmi_status_t dmi_get_stats(dmi_ring_t *r, dmi_stats_t *o)
     memset(o, 0, sizeof *o);
     o->observed_calls = r->observed_calls;
     o->launched_records = r->next_seq.load();
-    (void)r->hctrl->last_seq_plus1;
-    std::atomic_thread_fence(std::memory_order_acquire);
-    o->captured_records = r->hctrl->captured_records;
-    o->captured_rows = r->hctrl->captured_rows;
-    o->captured_bytes = r->hctrl->captured_bytes;
-    o->dropped_records = r->hctrl->dropped_records;
-    o->dropped_rows = r->hctrl->dropped_rows;
-    o->dropped_bytes = r->hctrl->dropped_bytes;
+    (void)hipSetDevice(r->dev);
+    (void)advance_commits(r, false);
+    {
+        std::lock_guard<std::mutex> lk(r->pmu);
+        o->captured_records = r->snap[0];
+        o->captured_rows = r->snap[1];
+        o->captured_bytes = r->snap[2];
+        o->dropped_records = r->snap[3];
+        o->dropped_rows = r->snap[4];
+        o->dropped_bytes = r->snap[5];
+    }
     o->sampled_out_calls = r->sampled_out_calls;
     o->sampled_out_rows = r->sampled_out_rows;
     o->disabled_calls = r->disabled_calls;
@@ -725,6 +838,13 @@ dmi_status_t dmi_get_stats(dmi_ring_t *r, dmi_stats_t *o)
     o->block_wait_ns = r->block_wait_ns;
     o->dev_ring_high_water = r->dev_high;
     o->host_ring_high_water = r->host_high;
+    {
+        std::lock_guard<std::mutex> lk(r->mu);
+        uint64_t bad = 0;
+        HIP_TRY(hipMemcpyAsync(&bad, &r->dctrl->bad_rows, 8, hipMemcpyDeviceToHost, r->drain_stream));
+        HIP_TRY(hipStreamSynchronize(r->drain_stream));
+        o->bad_rows = bad;
+    }
     return DMI_OK;
 }
 

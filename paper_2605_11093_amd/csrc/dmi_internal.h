@@ -7,33 +7,40 @@
 namespace dmi {
 
 constexpr uint32_t kThreads = 256;          // 4 wavefronts of 64 lanes per workgroup
-constexpr uint32_t kLaunchSlots = 64;       // per-launch control slots (done counter, tail consensus)
 constexpr uint32_t kMaxGrid = 2048;         // 256 CUs x 8 resident workgroups
 constexpr uint32_t kLdsTableMax = 1024;     // request tables up to this size are cached in LDS
-constexpr uint64_t kUnset = ~0ull;
 
-// Control block in device memory.  `head` and `tail` are logical stream offsets.
+// One slot per launch, written by workgroup 0 of the launch: where the head stands
+// after it, and the running counters.  Slot seq % kCommitSlots lives in device memory;
+// the host fetches it into a pinned mirror behind an event recorded after launch `seq`
+// (the role of the paper's CPU-side meta ring; the kernel-end release takes the place
+// of its in-kernel fence).
+constexpr uint32_t kCommitSlots = 1024;
+struct CommitSlot {
+    uint64_t seq_plus1;
+    uint64_t head;
+    uint64_t captured_records, captured_rows, captured_bytes;
+    uint64_t dropped_records, dropped_rows, dropped_bytes;
+};
+
+// Control block in device memory.  Offsets are logical stream offsets.
+//
+// Launches of one ring run one after another (stream order), so the head needs no
+// atomic reservation: launch `seq` reads head[seq & 1], which the previous launch
+// wrote and nobody writes during this one, and its workgroup 0 writes
+// head[(seq + 1) & 1], which nobody reads during this one.  No workgroup has to be
+// the last one, so the kernel has no completion counter and no fence.  The tail the
+// drop-newest decision uses travels the same way (tail_for), fed from `tail`, which the
+// drain advances at any time.
 struct DevCtrl {
-    uint64_t head;                  // next free stream byte (== committed: launches serialise)
-    uint64_t tail;                  // stream bytes below this have been drained
+    uint64_t head[2];               // next free stream byte, double buffered by launch parity
+    uint64_t tail_for[2];           // the tail as the previous launch saw it, same scheme
+    uint64_t tail;                  // stream bytes below this have been drained (set by the drain)
     uint64_t captured_records, captured_rows, captured_bytes;
     uint64_t dropped_records, dropped_rows, dropped_bytes;
     uint64_t bad_rows;              // rows whose device-side index left the tensor (stored as zeros)
-    uint64_t tail_seen[kLaunchSlots];   // one tail value agreed by all workgroups of a launch
-    uint32_t done[kLaunchSlots];        // workgroups of a launch that have finished
-    uint32_t drain_done;                // same, for the drain kernel
-    uint32_t pad_;
     uint32_t point_drops[4096];
-};
-
-// Control block in pinned host memory, written by the last workgroup of every
-// capture kernel, polled by the host (the role of the paper's CPU-side meta ring).
-struct HostCtrl {
-    volatile uint64_t committed;    // == DevCtrl::head after the launch
-    volatile uint64_t last_seq_plus1;   // launches with seq < this have finished
-    volatile uint64_t captured_records, captured_rows, captured_bytes;
-    volatile uint64_t dropped_records, dropped_rows, dropped_bytes;
-    volatile uint64_t bad_rows;
+    CommitSlot slots[kCommitSlots];
 };
 
 struct CaptureArgs {
@@ -50,7 +57,7 @@ struct CaptureArgs {
     uint32_t heads_sel[8];
     // selection (device slab)
     const uint4 *req_table;         // {req_id, tok_start, tok_step, tok_count}
-    const uint32_t *row_base;
+    const uint32_t *row0;           // dense: row_base + tok_start; paged: row of the block table
     const uint8_t *keep_mask;
     const int32_t *row_index;
     uint32_t n_reqs;
@@ -66,8 +73,10 @@ struct CaptureArgs {
     uint8_t *ring;
     uint64_t cap;
     DevCtrl *ctrl;
-    HostCtrl *hctrl;
-    uint32_t slot;
+    CommitSlot *cslot;              // this launch's commit slot (device memory)
+    uint64_t tail_floor;            // the host's view of the tail when the launch was issued
+    uint32_t simple;                // no keep mask and every request contributes exactly one row
+    uint32_t upr_shift;             // log2(units_per_row) if that is a power of two, else 32
     uint32_t drop_newest;
     uint32_t table_in_lds;
     uint32_t lds_bytes;
@@ -77,8 +86,9 @@ struct CaptureArgs {
 hipError_t launch_capture(const CaptureArgs &a, uint32_t grid, bool vec16, hipStream_t s);
 hipError_t launch_upload(uint32_t *dst, const uint32_t *words, uint32_t n_words, hipStream_t s);
 hipError_t launch_set_tail(DevCtrl *ctrl, uint64_t tail, hipStream_t s);
+hipError_t launch_fetch_slot(const CommitSlot *src, CommitSlot *dst_host, hipStream_t s);
 hipError_t launch_drain_kernel(const uint8_t *ring, uint64_t cap, uint8_t *host_ring, uint64_t host_cap,
-                               uint64_t from, uint64_t nbytes, DevCtrl *ctrl, uint32_t grid, hipStream_t s);
+                               uint64_t from, uint64_t nbytes, uint32_t grid, hipStream_t s);
 uint32_t capture_lds_bytes(uint32_t n_reqs, bool index_mode, bool table_in_lds);
 
 }  // namespace dmi

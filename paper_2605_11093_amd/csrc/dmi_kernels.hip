@@ -12,10 +12,17 @@
 //     displace the model's working set from the 4 MB per-XCD L2);
 //   * downcasts and fp32 row summaries happen in the same pass, summaries by
 //     wavefront shuffles (no matrix cores: nothing here is a contraction);
-//   * the record's place in the ring comes from a device-resident head that the
-//     last-finishing workgroup advances; under drop-newest all workgroups agree on
-//     one tail value through a compare-and-swap, with no spinning;
-//   * the last workgroup then writes the commit word into pinned host memory.
+//   * the record's place in the ring comes from a device-resident head, and the
+//     drop-newest decision from a device-resident tail, both double buffered by
+//     launch parity: every workgroup reads the same values with no atomic and no
+//     workgroup has to be "the last one" (a compare-and-swap on one word from a
+//     thousand workgroups measured 7 us here);
+//   * there is no fence and no completion counter in the kernel: on this GPU a
+//     device-scope fence writes back a whole L2, once per wavefront that issues it
+//     (measured: 19 us for a 64-workgroup capture, 300 us for 2048 workgroups).
+//     Workgroup 0 writes where the head stands into this launch's commit slot in
+//     device memory, and the host fetches a slot only behind an event recorded after
+//     the launch (the kernel-end release makes payload and slot visible).
 #include "dmi_internal.h"
 
 #include <hip/hip_fp16.h>
@@ -237,6 +244,14 @@ struct RowRef {
     bool ok;
 };
 
+// Optional phase timestamps (development builds with -DDMI_TRACE only).
+#ifdef DMI_TRACE
+__device__ uint64_t g_trace[256 * 8];
+#define DMI_STAMP(k) do { if (tid == 0 && blockIdx.x < 256) g_trace[blockIdx.x * 8 + (k)] = wall_clock64(); } while (0)
+#else
+#define DMI_STAMP(k) do { } while (0)
+#endif
+
 // ---------------------------------------------------------------- capture kernel
 template <int ES_IN, int VEC, int OUT, bool SUMM>
 __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
@@ -249,26 +264,37 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const uint32_t n_reqs = a.n_reqs;
     const bool index_mode = a.row_index != nullptr;
-    const LdsMap m = lds_map(n_reqs, index_mode, a.table_in_lds != 0);
+    const bool simple = a.simple != 0;          // no keep mask and one row per request
+    const LdsMap m = lds_map(simple ? 0u : n_reqs, index_mode, a.table_in_lds != 0);
     uint32_t *pref = lds + m.pref, *btot = lds + m.btot;
     uint32_t *pref_all = lds + m.pref_all, *btot_all = lds + m.btot_all;
     uint4 *ltab = reinterpret_cast<uint4 *>(lds + m.tab);
     uint32_t *lrb = lds + m.rb;
     const uint32_t nb = (n_reqs + 63u) / 64u;
+    const uint32_t par = (uint32_t)a.seq & 1u;
 
-    // -- control words: one lane fetches the head (and, under drop-newest, the tail the
-    //    whole launch agrees on) while the others start on the request table
-    if (tid == 0) {
-        const uint64_t h = ld_agent(&a.ctrl->head);
-        uint64_t t = 0;
+    DMI_STAMP(0);
+    // -- control words: lane 0 of the last wavefront fetches the head (under drop-newest
+    //    also the tail, in workgroup 0 also the running counters) while the first
+    //    wavefronts start on the request table.  All these loads are in flight together:
+    //    every dependent trip to memory costs most of a microsecond, and a small capture
+    //    is made of little else.  Head and tail are double buffered by launch parity:
+    //    this launch reads what the previous one left and writes the other copy, so the
+    //    values are the same for every workgroup with no atomic and no waiting.
+    constexpr uint32_t kCtlTid = kThreads - 64u;
+    uint64_t cnt_cap[3] = {0, 0, 0}, cnt_drop[3] = {0, 0, 0}, tail_now = 0;
+    if (tid == kCtlTid) {
+        const DevCtrl *c = a.ctrl;
+        const uint64_t h = c->head[par];
+        uint64_t t = a.tail_floor;
         if (a.drop_newest) {
-            // every workgroup proposes the tail it read; the first proposal wins and all use it
-            t = ld_agent(&a.ctrl->tail);
-            uint64_t expected = kUnset;
-            if (!__hip_atomic_compare_exchange_strong(&a.ctrl->tail_seen[a.slot], &expected, t,
-                                                      __ATOMIC_RELAXED, __ATOMIC_RELAXED,
-                                                      __HIP_MEMORY_SCOPE_AGENT))
-                t = expected;
+            const uint64_t tp = c->tail_for[par];
+            t = tp > t ? tp : t;
+        }
+        if (blockIdx.x == 0) {
+            cnt_cap[0] = c->captured_records; cnt_cap[1] = c->captured_rows; cnt_cap[2] = c->captured_bytes;
+            cnt_drop[0] = c->dropped_records; cnt_drop[1] = c->dropped_rows; cnt_drop[2] = c->dropped_bytes;
+            tail_now = ld_agent(&c->tail);
         }
         const uint64_t base = h % a.cap;
         lds[m.bcast + 4] = (uint32_t)base;
@@ -279,65 +305,69 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
         lds[m.bcast + 3] = (uint32_t)(t >> 32);
     }
     if (tid < 8) lds[m.heads + tid] = a.heads_sel[tid];
+    DMI_STAMP(1);
 
-    // -- per-request kept row counts -> exclusive prefix sums (wavefront shuffle scans)
-    for (uint32_t b = wave; b < nb; b += kThreads / 64u) {
-        const uint32_t r = b * 64u + lane;
-        uint32_t cnt = 0, cnt_all = 0;
-        if (r < n_reqs) {
-            uint4 e = a.req_table[r];
-            cnt_all = e.w;
-            const bool keep = a.keep_mask ? a.keep_mask[r] != 0 : true;
-            cnt = keep ? cnt_all : 0u;
-            if (a.table_in_lds) {
-                e.w = cnt;
-                ltab[r] = e;
-                lrb[r] = a.row_base[r];
+    if (!simple) {
+        // -- per-request kept row counts -> exclusive prefix sums (wavefront shuffle scans)
+        for (uint32_t b = wave; b < nb; b += kThreads / 64u) {
+            const uint32_t r = b * 64u + lane;
+            uint32_t cnt = 0, cnt_all = 0;
+            if (r < n_reqs) {
+                uint4 e = a.req_table[r];
+                cnt_all = e.w;
+                const bool keep = a.keep_mask ? a.keep_mask[r] != 0 : true;
+                cnt = keep ? cnt_all : 0u;
+                if (a.table_in_lds) {
+                    e.w = cnt;
+                    ltab[r] = e;
+                    lrb[r] = a.row0[r];
+                }
             }
-        }
-        const uint32_t inc = wave_incl_scan(cnt, lane);
-        if (r < n_reqs) pref[r] = inc - cnt;
-        if (lane == 63u) btot[b] = inc;
-        if (index_mode) {
-            const uint32_t inc_all = wave_incl_scan(cnt_all, lane);
-            if (r < n_reqs) pref_all[r] = inc_all - cnt_all;
-            if (lane == 63u) btot_all[b] = inc_all;
-        }
-    }
-    __syncthreads();
-    if (wave == 0) {
-        uint32_t carry = 0, carry_all = 0;
-        for (uint32_t b0 = 0; b0 < nb; b0 += 64u) {
-            const uint32_t b = b0 + lane;
-            const uint32_t v = b < nb ? btot[b] : 0u;
-            const uint32_t inc = wave_incl_scan(v, lane);
-            if (b < nb) btot[b] = carry + inc - v;
-            carry += __shfl(inc, 63, 64);
+            const uint32_t inc = wave_incl_scan(cnt, lane);
+            if (r < n_reqs) pref[r] = inc - cnt;
+            if (lane == 63u) btot[b] = inc;
             if (index_mode) {
-                const uint32_t va = b < nb ? btot_all[b] : 0u;
-                const uint32_t ia = wave_incl_scan(va, lane);
-                if (b < nb) btot_all[b] = carry_all + ia - va;
-                carry_all += __shfl(ia, 63, 64);
+                const uint32_t inc_all = wave_incl_scan(cnt_all, lane);
+                if (r < n_reqs) pref_all[r] = inc_all - cnt_all;
+                if (lane == 63u) btot_all[b] = inc_all;
             }
         }
-        if (lane == 0) {
-            btot[nb] = carry;
-            if (index_mode) btot_all[nb] = carry_all;
+        __syncthreads();
+        if (wave == 0) {
+            uint32_t carry = 0, carry_all = 0;
+            for (uint32_t b0 = 0; b0 < nb; b0 += 64u) {
+                const uint32_t b = b0 + lane;
+                const uint32_t v = b < nb ? btot[b] : 0u;
+                const uint32_t inc = wave_incl_scan(v, lane);
+                if (b < nb) btot[b] = carry + inc - v;
+                carry += __shfl(inc, 63, 64);
+                if (index_mode) {
+                    const uint32_t va = b < nb ? btot_all[b] : 0u;
+                    const uint32_t ia = wave_incl_scan(va, lane);
+                    if (b < nb) btot_all[b] = carry_all + ia - va;
+                    carry_all += __shfl(ia, 63, 64);
+                }
+            }
+            if (lane == 0) {
+                btot[nb] = carry;
+                if (index_mode) btot_all[nb] = carry_all;
+            }
         }
-    }
-    __syncthreads();
-    for (uint32_t r = tid; r < n_reqs; r += kThreads) {
-        pref[r] += btot[r >> 6];
-        if (index_mode) pref_all[r] += btot_all[r >> 6];
-    }
-    if (tid == 0) {
-        pref[n_reqs] = btot[nb];
-        if (index_mode) pref_all[n_reqs] = btot_all[nb];
+        __syncthreads();
+        for (uint32_t r = tid; r < n_reqs; r += kThreads) {
+            pref[r] += btot[r >> 6];
+            if (index_mode) pref_all[r] += btot_all[r >> 6];
+        }
+        if (tid == 0) {
+            pref[n_reqs] = btot[nb];
+            if (index_mode) pref_all[n_reqs] = btot_all[nb];
+        }
     }
     __syncthreads();
 
+    DMI_STAMP(2);
     // -- record geometry
-    const uint32_t n_rows = pref[n_reqs];
+    const uint32_t n_rows = simple ? n_reqs : pref[n_reqs];
     const uint32_t es_out = OUT == OUT_NONE ? 0u : OUT == OUT_FP8 ? 1u : (uint32_t)ES_IN;
     const uint64_t table_bytes = ((uint64_t)n_reqs * 16u + 63u) & ~63ull;
     const uint64_t payload_bytes = (uint64_t)n_rows * a.row_elems * es_out;
@@ -354,6 +384,34 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
         dropped = head - tail + record_bytes > a.cap;
     }
 
+    // ---- publish: workgroup 0 leaves head, tail and counters for the next launch and fills
+    //      this launch's commit slot, early, so that it overlaps the copy.  Everything here
+    //      is device memory; it becomes visible to the next launch and to the copy that
+    //      fetches the slot with the kernel-end release.
+    if (blockIdx.x == 0 && tid == kCtlTid) {
+        DevCtrl *c = a.ctrl;
+        const uint64_t new_head = dropped ? head : head + record_bytes;
+        if (dropped) {
+            cnt_drop[0] += 1; cnt_drop[1] += n_rows; cnt_drop[2] += record_bytes;
+            c->dropped_records = cnt_drop[0]; c->dropped_rows = cnt_drop[1]; c->dropped_bytes = cnt_drop[2];
+            c->point_drops[a.point_id & 4095u] += 1;
+        } else {
+            cnt_cap[0] += 1; cnt_cap[1] += n_rows; cnt_cap[2] += record_bytes;
+            c->captured_records = cnt_cap[0]; c->captured_rows = cnt_cap[1]; c->captured_bytes = cnt_cap[2];
+        }
+        c->head[par ^ 1u] = new_head;
+        c->tail_for[par ^ 1u] = tail_now;
+        CommitSlot *h = a.cslot;
+        h->head = new_head;
+        h->captured_records = cnt_cap[0];
+        h->captured_rows = cnt_cap[1];
+        h->captured_bytes = cnt_cap[2];
+        h->dropped_records = cnt_drop[0];
+        h->dropped_rows = cnt_drop[1];
+        h->dropped_bytes = cnt_drop[2];
+        h->seq_plus1 = a.seq + 1u;
+    }
+
     RingW w;
     w.ring = a.ring;
     w.cap = a.cap;
@@ -362,28 +420,38 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
     // row g -> request r (largest r with pref[r] <= g; requests with no rows are skipped
     // because their successor shares the same prefix) -> source location
     auto locate = [&](uint32_t g) -> RowRef {
-        uint32_t lo = 0, hi = n_reqs;
-        while (hi - lo > 1u) {
-            const uint32_t mid = (lo + hi) >> 1;
-            if (pref[mid] <= g) lo = mid; else hi = mid;
+        uint32_t r = g, j = 0;
+        if (!simple) {
+            uint32_t lo = 0, hi = n_reqs;
+            while (hi - lo > 1u) {
+                const uint32_t mid = (lo + hi) >> 1;
+                if (pref[mid] <= g) lo = mid; else hi = mid;
+            }
+            r = lo;
+            j = g - pref[r];
         }
-        const uint32_t r = lo, j = g - pref[r];
-        uint4 e;
-        uint32_t rbase;
-        if (a.table_in_lds) { e = ltab[r]; rbase = lrb[r]; }
-        else { e = a.req_table[r]; rbase = a.row_base[r]; }
         RowRef ref;
         if (!a.paged) {
             int64_t row;
-            if (index_mode) row = (int64_t)a.row_index[pref_all[r] + j];
-            else row = (int64_t)rbase + (int64_t)e.y + (int64_t)j * (int64_t)e.z;
+            if (index_mode) {
+                row = (int64_t)a.row_index[simple ? g : pref_all[r] + j];
+            } else if (a.table_in_lds) {
+                row = (int64_t)lrb[r] + (int64_t)j * (int64_t)ltab[r].z;
+            } else {
+                row = (int64_t)a.row0[r];
+                if (j) row += (int64_t)j * (int64_t)a.req_table[r].z;
+            }
             ref.ok = row >= 0 && row < a.n_src_rows;
             ref.base = a.src + (ref.ok ? row : 0) * a.row_stride_b;
         } else {
+            uint4 e;
+            uint32_t seq_row;
+            if (a.table_in_lds) { e = ltab[r]; seq_row = lrb[r]; }
+            else { e = a.req_table[r]; seq_row = a.row0[r]; }
             const uint32_t t = e.y + j * e.z;               // host keeps token positions below 2^31
             const uint32_t lb = t / a.block_size;
             const uint32_t slot = t - lb * a.block_size;
-            const int64_t blk = (int64_t)a.block_table[(int64_t)rbase * a.bt_stride + (int64_t)lb];
+            const int64_t blk = (int64_t)a.block_table[(int64_t)seq_row * a.bt_stride + (int64_t)lb];
             ref.ok = blk >= 0 && blk < a.n_src_rows;
             ref.base = a.src + (ref.ok ? blk : 0) * a.block_stride_b + (int64_t)slot * a.slot_stride_b;
         }
@@ -402,7 +470,8 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
     };
 
     if (!dropped) {
-        // ---- header, request table and all pad bytes: workgroup 0
+        // ---- header, request table and all pad bytes: workgroup 0.  The header is put
+        //      together in LDS and leaves as four 16-byte stores.
         if (blockIdx.x == 0) {
             if (tid == 0) {
                 uint32_t *h = lds + m.hdr;
@@ -428,7 +497,7 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
                 if (r < n_reqs) {
                     uint4 e;
                     if (a.table_in_lds) e = ltab[r];
-                    else { e = a.req_table[r]; e.w = pref[r + 1] - pref[r]; }
+                    else { e = a.req_table[r]; if (!simple) e.w = pref[r + 1] - pref[r]; }
                     v.x = e.x; v.y = e.y; v.z = e.z; v.w = e.w;
                 }
                 ring_store<u32x4>(w, 64u + 16ull * r, v);
@@ -444,6 +513,7 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
             }
         }
 
+        DMI_STAMP(3);
         if constexpr (!SUMM) {
             // ---- flat copy: the n_rows x units_per_row units are dealt to lanes in order, so
             //      stores are fully coalesced whatever the row length; 4 loads in flight per lane
@@ -451,18 +521,18 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
                 constexpr uint32_t U = 4;
                 const uint64_t total = (uint64_t)n_rows * a.units_per_row;
                 Accum dummy = {0.f, 0.f, 0.f};
-                for (uint64_t t0 = (uint64_t)blockIdx.x * U * kThreads; t0 < total;
+                for (uint64_t t0 = (uint64_t)blockIdx.x * kThreads; t0 < total;
                      t0 += (uint64_t)gridDim.x * U * kThreads) {
                     unit_t v[U];
                     bool live[U];
 #pragma unroll
                     for (uint32_t k = 0; k < U; k++) {
-                        const uint64_t u = t0 + (uint64_t)k * kThreads + tid;
+                        const uint64_t u = t0 + (uint64_t)k * gridDim.x * kThreads + tid;
                         live[k] = u < total;
                         v[k] = unit_t{};
                         if (live[k]) {
                             const uint32_t u32 = (uint32_t)u;       // host keeps total below 2^32
-                            const uint32_t g = u32 / a.units_per_row;
+                            const uint32_t g = a.upr_shift < 32u ? u32 >> a.upr_shift : u32 / a.units_per_row;
                             const uint32_t c = u32 - g * a.units_per_row;
                             const RowRef ref = locate(g);
                             if (!ref.ok && c == 0)
@@ -472,7 +542,7 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
                     }
 #pragma unroll
                     for (uint32_t k = 0; k < U; k++) {
-                        const uint64_t u = t0 + (uint64_t)k * kThreads + tid;
+                        const uint64_t u = t0 + (uint64_t)k * gridDim.x * kThreads + tid;
                         if (live[k])
                             emit_unit<ES_IN, VEC, OUT, false>(w, off_payload + u * NB_OUT, v[k],
                                                               a.src_dtype, dummy);
@@ -480,7 +550,9 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
                 }
             }
         } else {
-            // ---- row-wise pass with summaries: a workgroup (or a wavefront) per row
+            // ---- row-wise pass with summaries: a workgroup (or a wavefront) per row,
+            //      4 loads in flight per lane
+            constexpr uint32_t U = 4;
             const uint32_t rpw = a.rows_per_wg;
             const uint32_t gsz = kThreads / rpw;            // lanes per row: 256 or 64
             const uint32_t sub = tid / gsz, l = tid - sub * gsz;
@@ -493,10 +565,21 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
                     const RowRef ref = locate(g);
                     if (!ref.ok && l == 0) atomicAdd((unsigned long long *)&a.ctrl->bad_rows, 1ull);
                     const uint64_t row_off = off_payload + (uint64_t)g * a.units_per_row * NB_OUT;
-                    for (uint32_t c = l; c < a.units_per_row; c += gsz) {
-                        const unit_t v = load_unit(ref, c);
-                        emit_unit<ES_IN, VEC, OUT, true>(w, row_off + (uint64_t)c * NB_OUT, v,
-                                                         a.src_dtype, acc);
+                    for (uint32_t c0 = l; c0 < a.units_per_row; c0 += gsz * U) {
+                        unit_t v[U];
+#pragma unroll
+                        for (uint32_t k = 0; k < U; k++) {
+                            const uint32_t c = c0 + k * gsz;
+                            v[k] = unit_t{};
+                            if (c < a.units_per_row) v[k] = load_unit(ref, c);
+                        }
+#pragma unroll
+                        for (uint32_t k = 0; k < U; k++) {
+                            const uint32_t c = c0 + k * gsz;
+                            if (c < a.units_per_row)
+                                emit_unit<ES_IN, VEC, OUT, true>(w, row_off + (uint64_t)c * NB_OUT, v[k],
+                                                                 a.src_dtype, acc);
+                        }
                     }
                 }
                 acc.ss = wave_sum(acc.ss);
@@ -519,45 +602,15 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
             }
         }
     }
-
-    // ---- retire: the last workgroup to finish advances the head and publishes the record
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-        const uint32_t prev = __hip_atomic_fetch_add(&a.ctrl->done[a.slot], 1u, __ATOMIC_ACQ_REL,
-                                                     __HIP_MEMORY_SCOPE_AGENT);
-        if (prev == gridDim.x - 1u) {
-            DevCtrl *c = a.ctrl;
-            const uint64_t new_head = dropped ? head : head + record_bytes;
-            if (dropped) {
-                c->dropped_records += 1;
-                c->dropped_rows += n_rows;
-                c->dropped_bytes += record_bytes;
-                if (a.point_id < 4096u) c->point_drops[a.point_id] += 1;
-            } else {
-                c->captured_records += 1;
-                c->captured_rows += n_rows;
-                c->captured_bytes += record_bytes;
-            }
-            __hip_atomic_store(&c->done[a.slot], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            st_agent(&c->tail_seen[a.slot], kUnset);
-            st_agent(&c->head, new_head);
-            HostCtrl *h = a.hctrl;
-            h->captured_records = c->captured_records;
-            h->captured_rows = c->captured_rows;
-            h->captured_bytes = c->captured_bytes;
-            h->dropped_records = c->dropped_records;
-            h->dropped_rows = c->dropped_rows;
-            h->dropped_bytes = c->dropped_bytes;
-            h->bad_rows = __hip_atomic_load(&c->bad_rows, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __threadfence_system();
-            __hip_atomic_store(const_cast<uint64_t *>(&h->committed), new_head, __ATOMIC_RELEASE,
-                               __HIP_MEMORY_SCOPE_SYSTEM);
-            __hip_atomic_store(const_cast<uint64_t *>(&h->last_seq_plus1), a.seq + 1u, __ATOMIC_RELEASE,
-                               __HIP_MEMORY_SCOPE_SYSTEM);
-        }
-    }
+    DMI_STAMP(4);
 }
+
+#ifdef DMI_TRACE
+extern "C" int dmi_trace_read(uint64_t *out)
+{
+    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_trace), sizeof(uint64_t) * 256 * 8);
+}
+#endif
 
 // ---------------------------------------------------------------- small kernels
 struct UploadChunk {
@@ -574,11 +627,21 @@ __global__ void set_tail_kernel(DevCtrl *ctrl, uint64_t tail)
     st_agent(&ctrl->tail, tail);
 }
 
+// Fetch one commit slot into pinned host memory (runs on the library's control stream
+// behind an event of the producer's stream, so the capture kernel itself never writes
+// across PCIe: such a store is acknowledged only after some 4-5 microseconds, and a
+// kernel cannot retire before its stores have been).
+__global__ void fetch_slot_kernel(const CommitSlot *src, CommitSlot *dst_host)
+{
+    const uint32_t i = threadIdx.x;
+    if (i < sizeof(CommitSlot) / 8u)
+        reinterpret_cast<volatile uint64_t *>(dst_host)[i] = reinterpret_cast<const uint64_t *>(src)[i];
+}
+
 // Drain by kernel: 16-byte loads from the device ring, 16-byte stores into the pinned
-// host ring (posted PCIe writes), then the tail is advanced by the last workgroup.
+// host ring (posted PCIe writes).  The tail is advanced by set_tail_kernel behind it.
 __global__ void __launch_bounds__(kThreads) drain_kernel(const uint8_t *ring, uint64_t cap, uint8_t *host,
-                                                         uint64_t host_cap, uint64_t from, uint64_t nbytes,
-                                                         DevCtrl *ctrl)
+                                                         uint64_t host_cap, uint64_t from, uint64_t nbytes)
 {
     const uint64_t n_units = nbytes / 16u;
     const uint64_t s0 = from % cap, d0 = from % host_cap;
@@ -589,16 +652,6 @@ __global__ void __launch_bounds__(kThreads) drain_kernel(const uint8_t *ring, ui
         if (d >= host_cap) d -= host_cap;
         const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(ring + s));
         __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(host + d));
-    }
-    __threadfence_system();
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const uint32_t prev = __hip_atomic_fetch_add(&ctrl->drain_done, 1u, __ATOMIC_ACQ_REL,
-                                                     __HIP_MEMORY_SCOPE_AGENT);
-        if (prev == gridDim.x - 1u) {
-            __hip_atomic_store(&ctrl->drain_done, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            st_agent(&ctrl->tail, from + nbytes);
-        }
     }
 }
 
@@ -647,6 +700,12 @@ hipError_t launch_upload(uint32_t *dst, const uint32_t *words, uint32_t n_words,
     return hipSuccess;
 }
 
+hipError_t launch_fetch_slot(const CommitSlot *src, CommitSlot *dst_host, hipStream_t s)
+{
+    hipLaunchKernelGGL(fetch_slot_kernel, dim3(1), dim3(64), 0, s, src, dst_host);
+    return hipGetLastError();
+}
+
 hipError_t launch_set_tail(DevCtrl *ctrl, uint64_t tail, hipStream_t s)
 {
     hipLaunchKernelGGL(set_tail_kernel, dim3(1), dim3(1), 0, s, ctrl, tail);
@@ -654,10 +713,10 @@ hipError_t launch_set_tail(DevCtrl *ctrl, uint64_t tail, hipStream_t s)
 }
 
 hipError_t launch_drain_kernel(const uint8_t *ring, uint64_t cap, uint8_t *host_ring, uint64_t host_cap,
-                               uint64_t from, uint64_t nbytes, DevCtrl *ctrl, uint32_t grid, hipStream_t s)
+                               uint64_t from, uint64_t nbytes, uint32_t grid, hipStream_t s)
 {
     hipLaunchKernelGGL(drain_kernel, dim3(grid), dim3(kThreads), 0, s, ring, cap, host_ring, host_cap, from,
-                       nbytes, ctrl);
+                       nbytes);
     return hipGetLastError();
 }
 

@@ -6,6 +6,7 @@ stream handle.
 """
 from __future__ import annotations
 
+import time
 from dataclasses import dataclass, field
 from typing import Callable, List, Optional
 
@@ -73,7 +74,7 @@ def consume(ring: B.Ring, run: GpuRun, collect: bool, release: bool,
 def run_workload_gpu(wl, *, drain_every: int = 1, release: bool = True, collect: bool = True,
                      flags: int = 0, device_ring_bytes=None, host_ring_bytes=None,
                      max_steps=None, lockstep: bool = True, on_record=None,
-                     block_timeout_ms: int = 0, poison: Optional[int] = None,
+                     block_timeout_ms: int = 1, poison: Optional[int] = None,
                      ring: Optional[B.Ring] = None) -> GpuRun:
     """Lockstep schedule (the one the oracle's model follows): a step's observes,
     then every `drain_every` steps a flush-drain followed by poll + release.
@@ -95,22 +96,33 @@ def run_workload_gpu(wl, *, drain_every: int = 1, release: bool = True, collect:
                 break
             for c in calls:
                 rc = observe_call(ring, c, s.cuda_stream, keep_alive, allow=(B.ERR_AGAIN,))
-                if rc == B.ERR_AGAIN:
-                    # completeness policy, host ring full: consume, then try once more
+                tries = 0
+                while rc == B.ERR_AGAIN:
+                    # completeness policy, no room: this thread is also the consumer, so
+                    # consume what has arrived and try again
                     consume(ring, run, collect, release, on_record)
-                    observe_call(ring, c, s.cuda_stream, keep_alive)
+                    tries += 1
+                    rc = observe_call(ring, c, s.cuda_stream, keep_alive,
+                                      allow=(B.ERR_AGAIN,) if tries < 20000 else ())
             if (step + 1) % drain_every == 0:
+                if lockstep:
+                    s.synchronize()     # every kernel of the step has committed
                 ring.drain(B.DRAIN_FLUSH if lockstep else 0, allow=(B.ERR_AGAIN,))
                 consume(ring, run, collect, release, on_record)
                 keep_alive.clear() if lockstep else None
         # tail: everything still in flight
-        for _ in range(1 << 20):
+        s.synchronize()
+        deadline = time.monotonic() + 60.0
+        while True:
+            if time.monotonic() > deadline:
+                raise RuntimeError("final drain made no progress for 60 s")
             ring.drain(B.DRAIN_FLUSH, allow=(B.ERR_AGAIN,))
             before = run.n_records
             consume(ring, run, collect, release, on_record)
-            if ring.last_drain_status == B.OK or run.n_records == before:
+            if ring.last_drain_status == B.OK:
                 break
-        s.synchronize()
+            if run.n_records == before and not release:
+                break           # host ring full and the caller keeps the records
         run.stats = ring.get_stats()
     finally:
         if own:

@@ -49,7 +49,7 @@ def test_struct_sizes_match_the_header_layout():
     assert ctypes.sizeof(B.Tensor) == 48
     assert ctypes.sizeof(B.Selection) == 32
     assert ctypes.sizeof(B.RecordViewC) == 40
-    assert ctypes.sizeof(B.StatsC) == 17 * 8
+    assert ctypes.sizeof(B.StatsC) == 18 * 8
 
 
 @pytest.mark.skipif(torch.cuda.is_available(), reason="checks the no-GPU failure path")

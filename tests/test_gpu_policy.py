@@ -73,7 +73,7 @@ def test_too_large_and_invalid_arguments(B):
 
 
 def test_block_returns_again_when_the_host_ring_is_never_released(B):
-    t = _t(8, 192)          # record = 64 + 64 + 8*384 = 3200 bytes
+    t = _t(8, 192)          # record = 64 + 128 + 8*384 = 3264 bytes; rings of 6400 hold one whole record
     ref = OracleRing(6400, 6400, POLICY_BLOCK)
     with B.Ring(6400, 6400, block_timeout_ms=30) as ring:
         s = torch.cuda.current_stream().cuda_stream
@@ -81,13 +81,21 @@ def test_block_returns_again_when_the_host_ring_is_never_released(B):
         for step in range(6):
             rcs.append(ring.observe_tensor(0, t, _reqs(8), step_id=step, stream=s, allow=(B.ERR_AGAIN,)))
             want.append(ref.observe(t.cpu(), _reqs(8), point_id=0, step_id=step, out_dtype=1))
-        assert rcs == want == [0, 0, 0, 0, B.ERR_AGAIN, B.ERR_AGAIN]
+        assert rcs == want
+        assert want == [0, 0, 0, B.ERR_AGAIN, B.ERR_AGAIN, B.ERR_AGAIN]
+        assert ring.get_stats().launched_records == ref.next_seq == 3
         v = ring.poll_host()
-        assert [x.seq for x in v] == [0, 1]
-        ring.release_host(1)
+        assert [x.seq for x in v] == ref.polled_seqs() == [0]
+        ring.release_host(0)
+        ref.release(0)
         assert ring.observe_tensor(0, t, _reqs(8), step_id=6, stream=s) == B.OK
+        assert ref.observe(t.cpu(), _reqs(8), point_id=0, step_id=6, out_dtype=1) == 0
+        torch.cuda.current_stream().synchronize()
         ring.drain(B.DRAIN_FLUSH, allow=(B.ERR_AGAIN,))
-        assert [x.seq for x in ring.poll_host()] == [2, 3]
+        ref.drain()
+        assert ring.last_drain_status == B.ERR_AGAIN and ref.drained < ref.appended
+        got = [x.seq for x in ring.poll_host()]
+        assert got == ref.polled_seqs() and got
 
 
 def test_drop_newest_lockstep_counts_and_point_drops(B):
