@@ -27,6 +27,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0           # MI355X published HBM3E bandwidth
+# HBM bytes per launch of the config-2 capture kernel, from the two rocprofv3 --pmc runs
+# summarised in profiles/capture_kernel_config2_config3mlp.md (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000,
+# factors from a plain 256 MiB copy): 0.695 MB read + 0.530 MB written.
+TRAFFIC_CONFIG2_BYTES = 1225000
 SEED_NOTE = "synthetic (seeded ~N(0,1) bf16, shapes of the paper's LLM workloads)"
 
 
@@ -63,6 +67,7 @@ def main():
     bench_lib = C.CDLL(os.path.join(ROOT, "paper_2605_11093_amd", "libdmi_bench.so"))
     bench_lib.dmi_bench_sleep.argtypes = [C.c_void_p, C.c_uint32]
     bench_lib.dmi_bench_stream_gemv.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p]
+    bench_lib.dmi_bench_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]
     stream = torch.cuda.current_stream()
     sh = stream.cuda_stream
 
@@ -84,11 +89,11 @@ def main():
     def consume(ring):
         n = 0
         while True:
-            v = ring.poll_host()
-            if not v:
+            k, views = ring.poll_host_raw()
+            if not k:
                 return n
-            n += len(v)
-            ring.release_host(v[-1].seq)
+            n += k
+            ring.release_host(views[k - 1].seq)
 
     def settle(ring):
         stream.synchronize()
@@ -135,7 +140,26 @@ def main():
     log(f"capture kernel (config 2 record, {alg_bytes} algorithmic bytes): {cap_us:.2f} us/launch "
         f"= {alg_bytes / cap_us / 1e3:.1f} GB/s")
     if args.only_capture:
+        # profiling run: add a plain copy of known size (the reference the profiler's HBM
+        # byte counters are scaled by) and one large launch (config 3 MLP point, fp8)
         ring.destroy()
+        ca = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        cb = torch.empty_like(ca)
+        for _ in range(3):
+            bench_lib.dmi_bench_copy(cb.data_ptr(), ca.data_ptr(), 256 << 20, sh)
+        stream.synchronize()
+        w3 = configs.config3_prefill(device=dev, n_steps=1, n_resid=1, n_mlp=1)
+        c = [c for c in w3.step_calls(0) if c.point_id >= 100][0]
+        rows3 = int(c.reqs[:, 3].sum())
+        r3 = B.Ring(dmi.record_bytes(32, rows3, 14336, B.DT_FP8, 0) * 6, 1 << 26, max_reqs_per_observe=256)
+        r3.set_policy(B.POLICY_DROP_NEWEST)
+        po = dmi.PreparedObserve(r3, c.point_id, c.tensor, c.reqs, out_dtype=B.DT_FP8)
+        for i in range(5):
+            observe_checked(po, i)
+        stream.synchronize()
+        log(f"large launch: config 3 MLP point, {rows3} rows x 14336, fp8: "
+            f"{rows3 * 14336 * 3} algorithmic bytes per launch; plain copy: 268435456 B read + 268435456 B written")
+        r3.destroy()
         return
 
     # ------------------------------------------------------------------ whole path, timed
@@ -363,7 +387,7 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "capture_kernel<bf16, vec16, raw, summaries> (config 2 record)",
                      "achieved": round(cap_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(cap_gbs / HBM_PEAK_GBS, 4), "us_per_launch": round(cap_us, 3),
-                     "algorithmic_bytes_per_launch": alg_bytes, "traffic": None},
+                     "algorithmic_bytes_per_launch": alg_bytes, "traffic": TRAFFIC_CONFIG2_BYTES},
         "cpu_baseline": cpu,
     }
     out.update(extra)

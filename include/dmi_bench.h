@@ -23,6 +23,11 @@ int dmi_bench_sleep(void *hip_stream, uint32_t microseconds);
  * and w 16-byte aligned. */
 int dmi_bench_stream_gemv(const void *w, uint64_t n_elems, const void *x, float *out, void *hip_stream);
 
+/* Plain device-to-device copy of n_bytes (multiple of 16, both pointers 16-byte
+ * aligned): reads n_bytes, writes n_bytes.  The known-size reference the HBM traffic
+ * counters of the profiler are scaled by. */
+int dmi_bench_copy(void *dst, const void *src, uint64_t n_bytes, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -315,6 +315,12 @@ class Ring:
         _check(lib().dmi_poll_host(self._h, self._views, m, C.byref(n)))
         return [RecordView(v.seq, v.p0 or 0, v.n0, v.p1 or 0, v.n1) for v in self._views[: n.value]]
 
+    def poll_host_raw(self, max_records: int = 256):
+        """As poll_host, without building Python objects: (n, ctypes array of views)."""
+        n = C.c_uint32()
+        _check(lib().dmi_poll_host(self._h, self._views, min(max_records, len(self._views)), C.byref(n)))
+        return n.value, self._views
+
     def release_host(self, upto_seq: int):
         _check(lib().dmi_release_host(self._h, upto_seq))
 

@@ -51,6 +51,21 @@ __global__ void __launch_bounds__(256) stream_gemv_kernel(const u32x4 *__restric
     if ((threadIdx.x & 63u) == 0) atomicAdd(&out[(blockIdx.x * 4u + (threadIdx.x >> 6)) & 4095u], acc);
 }
 
+__global__ void __launch_bounds__(256) plain_copy_kernel(u32x4 *__restrict__ dst, const u32x4 *__restrict__ src,
+                                                         uint64_t n_vec)
+{
+    const uint64_t stride = (uint64_t)gridDim.x * 256u;
+    for (uint64_t i = (uint64_t)blockIdx.x * 256u + threadIdx.x; i < n_vec; i += stride) dst[i] = src[i];
+}
+
+extern "C" int dmi_bench_copy(void *dst, const void *src, uint64_t n_bytes, void *hip_stream)
+{
+    if (!dst || !src || n_bytes % 16u || (uintptr_t)dst % 16u || (uintptr_t)src % 16u) return (int)hipErrorInvalidValue;
+    hipLaunchKernelGGL(plain_copy_kernel, dim3(2048), dim3(256), 0, (hipStream_t)hip_stream, (u32x4 *)dst,
+                       (const u32x4 *)src, n_bytes / 16u);
+    return (int)hipGetLastError();
+}
+
 extern "C" int dmi_bench_sleep(void *hip_stream, uint32_t microseconds)
 {
     hipLaunchKernelGGL(sleep_kernel, dim3(1), dim3(64), 0, (hipStream_t)hip_stream, (uint64_t)microseconds * 100u);

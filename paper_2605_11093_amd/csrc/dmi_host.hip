@@ -115,7 +115,7 @@ struct dmi_ring {
     std::atomic<void *> last_stream{nullptr};
     std::deque<std::pair<uint64_t, uint64_t>> inflight;    // (seq, upper bound of record bytes)
     uint64_t inflight_sum = 0;
-    uint64_t unprobed_launches = 0, unprobed_bytes = 0, probe_bytes = 4u << 20;
+    uint64_t unprobed_launches = 0, unprobed_bytes = 0, probe_bytes = 8u << 20;
 
     // commit discovery: events recorded behind launches ("probes"), queried in order
     std::mutex pmu;
@@ -284,11 +284,16 @@ uint64_t head_upper_bound(dmi_ring *r)
 dmi_status_t wait_for_room(dmi_ring *r, uint64_t ub)
 {
     uint64_t t0 = 0;
+    dmi_status_t st;
     for (;;) {
-        dmi_status_t st = advance_commits(r, false);
-        if (st != DMI_OK) return st;
-        const uint64_t head_ub = head_upper_bound(r);
-        const uint64_t tail = r->drain_done.load(std::memory_order_acquire);
+        // what the drain side has confirmed so far is enough to decide in the common case
+        // (an older view only makes the bound more cautious)
+        uint64_t head_ub = head_upper_bound(r);
+        uint64_t tail = r->drain_done.load(std::memory_order_acquire);
+        if (head_ub - tail + ub <= r->dev_cap) break;
+        if ((st = advance_commits(r, false)) != DMI_OK) return st;
+        head_ub = head_upper_bound(r);
+        tail = r->drain_done.load(std::memory_order_acquire);
         if (head_ub - tail + ub <= r->dev_cap) break;
         if (!t0) t0 = now_ns();
         uint64_t moved = 0;
@@ -318,6 +323,20 @@ dmi_status_t stage_selection(dmi_ring *r, const dmi_selection_t *sel, bool paged
                              uint32_t *slot_out)
 {
     const uint32_t n = sel->n_reqs;
+    // first source row of the request (dense; the caller has checked that it fits 32 bits),
+    // or its row of the block table (paged)
+    auto row0 = [paged](const dmi_req_sel_t &q) { return paged ? q.row_base : q.row_base + q.tok_start; };
+    for (auto &c : r->cache) {
+        if (!c.valid || c.stream != s || c.paged != paged || c.words.size() != (size_t)n * 5u) continue;
+        const uint32_t *w = c.words.data();
+        bool same = true;
+        for (uint32_t i = 0; same && i < n; i++) {
+            const dmi_req_sel_t &q = sel->reqs[i];
+            same = w[4u * i] == q.req_id && w[4u * i + 1] == q.tok_start && w[4u * i + 2] == q.tok_step &&
+                   w[4u * i + 3] == q.tok_count && w[4u * n + i] == row0(q);
+        }
+        if (same) { *slot_out = c.slot; return DMI_OK; }
+    }
     std::vector<uint32_t> words((size_t)n * 5u);
     for (uint32_t i = 0; i < n; i++) {
         const dmi_req_sel_t &q = sel->reqs[i];
@@ -325,12 +344,7 @@ dmi_status_t stage_selection(dmi_ring *r, const dmi_selection_t *sel, bool paged
         words[4u * i + 1] = q.tok_start;
         words[4u * i + 2] = q.tok_step;
         words[4u * i + 3] = q.tok_count;
-        // first source row of the request (dense; the caller has checked that it fits 32 bits),
-        // or its row of the block table (paged)
-        words[4u * n + i] = paged ? q.row_base : q.row_base + q.tok_start;
-    }
-    for (auto &c : r->cache) {
-        if (c.valid && c.stream == s && c.paged == paged && c.words == words) { *slot_out = c.slot; return DMI_OK; }
+        words[4u * n + i] = row0(q);
     }
     const uint32_t slot = r->next_slab++ % kSlabSlots;
     for (auto &c : r->cache) if (c.valid && c.slot == slot) c.valid = false;
@@ -370,8 +384,6 @@ dmi_status_t observe_common(dmi_ring *r, uint32_t point_id, const dmi_selection_
         dmi_status_t st = wait_for_room(r, ub);
         if (st != DMI_OK) return st;
     } else {
-        dmi_status_t st = advance_commits(r, false);
-        if (st != DMI_OK) return st;
         head_upper_bound(r);    // keeps the in-flight list short
     }
     // a launch's host slot is reused kCommitSlots launches later: keep fewer than that unconfirmed
@@ -416,13 +428,17 @@ dmi_status_t observe_common(dmi_ring *r, uint32_t point_id, const dmi_selection_
     a.cslot = &r->dctrl->slots[seq % kCommitSlots];
     a.tail_floor = r->drain_done.load(std::memory_order_acquire);
     a.simple = simple ? 1u : 0u;
-    a.upr_shift = (upr & (upr - 1u)) == 0 ? (uint32_t)__builtin_ctzll(upr) : 32u;
+    auto shift_of = [](uint64_t v) { return v && (v & (v - 1u)) == 0 ? (uint32_t)__builtin_ctzll(v) : 32u; };
+    a.upr_shift = shift_of(upr);
+    a.bs_shift = shift_of(a.block_size);
+    a.seg_shift = shift_of(a.seg_units);
     a.drop_newest = mode == DMI_POLICY_DROP_NEWEST ? 1u : 0u;
     a.table_in_lds = tab_lds ? 1u : 0u;
     a.lds_bytes = capture_lds_bytes(simple ? 0u : sel->n_reqs, index_mode, tab_lds);
 
     uint64_t groups;
     if (xf->summary_mask) groups = (listed + a.rows_per_wg - 1u) / a.rows_per_wg;
+    else if (upr >= kThreads) groups = listed * ((upr + 4u * kThreads - 1u) / (4u * kThreads));
     else groups = (listed * upr + kThreads - 1u) / kThreads;
     uint32_t grid = groups < 1u ? 1u : groups > kMaxGrid ? kMaxGrid : (uint32_t)groups;
 
@@ -577,6 +593,8 @@ dmi_status_t dmi_ring_create(const dmi_ring_config_t *cfg, dmi_ring_t **out)
         return bail(e, "hipHostMalloc(host ring)");
     if ((e = hipHostGetDevicePointer((void **)&r->host_ring_dev, r->host_ring, 0)) != hipSuccess)
         return bail(e, "hipHostGetDevicePointer(host ring)");
+    // touch every page now: the consumer's first read of a page should not pay for a fault
+    memset(r->host_ring, 0, r->host_cap);
     if ((e = hipHostMalloc((void **)&r->hslots, sizeof(CommitSlot) * kCommitSlots,
                            hipHostMallocMapped | hipHostMallocCoherent)) != hipSuccess)
         return bail(e, "hipHostMalloc(commit slots)");

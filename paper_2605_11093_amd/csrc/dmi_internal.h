@@ -77,6 +77,7 @@ struct CaptureArgs {
     uint64_t tail_floor;            // the host's view of the tail when the launch was issued
     uint32_t simple;                // no keep mask and every request contributes exactly one row
     uint32_t upr_shift;             // log2(units_per_row) if that is a power of two, else 32
+    uint32_t bs_shift, seg_shift;   // same for block_size and seg_units
     uint32_t drop_newest;
     uint32_t table_in_lds;
     uint32_t lds_bytes;

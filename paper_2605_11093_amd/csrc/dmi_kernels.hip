@@ -71,7 +71,8 @@ __device__ __forceinline__ float wave_max(float v)
 
 // ---------------------------------------------------------------- conversions
 // bf16 -> fp8 E4M3FN (OCP: bias 7, max 448, no inf, S.1111.111 NaN), round to
-// nearest even, saturating.  Integer arithmetic on the bf16 bit pattern.
+// nearest even, saturating.  Integer arithmetic on the bf16 bit pattern; used on the
+// element-wise path (rows that cannot be moved as 16-byte vectors).
 __device__ __forceinline__ uint32_t bf16_to_fp8(uint32_t b)
 {
     const uint32_t sign = (b >> 8) & 0x80u;
@@ -92,6 +93,35 @@ __device__ __forceinline__ uint32_t bf16_to_fp8(uint32_t b)
     }
     if (a > 0x7F80u) code = 0x7Fu;
     return sign | code;
+}
+
+// Two bf16 (one 32-bit word) -> two fp8 E4M3FN codes in the low or high half of `acc`.
+// gfx950's packed convert rounds to nearest even into the OCP format, subnormals
+// included, but does not saturate (values that round beyond 448, and infinities, come
+// out as NaN) and drops a NaN's sign; so magnitudes are clamped to 448 first with a
+// packed 16-bit minimum, and words holding a NaN are patched afterwards.
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef short s16x2_t __attribute__((ext_vector_type(2)));
+typedef unsigned short u16x2_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ s16x2_t bf16x2_to_fp8x2(uint32_t w, s16x2_t acc, bool hi)
+{
+    const uint32_t mag = w & 0x7FFF7FFFu;
+    const u16x2_t lim = {0x43E0u, 0x43E0u};                                   // 448.0
+    const u16x2_t cl = __builtin_elementwise_min(__builtin_bit_cast(u16x2_t, mag), lim);
+    const uint32_t x = __builtin_bit_cast(uint32_t, cl) | (w & 0x80008000u);
+    const bf16x2_t v = __builtin_bit_cast(bf16x2_t, x);
+    acc = hi ? __builtin_amdgcn_cvt_scalef32_pk_fp8_bf16(acc, v, 1.0f, true)
+             : __builtin_amdgcn_cvt_scalef32_pk_fp8_bf16(acc, v, 1.0f, false);
+    const u16x2_t inf = {0x7F80u, 0x7F80u};
+    const u16x2_t over = __builtin_elementwise_sub_sat(__builtin_bit_cast(u16x2_t, mag), inf);
+    if (__builtin_bit_cast(uint32_t, over) != 0u) {                           // a NaN: sign | 0x7F
+        uint32_t pair = (uint32_t)(unsigned short)(hi ? acc.y : acc.x);
+        if (over.x) pair = (pair & 0xFF00u) | ((w >> 8) & 0x80u) | 0x7Fu;
+        if (over.y) pair = (pair & 0x00FFu) | (((w >> 24) & 0x80u) << 8) | 0x7F00u;
+        if (hi) acc.y = (short)pair; else acc.x = (short)pair;
+    }
+    return acc;
 }
 
 // bf16 -> fp16: exact widening to f32, then the hardware's round-to-nearest-even
@@ -171,15 +201,14 @@ __device__ __forceinline__ void emit_unit(const RingW &w, uint64_t out_off,
             o.x = ow[0]; o.y = ow[1]; o.z = ow[2]; o.w = ow[3];
             ring_store<u32x4>(w, out_off, o);
         } else if constexpr (OUT == OUT_FP8) {
-            uint32_t c[8];
-#pragma unroll
-            for (int k = 0; k < 4; k++) {
-                c[2 * k] = bf16_to_fp8(wd[k] & 0xFFFFu);
-                c[2 * k + 1] = bf16_to_fp8(wd[k] >> 16);
-            }
+            s16x2_t lo = {0, 0}, hi = {0, 0};
+            lo = bf16x2_to_fp8x2(wd[0], lo, false);
+            lo = bf16x2_to_fp8x2(wd[1], lo, true);
+            hi = bf16x2_to_fp8x2(wd[2], hi, false);
+            hi = bf16x2_to_fp8x2(wd[3], hi, true);
             u32x2 o;
-            o.x = c[0] | (c[1] << 8) | (c[2] << 16) | (c[3] << 24);
-            o.y = c[4] | (c[5] << 8) | (c[6] << 16) | (c[7] << 24);
+            o.x = __builtin_bit_cast(uint32_t, lo);
+            o.y = __builtin_bit_cast(uint32_t, hi);
             ring_store<u32x2>(w, out_off, o);
         }
     } else if constexpr (ES_IN == 4 && VEC == 4) {
@@ -449,7 +478,7 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
             if (a.table_in_lds) { e = ltab[r]; seq_row = lrb[r]; }
             else { e = a.req_table[r]; seq_row = a.row0[r]; }
             const uint32_t t = e.y + j * e.z;               // host keeps token positions below 2^31
-            const uint32_t lb = t / a.block_size;
+            const uint32_t lb = a.bs_shift < 32u ? t >> a.bs_shift : t / a.block_size;
             const uint32_t slot = t - lb * a.block_size;
             const int64_t blk = (int64_t)a.block_table[(int64_t)seq_row * a.bt_stride + (int64_t)lb];
             ref.ok = blk >= 0 && blk < a.n_src_rows;
@@ -459,7 +488,7 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
     };
     auto unit_ptr = [&](const RowRef &ref, uint32_t c) -> const uint8_t * {
         if (!a.paged) return ref.base + (uint64_t)c * NB_IN;
-        const uint32_t seg = c / a.seg_units;
+        const uint32_t seg = a.seg_shift < 32u ? c >> a.seg_shift : c / a.seg_units;
         const uint32_t cc = c - seg * a.seg_units;
         return ref.base + (int64_t)lds[m.heads + seg] * a.head_stride_b + (uint64_t)cc * NB_IN;
     };
@@ -515,37 +544,66 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
 
         DMI_STAMP(3);
         if constexpr (!SUMM) {
-            // ---- flat copy: the n_rows x units_per_row units are dealt to lanes in order, so
-            //      stores are fully coalesced whatever the row length; 4 loads in flight per lane
             if constexpr (OUT != OUT_NONE) {
                 constexpr uint32_t U = 4;
-                const uint64_t total = (uint64_t)n_rows * a.units_per_row;
                 Accum dummy = {0.f, 0.f, 0.f};
-                for (uint64_t t0 = (uint64_t)blockIdx.x * kThreads; t0 < total;
-                     t0 += (uint64_t)gridDim.x * U * kThreads) {
-                    unit_t v[U];
-                    bool live[U];
+                if (a.units_per_row >= kThreads) {
+                    // ---- long rows: a work item is 1024 consecutive units of one row (4 loads in
+                    //      flight per lane); the row is located once per item, not per unit
+                    constexpr uint32_t CH = U * kThreads;
+                    const uint32_t cpr = (a.units_per_row + CH - 1u) / CH;
+                    const uint64_t n_items = (uint64_t)n_rows * cpr;
+                    for (uint64_t it = blockIdx.x; it < n_items; it += gridDim.x) {
+                        const uint32_t g = cpr == 1u ? (uint32_t)it : (uint32_t)(it / cpr);
+                        const uint32_t c_begin = (uint32_t)(it - (uint64_t)g * cpr) * CH + tid;
+                        const RowRef ref = locate(g);
+                        if (!ref.ok && c_begin == 0) atomicAdd((unsigned long long *)&a.ctrl->bad_rows, 1ull);
+                        const uint64_t row_off = off_payload + (uint64_t)g * a.units_per_row * NB_OUT;
+                        unit_t v[U];
 #pragma unroll
-                    for (uint32_t k = 0; k < U; k++) {
-                        const uint64_t u = t0 + (uint64_t)k * gridDim.x * kThreads + tid;
-                        live[k] = u < total;
-                        v[k] = unit_t{};
-                        if (live[k]) {
-                            const uint32_t u32 = (uint32_t)u;       // host keeps total below 2^32
-                            const uint32_t g = a.upr_shift < 32u ? u32 >> a.upr_shift : u32 / a.units_per_row;
-                            const uint32_t c = u32 - g * a.units_per_row;
-                            const RowRef ref = locate(g);
-                            if (!ref.ok && c == 0)
-                                atomicAdd((unsigned long long *)&a.ctrl->bad_rows, 1ull);
-                            v[k] = load_unit(ref, c);
+                        for (uint32_t k = 0; k < U; k++) {
+                            const uint32_t c = c_begin + k * kThreads;
+                            v[k] = unit_t{};
+                            if (c < a.units_per_row) v[k] = load_unit(ref, c);
+                        }
+#pragma unroll
+                        for (uint32_t k = 0; k < U; k++) {
+                            const uint32_t c = c_begin + k * kThreads;
+                            if (c < a.units_per_row)
+                                emit_unit<ES_IN, VEC, OUT, false>(w, row_off + (uint64_t)c * NB_OUT, v[k],
+                                                                  a.src_dtype, dummy);
                         }
                     }
+                } else {
+                    // ---- short rows: the n_rows x units_per_row units are dealt to lanes in order,
+                    //      so stores stay fully coalesced; 4 loads in flight per lane
+                    const uint64_t total = (uint64_t)n_rows * a.units_per_row;
+                    for (uint64_t t0 = (uint64_t)blockIdx.x * kThreads; t0 < total;
+                         t0 += (uint64_t)gridDim.x * U * kThreads) {
+                        unit_t v[U];
+                        bool live[U];
 #pragma unroll
-                    for (uint32_t k = 0; k < U; k++) {
-                        const uint64_t u = t0 + (uint64_t)k * gridDim.x * kThreads + tid;
-                        if (live[k])
-                            emit_unit<ES_IN, VEC, OUT, false>(w, off_payload + u * NB_OUT, v[k],
-                                                              a.src_dtype, dummy);
+                        for (uint32_t k = 0; k < U; k++) {
+                            const uint64_t u = t0 + (uint64_t)k * gridDim.x * kThreads + tid;
+                            live[k] = u < total;
+                            v[k] = unit_t{};
+                            if (live[k]) {
+                                const uint32_t u32 = (uint32_t)u;       // host keeps total below 2^32
+                                const uint32_t g = a.upr_shift < 32u ? u32 >> a.upr_shift : u32 / a.units_per_row;
+                                const uint32_t c = u32 - g * a.units_per_row;
+                                const RowRef ref = locate(g);
+                                if (!ref.ok && c == 0)
+                                    atomicAdd((unsigned long long *)&a.ctrl->bad_rows, 1ull);
+                                v[k] = load_unit(ref, c);
+                            }
+                        }
+#pragma unroll
+                        for (uint32_t k = 0; k < U; k++) {
+                            const uint64_t u = t0 + (uint64_t)k * gridDim.x * kThreads + tid;
+                            if (live[k])
+                                emit_unit<ES_IN, VEC, OUT, false>(w, off_payload + u * NB_OUT, v[k],
+                                                                  a.src_dtype, dummy);
+                        }
                     }
                 }
             }

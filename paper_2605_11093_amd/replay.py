@@ -22,6 +22,7 @@ class GpuRun:
     records: List[tuple] = field(default_factory=list)     # (seq, bytes) when collecting
     n_records: int = 0
     n_bytes: int = 0
+    launched: List[object] = field(default_factory=list)   # launched[seq] = the call that got that seq
 
     @property
     def stream(self) -> np.ndarray:
@@ -75,7 +76,8 @@ def run_workload_gpu(wl, *, drain_every: int = 1, release: bool = True, collect:
                      flags: int = 0, device_ring_bytes=None, host_ring_bytes=None,
                      max_steps=None, lockstep: bool = True, on_record=None,
                      block_timeout_ms: int = 1, poison: Optional[int] = None,
-                     ring: Optional[B.Ring] = None) -> GpuRun:
+                     ring: Optional[B.Ring] = None, drain_flags: int = 0,
+                     bg_min_bytes: int = 0) -> GpuRun:
     """Lockstep schedule (the one the oracle's model follows): a step's observes,
     then every `drain_every` steps a flush-drain followed by poll + release.
     With lockstep=False the drain after a step moves only what has committed by
@@ -83,7 +85,8 @@ def run_workload_gpu(wl, *, drain_every: int = 1, release: bool = True, collect:
     own = ring is None
     if own:
         ring = B.Ring(device_ring_bytes or wl.device_ring_bytes, host_ring_bytes or wl.host_ring_bytes,
-                      flags=flags, max_reqs_per_observe=wl.max_reqs, block_timeout_ms=block_timeout_ms)
+                      flags=flags, max_reqs_per_observe=wl.max_reqs, block_timeout_ms=block_timeout_ms,
+                      bg_min_bytes=bg_min_bytes)
         ring.set_policy(wl.policy_mode, wl.sample_k, 0)
     if poison is not None:
         ring.debug_fill_rings(poison)
@@ -103,11 +106,13 @@ def run_workload_gpu(wl, *, drain_every: int = 1, release: bool = True, collect:
                     consume(ring, run, collect, release, on_record)
                     tries += 1
                     rc = observe_call(ring, c, s.cuda_stream, keep_alive,
-                                      allow=(B.ERR_AGAIN,) if tries < 20000 else ())
+                                      allow=(B.ERR_AGAIN,) if tries < 200000 else ())
+                if rc == B.OK:
+                    run.launched.append(c)
             if (step + 1) % drain_every == 0:
                 if lockstep:
                     s.synchronize()     # every kernel of the step has committed
-                ring.drain(B.DRAIN_FLUSH if lockstep else 0, allow=(B.ERR_AGAIN,))
+                ring.drain(B.DRAIN_FLUSH if lockstep else drain_flags, allow=(B.ERR_AGAIN,))
                 consume(ring, run, collect, release, on_record)
                 keep_alive.clear() if lockstep else None
         # tail: everything still in flight
