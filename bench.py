@@ -348,6 +348,98 @@ def main():
         log(f"overhead: {extra['overhead']}")
         del weights
 
+    # ------------------------------------------------------------------ the other configurations end to end
+    if not args.skip_extra:
+        from paper_2605_11093_amd.replay import run_workload_gpu
+        e2e = {}
+
+        def model_compute(call, stream_handle):
+            # stand-in for the layers between two observation points: 2 ms of stream time
+            # (a real 8B prefill layer over ~35k tokens takes several times longer)
+            bench_lib.dmi_bench_sleep(stream_handle, 2000)
+
+        def timed_replay(name, w, block_timeout_ms=2000):
+            rr = B.Ring(w.device_ring_bytes, w.host_ring_bytes, flags=B.BG_THREAD,
+                        max_reqs_per_observe=w.max_reqs, block_timeout_ms=block_timeout_ms)
+            rr.set_policy(w.policy_mode, w.sample_k, 0)
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            run = run_workload_gpu(w, collect=False, lockstep=False, ring=rr, before_observe=model_compute)
+            dt = time.perf_counter() - t
+            stt = run.stats
+            rr.destroy()
+            tot = stt.captured_bytes + stt.dropped_bytes
+            e2e[name] = {"drained_GBs": round(stt.drained_bytes / dt / 1e9, 2),
+                         "frac_of_d2h_peak": round(stt.drained_bytes / dt / 1e9 / d2h_peak, 3),
+                         "dropped_fraction": round(stt.dropped_bytes / tot, 4) if tot else 0.0,
+                         "records": stt.launched_records, "seconds": round(dt, 3),
+                         "model_compute_stand_in": "2 ms sleep kernel before every observe"}
+            log(f"end to end {name}: {e2e[name]}")
+
+        timed_replay("config3_prefill_4steps", configs.config3_prefill(device=dev, n_steps=4))
+        torch.cuda.empty_cache()
+        timed_replay("config4_paged_kv_12steps", configs.config4_paged_kv(device=dev, n_steps=12),
+                     block_timeout_ms=5000)
+        torch.cuda.empty_cache()
+        extra["end_to_end"] = e2e
+
+        # config 5: saturation.  80 layers of a 70B model's TP-8 share (219 MB of bf16 weights per
+        # layer) run as the interfering step; 320 MiB per captured step exceeds the host link.
+        n_l, n_w5 = 80, 219 * 1000 * 1000 // 2 // 8 * 8
+        w5 = configs.config5_saturation(device=dev, n_steps=4)
+        calls5 = [w5.step_calls(s) for s in range(4)]
+        weights5 = [torch.empty(n_w5, dtype=torch.bfloat16, device=dev).normal_() for _ in range(n_l)]
+        xv = torch.randn(4096, device=dev).to(torch.bfloat16)
+        ac = torch.zeros(4096, dtype=torch.float32, device=dev)
+        r5 = B.Ring(w5.device_ring_bytes, w5.host_ring_bytes, flags=B.BG_THREAD, max_reqs_per_observe=256)
+        p5 = [[dmi.PreparedObserve(r5, c.point_id, c.tensor, c.reqs) for c in calls5[slot]] for slot in range(4)]
+        sat = {}
+        n_steps5 = 100
+
+        def steps5(first, count, capture):
+            for s5 in range(first, first + count):
+                for l5 in range(n_l):
+                    bench_lib.dmi_bench_stream_gemv(weights5[l5].data_ptr(), n_w5, xv.data_ptr(), ac.data_ptr(), sh)
+                    if capture:
+                        rc = p5[s5 % 4][l5](s5, sh)
+                        if rc < 0:
+                            raise dmi.DmiError(rc, dmi.lib().dmi_last_error().decode())
+                if capture:
+                    consume(r5)
+
+        steps5(0, 3, False)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        steps5(0, 20, False)
+        torch.cuda.synchronize()
+        base5 = (time.perf_counter() - t) / 20
+        for k in (1, 2, 4, 8):
+            r5.set_policy(B.POLICY_DROP_NEWEST, k, 0)
+            settle(r5)
+            a0 = r5.get_stats()
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            steps5(1000 * k, n_steps5, True)
+            stream.synchronize()
+            dt = time.perf_counter() - t
+            a1 = r5.get_stats()
+            drained = a1.drained_bytes - a0.drained_bytes
+            settle(r5)
+            a2 = r5.get_stats()
+            cap = a2.captured_bytes - a0.captured_bytes
+            drp = a2.dropped_bytes - a0.dropped_bytes
+            sat[f"k={k}"] = {"drained_GBs": round(drained / dt / 1e9, 2),
+                             "dropped_fraction": round(drp / (cap + drp), 4) if cap + drp else 0.0,
+                             "ms_per_step": round(dt / n_steps5 * 1e3, 3),
+                             "overhead_pct": round((dt / n_steps5 - base5) / base5 * 100, 2)}
+            log(f"config 5 saturation k={k}: {sat[f'k={k}']}")
+        r5.destroy()
+        del weights5
+        torch.cuda.empty_cache()
+        extra["config5_saturation"] = {"no_capture_ms_per_step": round(base5 * 1e3, 3), "steps": n_steps5,
+                                       "interfering_workload": "80 x 219 MB bf16 weight-streaming GEMV per step",
+                                       "by_k": sat}
+
     # ------------------------------------------------------------------ CPU oracle baseline
     cpu = None
     if not args.skip_cpu_baseline:

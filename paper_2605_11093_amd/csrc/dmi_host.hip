@@ -66,6 +66,7 @@ bool transform_ok(uint32_t src, uint32_t out)
 }
 
 constexpr uint32_t kSlabSlots = 64;
+constexpr uint32_t kTailVals = 4096;
 constexpr uint32_t kSelCache = 4;
 
 struct SelCache {
@@ -99,6 +100,9 @@ struct dmi_ring {
     DevCtrl *dctrl = nullptr;
     CommitSlot *hslots = nullptr, *hslots_dev = nullptr;   // pinned mirror of DevCtrl::slots
     hipStream_t ctl_stream = nullptr;                      // fetches commit slots
+    bool use_copy_ctl = false;
+    uint64_t *tail_vals = nullptr;                         // pinned staging for tail values
+    uint32_t tail_rr = 0;
     uint32_t *slab = nullptr;
     uint32_t slab_slot_words = 0, next_slab = 0, max_reqs = 0;
     SelCache cache[kSelCache];
@@ -166,7 +170,11 @@ dmi_status_t record_probe(dmi_ring *r)
     const uint32_t slot = (uint32_t)((launched - 1u) % kCommitSlots);
     HIP_TRY(hipEventRecord(ev[0], (hipStream_t)r->last_stream.load(std::memory_order_acquire)));
     HIP_TRY(hipStreamWaitEvent(r->ctl_stream, ev[0], 0));
-    HIP_TRY(launch_fetch_slot(&r->dctrl->slots[slot], r->hslots_dev + slot, r->ctl_stream));
+    if (r->use_copy_ctl)
+        HIP_TRY(hipMemcpyAsync((void *)(r->hslots + slot), &r->dctrl->slots[slot], sizeof(CommitSlot),
+                               hipMemcpyDeviceToHost, r->ctl_stream));
+    else
+        HIP_TRY(launch_fetch_slot(&r->dctrl->slots[slot], r->hslots_dev + slot, r->ctl_stream));
     HIP_TRY(hipEventRecord(ev[1], r->ctl_stream));
     r->probes.push_back({ev[0], ev[1], launched});
     r->probed_upto = launched;
@@ -218,7 +226,7 @@ dmi_status_t reap(dmi_ring *r, bool wait)
 }
 
 // Issue copies for what is committed and fits the host ring.  Caller holds r->mu.
-dmi_status_t drain_locked(dmi_ring *r, bool wait, uint64_t *moved)
+dmi_status_t drain_issue_locked(dmi_ring *r, uint64_t *moved)
 {
     if (moved) *moved = 0;
     dmi_status_t st = reap(r, false);
@@ -227,7 +235,10 @@ dmi_status_t drain_locked(dmi_ring *r, bool wait, uint64_t *moved)
     atomic_max(r->dev_high, committed - r->drain_done.load(std::memory_order_relaxed));
     const uint64_t avail = committed - r->drain_issued;
     const uint64_t host_free = r->host_cap - (r->drain_issued - r->released);
-    const uint64_t n = avail < host_free ? avail : host_free;
+    uint64_t n = avail < host_free ? avail : host_free;
+    // bounded batches: the device tail (what drop-newest decides on) moves once per batch
+    const uint64_t batch = (r->dev_cap / 8u > (64u << 20) ? r->dev_cap / 8u : (64u << 20)) & ~63ull;
+    if (n > batch) n = batch;
     if (n > 0) {
         const uint64_t from = r->drain_issued;
         if (r->cfg.flags & DMI_DRAIN_KERNEL) {
@@ -250,7 +261,13 @@ dmi_status_t drain_locked(dmi_ring *r, bool wait, uint64_t *moved)
             }
         }
         // the device may reuse the span only after the copies before this have run
-        HIP_TRY(launch_set_tail(r->dctrl, from + n, r->drain_stream));
+        if (r->use_copy_ctl) {
+            uint64_t *slot = r->tail_vals + (r->tail_rr++ % kTailVals);
+            *slot = from + n;
+            HIP_TRY(hipMemcpyAsync(&r->dctrl->tail, slot, 8, hipMemcpyHostToDevice, r->drain_stream));
+        } else {
+            HIP_TRY(launch_set_tail(r->dctrl, from + n, r->drain_stream));
+        }
         hipEvent_t ev;
         if (r->ev_pool.empty()) HIP_TRY(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
         else { ev = r->ev_pool.back(); r->ev_pool.pop_back(); }
@@ -262,8 +279,27 @@ dmi_status_t drain_locked(dmi_ring *r, bool wait, uint64_t *moved)
         atomic_max(r->host_high, r->drain_issued - r->released);
         if (moved) *moved = n;
     }
-    if (wait) return reap(r, true);
     return DMI_OK;
+}
+
+// Issue the copies and, if asked, wait for them.  The ring's lock is held only while the
+// bookkeeping is touched, never across the wait: the consumer polls and releases, and the
+// producer asks for room, while a copy is in flight.
+dmi_status_t drain(dmi_ring *r, bool wait, uint64_t *moved)
+{
+    hipEvent_t last = nullptr;
+    {
+        std::lock_guard<std::mutex> lk(r->mu);
+        dmi_status_t st = drain_issue_locked(r, moved);
+        if (st != DMI_OK) return st;
+        if (!r->pending.empty()) last = r->pending.back().ev;
+    }
+    if (!wait || !last) return DMI_OK;
+    // an event that another thread retires meanwhile has completed, so this returns at once
+    hipError_t e = hipEventSynchronize(last);
+    if (e != hipSuccess) return fail(DMI_ERR_HIP, "drain event: %s", hipGetErrorString(e));
+    std::lock_guard<std::mutex> lk(r->mu);
+    return reap(r, false);
 }
 
 // Pop launches known to have finished; returns an upper bound of the device head once
@@ -297,11 +333,7 @@ dmi_status_t wait_for_room(dmi_ring *r, uint64_t ub)
         if (head_ub - tail + ub <= r->dev_cap) break;
         if (!t0) t0 = now_ns();
         uint64_t moved = 0;
-        {
-            std::lock_guard<std::mutex> lk(r->mu);
-            st = drain_locked(r, true, &moved);
-            if (st != DMI_OK) return st;
-        }
+        if ((st = drain(r, true, &moved)) != DMI_OK) return st;
         if (moved) continue;
         st = record_probe(r);       // make sure the launches we wait for will report
         if (st != DMI_OK) return st;
@@ -442,7 +474,28 @@ dmi_status_t observe_common(dmi_ring *r, uint32_t point_id, const dmi_selection_
     else groups = (listed * upr + kThreads - 1u) / kThreads;
     uint32_t grid = groups < 1u ? 1u : groups > kMaxGrid ? kMaxGrid : (uint32_t)groups;
 
-    hipError_t e = launch_capture(a, grid, geo.vec16, s);
+    hipError_t e;
+    if (decode_kernel_applies(a, geo.vec16)) {
+        // the host knows this record exactly: geometry and header travel as kernel arguments
+        const uint64_t table_bytes = pad64((uint64_t)sel->n_reqs * 16u);
+        a.payload_bytes = listed * geo.row_elems * dtype_size(xf->out_dtype);
+        a.off_payload = DMI_HEADER_BYTES + table_bytes;
+        a.off_sum = a.off_payload + pad64(a.payload_bytes);
+        a.sum_arr = pad64(listed * 4u);
+        a.record_bytes = ub;
+        a.hdr[0] = DMI_MAGIC;
+        a.hdr[1] = 1u | (DMI_HEADER_BYTES << 16);
+        a.hdr[2] = (uint32_t)seq;            a.hdr[3] = (uint32_t)(seq >> 32);
+        a.hdr[4] = (uint32_t)step_id;        a.hdr[5] = (uint32_t)(step_id >> 32);
+        a.hdr[6] = point_id;
+        a.hdr[7] = a.src_dtype | (a.out_dtype << 8) | (a.summary_mask << 16) | (a.rec_flags << 24);
+        a.hdr[8] = sel->n_reqs;  a.hdr[9] = (uint32_t)listed;  a.hdr[10] = geo.row_elems;  a.hdr[11] = a.rank_tag;
+        a.hdr[12] = (uint32_t)ub;               a.hdr[13] = (uint32_t)(ub >> 32);
+        a.hdr[14] = (uint32_t)a.payload_bytes;  a.hdr[15] = (uint32_t)(a.payload_bytes >> 32);
+        e = launch_capture_decode(a, s);
+    } else {
+        e = launch_capture(a, grid, geo.vec16, s);
+    }
     if (e != hipSuccess) return fail(DMI_ERR_HIP, "capture launch failed: %s", hipGetErrorString(e));
     r->next_seq.store(seq + 1, std::memory_order_release);
     r->inflight.emplace_back(seq, ub);
@@ -489,14 +542,19 @@ void bg_loop(dmi_ring *r)
     (void)hipSetDevice(r->dev);
     const uint64_t min_bytes = r->cfg.bg_min_bytes ? r->cfg.bg_min_bytes : (1u << 20);
     const uint64_t timeout_ns = (uint64_t)(r->cfg.bg_timeout_us ? r->cfg.bg_timeout_us : 200u) * 1000ull;
-    uint64_t waiting_since = 0;
+    uint64_t waiting_since = 0, last_probe = 0;
     while (!r->stop.load(std::memory_order_acquire)) {
         bool idle_probes;
         {
             std::lock_guard<std::mutex> lk(r->pmu);
             idle_probes = r->probes.empty();
         }
-        if (idle_probes) (void)record_probe(r);     // covers launches the producer left unprobed
+        // cover launches the producer left unprobed, but rarely: every event recorded on the
+        // producer's stream is a barrier in the inference queue
+        if (idle_probes && now_ns() - last_probe >= timeout_ns) {
+            (void)record_probe(r);
+            last_probe = now_ns();
+        }
         (void)advance_commits(r, false);
         uint64_t pending_bytes;
         {
@@ -507,13 +565,12 @@ void bg_loop(dmi_ring *r)
         if (pending_bytes == 0) waiting_since = 0;
         else if (!waiting_since) waiting_since = t;
         if (pending_bytes >= min_bytes || (pending_bytes && t - waiting_since >= timeout_ns)) {
-            std::lock_guard<std::mutex> lk(r->mu);
             uint64_t moved = 0;
-            (void)drain_locked(r, true, &moved);
+            (void)drain(r, true, &moved);
             waiting_since = 0;
             if (moved) continue;
         }
-        std::this_thread::sleep_for(std::chrono::microseconds(20));
+        std::this_thread::sleep_for(std::chrono::microseconds(getenv("DMI_BG_SLEEP_US") ? atoi(getenv("DMI_BG_SLEEP_US")) : 20));
     }
 }
 
@@ -531,6 +588,7 @@ void free_ring(dmi_ring *r)
     if (r->slab) (void)hipFree(r->slab);
     if (r->host_ring) (void)hipHostFree(r->host_ring);
     if (r->hslots) (void)hipHostFree((void *)r->hslots);
+    if (r->tail_vals) (void)hipHostFree(r->tail_vals);
     delete r;
 }
 
@@ -601,6 +659,9 @@ dmi_status_t dmi_ring_create(const dmi_ring_config_t *cfg, dmi_ring_t **out)
     if ((e = hipHostGetDevicePointer((void **)&r->hslots_dev, (void *)r->hslots, 0)) != hipSuccess)
         return bail(e, "hipHostGetDevicePointer(commit slots)");
     memset((void *)r->hslots, 0, sizeof(CommitSlot) * kCommitSlots);
+    if ((e = hipHostMalloc((void **)&r->tail_vals, sizeof(uint64_t) * kTailVals, hipHostMallocDefault)) != hipSuccess)
+        return bail(e, "hipHostMalloc(tail staging)");
+    r->use_copy_ctl = getenv("DMI_COPY_CTL") != nullptr;
     {
         DevCtrl *init = new (std::nothrow) DevCtrl;
         if (!init) { free_ring(r); return fail(DMI_ERR_NOMEM, "out of host memory"); }
@@ -736,8 +797,7 @@ dmi_status_t dmi_drain(dmi_ring_t *r, uint32_t flags, uint64_t *bytes_moved)
         }
         if (idle_probes && (st = record_probe(r)) != DMI_OK) return st;
         if ((st = advance_commits(r, false)) != DMI_OK) return st;
-        std::lock_guard<std::mutex> lk(r->mu);
-        return drain_locked(r, wait, bytes_moved);
+        return drain(r, wait, bytes_moved);
     }
     // flush: everything issued so far must finish, then all of it is moved
     const uint64_t want_seq = r->next_seq.load(std::memory_order_acquire);
@@ -748,10 +808,9 @@ dmi_status_t dmi_drain(dmi_ring_t *r, uint32_t flags, uint64_t *bytes_moved)
         if ((st = advance_commits(r, false)) != DMI_OK) return st;
         const uint64_t done = r->confirmed.load(std::memory_order_acquire);
         uint64_t moved = 0, left;
+        if ((st = drain(r, true, &moved)) != DMI_OK) return st;
         {
             std::lock_guard<std::mutex> lk(r->mu);
-            st = drain_locked(r, true, &moved);
-            if (st != DMI_OK) return st;
             left = read_committed(r) - r->drain_issued;
         }
         total += moved;
@@ -772,8 +831,12 @@ dmi_status_t dmi_poll_host(dmi_ring_t *r, dmi_record_view_t *out, uint32_t max, 
     if (!r || !n || (max && !out)) return fail(DMI_ERR_INVALID_ARG, "NULL argument");
     *n = 0;
     std::lock_guard<std::mutex> lk(r->mu);
-    dmi_status_t st = reap(r, false);
-    if (st != DMI_OK) return st;
+    // with the library's drain thread running, arrivals are noted by that thread; a HIP call
+    // on the drain stream's events from here would queue up behind its blocking wait
+    if (!(r->cfg.flags & DMI_BG_THREAD)) {
+        dmi_status_t st = reap(r, false);
+        if (st != DMI_OK) return st;
+    }
     const uint64_t done = r->drain_done.load(std::memory_order_acquire);
     while (*n < max && r->poll_cursor + DMI_HEADER_BYTES <= done) {
         const uint64_t off = r->poll_cursor % r->host_cap;
@@ -859,8 +922,8 @@ dmi_status_t dmi_get_stats(dmi_ring_t *r, dmi_stats_t *o)
     {
         std::lock_guard<std::mutex> lk(r->mu);
         uint64_t bad = 0;
-        HIP_TRY(hipMemcpyAsync(&bad, &r->dctrl->bad_rows, 8, hipMemcpyDeviceToHost, r->drain_stream));
-        HIP_TRY(hipStreamSynchronize(r->drain_stream));
+        HIP_TRY(hipMemcpyAsync(&bad, &r->dctrl->bad_rows, 8, hipMemcpyDeviceToHost, r->ctl_stream));
+        HIP_TRY(hipStreamSynchronize(r->ctl_stream));
         o->bad_rows = bad;
     }
     return DMI_OK;
@@ -872,8 +935,8 @@ dmi_status_t dmi_get_point_drops(dmi_ring_t *r, uint32_t point_id, uint64_t *n)
     (void)hipSetDevice(r->dev);
     uint32_t v = 0;
     std::lock_guard<std::mutex> lk(r->mu);
-    HIP_TRY(hipMemcpyAsync(&v, &r->dctrl->point_drops[point_id], 4, hipMemcpyDeviceToHost, r->drain_stream));
-    HIP_TRY(hipStreamSynchronize(r->drain_stream));
+    HIP_TRY(hipMemcpyAsync(&v, &r->dctrl->point_drops[point_id], 4, hipMemcpyDeviceToHost, r->ctl_stream));
+    HIP_TRY(hipStreamSynchronize(r->ctl_stream));
     *n = v;
     return DMI_OK;
 }

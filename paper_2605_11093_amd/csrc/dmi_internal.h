@@ -81,10 +81,18 @@ struct CaptureArgs {
     uint32_t drop_newest;
     uint32_t table_in_lds;
     uint32_t lds_bytes;
+    // record geometry and header, filled by the host when it knows them exactly (no keep
+    // mask: the row count is the listed one); used by the decode-shaped kernel
+    uint32_t hdr[16];
+    uint64_t off_payload, off_sum, sum_arr, record_bytes, payload_bytes;
 };
 
 // Launchers (dmi_kernels.hip).  All return the launch's hipError_t.
 hipError_t launch_capture(const CaptureArgs &a, uint32_t grid, bool vec16, hipStream_t s);
+// decode-shaped captures: bf16 source, dense, one row per request, no mask, 16-byte movable
+// rows of at most 1024 units; grid is n_reqs + 1
+bool decode_kernel_applies(const CaptureArgs &a, bool vec16);
+hipError_t launch_capture_decode(const CaptureArgs &a, hipStream_t s);
 hipError_t launch_upload(uint32_t *dst, const uint32_t *words, uint32_t n_words, hipStream_t s);
 hipError_t launch_set_tail(DevCtrl *ctrl, uint64_t tail, hipStream_t s);
 hipError_t launch_fetch_slot(const CommitSlot *src, CommitSlot *dst_host, hipStream_t s);

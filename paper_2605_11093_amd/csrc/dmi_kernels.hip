@@ -62,10 +62,13 @@ __device__ __forceinline__ float wave_sum(float v)
     for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
     return v;
 }
-__device__ __forceinline__ float wave_max(float v)
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
 {
 #pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) v = fmaxf(v, __shfl_xor(v, d, 64));
+    for (int d = 32; d >= 1; d >>= 1) {
+        const uint32_t o = (uint32_t)__shfl_xor((int)v, d, 64);
+        v = o > v ? o : v;
+    }
     return v;
 }
 
@@ -161,18 +164,74 @@ __device__ __forceinline__ void ring_store(const RingW &w, uint64_t off, T v)
 {
     uint64_t p = w.base + off;
     if (p >= w.cap) p -= w.cap;
+#ifdef DMI_PLAIN_STORES
+    *reinterpret_cast<T *>(w.ring + p) = v;
+#else
     __builtin_nontemporal_store(v, reinterpret_cast<T *>(w.ring + p));
+#endif
 }
 
+// Per-lane partial row summaries.  Sum of squares and sum are fp32; the largest magnitude is
+// kept as the bit pattern of |x| in the source format (sign-magnitude formats order like
+// unsigned integers, and a NaN, whose pattern is above infinity's, wins the maximum and so
+// surfaces as NaN).  16-bit sources keep two independent 16-bit maxima in one word.
 struct Accum {
-    float ss, s, am;
+    float ss, s;
+    uint32_t am;
 };
 
-__device__ __forceinline__ void accum1(Accum &a, float x)
+typedef _Float16 h16x2_t __attribute__((ext_vector_type(2)));
+
+// two 16-bit elements in one word: v_dot2 does x0*x0 + x1*x1 + acc (and x0 + x1 + acc with a
+// vector of ones) without unpacking; v_pk_max_u16 tracks the magnitudes
+__device__ __forceinline__ void accum_pair(Accum &a, uint32_t w, bool is_bf16)
 {
+    if (is_bf16) {
+        const bf16x2_t x = __builtin_bit_cast(bf16x2_t, w);
+        const bf16x2_t one = __builtin_bit_cast(bf16x2_t, 0x3F803F80u);
+        a.ss = __builtin_amdgcn_fdot2_f32_bf16(x, x, a.ss, false);
+        a.s = __builtin_amdgcn_fdot2_f32_bf16(x, one, a.s, false);
+    } else {
+        const h16x2_t x = __builtin_bit_cast(h16x2_t, w);
+        const h16x2_t one = __builtin_bit_cast(h16x2_t, 0x3C003C00u);
+        a.ss = __builtin_amdgcn_fdot2(x, x, a.ss, false);
+        a.s = __builtin_amdgcn_fdot2(x, one, a.s, false);
+    }
+    a.am = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(u16x2_t, a.am),
+                                                                  __builtin_bit_cast(u16x2_t, w & 0x7FFF7FFFu)));
+}
+
+__device__ __forceinline__ void accum_f32(Accum &a, uint32_t bits)
+{
+    const float x = __uint_as_float(bits);
     a.ss = fmaf(x, x, a.ss);
     a.s += x;
-    a.am = fmaxf(a.am, fabsf(x));
+    const uint32_t m = bits & 0x7FFFFFFFu;
+    a.am = m > a.am ? m : a.am;
+}
+
+// one 16-bit element (element-wise path)
+__device__ __forceinline__ void accum_16(Accum &a, uint32_t bits, uint32_t src_dtype)
+{
+    const float x = widen16(bits, src_dtype);
+    a.ss = fmaf(x, x, a.ss);
+    a.s += x;
+    const uint32_t m = bits & 0x7FFFu;
+    a.am = m > a.am ? m : a.am;
+}
+
+// the lane's magnitude maximum as one value comparable across lanes
+template <int ES_IN, int VEC>
+__device__ __forceinline__ uint32_t fold_am(uint32_t am)
+{
+    if constexpr (ES_IN == 2 && VEC == 8) return (am & 0xFFFFu) > (am >> 16) ? (am & 0xFFFFu) : (am >> 16);
+    else return am;
+}
+
+__device__ __forceinline__ float am_value(uint32_t m, uint32_t src_dtype)
+{
+    if (src_dtype == 3u) return __uint_as_float(m);
+    return widen16(m, src_dtype);
 }
 
 // Convert one source unit and store it; optionally accumulate the row summaries.
@@ -184,11 +243,9 @@ __device__ __forceinline__ void emit_unit(const RingW &w, uint64_t out_off,
     if constexpr (ES_IN == 2 && VEC == 8) {
         uint32_t wd[4] = {v.x, v.y, v.z, v.w};
         if constexpr (SUMM) {
+            const bool is_bf16 = src_dtype == 1u;
 #pragma unroll
-            for (int k = 0; k < 4; k++) {
-                accum1(acc, widen16(wd[k] & 0xFFFFu, src_dtype));
-                accum1(acc, widen16(wd[k] >> 16, src_dtype));
-            }
+            for (int k = 0; k < 4; k++) accum_pair(acc, wd[k], is_bf16);
         }
         if constexpr (OUT == OUT_RAW) {
             ring_store<u32x4>(w, out_off, v);
@@ -213,20 +270,20 @@ __device__ __forceinline__ void emit_unit(const RingW &w, uint64_t out_off,
         }
     } else if constexpr (ES_IN == 4 && VEC == 4) {
         if constexpr (SUMM) {
-            accum1(acc, __uint_as_float(v.x));
-            accum1(acc, __uint_as_float(v.y));
-            accum1(acc, __uint_as_float(v.z));
-            accum1(acc, __uint_as_float(v.w));
+            accum_f32(acc, v.x);
+            accum_f32(acc, v.y);
+            accum_f32(acc, v.z);
+            accum_f32(acc, v.w);
         }
         if constexpr (OUT == OUT_RAW) ring_store<u32x4>(w, out_off, v);
     } else if constexpr (ES_IN == 2) {      // one 2-byte element
         const uint32_t b = v;
-        if constexpr (SUMM) accum1(acc, widen16(b, src_dtype));
+        if constexpr (SUMM) accum_16(acc, b, src_dtype);
         if constexpr (OUT == OUT_RAW) ring_store<uint16_t>(w, out_off, (uint16_t)b);
         else if constexpr (OUT == OUT_FP16) ring_store<uint16_t>(w, out_off, (uint16_t)bf16_to_fp16(b));
         else if constexpr (OUT == OUT_FP8) ring_store<uint8_t>(w, out_off, (uint8_t)bf16_to_fp8(b));
     } else {                                // one 4-byte element
-        if constexpr (SUMM) accum1(acc, __uint_as_float(v));
+        if constexpr (SUMM) accum_f32(acc, v);
         if constexpr (OUT == OUT_RAW) ring_store<uint32_t>(w, out_off, v);
     }
 }
@@ -392,6 +449,36 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
             if (index_mode) pref_all[n_reqs] = btot_all[nb];
         }
     }
+    // -- decode-shaped selections (no mask, one row per request, dense): the first work
+    //    item's rows do not depend on anything computed above, so their loads are issued
+    //    now and travel together with the control fetch instead of behind it
+    constexpr uint32_t U = 4;                               // loads in flight per lane
+    constexpr uint32_t CH = U * kThreads;                   // units per long-row work item
+    const uint32_t rpw = SUMM ? a.rows_per_wg : 1u;
+    const uint32_t gsz = kThreads / rpw;                    // lanes per row (summary passes)
+    const uint32_t sub = tid / gsz, l = tid - sub * gsz;
+    const uint32_t cpr = (a.units_per_row + CH - 1u) / CH;  // long-row items per row
+    unit_t pre_v[U];
+    RowRef pre_ref = {nullptr, false};
+    bool pre = false;
+    if (simple && !a.paged && (SUMM || (OUT != OUT_NONE && a.units_per_row >= kThreads))) {
+        uint32_t g, c_begin, stride;
+        if constexpr (SUMM) { g = blockIdx.x * rpw + sub; c_begin = l; stride = gsz; }
+        else { g = blockIdx.x / cpr; c_begin = (blockIdx.x - g * cpr) * CH + tid; stride = kThreads; }
+        if (g < n_reqs) {
+            const int64_t row = index_mode ? (int64_t)a.row_index[g] : (int64_t)a.row0[g];
+            pre_ref.ok = row >= 0 && row < a.n_src_rows;
+            pre_ref.base = a.src + (pre_ref.ok ? row : 0) * a.row_stride_b;
+#pragma unroll
+            for (uint32_t k = 0; k < U; k++) {
+                const uint32_t c = c_begin + k * stride;
+                pre_v[k] = unit_t{};
+                if (pre_ref.ok && c < a.units_per_row)
+                    pre_v[k] = *reinterpret_cast<const unit_t *>(pre_ref.base + (uint64_t)c * NB_IN);
+            }
+            pre = true;
+        }
+    }
     __syncthreads();
 
     DMI_STAMP(2);
@@ -545,27 +632,32 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
         DMI_STAMP(3);
         if constexpr (!SUMM) {
             if constexpr (OUT != OUT_NONE) {
-                constexpr uint32_t U = 4;
-                Accum dummy = {0.f, 0.f, 0.f};
+                Accum dummy = {0.f, 0.f, 0u};
                 if (a.units_per_row >= kThreads) {
                     // ---- long rows: a work item is 1024 consecutive units of one row (4 loads in
                     //      flight per lane); the row is located once per item, not per unit
-                    constexpr uint32_t CH = U * kThreads;
-                    const uint32_t cpr = (a.units_per_row + CH - 1u) / CH;
                     const uint64_t n_items = (uint64_t)n_rows * cpr;
-                    for (uint64_t it = blockIdx.x; it < n_items; it += gridDim.x) {
+                    bool first = true;
+                    for (uint64_t it = blockIdx.x; it < n_items; it += gridDim.x, first = false) {
                         const uint32_t g = cpr == 1u ? (uint32_t)it : (uint32_t)(it / cpr);
                         const uint32_t c_begin = (uint32_t)(it - (uint64_t)g * cpr) * CH + tid;
-                        const RowRef ref = locate(g);
+                        RowRef ref;
+                        unit_t v[U];
+                        if (first && pre) {
+                            ref = pre_ref;
+#pragma unroll
+                            for (uint32_t k = 0; k < U; k++) v[k] = pre_v[k];
+                        } else {
+                            ref = locate(g);
+#pragma unroll
+                            for (uint32_t k = 0; k < U; k++) {
+                                const uint32_t c = c_begin + k * kThreads;
+                                v[k] = unit_t{};
+                                if (c < a.units_per_row) v[k] = load_unit(ref, c);
+                            }
+                        }
                         if (!ref.ok && c_begin == 0) atomicAdd((unsigned long long *)&a.ctrl->bad_rows, 1ull);
                         const uint64_t row_off = off_payload + (uint64_t)g * a.units_per_row * NB_OUT;
-                        unit_t v[U];
-#pragma unroll
-                        for (uint32_t k = 0; k < U; k++) {
-                            const uint32_t c = c_begin + k * kThreads;
-                            v[k] = unit_t{};
-                            if (c < a.units_per_row) v[k] = load_unit(ref, c);
-                        }
 #pragma unroll
                         for (uint32_t k = 0; k < U; k++) {
                             const uint32_t c = c_begin + k * kThreads;
@@ -610,27 +702,32 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
         } else {
             // ---- row-wise pass with summaries: a workgroup (or a wavefront) per row,
             //      4 loads in flight per lane
-            constexpr uint32_t U = 4;
-            const uint32_t rpw = a.rows_per_wg;
-            const uint32_t gsz = kThreads / rpw;            // lanes per row: 256 or 64
-            const uint32_t sub = tid / gsz, l = tid - sub * gsz;
             float *red = reinterpret_cast<float *>(lds + m.red);
-            for (uint64_t g0 = (uint64_t)blockIdx.x * rpw; g0 < n_rows; g0 += (uint64_t)gridDim.x * rpw) {
+            bool first = true;
+            for (uint64_t g0 = (uint64_t)blockIdx.x * rpw; g0 < n_rows;
+                 g0 += (uint64_t)gridDim.x * rpw, first = false) {
                 const uint32_t g = (uint32_t)(g0 + sub);
                 const bool active = g0 + sub < n_rows;
-                Accum acc = {0.f, 0.f, 0.f};
+                Accum acc = {0.f, 0.f, 0u};
                 if (active) {
-                    const RowRef ref = locate(g);
-                    if (!ref.ok && l == 0) atomicAdd((unsigned long long *)&a.ctrl->bad_rows, 1ull);
-                    const uint64_t row_off = off_payload + (uint64_t)g * a.units_per_row * NB_OUT;
-                    for (uint32_t c0 = l; c0 < a.units_per_row; c0 += gsz * U) {
-                        unit_t v[U];
+                    RowRef ref;
+                    unit_t v[U];
+                    if (first && pre) {
+                        ref = pre_ref;
+#pragma unroll
+                        for (uint32_t k = 0; k < U; k++) v[k] = pre_v[k];
+                    } else {
+                        ref = locate(g);
 #pragma unroll
                         for (uint32_t k = 0; k < U; k++) {
-                            const uint32_t c = c0 + k * gsz;
+                            const uint32_t c = l + k * gsz;
                             v[k] = unit_t{};
                             if (c < a.units_per_row) v[k] = load_unit(ref, c);
                         }
+                    }
+                    if (!ref.ok && l == 0) atomicAdd((unsigned long long *)&a.ctrl->bad_rows, 1ull);
+                    const uint64_t row_off = off_payload + (uint64_t)g * a.units_per_row * NB_OUT;
+                    for (uint32_t c0 = l;;) {
 #pragma unroll
                         for (uint32_t k = 0; k < U; k++) {
                             const uint32_t c = c0 + k * gsz;
@@ -638,24 +735,41 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
                                 emit_unit<ES_IN, VEC, OUT, true>(w, row_off + (uint64_t)c * NB_OUT, v[k],
                                                                  a.src_dtype, acc);
                         }
+                        c0 += gsz * U;
+                        if (c0 >= a.units_per_row) break;
+#pragma unroll
+                        for (uint32_t k = 0; k < U; k++) {
+                            const uint32_t c = c0 + k * gsz;
+                            v[k] = unit_t{};
+                            if (c < a.units_per_row) v[k] = load_unit(ref, c);
+                        }
                     }
                 }
+                DMI_STAMP(5);
                 acc.ss = wave_sum(acc.ss);
                 acc.s = wave_sum(acc.s);
-                acc.am = wave_max(acc.am);
+                uint32_t am = wave_max_u32(fold_am<ES_IN, VEC>(acc.am));
+                DMI_STAMP(6);
                 if (rpw == 1u) {
                     __syncthreads();        // previous iteration's readers are done with red[]
-                    if (lane == 0) { red[wave] = acc.ss; red[4 + wave] = acc.s; red[8 + wave] = acc.am; }
+                    if (lane == 0) {
+                        red[wave] = acc.ss;
+                        red[4 + wave] = acc.s;
+                        reinterpret_cast<uint32_t *>(red)[8 + wave] = am;
+                    }
                     __syncthreads();
                     acc.ss = (red[0] + red[1]) + (red[2] + red[3]);
                     acc.s = (red[4] + red[5]) + (red[6] + red[7]);
-                    acc.am = fmaxf(fmaxf(red[8], red[9]), fmaxf(red[10], red[11]));
+                    const uint32_t *ra = reinterpret_cast<const uint32_t *>(red) + 8;
+                    const uint32_t m01 = ra[0] > ra[1] ? ra[0] : ra[1], m23 = ra[2] > ra[3] ? ra[2] : ra[3];
+                    am = m01 > m23 ? m01 : m23;
                 }
+                DMI_STAMP(7);
                 if (active && l == 0) {
                     uint64_t o = off_sum + (uint64_t)g * 4u;
                     if (a.summary_mask & 1u) { ring_store<float>(w, o, sqrtf(acc.ss)); o += sum_arr; }
                     if (a.summary_mask & 2u) { ring_store<float>(w, o, acc.s / (float)a.row_elems); o += sum_arr; }
-                    if (a.summary_mask & 4u) { ring_store<float>(w, o, acc.am); }
+                    if (a.summary_mask & 4u) { ring_store<float>(w, o, am_value(am, a.src_dtype)); }
                 }
             }
         }
@@ -669,6 +783,147 @@ extern "C" int dmi_trace_read(uint64_t *out)
     return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_trace), sizeof(uint64_t) * 256 * 8);
 }
 #endif
+
+// ---------------------------------------------------------------- decode-shaped capture
+// The common case of the paper's workloads (every layer's hidden state at a decode step):
+// bf16 rows, one per request, no keep mask.  Everything about the record except its place
+// in the ring is known on the host, so the kernel is straight-line: a workgroup per row
+// issues its loads at once, an extra workgroup writes header, table and pads and publishes.
+// A small capture is bound by instructions issued and dependent memory trips, not by
+// bytes; the general kernel above executes several times as many instructions per row.
+template <int OUT, bool SUMM>
+__global__ void __launch_bounds__(kThreads) capture_decode_kernel(const CaptureArgs a)
+{
+    __shared__ uint32_t sh[24];
+    constexpr uint32_t U = 4;
+    constexpr uint32_t NB_OUT = out_unit_bytes<2, 8, OUT>();
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const uint32_t par = (uint32_t)a.seq & 1u;
+    const bool meta_wg = blockIdx.x == a.n_reqs;
+    constexpr uint32_t kCtlTid = kThreads - 64u;
+
+    u32x4 v[U];
+    bool ok = false;
+    if (!meta_wg) {
+        const uint32_t g = blockIdx.x;
+        const int64_t row = a.row_index ? (int64_t)a.row_index[g] : (int64_t)a.row0[g];
+        ok = row >= 0 && row < a.n_src_rows;
+        const uint8_t *base = a.src + (ok ? row : 0) * a.row_stride_b;
+#pragma unroll
+        for (uint32_t k = 0; k < U; k++) {
+            const uint32_t c = tid + k * kThreads;
+            v[k] = u32x4{0u, 0u, 0u, 0u};
+            if (ok && c < a.units_per_row) v[k] = *reinterpret_cast<const u32x4 *>(base + (uint64_t)c * 16u);
+        }
+    }
+    uint64_t cnt_cap[3] = {0, 0, 0}, cnt_drop[3] = {0, 0, 0}, tail_now = 0;
+    if (tid == kCtlTid) {
+        const DevCtrl *c = a.ctrl;
+        const uint64_t h = c->head[par];
+        uint64_t t = a.tail_floor;
+        if (a.drop_newest) {
+            const uint64_t tp = c->tail_for[par];
+            t = tp > t ? tp : t;
+        }
+        if (meta_wg) {
+            cnt_cap[0] = c->captured_records; cnt_cap[1] = c->captured_rows; cnt_cap[2] = c->captured_bytes;
+            cnt_drop[0] = c->dropped_records; cnt_drop[1] = c->dropped_rows; cnt_drop[2] = c->dropped_bytes;
+            tail_now = ld_agent(&c->tail);
+        }
+        const uint64_t base = h % a.cap;
+        sh[0] = (uint32_t)h;    sh[1] = (uint32_t)(h >> 32);
+        sh[2] = (uint32_t)t;    sh[3] = (uint32_t)(t >> 32);
+        sh[4] = (uint32_t)base; sh[5] = (uint32_t)(base >> 32);
+    }
+    __syncthreads();
+    const uint64_t head = (uint64_t)sh[0] | ((uint64_t)sh[1] << 32);
+    const uint64_t tail = (uint64_t)sh[2] | ((uint64_t)sh[3] << 32);
+    const bool dropped = a.drop_newest && head - tail + a.record_bytes > a.cap;
+    RingW w;
+    w.ring = a.ring;
+    w.cap = a.cap;
+    w.base = (uint64_t)sh[4] | ((uint64_t)sh[5] << 32);
+    const uint32_t n_rows = a.n_reqs;
+
+    if (meta_wg) {
+        if (tid == kCtlTid) {
+            DevCtrl *c = a.ctrl;
+            const uint64_t new_head = dropped ? head : head + a.record_bytes;
+            if (dropped) {
+                cnt_drop[0] += 1; cnt_drop[1] += n_rows; cnt_drop[2] += a.record_bytes;
+                c->dropped_records = cnt_drop[0]; c->dropped_rows = cnt_drop[1]; c->dropped_bytes = cnt_drop[2];
+                c->point_drops[a.point_id & 4095u] += 1;
+            } else {
+                cnt_cap[0] += 1; cnt_cap[1] += n_rows; cnt_cap[2] += a.record_bytes;
+                c->captured_records = cnt_cap[0]; c->captured_rows = cnt_cap[1]; c->captured_bytes = cnt_cap[2];
+            }
+            c->head[par ^ 1u] = new_head;
+            c->tail_for[par ^ 1u] = tail_now;
+            CommitSlot *h = a.cslot;
+            h->head = new_head;
+            h->captured_records = cnt_cap[0]; h->captured_rows = cnt_cap[1]; h->captured_bytes = cnt_cap[2];
+            h->dropped_records = cnt_drop[0]; h->dropped_rows = cnt_drop[1]; h->dropped_bytes = cnt_drop[2];
+            h->seq_plus1 = a.seq + 1u;
+        }
+        if (dropped) return;
+        if (tid < 4) {
+            u32x4 hv = {a.hdr[4 * tid], a.hdr[4 * tid + 1], a.hdr[4 * tid + 2], a.hdr[4 * tid + 3]};
+            ring_store<u32x4>(w, 16u * tid, hv);
+        }
+        const uint32_t tab_slots = (uint32_t)((a.off_payload - 64u) / 16u);
+        for (uint32_t r = tid; r < tab_slots; r += kThreads) {
+            u32x4 tv = {0u, 0u, 0u, 0u};
+            if (r < n_rows) {
+                const uint4 e = a.req_table[r];
+                tv.x = e.x; tv.y = e.y; tv.z = e.z; tv.w = e.w;
+            }
+            ring_store<u32x4>(w, 64u + 16ull * r, tv);
+        }
+        const uint32_t pad = (uint32_t)(a.off_sum - a.off_payload - a.payload_bytes);
+        if (tid < pad) ring_store<uint8_t>(w, a.off_payload + a.payload_bytes + tid, (uint8_t)0);
+        const uint32_t n_sum = __popc(a.summary_mask & 7u);
+        const uint32_t spad = (uint32_t)(a.sum_arr - (uint64_t)n_rows * 4u) / 4u;
+        for (uint32_t k = tid; k < n_sum * spad; k += kThreads) {
+            const uint32_t arr = k / spad, i = k - arr * spad;
+            ring_store<uint32_t>(w, a.off_sum + arr * a.sum_arr + (uint64_t)n_rows * 4u + 4ull * i, 0u);
+        }
+        return;
+    }
+
+    if (dropped) return;
+    const uint32_t g = blockIdx.x;
+    if (!ok && tid == 0) atomicAdd((unsigned long long *)&a.ctrl->bad_rows, 1ull);
+    Accum acc = {0.f, 0.f, 0u};
+    const uint64_t row_off = a.off_payload + (uint64_t)g * a.units_per_row * NB_OUT;
+#pragma unroll
+    for (uint32_t k = 0; k < U; k++) {
+        const uint32_t c = tid + k * kThreads;
+        if (c < a.units_per_row)
+            emit_unit<2, 8, OUT, SUMM>(w, row_off + (uint64_t)c * NB_OUT, v[k], 1u, acc);
+    }
+    if constexpr (SUMM) {
+        acc.ss = wave_sum(acc.ss);
+        acc.s = wave_sum(acc.s);
+        uint32_t am = wave_max_u32(fold_am<2, 8>(acc.am));
+        float *red = reinterpret_cast<float *>(sh + 8);
+        if (lane == 0) {
+            red[wave] = acc.ss;
+            red[4 + wave] = acc.s;
+            sh[16 + wave] = am;
+        }
+        __syncthreads();
+        if (tid == 0) {
+            const float ss = (red[0] + red[1]) + (red[2] + red[3]);
+            const float sm = (red[4] + red[5]) + (red[6] + red[7]);
+            const uint32_t m01 = sh[16] > sh[17] ? sh[16] : sh[17], m23 = sh[18] > sh[19] ? sh[18] : sh[19];
+            am = m01 > m23 ? m01 : m23;
+            uint64_t o = a.off_sum + (uint64_t)g * 4u;
+            if (a.summary_mask & 1u) { ring_store<float>(w, o, sqrtf(ss)); o += a.sum_arr; }
+            if (a.summary_mask & 2u) { ring_store<float>(w, o, sm / (float)a.row_elems); o += a.sum_arr; }
+            if (a.summary_mask & 4u) { ring_store<float>(w, o, __uint_as_float(am << 16)); }
+        }
+    }
+}
 
 // ---------------------------------------------------------------- small kernels
 struct UploadChunk {
@@ -743,6 +998,34 @@ hipError_t launch_capture(const CaptureArgs &a, uint32_t grid, bool vec16, hipSt
     const bool four = a.src_dtype == 3;
     if (four) return vec16 ? launch_o<4, 4>(a, grid, s) : launch_o<4, 1>(a, grid, s);
     return vec16 ? launch_o<2, 8>(a, grid, s) : launch_o<2, 1>(a, grid, s);
+}
+
+bool decode_kernel_applies(const CaptureArgs &a, bool vec16)
+{
+    return a.simple && !a.paged && vec16 && a.src_dtype == 1u && a.units_per_row <= 4u * kThreads &&
+           a.n_reqs >= 1u;
+}
+
+template <int OUT>
+static hipError_t launch_decode_t(const CaptureArgs &a, hipStream_t s)
+{
+    const dim3 grid(a.n_reqs + 1u);
+    if (a.summary_mask)
+        hipLaunchKernelGGL((capture_decode_kernel<OUT, true>), grid, dim3(kThreads), 0, s, a);
+    else
+        hipLaunchKernelGGL((capture_decode_kernel<OUT, false>), grid, dim3(kThreads), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_capture_decode(const CaptureArgs &a, hipStream_t s)
+{
+    switch (a.out_dtype) {
+    case 0: return launch_decode_t<OUT_NONE>(a, s);
+    case 1: return launch_decode_t<OUT_RAW>(a, s);
+    case 2: return launch_decode_t<OUT_FP16>(a, s);
+    case 4: return launch_decode_t<OUT_FP8>(a, s);
+    default: return hipErrorInvalidValue;
+    }
 }
 
 hipError_t launch_upload(uint32_t *dst, const uint32_t *words, uint32_t n_words, hipStream_t s)

@@ -77,7 +77,7 @@ def run_workload_gpu(wl, *, drain_every: int = 1, release: bool = True, collect:
                      max_steps=None, lockstep: bool = True, on_record=None,
                      block_timeout_ms: int = 1, poison: Optional[int] = None,
                      ring: Optional[B.Ring] = None, drain_flags: int = 0,
-                     bg_min_bytes: int = 0) -> GpuRun:
+                     bg_min_bytes: int = 0, before_observe: Optional[Callable] = None) -> GpuRun:
     """Lockstep schedule (the one the oracle's model follows): a step's observes,
     then every `drain_every` steps a flush-drain followed by poll + release.
     With lockstep=False the drain after a step moves only what has committed by
@@ -98,6 +98,8 @@ def run_workload_gpu(wl, *, drain_every: int = 1, release: bool = True, collect:
             if max_steps is not None and step >= max_steps:
                 break
             for c in calls:
+                if before_observe is not None:
+                    before_observe(c, s.cuda_stream)       # e.g. the model compute that produces the tensor
                 rc = observe_call(ring, c, s.cuda_stream, keep_alive, allow=(B.ERR_AGAIN,))
                 tries = 0
                 while rc == B.ERR_AGAIN:
