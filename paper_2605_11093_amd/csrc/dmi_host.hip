@@ -66,7 +66,6 @@ bool transform_ok(uint32_t src, uint32_t out)
 }
 
 constexpr uint32_t kSlabSlots = 64;
-constexpr uint32_t kTailVals = 4096;
 constexpr uint32_t kSelCache = 4;
 
 struct SelCache {
@@ -100,9 +99,6 @@ struct dmi_ring {
     DevCtrl *dctrl = nullptr;
     CommitSlot *hslots = nullptr, *hslots_dev = nullptr;   // pinned mirror of DevCtrl::slots
     hipStream_t ctl_stream = nullptr;                      // fetches commit slots
-    bool use_copy_ctl = false;
-    uint64_t *tail_vals = nullptr;                         // pinned staging for tail values
-    uint32_t tail_rr = 0;
     uint32_t *slab = nullptr;
     uint32_t slab_slot_words = 0, next_slab = 0, max_reqs = 0;
     SelCache cache[kSelCache];
@@ -170,11 +166,7 @@ dmi_status_t record_probe(dmi_ring *r)
     const uint32_t slot = (uint32_t)((launched - 1u) % kCommitSlots);
     HIP_TRY(hipEventRecord(ev[0], (hipStream_t)r->last_stream.load(std::memory_order_acquire)));
     HIP_TRY(hipStreamWaitEvent(r->ctl_stream, ev[0], 0));
-    if (r->use_copy_ctl)
-        HIP_TRY(hipMemcpyAsync((void *)(r->hslots + slot), &r->dctrl->slots[slot], sizeof(CommitSlot),
-                               hipMemcpyDeviceToHost, r->ctl_stream));
-    else
-        HIP_TRY(launch_fetch_slot(&r->dctrl->slots[slot], r->hslots_dev + slot, r->ctl_stream));
+    HIP_TRY(launch_fetch_slot(&r->dctrl->slots[slot], r->hslots_dev + slot, r->ctl_stream));
     HIP_TRY(hipEventRecord(ev[1], r->ctl_stream));
     r->probes.push_back({ev[0], ev[1], launched});
     r->probed_upto = launched;
@@ -261,13 +253,7 @@ dmi_status_t drain_issue_locked(dmi_ring *r, uint64_t *moved)
             }
         }
         // the device may reuse the span only after the copies before this have run
-        if (r->use_copy_ctl) {
-            uint64_t *slot = r->tail_vals + (r->tail_rr++ % kTailVals);
-            *slot = from + n;
-            HIP_TRY(hipMemcpyAsync(&r->dctrl->tail, slot, 8, hipMemcpyHostToDevice, r->drain_stream));
-        } else {
-            HIP_TRY(launch_set_tail(r->dctrl, from + n, r->drain_stream));
-        }
+        HIP_TRY(launch_set_tail(r->dctrl, from + n, r->drain_stream));
         hipEvent_t ev;
         if (r->ev_pool.empty()) HIP_TRY(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
         else { ev = r->ev_pool.back(); r->ev_pool.pop_back(); }
@@ -449,7 +435,9 @@ dmi_status_t observe_common(dmi_ring *r, uint32_t point_id, const dmi_selection_
                   (index_mode ? DMI_REC_INDEXED : 0u);
     a.row_elems = geo.row_elems;
     a.units_per_row = (uint32_t)upr;
-    a.rows_per_wg = upr <= 128u ? 4u : 1u;
+    // a wavefront per row when rows are short, or of moderate length and plentiful (no block-level
+    // reduction, four rows in flight per workgroup); otherwise a workgroup per row
+    a.rows_per_wg = (upr <= 128u || (upr <= 1024u && listed >= 2048u)) ? 4u : 1u;
     a.point_id = point_id;
     a.rank_tag = r->cfg.rank_tag;
     a.seq = seq;
@@ -470,6 +458,8 @@ dmi_status_t observe_common(dmi_ring *r, uint32_t point_id, const dmi_selection_
 
     uint64_t groups;
     if (xf->summary_mask) groups = (listed + a.rows_per_wg - 1u) / a.rows_per_wg;
+    else if (upr >= kThreads && upr < 4u * kThreads && (4u * kThreads) % upr == 0)
+        groups = (listed + 4u * kThreads / upr - 1u) / (4u * kThreads / upr);      // 2 or 4 rows per work item
     else if (upr >= kThreads) groups = listed * ((upr + 4u * kThreads - 1u) / (4u * kThreads));
     else groups = (listed * upr + kThreads - 1u) / kThreads;
     uint32_t grid = groups < 1u ? 1u : groups > kMaxGrid ? kMaxGrid : (uint32_t)groups;
@@ -570,7 +560,7 @@ void bg_loop(dmi_ring *r)
             waiting_since = 0;
             if (moved) continue;
         }
-        std::this_thread::sleep_for(std::chrono::microseconds(getenv("DMI_BG_SLEEP_US") ? atoi(getenv("DMI_BG_SLEEP_US")) : 20));
+        std::this_thread::sleep_for(std::chrono::microseconds(20));
     }
 }
 
@@ -588,7 +578,6 @@ void free_ring(dmi_ring *r)
     if (r->slab) (void)hipFree(r->slab);
     if (r->host_ring) (void)hipHostFree(r->host_ring);
     if (r->hslots) (void)hipHostFree((void *)r->hslots);
-    if (r->tail_vals) (void)hipHostFree(r->tail_vals);
     delete r;
 }
 
@@ -659,9 +648,6 @@ dmi_status_t dmi_ring_create(const dmi_ring_config_t *cfg, dmi_ring_t **out)
     if ((e = hipHostGetDevicePointer((void **)&r->hslots_dev, (void *)r->hslots, 0)) != hipSuccess)
         return bail(e, "hipHostGetDevicePointer(commit slots)");
     memset((void *)r->hslots, 0, sizeof(CommitSlot) * kCommitSlots);
-    if ((e = hipHostMalloc((void **)&r->tail_vals, sizeof(uint64_t) * kTailVals, hipHostMallocDefault)) != hipSuccess)
-        return bail(e, "hipHostMalloc(tail staging)");
-    r->use_copy_ctl = getenv("DMI_COPY_CTL") != nullptr;
     {
         DevCtrl *init = new (std::nothrow) DevCtrl;
         if (!init) { free_ring(r); return fail(DMI_ERR_NOMEM, "out of host memory"); }

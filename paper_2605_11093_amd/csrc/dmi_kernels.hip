@@ -327,7 +327,8 @@ uint32_t capture_lds_bytes(uint32_t n_reqs, bool index_mode, bool table_in_lds)
 // Where one output row comes from.
 struct RowRef {
     const uint8_t *base;    // dense: first byte of the row; paged: first byte of the slot
-    bool ok;
+    uint64_t ok;            // 0 if a device-side index left the source (a full word: the struct
+                            // is copied around and should stay in registers)
 };
 
 // Optional phase timestamps (development builds with -DDMI_TRACE only).
@@ -459,9 +460,10 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
     const uint32_t sub = tid / gsz, l = tid - sub * gsz;
     const uint32_t cpr = (a.units_per_row + CH - 1u) / CH;  // long-row items per row
     unit_t pre_v[U];
-    RowRef pre_ref = {nullptr, false};
+    RowRef pre_ref = {nullptr, 0};
     bool pre = false;
-    if (simple && !a.paged && (SUMM || (OUT != OUT_NONE && a.units_per_row >= kThreads))) {
+    const bool multi_row_items = a.units_per_row < CH && CH % a.units_per_row == 0u;
+    if (simple && !a.paged && (SUMM || (OUT != OUT_NONE && a.units_per_row >= kThreads && !multi_row_items))) {
         uint32_t g, c_begin, stride;
         if constexpr (SUMM) { g = blockIdx.x * rpw + sub; c_begin = l; stride = gsz; }
         else { g = blockIdx.x / cpr; c_begin = (blockIdx.x - g * cpr) * CH + tid; stride = kThreads; }
@@ -634,36 +636,78 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
             if constexpr (OUT != OUT_NONE) {
                 Accum dummy = {0.f, 0.f, 0u};
                 if (a.units_per_row >= kThreads) {
-                    // ---- long rows: a work item is 1024 consecutive units of one row (4 loads in
-                    //      flight per lane); the row is located once per item, not per unit
-                    const uint64_t n_items = (uint64_t)n_rows * cpr;
-                    bool first = true;
-                    for (uint64_t it = blockIdx.x; it < n_items; it += gridDim.x, first = false) {
-                        const uint32_t g = cpr == 1u ? (uint32_t)it : (uint32_t)(it / cpr);
-                        const uint32_t c_begin = (uint32_t)(it - (uint64_t)g * cpr) * CH + tid;
-                        RowRef ref;
-                        unit_t v[U];
-                        if (first && pre) {
-                            ref = pre_ref;
-#pragma unroll
-                            for (uint32_t k = 0; k < U; k++) v[k] = pre_v[k];
-                        } else {
-                            ref = locate(g);
-#pragma unroll
-                            for (uint32_t k = 0; k < U; k++) {
-                                const uint32_t c = c_begin + k * kThreads;
-                                v[k] = unit_t{};
-                                if (c < a.units_per_row) v[k] = load_unit(ref, c);
-                            }
-                        }
-                        if (!ref.ok && c_begin == 0) atomicAdd((unsigned long long *)&a.ctrl->bad_rows, 1ull);
-                        const uint64_t row_off = off_payload + (uint64_t)g * a.units_per_row * NB_OUT;
+                    // ---- long rows: a work item is 1024 consecutive units: a quarter or more of one
+                    //      row, or 2 / 4 whole rows of 512 / 256 units; rows are located once per
+                    //      item, not per unit.  Software pipelined: the next item's 4 loads per lane
+                    //      are in flight while this one is converted and stored.
+                    const uint32_t rpi = (a.units_per_row < CH && CH % a.units_per_row == 0u)
+                                             ? CH / a.units_per_row : 1u;          // rows per item
+                    const uint64_t n_items = rpi > 1u ? ((uint64_t)n_rows + rpi - 1u) / rpi
+                                                      : (uint64_t)n_rows * cpr;
+                    // unit k of this lane in item `it`: its flat position in the payload, loaded value
+                    auto fetch = [&](uint64_t it, unit_t (&v)[U], uint64_t (&pos)[U], bool (&live)[U]) {
+                        RowRef ref = {nullptr, 0};
+                        uint32_t g_prev = 0xFFFFFFFFu;
 #pragma unroll
                         for (uint32_t k = 0; k < U; k++) {
-                            const uint32_t c = c_begin + k * kThreads;
-                            if (c < a.units_per_row)
-                                emit_unit<ES_IN, VEC, OUT, false>(w, row_off + (uint64_t)c * NB_OUT, v[k],
-                                                                  a.src_dtype, dummy);
+                            uint32_t g, c;
+                            if (rpi > 1u) {
+                                const uint32_t idx = k * kThreads + tid;
+                                const uint32_t rk = idx >> a.upr_shift;        // units_per_row is 256 or 512
+                                g = (uint32_t)it * rpi + rk;
+                                c = idx - (rk << a.upr_shift);
+                            } else {
+                                g = cpr == 1u ? (uint32_t)it : (uint32_t)(it / cpr);
+                                c = (uint32_t)(it - (uint64_t)g * cpr) * CH + k * kThreads + tid;
+                            }
+                            live[k] = g < n_rows && c < a.units_per_row;
+                            pos[k] = (uint64_t)g * a.units_per_row + c;
+                            v[k] = unit_t{};
+                            if (live[k]) {
+                                if (g != g_prev) {
+                                    ref = locate(g);
+                                    g_prev = g;
+                                    if (!ref.ok && c == 0) atomicAdd((unsigned long long *)&a.ctrl->bad_rows, 1ull);
+                                }
+                                v[k] = load_unit(ref, c);
+                            }
+                        }
+                    };
+                    uint64_t it = blockIdx.x;
+                    if (it < n_items) {
+                        unit_t v[U];
+                        uint64_t pos[U];
+                        bool live[U];
+                        if (pre) {      // decode-shaped, rows of >= 1024 units handled one per item
+                            const uint32_t g = cpr == 1u ? (uint32_t)it : (uint32_t)(it / cpr);
+                            const uint32_t c0 = (uint32_t)(it - (uint64_t)g * cpr) * CH + tid;
+#pragma unroll
+                            for (uint32_t k = 0; k < U; k++) {
+                                const uint32_t c = c0 + k * kThreads;
+                                v[k] = pre_v[k];
+                                live[k] = c < a.units_per_row;
+                                pos[k] = (uint64_t)g * a.units_per_row + c;
+                            }
+                            if (!pre_ref.ok && c0 == 0) atomicAdd((unsigned long long *)&a.ctrl->bad_rows, 1ull);
+                        } else {
+                            fetch(it, v, pos, live);
+                        }
+                        for (;;) {
+                            const uint64_t nxt = it + gridDim.x;
+                            const bool more = nxt < n_items;
+                            unit_t v_n[U];
+                            uint64_t pos_n[U];
+                            bool live_n[U];
+                            if (more) fetch(nxt, v_n, pos_n, live_n);
+#pragma unroll
+                            for (uint32_t k = 0; k < U; k++)
+                                if (live[k])
+                                    emit_unit<ES_IN, VEC, OUT, false>(w, off_payload + pos[k] * NB_OUT, v[k],
+                                                                      a.src_dtype, dummy);
+                            if (!more) break;
+                            it = nxt;
+#pragma unroll
+                            for (uint32_t k = 0; k < U; k++) { v[k] = v_n[k]; pos[k] = pos_n[k]; live[k] = live_n[k]; }
                         }
                     }
                 } else {
@@ -700,76 +744,97 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
                 }
             }
         } else {
-            // ---- row-wise pass with summaries: a workgroup (or a wavefront) per row,
-            //      4 loads in flight per lane
+            // ---- row-wise pass with summaries: a workgroup (or a wavefront) per row.  A step is
+            //      4 units per lane of one row; rows longer than that take several steps.  Steps
+            //      are software pipelined (the next step's loads are issued before this step is
+            //      converted, stored and accumulated), across row boundaries too.
             float *red = reinterpret_cast<float *>(lds + m.red);
-            bool first = true;
-            for (uint64_t g0 = (uint64_t)blockIdx.x * rpw; g0 < n_rows;
-                 g0 += (uint64_t)gridDim.x * rpw, first = false) {
-                const uint32_t g = (uint32_t)(g0 + sub);
-                const bool active = g0 + sub < n_rows;
-                Accum acc = {0.f, 0.f, 0u};
-                if (active) {
-                    RowRef ref;
-                    unit_t v[U];
-                    if (first && pre) {
-                        ref = pre_ref;
-#pragma unroll
-                        for (uint32_t k = 0; k < U; k++) v[k] = pre_v[k];
-                    } else {
-                        ref = locate(g);
-#pragma unroll
-                        for (uint32_t k = 0; k < U; k++) {
-                            const uint32_t c = l + k * gsz;
-                            v[k] = unit_t{};
-                            if (c < a.units_per_row) v[k] = load_unit(ref, c);
-                        }
+            const uint32_t spr = (a.units_per_row + gsz * U - 1u) / (gsz * U);     // steps per row
+            const uint64_t row_stride_g = (uint64_t)gridDim.x * rpw;
+            // a step = (g0: first row of the workgroup's current group, pass)
+            auto fetch = [&](uint64_t st_g0, uint32_t st_pass, RowRef &ref, unit_t (&v)[U]) {
+                const uint64_t g = st_g0 + sub;
+                if (g < n_rows) {
+                    if (st_pass == 0) {
+                        ref = locate((uint32_t)g);
+                        if (!ref.ok && l == 0) atomicAdd((unsigned long long *)&a.ctrl->bad_rows, 1ull);
                     }
-                    if (!ref.ok && l == 0) atomicAdd((unsigned long long *)&a.ctrl->bad_rows, 1ull);
-                    const uint64_t row_off = off_payload + (uint64_t)g * a.units_per_row * NB_OUT;
-                    for (uint32_t c0 = l;;) {
+#pragma unroll
+                    for (uint32_t k = 0; k < U; k++) {
+                        const uint32_t c = l + (st_pass * U + k) * gsz;
+                        v[k] = unit_t{};
+                        if (c < a.units_per_row) v[k] = load_unit(ref, c);
+                    }
+                }
+            };
+            uint64_t cur_g0 = (uint64_t)blockIdx.x * rpw;
+            uint32_t cur_pass = 0;
+            if (cur_g0 < n_rows) {
+                RowRef ref = {nullptr, 0};
+                unit_t v[U];
+                if (pre) {
+                    ref = pre_ref;
+#pragma unroll
+                    for (uint32_t k = 0; k < U; k++) v[k] = pre_v[k];
+                } else {
+                    fetch(cur_g0, cur_pass, ref, v);
+                }
+                Accum acc = {0.f, 0.f, 0u};
+                for (;;) {
+                    uint64_t nxt_g0 = cur_g0;
+                    uint32_t nxt_pass = cur_pass + 1u;
+                    if (nxt_pass == spr) { nxt_pass = 0; nxt_g0 += row_stride_g; }
+                    const bool more = nxt_g0 < n_rows;
+                    RowRef ref_n = ref;             // a later pass of the same row keeps the row
+                    unit_t v_n[U];
+                    if (more) fetch(nxt_g0, nxt_pass, ref_n, v_n);
+                    const uint64_t g = cur_g0 + sub;
+                    const bool active = g < n_rows;
+                    if (active) {
+                        const uint64_t row_off = off_payload + g * a.units_per_row * NB_OUT;
 #pragma unroll
                         for (uint32_t k = 0; k < U; k++) {
-                            const uint32_t c = c0 + k * gsz;
+                            const uint32_t c = l + (cur_pass * U + k) * gsz;
                             if (c < a.units_per_row)
                                 emit_unit<ES_IN, VEC, OUT, true>(w, row_off + (uint64_t)c * NB_OUT, v[k],
                                                                  a.src_dtype, acc);
                         }
-                        c0 += gsz * U;
-                        if (c0 >= a.units_per_row) break;
-#pragma unroll
-                        for (uint32_t k = 0; k < U; k++) {
-                            const uint32_t c = c0 + k * gsz;
-                            v[k] = unit_t{};
-                            if (c < a.units_per_row) v[k] = load_unit(ref, c);
+                    }
+                    if (cur_pass == spr - 1u) {     // the row is complete: reduce and store its summaries
+                        DMI_STAMP(5);
+                        acc.ss = wave_sum(acc.ss);
+                        acc.s = wave_sum(acc.s);
+                        uint32_t am = wave_max_u32(fold_am<ES_IN, VEC>(acc.am));
+                        DMI_STAMP(6);
+                        if (rpw == 1u) {
+                            __syncthreads();        // the previous row's readers are done with red[]
+                            if (lane == 0) {
+                                red[wave] = acc.ss;
+                                red[4 + wave] = acc.s;
+                                reinterpret_cast<uint32_t *>(red)[8 + wave] = am;
+                            }
+                            __syncthreads();
+                            acc.ss = (red[0] + red[1]) + (red[2] + red[3]);
+                            acc.s = (red[4] + red[5]) + (red[6] + red[7]);
+                            const uint32_t *ra = reinterpret_cast<const uint32_t *>(red) + 8;
+                            const uint32_t m01 = ra[0] > ra[1] ? ra[0] : ra[1], m23 = ra[2] > ra[3] ? ra[2] : ra[3];
+                            am = m01 > m23 ? m01 : m23;
                         }
+                        DMI_STAMP(7);
+                        if (active && l == 0) {
+                            uint64_t o = off_sum + g * 4u;
+                            if (a.summary_mask & 1u) { ring_store<float>(w, o, sqrtf(acc.ss)); o += sum_arr; }
+                            if (a.summary_mask & 2u) { ring_store<float>(w, o, acc.s / (float)a.row_elems); o += sum_arr; }
+                            if (a.summary_mask & 4u) { ring_store<float>(w, o, am_value(am, a.src_dtype)); }
+                        }
+                        acc = Accum{0.f, 0.f, 0u};
                     }
-                }
-                DMI_STAMP(5);
-                acc.ss = wave_sum(acc.ss);
-                acc.s = wave_sum(acc.s);
-                uint32_t am = wave_max_u32(fold_am<ES_IN, VEC>(acc.am));
-                DMI_STAMP(6);
-                if (rpw == 1u) {
-                    __syncthreads();        // previous iteration's readers are done with red[]
-                    if (lane == 0) {
-                        red[wave] = acc.ss;
-                        red[4 + wave] = acc.s;
-                        reinterpret_cast<uint32_t *>(red)[8 + wave] = am;
-                    }
-                    __syncthreads();
-                    acc.ss = (red[0] + red[1]) + (red[2] + red[3]);
-                    acc.s = (red[4] + red[5]) + (red[6] + red[7]);
-                    const uint32_t *ra = reinterpret_cast<const uint32_t *>(red) + 8;
-                    const uint32_t m01 = ra[0] > ra[1] ? ra[0] : ra[1], m23 = ra[2] > ra[3] ? ra[2] : ra[3];
-                    am = m01 > m23 ? m01 : m23;
-                }
-                DMI_STAMP(7);
-                if (active && l == 0) {
-                    uint64_t o = off_sum + (uint64_t)g * 4u;
-                    if (a.summary_mask & 1u) { ring_store<float>(w, o, sqrtf(acc.ss)); o += sum_arr; }
-                    if (a.summary_mask & 2u) { ring_store<float>(w, o, acc.s / (float)a.row_elems); o += sum_arr; }
-                    if (a.summary_mask & 4u) { ring_store<float>(w, o, am_value(am, a.src_dtype)); }
+                    if (!more) break;
+                    cur_g0 = nxt_g0;
+                    cur_pass = nxt_pass;
+                    ref = ref_n;
+#pragma unroll
+                    for (uint32_t k = 0; k < U; k++) v[k] = v_n[k];
                 }
             }
         }
