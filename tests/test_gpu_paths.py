@@ -1,0 +1,207 @@
+"""Every copy path of the capture kernels, with records wrapping the device ring at
+varying offsets, and the device-side bounds handling.  Streams are compared with
+the oracle's (bit-exact except the fp32 summaries, see _util)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as orc
+from oracle.decode import decode_record
+from oracle.stream import OracleRing, POLICY_BLOCK
+from workloads import configs, prng
+from _util import compare_record, compare_streams
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def B():
+    assert torch.cuda.is_available()
+    from paper_2605_11093_amd import binding
+    binding.lib()
+    return binding
+
+
+def _stream_through_small_ring(B, make_call_args, n_obs, rec_bytes, paged=None):
+    """n_obs observes through a device ring of ~2.3 records (so that records wrap at
+    many different offsets) under the completeness policy; returns (gpu stream, oracle stream)."""
+    dev_cap = max(4096, (int(rec_bytes * 2.3) // 64 + 1) * 64)
+    host_cap = max(4096, (int(rec_bytes * 3.1) // 64 + 1) * 64)
+    ref = OracleRing(dev_cap, host_cap, POLICY_BLOCK)
+    got = []
+    with B.Ring(dev_cap, host_cap, block_timeout_ms=1, max_reqs_per_observe=4096) as ring:
+        ring.debug_fill_rings(0xA5)
+        s = torch.cuda.current_stream()
+
+        def consume():
+            vs = ring.poll_host()
+            for v in vs:
+                got.append(v.bytes())
+            if vs:
+                ring.release_host(vs[-1].seq)
+            seqs = ref.polled_seqs()
+            if seqs:
+                ref.release(seqs[-1])
+
+        for i in range(n_obs):
+            tensor, reqs, kw, okw = make_call_args(i)
+            while True:
+                if paged is None:
+                    rc = ring.observe_tensor(i % 5, tensor, reqs, step_id=i, stream=s.cuda_stream,
+                                             allow=(B.ERR_AGAIN,), **kw)
+                else:
+                    rc = ring.observe_paged(i % 5, tensor, paged.block_table, reqs, block_size=paged.block_size,
+                                            n_heads=paged.n_heads, head_dim=paged.head_dim,
+                                            heads_sel=paged.heads_sel, step_id=i, stream=s.cuda_stream,
+                                            allow=(B.ERR_AGAIN,), **kw)
+                if rc != B.ERR_AGAIN:
+                    break
+                s.synchronize()
+                ring.drain(B.DRAIN_FLUSH, allow=(B.ERR_AGAIN,))
+                consume()
+            cpu_paged = None if paged is None else configs.PagedSpec(paged.block_size, paged.n_heads, paged.head_dim,
+                                                                     paged.heads_sel, paged.block_table.cpu())
+            while True:
+                rc = ref.observe(tensor.cpu(), reqs, point_id=i % 5, step_id=i, paged=cpu_paged, **okw)
+                if rc != -5:
+                    break
+                ref.drain()
+                seqs = ref.polled_seqs()
+                if seqs:
+                    ref.release(seqs[-1])
+            assert rc == 0
+        s.synchronize()
+        for _ in range(1000):
+            ring.drain(B.DRAIN_FLUSH, allow=(B.ERR_AGAIN,))
+            consume()
+            if ring.last_drain_status == B.OK:
+                break
+        st = ring.get_stats()
+        assert st.dropped_records == 0 and st.bad_rows == 0
+    while ref.drained < ref.appended:
+        ref.drain()
+        seqs = ref.polled_seqs()
+        if seqs:
+            ref.release(seqs[-1])
+    return np.concatenate(got), ref.stream()
+
+
+CASES = {
+    # name: (T, E, dtype, reqs builder, out_dtype, summary_mask)
+    "decode_lean_sum": (64, 4096, torch.bfloat16, "ones", 1, 5),
+    "decode_lean_fp8": (256, 8192, torch.bfloat16, "ones", 4, 0),
+    "decode_generic_fp16src": (64, 4096, torch.float16, "ones", 2, 7),
+    "decode_generic_fp32src": (48, 1024, torch.float32, "ones", 3, 0),
+    "long_rows_single_item": (300, 14336, torch.bfloat16, "ragged", 4, 0),
+    "long_rows_multi_item": (40, 20480, torch.bfloat16, "ragged", 1, 0),
+    "multi_row_items_512": (900, 4096, torch.bfloat16, "ragged", 4, 0),
+    "multi_row_items_256": (900, 2048, torch.bfloat16, "ragged", 1, 0),
+    "summ_wg_per_row_multipass": (60, 14336, torch.bfloat16, "ragged", 1, 7),
+    "summ_wave_per_row_mid": (5000, 2048, torch.bfloat16, "ragged", 4, 5),
+    "summ_wave_per_row_short": (700, 512, torch.bfloat16, "ragged", 2, 7),
+    "short_rows_flat": (3000, 256, torch.bfloat16, "ragged", 1, 0),
+    "elementwise_odd": (120, 1001, torch.bfloat16, "ragged", 4, 7),
+    "summary_only_long": (2100, 8192, torch.bfloat16, "ragged", 0, 7),
+}
+
+
+@pytest.mark.parametrize("name", sorted(CASES))
+def test_path_through_a_wrapping_ring(B, name):
+    T, E, dt, kind, out_dtype, sm = CASES[name]
+    pool = [prng.randn_bf16(prng.sub_seed(31, len(name), k), T * E, DEV).view(T, E).to(dt) for k in range(2)]
+    if kind == "ones":
+        reqs = np.array([(i, i, 0, 1, 1) for i in range(T)], dtype=np.uint32)
+    else:
+        n = 7
+        per = T // n
+        reqs = np.array([(100 + i, i * per, i % 3, max(1, (per - 3) // (1 + i % 2)), 1 + i % 2) for i in range(n)],
+                        dtype=np.uint32)
+    rows = int(reqs[:, 3].sum())
+    rec = orc.record_bytes(len(reqs), rows, E, out_dtype, sm)
+
+    def args(i):
+        kw = dict(out_dtype=out_dtype, summary_mask=sm)
+        return pool[i % 2], reqs, kw, kw
+
+    got, ref = _stream_through_small_ring(B, args, 9, rec)
+    compare_streams(got, ref)
+
+
+def test_paged_path_through_a_wrapping_ring(B):
+    NB, BS, NH, HD = 256, 16, 8, 128
+    cache = prng.randn_bf16(prng.sub_seed(32, 1), NB * BS * NH * HD, DEV).view(NB, BS, NH, HD)
+    table = torch.from_numpy(prng.permutation(5, NB).astype(np.int32).reshape(8, 32)).to(DEV)
+    spec = configs.PagedSpec(BS, NH, HD, [1, 5], table)
+    reqs = np.array([(1, 0, 0, 500, 1), (2, 3, 7, 300, 1), (3, 7, 0, 170, 3)], dtype=np.uint32)
+    rec = orc.record_bytes(3, 970, 256, 1, 0)
+
+    def args(i):
+        kw = dict(out_dtype=1 if i % 2 else 4, summary_mask=0)
+        return cache, reqs, kw, kw
+
+    got, ref = _stream_through_small_ring(B, args, 8, rec, paged=spec)
+    compare_streams(got, ref)
+
+
+def test_four_thousand_requests_with_mask_and_index(B):
+    n = 4096
+    t = prng.randn_bf16(prng.sub_seed(33, 1), 6000 * 128, DEV).view(6000, 128)
+    reqs = np.array([(i, i, 0, 1 + (i % 3 == 0), 1) for i in range(n)], dtype=np.uint32)
+    mask = (np.arange(n) % 5 != 2).astype(np.uint8)
+    listed = int(reqs[:, 3].sum())
+    idx = ((np.arange(listed) * 7919) % 6000).astype(np.int32)
+    with B.Ring(1 << 23, 1 << 23, max_reqs_per_observe=4096) as ring:
+        s = torch.cuda.current_stream()
+        km = torch.from_numpy(mask).to(DEV)
+        ri = torch.from_numpy(idx).to(DEV)
+        ring.observe_tensor(0, t, reqs, step_id=0, stream=s.cuda_stream, keep_mask=km, summary_mask=7)
+        ring.observe_tensor(1, t, reqs, step_id=0, stream=s.cuda_stream, keep_mask=km, row_index=ri, out_dtype=4)
+        ring.observe_tensor(2, t, reqs, step_id=0, stream=s.cuda_stream, row_index=ri)
+        ring.drain(B.DRAIN_FLUSH)
+        v = ring.poll_host()
+        assert len(v) == 3
+        tc = t.cpu()
+        compare_record(v[0].bytes(), orc.build_record(tc, reqs, seq=0, step_id=0, point_id=0, out_dtype=1,
+                                                      summary_mask=7, keep_mask=mask))
+        compare_record(v[1].bytes(), orc.build_record(tc, reqs, seq=1, step_id=0, point_id=1, out_dtype=4,
+                                                      keep_mask=mask, row_index=idx))
+        compare_record(v[2].bytes(), orc.build_record(tc, reqs, seq=2, step_id=0, point_id=2, out_dtype=1,
+                                                      row_index=idx))
+
+
+def test_out_of_range_device_indices_give_zero_rows_and_are_counted(B):
+    t = prng.randn_bf16(prng.sub_seed(34, 1), 50 * 512, DEV).view(50, 512)
+    reqs = np.array([(i, 0, 0, 1, 1) for i in range(6)], dtype=np.uint32)
+    idx = np.array([3, 50, 7, -1, 49, 1 << 20], dtype=np.int32)          # three of them leave the tensor
+    with B.Ring(1 << 20, 1 << 20) as ring:
+        s = torch.cuda.current_stream()
+        ri = torch.from_numpy(idx).to(DEV)
+        ring.observe_tensor(0, t, reqs, step_id=0, stream=s.cuda_stream, row_index=ri, summary_mask=5)
+        ring.drain(B.DRAIN_FLUSH)
+        r = decode_record(ring.poll_host()[0].bytes())
+        bits = t.cpu().view(torch.int16).numpy().astype(np.uint16)
+        for g, src in enumerate(idx):
+            if 0 <= src < 50:
+                assert (r.payload[g] == bits[src]).all()
+            else:
+                assert not r.payload[g].any() and r.summaries[1][g] == 0 and r.summaries[4][g] == 0
+        assert ring.get_stats().bad_rows == 3
+    # a block-table entry beyond the cache
+    NB, BS, NH, HD = 8, 16, 2, 128
+    cache = prng.randn_bf16(prng.sub_seed(34, 2), NB * BS * NH * HD, DEV).view(NB, BS, NH, HD)
+    table = torch.tensor([[0, 9, 2, 3]], dtype=torch.int32, device=DEV)    # 9 >= NB
+    with B.Ring(1 << 20, 1 << 20) as ring:
+        s = torch.cuda.current_stream()
+        ring.observe_paged(0, cache, table, np.array([(1, 0, 0, 40, 1)], np.uint32), block_size=BS, n_heads=NH,
+                           head_dim=HD, heads_sel=[1], step_id=0, stream=s.cuda_stream)
+        ring.drain(B.DRAIN_FLUSH)
+        r = decode_record(ring.poll_host()[0].bytes())
+        bits = cache.cpu().view(torch.int16).numpy().astype(np.uint16)
+        for tkn in range(40):
+            blk = [0, 9, 2, 3][tkn // BS]
+            if blk < NB:
+                assert (r.payload[tkn] == bits[blk, tkn % BS, 1]).all()
+            else:
+                assert not r.payload[tkn].any()
+        assert ring.get_stats().bad_rows == 16
