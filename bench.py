@@ -29,8 +29,8 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0           # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the config-2 capture kernel, from the two rocprofv3 --pmc runs
 # summarised in profiles/capture_kernel_config2_config3mlp.md (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000,
-# factors from a plain 256 MiB copy): 0.695 MB read + 0.530 MB written.
-TRAFFIC_CONFIG2_BYTES = 1225000
+# factors from a plain 256 MiB copy): 0.627 MB read + 0.530 MB written.
+TRAFFIC_CONFIG2_BYTES = 1157000
 SEED_NOTE = "synthetic (seeded ~N(0,1) bf16, shapes of the paper's LLM workloads)"
 
 
@@ -476,7 +476,7 @@ def main():
                                "64 requests x 1 row, raw bf16 + L2 + absmax per row, device ring 256 MiB, "
                                "host ring 2 GiB, policy block",
                    "bytes_per_step": step_bytes, "drain": "copy engine, issued by the producer thread each step"},
-        "roofline": {"bound": "hbm", "kernel": "capture_kernel<bf16, vec16, raw, summaries> (config 2 record)",
+        "roofline": {"bound": "hbm", "kernel": "capture_decode_kernel<raw, summaries> (config 2 record)",
                      "achieved": round(cap_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(cap_gbs / HBM_PEAK_GBS, 4), "us_per_launch": round(cap_us, 3),
                      "algorithmic_bytes_per_launch": alg_bytes, "traffic": TRAFFIC_CONFIG2_BYTES},
