@@ -358,13 +358,14 @@ def main():
             # (a real 8B prefill layer over ~35k tokens takes several times longer)
             bench_lib.dmi_bench_sleep(stream_handle, 2000)
 
-        def timed_replay(name, w, block_timeout_ms=2000):
+        def timed_replay(name, w, block_timeout_ms=2000, compute=True):
             rr = B.Ring(w.device_ring_bytes, w.host_ring_bytes, flags=B.BG_THREAD,
                         max_reqs_per_observe=w.max_reqs, block_timeout_ms=block_timeout_ms)
             rr.set_policy(w.policy_mode, w.sample_k, 0)
             torch.cuda.synchronize()
             t = time.perf_counter()
-            run = run_workload_gpu(w, collect=False, lockstep=False, ring=rr, before_observe=model_compute)
+            run = run_workload_gpu(w, collect=False, lockstep=False, ring=rr,
+                                   before_observe=model_compute if compute else None)
             dt = time.perf_counter() - t
             stt = run.stats
             rr.destroy()
@@ -373,13 +374,19 @@ def main():
                          "frac_of_d2h_peak": round(stt.drained_bytes / dt / 1e9 / d2h_peak, 3),
                          "dropped_fraction": round(stt.dropped_bytes / tot, 4) if tot else 0.0,
                          "records": stt.launched_records, "seconds": round(dt, 3),
-                         "model_compute_stand_in": "2 ms sleep kernel before every observe"}
+                         "model_compute_stand_in": "2 ms sleep kernel before every observe" if compute
+                         else "none: captures issued back to back, the host link is the limit"}
             log(f"end to end {name}: {e2e[name]}")
 
-        timed_replay("config3_prefill_4steps", configs.config3_prefill(device=dev, n_steps=4))
+        w3e = configs.config3_prefill(device=dev, n_steps=4)
+        timed_replay("config3_prefill_4steps", w3e)
+        timed_replay("config3_prefill_4steps_back_to_back", w3e, compute=False)
+        del w3e
         torch.cuda.empty_cache()
-        timed_replay("config4_paged_kv_12steps", configs.config4_paged_kv(device=dev, n_steps=12),
-                     block_timeout_ms=5000)
+        w4e = configs.config4_paged_kv(device=dev, n_steps=12)
+        timed_replay("config4_paged_kv_12steps", w4e, block_timeout_ms=5000)
+        timed_replay("config4_paged_kv_12steps_back_to_back", w4e, block_timeout_ms=5000, compute=False)
+        del w4e
         torch.cuda.empty_cache()
         extra["end_to_end"] = e2e
 

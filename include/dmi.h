@@ -237,6 +237,35 @@ dmi_status_t dmi_poll_host(dmi_ring_t *ring, dmi_record_view_t *out /*[host]*/, 
 /* Give back every polled record with seq <= upto_seq_inclusive. */
 dmi_status_t dmi_release_host(dmi_ring_t *ring, uint64_t upto_seq_inclusive);
 
+/*
+ * Exporter stages 2-3 (section 4.3): a library thread takes whole records out of the
+ * pinned host ring, copies each into pageable memory, gives the pinned space back at once
+ * (pinned memory is the scarce resource), rebuilds shape and dtype from the header and
+ * slices the record by request.  While the exporter runs it is the ring's only consumer:
+ * do not call dmi_poll_host / dmi_release_host yourself.  The queue of finished slices is
+ * bounded by max_pageable_bytes; when it is full the exporter waits, and the pressure
+ * travels back through the host ring to the device ring, where the backpressure policy
+ * decides (stall or drop).
+ */
+typedef struct {
+    uint64_t seq, step_id;
+    uint32_t point_id, rank_tag;
+    uint32_t req_index;         /* position of the request in the record's table */
+    uint32_t req_id, tok_start, tok_step;
+    uint32_t n_rows, row_elems; /* this request's rows: token tok_start + j*tok_step is row j */
+    uint32_t src_dtype, out_dtype, summary_mask, flags;
+    const void *rows;           /* [host, pageable] n_rows x row_elems of out_dtype; NULL if NONE */
+    const float *l2, *mean, *absmax;    /* n_rows values each, NULL if not requested */
+    void *owner;                /* the record copy this slice points into (library-owned) */
+} dmi_slice_t;
+dmi_status_t dmi_exporter_start(dmi_ring_t *ring, uint64_t max_pageable_bytes);
+/* Next slice in (seq, request) order; waits up to timeout_ms, then DMI_ERR_AGAIN. */
+dmi_status_t dmi_exporter_next(dmi_ring_t *ring, dmi_slice_t *out /*[host]*/, uint32_t timeout_ms);
+/* Done with a slice; the record copy is freed when all of its slices have been released. */
+dmi_status_t dmi_exporter_release(dmi_ring_t *ring, const dmi_slice_t *slice /*[host]*/);
+/* Stops the thread; slices not yet handed out are discarded. */
+dmi_status_t dmi_exporter_stop(dmi_ring_t *ring);
+
 /* Backpressure policy (section 4.4), effective from the next dmi_observe. */
 typedef struct {
     uint32_t mode;              /* DMI_POLICY_* */
@@ -244,6 +273,43 @@ typedef struct {
     uint32_t sample_phase;      /* < sample_k */
 } dmi_policy_t;
 dmi_status_t dmi_set_policy(dmi_ring_t *ring, const dmi_policy_t *policy /*[host]*/);
+
+/*
+ * Request-granular best effort (section 4.4, "best-effort policy" and Fig. "drop-recent"):
+ * when the ring is under pressure, decide on the host, before the forward step, which
+ * requests of the batch stay observed; the kernels then see the decision as a keep vector.
+ *   DMI_SELECT_DROP_RECENT      the most recently admitted requests are dropped first
+ *   DMI_SELECT_KEEP_BY_PATTERN  requests matching the user's predicate are kept first;
+ *                               within each class the most recently admitted go first
+ * dmi_policy_select is a pure host function: it orders the requests (matching ones first
+ * under KEEP_BY_PATTERN, then by admit_order ascending, ties by position), and keeps the
+ * longest prefix of that order whose cost, sum(rows) * bytes_per_row, fits budget_bytes.
+ * keep[i] [host, n_reqs bytes] is set to 1 or 0 in the caller's request order.
+ */
+enum { DMI_SELECT_DROP_RECENT = 0, DMI_SELECT_KEEP_BY_PATTERN = 1 };
+typedef struct {
+    uint32_t req_id;
+    uint32_t rows;          /* rows the request contributes per observe in the coming step */
+    uint64_t admit_order;   /* smaller = admitted earlier */
+    uint32_t matches;       /* KEEP_BY_PATTERN: non-zero if the predicate holds for the request */
+    uint32_t reserved;
+} dmi_req_info_t;
+dmi_status_t dmi_policy_select(uint32_t strategy, const dmi_req_info_t *reqs /*[host]*/, uint32_t n_reqs,
+                               uint64_t bytes_per_row, uint64_t budget_bytes, uint8_t *keep /*[host]*/,
+                               uint32_t *n_kept /*[host, optional]*/);
+
+/* Room the device ring is sure to have once everything launched so far has run (capacity
+ * minus an upper bound of undrained bytes): the budget a policy manager works with.
+ * Producer thread only. */
+dmi_status_t dmi_ring_free_bytes(dmi_ring_t *ring, uint64_t *free_bytes /*[host]*/);
+
+/* Copy a keep vector into a library-owned device buffer, ordered on hip_stream before any
+ * later work of that stream.  *keep_mask_dev [device] may be passed as
+ * dmi_selection_t::keep_mask_dev by observes issued on the same stream; it stays valid for
+ * the next three calls of this function.  Updating the vector between steps does not
+ * change what is launched, only what the launches copy (section 4.4). */
+dmi_status_t dmi_set_keep_mask(dmi_ring_t *ring, const uint8_t *keep /*[host]*/, uint32_t n_reqs,
+                               void *hip_stream, const uint8_t **keep_mask_dev /*[host]*/);
 
 /* Hook filtering (section 4.4): a disabled point launches nothing. */
 dmi_status_t dmi_point_enable(dmi_ring_t *ring, uint32_t point_id, int enabled);

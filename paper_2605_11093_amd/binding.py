@@ -71,6 +71,20 @@ class RecordViewC(C.Structure):
                 ("seq", C.c_uint64)]
 
 
+class ReqInfo(C.Structure):
+    _fields_ = [("req_id", C.c_uint32), ("rows", C.c_uint32), ("admit_order", C.c_uint64),
+                ("matches", C.c_uint32), ("reserved", C.c_uint32)]
+
+
+class SliceC(C.Structure):
+    _fields_ = [("seq", C.c_uint64), ("step_id", C.c_uint64), ("point_id", C.c_uint32), ("rank_tag", C.c_uint32),
+                ("req_index", C.c_uint32), ("req_id", C.c_uint32), ("tok_start", C.c_uint32),
+                ("tok_step", C.c_uint32), ("n_rows", C.c_uint32), ("row_elems", C.c_uint32),
+                ("src_dtype", C.c_uint32), ("out_dtype", C.c_uint32), ("summary_mask", C.c_uint32),
+                ("flags", C.c_uint32), ("rows", C.c_void_p), ("l2", C.c_void_p), ("mean", C.c_void_p),
+                ("absmax", C.c_void_p), ("owner", C.c_void_p)]
+
+
 class Policy(C.Structure):
     _fields_ = [("mode", C.c_uint32), ("sample_k", C.c_uint32), ("sample_phase", C.c_uint32)]
 
@@ -160,9 +174,19 @@ def lib():
     L.dmi_get_stats.argtypes = [C.c_void_p, P(StatsC)]
     L.dmi_get_point_drops.argtypes = [C.c_void_p, C.c_uint32, P(C.c_uint64)]
     L.dmi_debug_fill_rings.argtypes = [C.c_void_p, C.c_uint8]
+    L.dmi_exporter_start.argtypes = [C.c_void_p, C.c_uint64]
+    L.dmi_exporter_next.argtypes = [C.c_void_p, P(SliceC), C.c_uint32]
+    L.dmi_exporter_release.argtypes = [C.c_void_p, P(SliceC)]
+    L.dmi_exporter_stop.argtypes = [C.c_void_p]
+    L.dmi_policy_select.argtypes = [C.c_uint32, P(ReqInfo), C.c_uint32, C.c_uint64, C.c_uint64, C.c_void_p,
+                                    P(C.c_uint32)]
+    L.dmi_ring_free_bytes.argtypes = [C.c_void_p, P(C.c_uint64)]
+    L.dmi_set_keep_mask.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, P(C.c_void_p)]
     for name in ("dmi_ring_create", "dmi_ring_destroy", "dmi_observe", "dmi_observe_paged", "dmi_drain",
                  "dmi_poll_host", "dmi_release_host", "dmi_set_policy", "dmi_point_enable",
-                 "dmi_get_stats", "dmi_get_point_drops", "dmi_debug_fill_rings"):
+                 "dmi_get_stats", "dmi_get_point_drops", "dmi_debug_fill_rings", "dmi_policy_select",
+                 "dmi_ring_free_bytes", "dmi_set_keep_mask", "dmi_exporter_start", "dmi_exporter_next",
+                 "dmi_exporter_release", "dmi_exporter_stop"):
         getattr(L, name).restype = C.c_int32
     _lib = L
     return L
@@ -174,6 +198,21 @@ def version() -> str:
 
 def record_bytes(n_reqs: int, n_rows: int, row_elems: int, out_dtype: int, summary_mask: int) -> int:
     return int(lib().dmi_record_bytes(n_reqs, n_rows, row_elems, out_dtype, summary_mask))
+
+
+SELECT_DROP_RECENT, SELECT_KEEP_BY_PATTERN = 0, 1
+
+
+def policy_select(strategy: int, reqs, bytes_per_row: int, budget_bytes: int) -> np.ndarray:
+    """reqs: iterable of (req_id, rows, admit_order, matches).  Returns the keep vector (uint8)."""
+    rows = list(reqs)
+    arr = (ReqInfo * max(1, len(rows)))(*[ReqInfo(int(a), int(b), int(c), int(d), 0) for a, b, c, d in rows])
+    keep = np.zeros(len(rows), dtype=np.uint8)
+    n = C.c_uint32()
+    _check(lib().dmi_policy_select(strategy, arr, len(rows), bytes_per_row, budget_bytes,
+                                   keep.ctypes.data if len(rows) else None, C.byref(n)))
+    assert int(n.value) == int(keep.sum())
+    return keep
 
 
 def _check(code: int, allow: Sequence[int] = ()) -> int:
@@ -341,6 +380,35 @@ class Ring:
         n = C.c_uint64()
         _check(lib().dmi_get_point_drops(self._h, point_id, C.byref(n)))
         return int(n.value)
+
+    def free_bytes(self) -> int:
+        n = C.c_uint64()
+        _check(lib().dmi_ring_free_bytes(self._h, C.byref(n)))
+        return int(n.value)
+
+    def set_keep_mask(self, keep, stream: int = 0) -> int:
+        """Upload a keep vector; returns the device address to pass as keep_mask_dev."""
+        k = np.ascontiguousarray(np.asarray(keep, dtype=np.uint8))
+        out = C.c_void_p()
+        _check(lib().dmi_set_keep_mask(self._h, k.ctypes.data if k.size else None, k.size, stream or None,
+                                       C.byref(out)))
+        return int(out.value or 0)
+
+    # -- exporter stages 2-3 -----------------------------------------------
+    def exporter_start(self, max_pageable_bytes: int):
+        _check(lib().dmi_exporter_start(self._h, max_pageable_bytes))
+
+    def exporter_next(self, timeout_ms: int = 100) -> Optional["SliceC"]:
+        """The next per-request slice, or None after timeout_ms.  Release it when done."""
+        sl = SliceC()
+        rc = _check(lib().dmi_exporter_next(self._h, C.byref(sl), timeout_ms), allow=(ERR_AGAIN,))
+        return None if rc == ERR_AGAIN else sl
+
+    def exporter_release(self, sl: "SliceC"):
+        _check(lib().dmi_exporter_release(self._h, C.byref(sl)))
+
+    def exporter_stop(self):
+        _check(lib().dmi_exporter_stop(self._h))
 
     def debug_fill_rings(self, value: int):
         _check(lib().dmi_debug_fill_rings(self._h, value))

@@ -4,8 +4,10 @@
 #include "dmi.h"
 #include "dmi_internal.h"
 
+#include <algorithm>
 #include <atomic>
 #include <chrono>
+#include <condition_variable>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -81,6 +83,13 @@ struct Pending {
     uint64_t upto;
 };
 
+// One record copied out of the pinned ring (exporter stage 2) and shared by its slices.
+struct RecordCopy {
+    uint8_t *bytes;
+    uint64_t size;
+    std::atomic<uint32_t> refs;
+};
+
 struct Probe {
     hipEvent_t ev_user;     // recorded on the producer's stream behind the launches
     hipEvent_t ev_done;     // recorded on the control stream behind the slot fetch
@@ -99,6 +108,8 @@ struct dmi_ring {
     DevCtrl *dctrl = nullptr;
     CommitSlot *hslots = nullptr, *hslots_dev = nullptr;   // pinned mirror of DevCtrl::slots
     hipStream_t ctl_stream = nullptr;                      // fetches commit slots
+    uint8_t *mask_buf = nullptr;                           // 4 rotating keep vectors of max_reqs bytes
+    uint32_t mask_rr = 0, mask_stride = 0;
     uint32_t *slab = nullptr;
     uint32_t slab_slot_words = 0, next_slab = 0, max_reqs = 0;
     SelCache cache[kSelCache];
@@ -141,6 +152,15 @@ struct dmi_ring {
 
     std::thread bg;
     std::atomic<bool> stop{false};
+
+    // exporter stages 2-3
+    std::thread exporter;
+    std::atomic<bool> exp_stop{false}, exp_running{false};
+    std::mutex emu;
+    std::condition_variable ecv_data, ecv_space;
+    std::deque<dmi_slice_t> slices;
+    uint64_t exp_bytes = 0, exp_max_bytes = 0;
+    std::atomic<uint64_t> exp_records{0}, exp_copied_bytes{0};
 };
 
 namespace {
@@ -576,9 +596,102 @@ void free_ring(dmi_ring *r)
     if (r->dev_ring) (void)hipFree(r->dev_ring);
     if (r->dctrl) (void)hipFree(r->dctrl);
     if (r->slab) (void)hipFree(r->slab);
+    if (r->mask_buf) (void)hipFree(r->mask_buf);
     if (r->host_ring) (void)hipHostFree(r->host_ring);
     if (r->hslots) (void)hipHostFree((void *)r->hslots);
     delete r;
+}
+
+dmi_status_t poll_host_impl(dmi_ring *r, dmi_record_view_t *out, uint32_t max, uint32_t *n);
+dmi_status_t release_host_impl(dmi_ring *r, uint64_t upto);
+
+// Exporter thread: pinned ring -> pageable copies -> per-request slices.
+void exporter_loop(dmi_ring *r)
+{
+    (void)hipSetDevice(r->dev);
+    dmi_record_view_t views[64];
+    while (!r->exp_stop.load(std::memory_order_acquire)) {
+        uint32_t n = 0;
+        if (poll_host_impl(r, views, 64, &n) != DMI_OK || n == 0) {
+            std::this_thread::sleep_for(std::chrono::microseconds(50));
+            continue;
+        }
+        for (uint32_t i = 0; i < n && !r->exp_stop.load(std::memory_order_acquire); i++) {
+            const dmi_record_view_t &v = views[i];
+            const uint64_t size = v.n0 + v.n1;
+            {   // bounded queue: wait for room (this is where back-pressure starts)
+                std::unique_lock<std::mutex> lk(r->emu);
+                r->ecv_space.wait(lk, [&] {
+                    return r->exp_stop.load() || r->exp_bytes == 0 || r->exp_bytes + size <= r->exp_max_bytes;
+                });
+                if (r->exp_stop.load()) break;
+                r->exp_bytes += size;
+            }
+            RecordCopy *rc = new RecordCopy;
+            rc->bytes = static_cast<uint8_t *>(malloc(size));
+            rc->size = size;
+            memcpy(rc->bytes, v.p0, v.n0);
+            if (v.n1) memcpy(rc->bytes + v.n0, v.p1, v.n1);
+            (void)release_host_impl(r, v.seq);          // pinned space is free again
+            r->exp_records++;
+            r->exp_copied_bytes += size;
+
+            // stage 3: shape / dtype from the header, one slice per request with rows
+            const uint8_t *b = rc->bytes;
+            uint32_t n_reqs, n_rows, row_elems, point_id, rank_tag;
+            uint64_t seq, step_id, payload_bytes;
+            memcpy(&seq, b + 8, 8);
+            memcpy(&step_id, b + 16, 8);
+            memcpy(&point_id, b + 24, 4);
+            memcpy(&n_reqs, b + 32, 4);
+            memcpy(&n_rows, b + 36, 4);
+            memcpy(&row_elems, b + 40, 4);
+            memcpy(&rank_tag, b + 44, 4);
+            memcpy(&payload_bytes, b + 56, 8);
+            const uint32_t src_dtype = b[28], out_dtype = b[29], smask = b[30], flags = b[31];
+            const uint64_t es = dtype_size(out_dtype);
+            const uint8_t *table = b + DMI_HEADER_BYTES;
+            const uint8_t *payload = table + pad64((uint64_t)n_reqs * 16u);
+            const uint8_t *sums = payload + pad64(payload_bytes);
+            const uint64_t sum_arr = pad64((uint64_t)n_rows * 4u);
+            const float *arr[3] = {nullptr, nullptr, nullptr};
+            {
+                const uint8_t *p = sums;
+                for (int bit = 0; bit < 3; bit++)
+                    if (smask & (1u << bit)) { arr[bit] = reinterpret_cast<const float *>(p); p += sum_arr; }
+            }
+            std::vector<dmi_slice_t> made;
+            uint64_t row0 = 0;
+            for (uint32_t q = 0; q < n_reqs; q++) {
+                uint32_t e[4];
+                memcpy(e, table + 16ull * q, 16);
+                if (e[3] == 0) continue;
+                dmi_slice_t sl;
+                memset(&sl, 0, sizeof sl);
+                sl.seq = seq; sl.step_id = step_id; sl.point_id = point_id; sl.rank_tag = rank_tag;
+                sl.req_index = q; sl.req_id = e[0]; sl.tok_start = e[1]; sl.tok_step = e[2]; sl.n_rows = e[3];
+                sl.row_elems = row_elems; sl.src_dtype = src_dtype; sl.out_dtype = out_dtype;
+                sl.summary_mask = smask; sl.flags = flags;
+                sl.rows = es ? payload + row0 * row_elems * es : nullptr;
+                sl.l2 = arr[0] ? arr[0] + row0 : nullptr;
+                sl.mean = arr[1] ? arr[1] + row0 : nullptr;
+                sl.absmax = arr[2] ? arr[2] + row0 : nullptr;
+                sl.owner = rc;
+                made.push_back(sl);
+                row0 += e[3];
+            }
+            std::lock_guard<std::mutex> lk(r->emu);
+            if (made.empty()) {         // nothing to hand out: the copy goes at once
+                r->exp_bytes -= size;
+                free(rc->bytes);
+                delete rc;
+            } else {
+                rc->refs.store((uint32_t)made.size());
+                for (auto &sl : made) r->slices.push_back(sl);
+                r->ecv_data.notify_all();
+            }
+        }
+    }
 }
 
 }  // namespace
@@ -636,6 +749,9 @@ dmi_status_t dmi_ring_create(const dmi_ring_config_t *cfg, dmi_ring_t **out)
     if ((e = hipMalloc((void **)&r->dctrl, sizeof(DevCtrl))) != hipSuccess) return bail(e, "hipMalloc(ctrl)");
     if ((e = hipMalloc((void **)&r->slab, (size_t)kSlabSlots * r->slab_slot_words * 4u)) != hipSuccess)
         return bail(e, "hipMalloc(selection slab)");
+    r->mask_stride = (max_reqs + 255u) & ~255u;
+    if ((e = hipMalloc((void **)&r->mask_buf, (size_t)4u * r->mask_stride)) != hipSuccess)
+        return bail(e, "hipMalloc(keep vectors)");
     if ((e = hipHostMalloc((void **)&r->host_ring, r->host_cap, hipHostMallocMapped)) != hipSuccess)
         return bail(e, "hipHostMalloc(host ring)");
     if ((e = hipHostGetDevicePointer((void **)&r->host_ring_dev, r->host_ring, 0)) != hipSuccess)
@@ -670,6 +786,7 @@ dmi_status_t dmi_ring_destroy(dmi_ring_t *r)
 {
     if (!r) return fail(DMI_ERR_INVALID_ARG, "ring is NULL");
     (void)hipSetDevice(r->dev);
+    (void)dmi_exporter_stop(r);
     r->stop.store(true, std::memory_order_release);
     if (r->bg.joinable()) r->bg.join();
     free_ring(r);
@@ -815,6 +932,15 @@ dmi_status_t dmi_drain(dmi_ring_t *r, uint32_t flags, uint64_t *bytes_moved)
 dmi_status_t dmi_poll_host(dmi_ring_t *r, dmi_record_view_t *out, uint32_t max, uint32_t *n)
 {
     if (!r || !n || (max && !out)) return fail(DMI_ERR_INVALID_ARG, "NULL argument");
+    if (r->exp_running.load()) return fail(DMI_ERR_INVALID_ARG, "the exporter is this ring's consumer");
+    return poll_host_impl(r, out, max, n);
+}
+
+}  // extern "C"
+
+namespace {
+dmi_status_t poll_host_impl(dmi_ring *r, dmi_record_view_t *out, uint32_t max, uint32_t *n)
+{
     *n = 0;
     std::lock_guard<std::mutex> lk(r->mu);
     // with the library's drain thread running, arrivals are noted by that thread; a HIP call
@@ -849,15 +975,80 @@ dmi_status_t dmi_poll_host(dmi_ring_t *r, dmi_record_view_t *out, uint32_t max, 
     return DMI_OK;
 }
 
-dmi_status_t dmi_release_host(dmi_ring_t *r, uint64_t upto)
+dmi_status_t release_host_impl(dmi_ring *r, uint64_t upto)
 {
-    if (!r) return fail(DMI_ERR_INVALID_ARG, "ring is NULL");
     std::lock_guard<std::mutex> lk(r->mu);
     while (!r->polled.empty() && r->polled.front().first <= upto) {
         r->released_bytes += r->polled.front().second - r->released;
         r->released = r->polled.front().second;
         r->polled.pop_front();
     }
+    return DMI_OK;
+}
+}  // namespace
+
+extern "C" {
+
+dmi_status_t dmi_release_host(dmi_ring_t *r, uint64_t upto)
+{
+    if (!r) return fail(DMI_ERR_INVALID_ARG, "ring is NULL");
+    if (r->exp_running.load()) return fail(DMI_ERR_INVALID_ARG, "the exporter is this ring's consumer");
+    return release_host_impl(r, upto);
+}
+
+dmi_status_t dmi_exporter_start(dmi_ring_t *r, uint64_t max_pageable_bytes)
+{
+    if (!r || !max_pageable_bytes) return fail(DMI_ERR_INVALID_ARG, "bad argument");
+    if (r->exp_running.exchange(true)) return fail(DMI_ERR_INVALID_ARG, "exporter already running");
+    r->exp_stop.store(false);
+    r->exp_max_bytes = max_pageable_bytes;
+    r->exporter = std::thread(exporter_loop, r);
+    return DMI_OK;
+}
+
+dmi_status_t dmi_exporter_next(dmi_ring_t *r, dmi_slice_t *out, uint32_t timeout_ms)
+{
+    if (!r || !out) return fail(DMI_ERR_INVALID_ARG, "NULL argument");
+    std::unique_lock<std::mutex> lk(r->emu);
+    if (!r->ecv_data.wait_for(lk, std::chrono::milliseconds(timeout_ms), [&] { return !r->slices.empty(); }))
+        return fail(DMI_ERR_AGAIN, "no slice within %u ms", timeout_ms);
+    *out = r->slices.front();
+    r->slices.pop_front();
+    return DMI_OK;
+}
+
+dmi_status_t dmi_exporter_release(dmi_ring_t *r, const dmi_slice_t *sl)
+{
+    if (!r || !sl || !sl->owner) return fail(DMI_ERR_INVALID_ARG, "NULL argument");
+    RecordCopy *rc = static_cast<RecordCopy *>(sl->owner);
+    if (rc->refs.fetch_sub(1) == 1) {
+        {
+            std::lock_guard<std::mutex> lk(r->emu);
+            r->exp_bytes -= rc->size;
+        }
+        r->ecv_space.notify_all();
+        free(rc->bytes);
+        delete rc;
+    }
+    return DMI_OK;
+}
+
+dmi_status_t dmi_exporter_stop(dmi_ring_t *r)
+{
+    if (!r) return fail(DMI_ERR_INVALID_ARG, "ring is NULL");
+    if (!r->exp_running.load()) return DMI_OK;
+    r->exp_stop.store(true);
+    r->ecv_space.notify_all();
+    if (r->exporter.joinable()) r->exporter.join();
+    {   // discard what was not handed out
+        std::lock_guard<std::mutex> lk(r->emu);
+        for (auto &sl : r->slices) {
+            RecordCopy *rc = static_cast<RecordCopy *>(sl.owner);
+            if (rc->refs.fetch_sub(1) == 1) { r->exp_bytes -= rc->size; free(rc->bytes); delete rc; }
+        }
+        r->slices.clear();
+    }
+    r->exp_running.store(false);
     return DMI_OK;
 }
 
@@ -869,6 +1060,66 @@ dmi_status_t dmi_set_policy(dmi_ring_t *r, const dmi_policy_t *p)
     r->mode.store(p->mode);
     r->sample_k.store(p->sample_k);
     r->sample_phase.store(p->sample_phase);
+    return DMI_OK;
+}
+
+dmi_status_t dmi_policy_select(uint32_t strategy, const dmi_req_info_t *reqs, uint32_t n, uint64_t bytes_per_row,
+                               uint64_t budget, uint8_t *keep, uint32_t *n_kept)
+{
+    if (strategy > DMI_SELECT_KEEP_BY_PATTERN) return fail(DMI_ERR_INVALID_ARG, "unknown selection strategy");
+    if (n && (!reqs || !keep)) return fail(DMI_ERR_INVALID_ARG, "NULL argument");
+    std::vector<uint32_t> order(n);
+    for (uint32_t i = 0; i < n; i++) order[i] = i;
+    const bool by_pattern = strategy == DMI_SELECT_KEEP_BY_PATTERN;
+    std::stable_sort(order.begin(), order.end(), [&](uint32_t x, uint32_t y) {
+        if (by_pattern) {
+            const bool mx = reqs[x].matches != 0, my = reqs[y].matches != 0;
+            if (mx != my) return mx;
+        }
+        return reqs[x].admit_order < reqs[y].admit_order;
+    });
+    uint64_t used = 0;
+    uint32_t kept = 0;
+    bool open = true;       // a prefix: once a request does not fit, nothing after it is kept
+    for (uint32_t k = 0; k < n; k++) {
+        const uint32_t i = order[k];
+        const unsigned __int128 cost = (unsigned __int128)reqs[i].rows * bytes_per_row;
+        if (open && cost <= (unsigned __int128)(budget - used)) {
+            used += (uint64_t)cost;
+            keep[i] = 1;
+            kept++;
+        } else {
+            open = false;
+            keep[i] = 0;
+        }
+    }
+    if (n_kept) *n_kept = kept;
+    return DMI_OK;
+}
+
+dmi_status_t dmi_ring_free_bytes(dmi_ring_t *r, uint64_t *free_bytes)
+{
+    if (!r || !free_bytes) return fail(DMI_ERR_INVALID_ARG, "NULL argument");
+    (void)hipSetDevice(r->dev);
+    dmi_status_t st = advance_commits(r, false);
+    if (st != DMI_OK) return st;
+    const uint64_t used = head_upper_bound(r) - r->drain_done.load(std::memory_order_acquire);
+    *free_bytes = used < r->dev_cap ? r->dev_cap - used : 0;
+    return DMI_OK;
+}
+
+dmi_status_t dmi_set_keep_mask(dmi_ring_t *r, const uint8_t *keep, uint32_t n, void *hip_stream,
+                               const uint8_t **keep_mask_dev)
+{
+    if (!r || !keep_mask_dev || (n && !keep)) return fail(DMI_ERR_INVALID_ARG, "NULL argument");
+    if (n > r->max_reqs) return fail(DMI_ERR_INVALID_ARG, "n_reqs %u exceeds max_reqs_per_observe %u", n, r->max_reqs);
+    (void)hipSetDevice(r->dev);
+    uint8_t *dst = r->mask_buf + (size_t)(r->mask_rr++ % 4u) * r->mask_stride;
+    std::vector<uint32_t> words((n + 3u) / 4u, 0u);
+    if (n) memcpy(words.data(), keep, n);
+    if (n) HIP_TRY(launch_upload(reinterpret_cast<uint32_t *>(dst), words.data(), (uint32_t)words.size(),
+                                 (hipStream_t)hip_stream));
+    *keep_mask_dev = dst;
     return DMI_OK;
 }
 

@@ -1,0 +1,91 @@
+"""Request-granular best effort (drop-recent, keep-by-pattern): the library's host
+function against the oracle's definition and against the properties the paper
+states, on the CPU; the resulting keep vector through a capture on the GPU."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import policy as opol
+from paper_2605_11093_amd import binding as B
+
+
+def _random_batch(rng, n):
+    return [(1000 + i, int(rng.integers(0, 9)), int(rng.integers(0, 50)), int(rng.random() < 0.3))
+            for i in range(n)]
+
+
+@pytest.mark.parametrize("strategy", [B.SELECT_DROP_RECENT, B.SELECT_KEEP_BY_PATTERN])
+def test_select_matches_the_oracle_on_random_batches(strategy):
+    rng = np.random.default_rng(7 + strategy)
+    for _ in range(300):
+        reqs = _random_batch(rng, int(rng.integers(0, 40)))
+        bpr = int(rng.integers(1, 5000))
+        budget = int(rng.integers(0, 9 * 40 * 5000 // 3))
+        got = B.policy_select(strategy, reqs, bpr, budget)
+        assert got.tolist() == opol.select(strategy, reqs, bpr, budget)
+
+
+def test_drop_recent_keeps_the_oldest_requests():
+    # admit order 0..7, one row each, 100 bytes per row, room for 5
+    reqs = [(i, 1, 7 - i, 0) for i in range(8)]             # position 0 is the most recent
+    keep = B.policy_select(B.SELECT_DROP_RECENT, reqs, 100, 599)
+    assert keep.tolist() == [0, 0, 0, 1, 1, 1, 1, 1]
+    assert B.policy_select(B.SELECT_DROP_RECENT, reqs, 100, 10 ** 9).all()
+    assert not B.policy_select(B.SELECT_DROP_RECENT, reqs, 100, 99).any()
+
+
+def test_keep_by_pattern_drops_non_matching_first():
+    reqs = [(0, 2, 0, 0), (1, 2, 1, 1), (2, 2, 2, 0), (3, 2, 3, 1), (4, 2, 4, 0)]
+    # budget for three requests: both matching ones, then the oldest of the others
+    assert B.policy_select(B.SELECT_KEEP_BY_PATTERN, reqs, 10, 60).tolist() == [1, 1, 0, 1, 0]
+    # budget for one: the older matching request
+    assert B.policy_select(B.SELECT_KEEP_BY_PATTERN, reqs, 10, 25).tolist() == [0, 1, 0, 0, 0]
+    # same data under drop-recent ignores the predicate
+    assert B.policy_select(B.SELECT_DROP_RECENT, reqs, 10, 60).tolist() == [1, 1, 1, 0, 0]
+
+
+def test_kept_set_is_a_maximal_prefix_of_the_ranking():
+    rng = np.random.default_rng(3)
+    for _ in range(200):
+        reqs = _random_batch(rng, 12)
+        bpr, budget = 64, int(rng.integers(0, 12 * 8 * 64))
+        for strategy in (0, 1):
+            keep = B.policy_select(strategy, reqs, bpr, budget)
+            order = sorted(range(12), key=lambda i: ((0 if (strategy and reqs[i][3]) else strategy), reqs[i][2], i))
+            flags = [int(keep[i]) for i in order]
+            k = sum(flags)
+            assert flags == [1] * k + [0] * (12 - k)                       # a prefix
+            cost = sum(reqs[i][1] for i in order[:k]) * bpr
+            assert cost <= budget
+            if k < 12:
+                assert cost + reqs[order[k]][1] * bpr > budget             # and the next one does not fit
+
+
+@pytest.mark.gpu
+def test_selection_reaches_the_kernel_as_a_keep_vector():
+    import oracle as orc
+    from workloads import prng
+    dev = "cuda:0"
+    t = prng.randn_bf16(prng.sub_seed(41, 1), 64 * 4096, dev).view(64, 4096)
+    reqs = np.array([(500 + i, i, 0, 1, 1) for i in range(64)], dtype=np.uint32)
+    info = [(500 + i, 1, (i * 37) % 64, int(i % 4 == 0)) for i in range(64)]
+    with B.Ring(8 << 20, 16 << 20) as ring:
+        s = torch.cuda.current_stream().cuda_stream
+        free = ring.free_bytes()
+        assert free == 8 << 20
+        per_row = 4096 * 2 * 3                                 # three observation points per step
+        keep = B.policy_select(B.SELECT_KEEP_BY_PATTERN, info, per_row, 20 * per_row)
+        assert keep.sum() == 20 and keep[::4].all()
+        km = ring.set_keep_mask(keep, s)
+        for p in range(3):
+            ring.observe(p, t.data_ptr(), B.DT_BF16, t.shape, t.stride(), reqs, step_id=0, stream=s,
+                         keep_mask_dev=km, summary_mask=5)
+        ring.drain(B.DRAIN_FLUSH)
+        views = ring.poll_host()
+        assert len(views) == 3
+        for p, v in enumerate(views):
+            ref = orc.build_record(t.cpu(), reqs, seq=p, step_id=0, point_id=p, out_dtype=1, summary_mask=5,
+                                   keep_mask=keep)
+            from _util import compare_record
+            compare_record(v.bytes(), ref)
+        assert ring.free_bytes() == (8 << 20)                  # everything drained
