@@ -1,0 +1,74 @@
+"""HookPoint front end (paper section 4.1): an nn.Module that can be put at any tensor
+in a model's forward; reaching it launches one capture on the current stream and
+returns the tensor itself.  No Python callback runs on the GPU's time line, no host
+synchronisation happens, the tensor is neither modified nor retained.
+
+The work is the C ABI's dmi_observe; this file only finds the arguments: the ring, the
+point id, and the step context (request selection, step id) that the serving loop sets
+once per forward step (the paper's prepare_step).
+"""
+from __future__ import annotations
+
+from typing import Dict, Iterable, Optional
+
+import numpy as np
+import torch
+from torch import nn
+
+from . import binding as B
+
+
+class StepContext:
+    """What every HookPoint of a forward step shares: which rows belong to which
+    request, the step id, an optional keep vector (device address)."""
+
+    def __init__(self):
+        self.reqs: Optional[np.ndarray] = None
+        self.step_id = 0
+        self.keep_mask_dev = 0
+
+    def prepare_step(self, step_id: int, reqs, keep_mask_dev: int = 0):
+        self.reqs = np.ascontiguousarray(np.asarray(reqs, dtype=np.uint32).reshape(-1, 5))
+        self.step_id = int(step_id)
+        self.keep_mask_dev = int(keep_mask_dev)
+
+
+class HookPoint(nn.Module):
+    """Identity module that observes its input.  `enabled=False` makes it a plain
+    identity: nothing is launched (hook filtering)."""
+
+    def __init__(self, ring: B.Ring, point_id: int, ctx: StepContext, *, out_dtype: Optional[int] = None,
+                 summary_mask: int = 0, enabled: bool = True, name: str = ""):
+        super().__init__()
+        self.ring, self.point_id, self.ctx = ring, int(point_id), ctx
+        self.out_dtype, self.summary_mask, self.enabled, self.hook_name = out_dtype, summary_mask, enabled, name
+
+    def forward(self, x: torch.Tensor) -> torch.Tensor:
+        if not self.enabled or self.ctx.reqs is None:
+            return x
+        t = x if x.dim() == 2 else x.reshape(-1, x.shape[-1])      # [tokens, features] view, no copy
+        if t.stride(-1) != 1 or t.data_ptr() != x.data_ptr():
+            raise ValueError("HookPoint needs a tensor whose rows are contiguous in memory")
+        dt = B._torch_dtype_code(t)
+        self.ring.observe(self.point_id, t.data_ptr(), dt, tuple(t.shape), tuple(t.stride()), self.ctx.reqs,
+                          step_id=self.ctx.step_id, stream=torch.cuda.current_stream(x.device).cuda_stream,
+                          out_dtype=dt if self.out_dtype is None else self.out_dtype,
+                          summary_mask=self.summary_mask, keep_mask_dev=self.ctx.keep_mask_dev,
+                          allow=())
+        return x
+
+
+def install_hookpoints(model: nn.Module, ring: B.Ring, ctx: StepContext, where: Dict[str, int],
+                       enabled: Optional[Iterable[str]] = None, **kw) -> Dict[str, HookPoint]:
+    """Wrap the named sub-modules so that their output passes through a HookPoint.
+    where: sub-module path -> point id.  enabled: the hook set to switch on (default all)."""
+    made = {}
+    on = None if enabled is None else set(enabled)
+    for path, pid in where.items():
+        parent_path, _, leaf = path.rpartition(".")
+        parent = model.get_submodule(parent_path) if parent_path else model
+        inner = getattr(parent, leaf)
+        hp = HookPoint(ring, pid, ctx, enabled=on is None or path in on, name=path, **kw)
+        setattr(parent, leaf, nn.Sequential(inner, hp))
+        made[path] = hp
+    return made

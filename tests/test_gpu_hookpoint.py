@@ -1,0 +1,56 @@
+"""HookPoint front end: observing does not change the model's output, disabled hooks
+launch nothing, and what is captured equals the oracle's record of the same tensor."""
+import numpy as np
+import pytest
+import torch
+from torch import nn
+
+import oracle as orc
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+class Block(nn.Module):
+    def __init__(self, d):
+        super().__init__()
+        self.ln = nn.LayerNorm(d)
+        self.up = nn.Linear(d, 4 * d)
+        self.down = nn.Linear(4 * d, d)
+
+    def forward(self, x):
+        return x + self.down(torch.nn.functional.gelu(self.up(self.ln(x))))
+
+
+def test_hookpoints_capture_without_changing_the_forward():
+    from paper_2605_11093_amd import binding as B
+    from paper_2605_11093_amd.hookpoint import HookPoint, StepContext, install_hookpoints
+    torch.manual_seed(0)
+    d, T = 256, 24
+    model = nn.Sequential(*[Block(d) for _ in range(3)]).to(DEV).to(torch.bfloat16).eval()
+    x = torch.randn(T, d, device=DEV).to(torch.bfloat16)
+    with torch.no_grad():
+        plain = model(x).clone()
+    captured = {}
+    with B.Ring(1 << 20, 1 << 20) as ring:
+        ctx = StepContext()
+        hooks = install_hookpoints(model, ring, ctx, {"0": 10, "1.up": 11, "2": 12}, enabled=["0", "1.up"],
+                                   summary_mask=5)
+        # spy on the tensors that reach the enabled hooks (test only; the hook itself keeps nothing)
+        for name, hp in hooks.items():
+            hp.register_forward_pre_hook(lambda m, a, n=name: captured.__setitem__(n, a[0].detach().clone()))
+        reqs = [(70, 0, 20, 4, 1), (71, 0, 3, 2, 5)]       # rows 20..23 and rows 3, 8
+        ctx.prepare_step(5, reqs)
+        with torch.no_grad():
+            hooked = model(x)
+        assert torch.equal(hooked, plain)
+        ring.drain(B.DRAIN_FLUSH)
+        views = ring.poll_host()
+        assert [v.seq for v in views] == [0, 1]            # the disabled hook launched nothing
+        st = ring.get_stats()
+        assert st.observed_calls == 2 and st.launched_records == 2
+        from _util import compare_record
+        for v, (name, pid) in zip(views, (("0", 10), ("1.up", 11))):
+            t = captured[name].reshape(-1, captured[name].shape[-1]).cpu()
+            ref = orc.build_record(t, reqs, seq=v.seq, step_id=5, point_id=pid, out_dtype=1, summary_mask=5)
+            compare_record(v.bytes(), ref)
