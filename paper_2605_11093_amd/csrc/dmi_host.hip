@@ -493,6 +493,10 @@ dmi_status_t observe_common(dmi_ring *r, uint32_t point_id, const dmi_selection_
         a.off_sum = a.off_payload + pad64(a.payload_bytes);
         a.sum_arr = pad64(listed * 4u);
         a.record_bytes = ub;
+        a.rows_consecutive = sel->row_index_dev == nullptr;
+        a.row_first = sel->reqs[0].row_base + sel->reqs[0].tok_start;
+        for (uint32_t i = 1; a.rows_consecutive && i < sel->n_reqs; i++)
+            a.rows_consecutive = sel->reqs[i].row_base + sel->reqs[i].tok_start == a.row_first + i;
         a.hdr[0] = DMI_MAGIC;
         a.hdr[1] = 1u | (DMI_HEADER_BYTES << 16);
         a.hdr[2] = (uint32_t)seq;            a.hdr[3] = (uint32_t)(seq >> 32);

@@ -85,6 +85,8 @@ struct CaptureArgs {
     // mask: the row count is the listed one); used by the decode-shaped kernel
     uint32_t hdr[16];
     uint64_t off_payload, off_sum, sum_arr, record_bytes, payload_bytes;
+    uint32_t rows_consecutive;      // request i's row is row_first + i: no table lookup needed
+    uint32_t row_first;
 };
 
 // Launchers (dmi_kernels.hip).  All return the launch's hipError_t.

@@ -56,20 +56,35 @@ __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v, uint32_t lane)
     }
     return v;
 }
+// Wavefront reductions with DPP (data-parallel primitives: the cross-lane operand rides on the
+// ALU instruction, no trip through LDS).  quad_perm / row_half_mirror / row_mirror combine the 16
+// lanes of a row, row_bcast15 / row_bcast31 carry row totals forward; lane 63 ends up with the
+// total, which is read back as a scalar.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xF, false);
+}
 __device__ __forceinline__ float wave_sum(float v)
 {
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
-    return v;
+    v += __uint_as_float(dpp_u32<0xB1, 0xF>(__float_as_uint(v)));      // quad_perm [1,0,3,2]
+    v += __uint_as_float(dpp_u32<0x4E, 0xF>(__float_as_uint(v)));      // quad_perm [2,3,0,1]
+    v += __uint_as_float(dpp_u32<0x141, 0xF>(__float_as_uint(v)));     // row_half_mirror
+    v += __uint_as_float(dpp_u32<0x140, 0xF>(__float_as_uint(v)));     // row_mirror
+    v += __uint_as_float(dpp_u32<0x142, 0xA>(__float_as_uint(v)));     // row_bcast15 into rows 1, 3
+    v += __uint_as_float(dpp_u32<0x143, 0xC>(__float_as_uint(v)));     // row_bcast31 into rows 2, 3
+    return __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(v), 63));
 }
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
 {
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) {
-        const uint32_t o = (uint32_t)__shfl_xor((int)v, d, 64);
-        v = o > v ? o : v;
-    }
-    return v;
+    uint32_t o;
+    o = dpp_u32<0xB1, 0xF>(v);  v = o > v ? o : v;
+    o = dpp_u32<0x4E, 0xF>(v);  v = o > v ? o : v;
+    o = dpp_u32<0x141, 0xF>(v); v = o > v ? o : v;
+    o = dpp_u32<0x140, 0xF>(v); v = o > v ? o : v;
+    o = dpp_u32<0x142, 0xA>(v); v = o > v ? o : v;
+    o = dpp_u32<0x143, 0xC>(v); v = o > v ? o : v;
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
 }
 
 // ---------------------------------------------------------------- conversions
@@ -164,11 +179,7 @@ __device__ __forceinline__ void ring_store(const RingW &w, uint64_t off, T v)
 {
     uint64_t p = w.base + off;
     if (p >= w.cap) p -= w.cap;
-#ifdef DMI_PLAIN_STORES
-    *reinterpret_cast<T *>(w.ring + p) = v;
-#else
     __builtin_nontemporal_store(v, reinterpret_cast<T *>(w.ring + p));
-#endif
 }
 
 // Per-lane partial row summaries.  Sum of squares and sum are fp32; the largest magnitude is
@@ -871,7 +882,9 @@ __global__ void __launch_bounds__(kThreads) capture_decode_kernel(const CaptureA
     bool ok = false;
     if (!meta_wg) {
         const uint32_t g = blockIdx.x;
-        const int64_t row = a.row_index ? (int64_t)a.row_index[g] : (int64_t)a.row0[g];
+        // the usual decode layout (request i in row first + i) saves the dependent trip to the table
+        const int64_t row = a.rows_consecutive ? (int64_t)a.row_first + g
+                            : a.row_index ? (int64_t)a.row_index[g] : (int64_t)a.row0[g];
         ok = row >= 0 && row < a.n_src_rows;
         const uint8_t *base = a.src + (ok ? row : 0) * a.row_stride_b;
 #pragma unroll
