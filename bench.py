@@ -447,6 +447,35 @@ def main():
                                        "interfering_workload": "80 x 219 MB bf16 weight-streaming GEMV per step",
                                        "by_k": sat}
 
+    # ------------------------------------------------------------------ exporter stages 2-3
+    if not args.skip_extra:
+        r6 = B.Ring(wl.device_ring_bytes, wl.host_ring_bytes, flags=B.BG_THREAD, max_reqs_per_observe=256)
+        p6 = prepared(r6)
+        r6.exporter_start(1 << 30, 4)
+        buf = (B.SliceC * 4096)()
+        n_exp_steps, got_bytes, got_slices = 64, 0, 0
+        want_slices = n_exp_steps * n_points * n_reqs
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        s6 = 0
+        while got_slices < want_slices:
+            if s6 < n_exp_steps:
+                for po in p6[s6 % 4]:
+                    observe_checked(po, s6)
+                s6 += 1
+            k = r6.exporter_next_many(buf, 1 if s6 < n_exp_steps else 1000)
+            got_slices += k
+            if k:
+                r6.exporter_release_many(buf, k)
+        dt = time.perf_counter() - t
+        r6.exporter_stop()
+        stream.synchronize()
+        r6.destroy()
+        extra["exporter"] = {"GBs": round(n_exp_steps * step_bytes / dt / 1e9, 2), "slices_per_s": round(got_slices / dt),
+                             "what": "config 2 stream through capture, drain thread, pageable copy (4 workers), "
+                                     "slice by request; Python consumer releasing in batches"}
+        log(f"exporter: {extra['exporter']}")
+
     # ------------------------------------------------------------------ CPU oracle baseline
     cpu = None
     if not args.skip_cpu_baseline:

@@ -258,9 +258,15 @@ typedef struct {
     const float *l2, *mean, *absmax;    /* n_rows values each, NULL if not requested */
     void *owner;                /* the record copy this slice points into (library-owned) */
 } dmi_slice_t;
-dmi_status_t dmi_exporter_start(dmi_ring_t *ring, uint64_t max_pageable_bytes);
+/* n_copy_threads: pageable-copy workers (0 = 3, at most 16); results come out in ring order whatever their number. */
+dmi_status_t dmi_exporter_start(dmi_ring_t *ring, uint64_t max_pageable_bytes, uint32_t n_copy_threads);
 /* Next slice in (seq, request) order; waits up to timeout_ms, then DMI_ERR_AGAIN. */
 dmi_status_t dmi_exporter_next(dmi_ring_t *ring, dmi_slice_t *out /*[host]*/, uint32_t timeout_ms);
+/* Up to max slices that are ready now (waits up to timeout_ms for the first one); *n = how many. */
+dmi_status_t dmi_exporter_next_many(dmi_ring_t *ring, dmi_slice_t *out /*[host]*/, uint32_t max,
+                                    uint32_t *n /*[host]*/, uint32_t timeout_ms);
+/* Release n slices at once. */
+dmi_status_t dmi_exporter_release_many(dmi_ring_t *ring, const dmi_slice_t *slices /*[host]*/, uint32_t n);
 /* Done with a slice; the record copy is freed when all of its slices have been released. */
 dmi_status_t dmi_exporter_release(dmi_ring_t *ring, const dmi_slice_t *slice /*[host]*/);
 /* Stops the thread; slices not yet handed out are discarded. */

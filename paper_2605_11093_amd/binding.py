@@ -174,9 +174,11 @@ def lib():
     L.dmi_get_stats.argtypes = [C.c_void_p, P(StatsC)]
     L.dmi_get_point_drops.argtypes = [C.c_void_p, C.c_uint32, P(C.c_uint64)]
     L.dmi_debug_fill_rings.argtypes = [C.c_void_p, C.c_uint8]
-    L.dmi_exporter_start.argtypes = [C.c_void_p, C.c_uint64]
+    L.dmi_exporter_start.argtypes = [C.c_void_p, C.c_uint64, C.c_uint32]
     L.dmi_exporter_next.argtypes = [C.c_void_p, P(SliceC), C.c_uint32]
     L.dmi_exporter_release.argtypes = [C.c_void_p, P(SliceC)]
+    L.dmi_exporter_next_many.argtypes = [C.c_void_p, P(SliceC), C.c_uint32, P(C.c_uint32), C.c_uint32]
+    L.dmi_exporter_release_many.argtypes = [C.c_void_p, P(SliceC), C.c_uint32]
     L.dmi_exporter_stop.argtypes = [C.c_void_p]
     L.dmi_policy_select.argtypes = [C.c_uint32, P(ReqInfo), C.c_uint32, C.c_uint64, C.c_uint64, C.c_void_p,
                                     P(C.c_uint32)]
@@ -186,7 +188,8 @@ def lib():
                  "dmi_poll_host", "dmi_release_host", "dmi_set_policy", "dmi_point_enable",
                  "dmi_get_stats", "dmi_get_point_drops", "dmi_debug_fill_rings", "dmi_policy_select",
                  "dmi_ring_free_bytes", "dmi_set_keep_mask", "dmi_exporter_start", "dmi_exporter_next",
-                 "dmi_exporter_release", "dmi_exporter_stop"):
+                 "dmi_exporter_release", "dmi_exporter_stop", "dmi_exporter_next_many",
+                 "dmi_exporter_release_many"):
         getattr(L, name).restype = C.c_int32
     _lib = L
     return L
@@ -395,14 +398,23 @@ class Ring:
         return int(out.value or 0)
 
     # -- exporter stages 2-3 -----------------------------------------------
-    def exporter_start(self, max_pageable_bytes: int):
-        _check(lib().dmi_exporter_start(self._h, max_pageable_bytes))
+    def exporter_start(self, max_pageable_bytes: int, n_copy_threads: int = 0):
+        _check(lib().dmi_exporter_start(self._h, max_pageable_bytes, n_copy_threads))
 
     def exporter_next(self, timeout_ms: int = 100) -> Optional["SliceC"]:
         """The next per-request slice, or None after timeout_ms.  Release it when done."""
         sl = SliceC()
         rc = _check(lib().dmi_exporter_next(self._h, C.byref(sl), timeout_ms), allow=(ERR_AGAIN,))
         return None if rc == ERR_AGAIN else sl
+
+    def exporter_next_many(self, buf, timeout_ms: int = 100) -> int:
+        """Fill a (SliceC * n) array with the slices ready now; returns how many."""
+        n = C.c_uint32()
+        _check(lib().dmi_exporter_next_many(self._h, buf, len(buf), C.byref(n), timeout_ms), allow=(ERR_AGAIN,))
+        return int(n.value)
+
+    def exporter_release_many(self, buf, n: int):
+        _check(lib().dmi_exporter_release_many(self._h, buf, n))
 
     def exporter_release(self, sl: "SliceC"):
         _check(lib().dmi_exporter_release(self._h, C.byref(sl)))

@@ -12,6 +12,7 @@
 #include <cstdio>
 #include <cstring>
 #include <deque>
+#include <map>
 #include <mutex>
 #include <new>
 #include <string>
@@ -90,6 +91,17 @@ struct RecordCopy {
     std::atomic<uint32_t> refs;
 };
 
+struct ExportJob {
+    dmi_record_view_t view;
+    uint64_t ticket;
+};
+
+struct ExportDone {
+    uint64_t seq;
+    RecordCopy *rc;
+    std::vector<dmi_slice_t> slices;
+};
+
 struct Probe {
     hipEvent_t ev_user;     // recorded on the producer's stream behind the launches
     hipEvent_t ev_done;     // recorded on the control stream behind the slot fetch
@@ -159,7 +171,12 @@ struct dmi_ring {
     std::mutex emu;
     std::condition_variable ecv_data, ecv_space;
     std::deque<dmi_slice_t> slices;
-    uint64_t exp_bytes = 0, exp_max_bytes = 0;
+    uint64_t exp_bytes = 0, exp_max_bytes = 0, next_emit = 0;
+    std::vector<std::thread> exp_workers;
+    std::mutex jmu;
+    std::condition_variable jcv;
+    std::deque<ExportJob> jobs;
+    std::map<uint64_t, ExportDone> done_jobs;
     std::atomic<uint64_t> exp_records{0}, exp_copied_bytes{0};
 };
 
@@ -609,91 +626,128 @@ void free_ring(dmi_ring *r)
 dmi_status_t poll_host_impl(dmi_ring *r, dmi_record_view_t *out, uint32_t max, uint32_t *n);
 dmi_status_t release_host_impl(dmi_ring *r, uint64_t upto);
 
-// Exporter thread: pinned ring -> pageable copies -> per-request slices.
+// Exporter stage 3 for one record copy: shape / dtype from the header, one slice per request with rows.
+void slice_record(RecordCopy *rc, std::vector<dmi_slice_t> &made)
+{
+    const uint8_t *b = rc->bytes;
+    uint32_t n_reqs, n_rows, row_elems, point_id, rank_tag;
+    uint64_t seq, step_id, payload_bytes;
+    memcpy(&seq, b + 8, 8);
+    memcpy(&step_id, b + 16, 8);
+    memcpy(&point_id, b + 24, 4);
+    memcpy(&n_reqs, b + 32, 4);
+    memcpy(&n_rows, b + 36, 4);
+    memcpy(&row_elems, b + 40, 4);
+    memcpy(&rank_tag, b + 44, 4);
+    memcpy(&payload_bytes, b + 56, 8);
+    const uint32_t src_dtype = b[28], out_dtype = b[29], smask = b[30], flags = b[31];
+    const uint64_t es = dtype_size(out_dtype);
+    const uint8_t *table = b + DMI_HEADER_BYTES;
+    const uint8_t *payload = table + pad64((uint64_t)n_reqs * 16u);
+    const uint8_t *sums = payload + pad64(payload_bytes);
+    const uint64_t sum_arr = pad64((uint64_t)n_rows * 4u);
+    const float *arr[3] = {nullptr, nullptr, nullptr};
+    {
+        const uint8_t *p = sums;
+        for (int bit = 0; bit < 3; bit++)
+            if (smask & (1u << bit)) { arr[bit] = reinterpret_cast<const float *>(p); p += sum_arr; }
+    }
+    uint64_t row0 = 0;
+    for (uint32_t q = 0; q < n_reqs; q++) {
+        uint32_t e[4];
+        memcpy(e, table + 16ull * q, 16);
+        if (e[3] == 0) continue;
+        dmi_slice_t sl;
+        memset(&sl, 0, sizeof sl);
+        sl.seq = seq; sl.step_id = step_id; sl.point_id = point_id; sl.rank_tag = rank_tag;
+        sl.req_index = q; sl.req_id = e[0]; sl.tok_start = e[1]; sl.tok_step = e[2]; sl.n_rows = e[3];
+        sl.row_elems = row_elems; sl.src_dtype = src_dtype; sl.out_dtype = out_dtype;
+        sl.summary_mask = smask; sl.flags = flags;
+        sl.rows = es ? payload + row0 * row_elems * es : nullptr;
+        sl.l2 = arr[0] ? arr[0] + row0 : nullptr;
+        sl.mean = arr[1] ? arr[1] + row0 : nullptr;
+        sl.absmax = arr[2] ? arr[2] + row0 : nullptr;
+        sl.owner = rc;
+        made.push_back(sl);
+        row0 += e[3];
+    }
+}
+
+// Exporter copy worker: takes records (with a ticket in ring order) from the dispatcher,
+// copies each into pageable memory, slices it, and commits the results in ticket order
+// (the pinned space is given back in that order too).
+void exporter_worker(dmi_ring *r)
+{
+    for (;;) {
+        ExportJob job;
+        {
+            std::unique_lock<std::mutex> lk(r->jmu);
+            r->jcv.wait(lk, [&] { return r->exp_stop.load() || !r->jobs.empty(); });
+            if (r->jobs.empty()) return;        // stopping
+            job = r->jobs.front();
+            r->jobs.pop_front();
+        }
+        RecordCopy *rc = new RecordCopy;
+        rc->size = job.view.n0 + job.view.n1;
+        rc->bytes = static_cast<uint8_t *>(malloc(rc->size));
+        memcpy(rc->bytes, job.view.p0, job.view.n0);
+        if (job.view.n1) memcpy(rc->bytes + job.view.n0, job.view.p1, job.view.n1);
+        std::vector<dmi_slice_t> made;
+        slice_record(rc, made);
+        rc->refs.store((uint32_t)made.size());
+        r->exp_records++;
+        r->exp_copied_bytes += rc->size;
+
+        std::lock_guard<std::mutex> lk(r->emu);
+        r->done_jobs.emplace(job.ticket, ExportDone{job.view.seq, rc, std::move(made)});
+        bool any = false;
+        while (!r->done_jobs.empty() && r->done_jobs.begin()->first == r->next_emit) {
+            ExportDone &d = r->done_jobs.begin()->second;
+            (void)release_host_impl(r, d.seq);      // pinned space is free again, in ring order
+            if (d.slices.empty()) {                 // nothing to hand out: the copy goes at once
+                r->exp_bytes -= d.rc->size;
+                free(d.rc->bytes);
+                delete d.rc;
+                r->ecv_space.notify_all();
+            } else {
+                for (auto &sl : d.slices) r->slices.push_back(sl);
+                any = true;
+            }
+            r->done_jobs.erase(r->done_jobs.begin());
+            r->next_emit++;
+        }
+        if (any) r->ecv_data.notify_all();
+    }
+}
+
+// Exporter dispatcher: polls whole records out of the pinned ring and hands them to the
+// copy workers, bounded by the pageable budget (this is where back-pressure starts).
 void exporter_loop(dmi_ring *r)
 {
     (void)hipSetDevice(r->dev);
     dmi_record_view_t views[64];
+    uint64_t ticket = 0;
     while (!r->exp_stop.load(std::memory_order_acquire)) {
         uint32_t n = 0;
         if (poll_host_impl(r, views, 64, &n) != DMI_OK || n == 0) {
             std::this_thread::sleep_for(std::chrono::microseconds(50));
             continue;
         }
-        for (uint32_t i = 0; i < n && !r->exp_stop.load(std::memory_order_acquire); i++) {
-            const dmi_record_view_t &v = views[i];
-            const uint64_t size = v.n0 + v.n1;
-            {   // bounded queue: wait for room (this is where back-pressure starts)
+        for (uint32_t i = 0; i < n; i++) {
+            const uint64_t size = views[i].n0 + views[i].n1;
+            {
                 std::unique_lock<std::mutex> lk(r->emu);
                 r->ecv_space.wait(lk, [&] {
                     return r->exp_stop.load() || r->exp_bytes == 0 || r->exp_bytes + size <= r->exp_max_bytes;
                 });
-                if (r->exp_stop.load()) break;
+                if (r->exp_stop.load()) return;
                 r->exp_bytes += size;
             }
-            RecordCopy *rc = new RecordCopy;
-            rc->bytes = static_cast<uint8_t *>(malloc(size));
-            rc->size = size;
-            memcpy(rc->bytes, v.p0, v.n0);
-            if (v.n1) memcpy(rc->bytes + v.n0, v.p1, v.n1);
-            (void)release_host_impl(r, v.seq);          // pinned space is free again
-            r->exp_records++;
-            r->exp_copied_bytes += size;
-
-            // stage 3: shape / dtype from the header, one slice per request with rows
-            const uint8_t *b = rc->bytes;
-            uint32_t n_reqs, n_rows, row_elems, point_id, rank_tag;
-            uint64_t seq, step_id, payload_bytes;
-            memcpy(&seq, b + 8, 8);
-            memcpy(&step_id, b + 16, 8);
-            memcpy(&point_id, b + 24, 4);
-            memcpy(&n_reqs, b + 32, 4);
-            memcpy(&n_rows, b + 36, 4);
-            memcpy(&row_elems, b + 40, 4);
-            memcpy(&rank_tag, b + 44, 4);
-            memcpy(&payload_bytes, b + 56, 8);
-            const uint32_t src_dtype = b[28], out_dtype = b[29], smask = b[30], flags = b[31];
-            const uint64_t es = dtype_size(out_dtype);
-            const uint8_t *table = b + DMI_HEADER_BYTES;
-            const uint8_t *payload = table + pad64((uint64_t)n_reqs * 16u);
-            const uint8_t *sums = payload + pad64(payload_bytes);
-            const uint64_t sum_arr = pad64((uint64_t)n_rows * 4u);
-            const float *arr[3] = {nullptr, nullptr, nullptr};
             {
-                const uint8_t *p = sums;
-                for (int bit = 0; bit < 3; bit++)
-                    if (smask & (1u << bit)) { arr[bit] = reinterpret_cast<const float *>(p); p += sum_arr; }
+                std::lock_guard<std::mutex> lk(r->jmu);
+                r->jobs.push_back(ExportJob{views[i], ticket++});
             }
-            std::vector<dmi_slice_t> made;
-            uint64_t row0 = 0;
-            for (uint32_t q = 0; q < n_reqs; q++) {
-                uint32_t e[4];
-                memcpy(e, table + 16ull * q, 16);
-                if (e[3] == 0) continue;
-                dmi_slice_t sl;
-                memset(&sl, 0, sizeof sl);
-                sl.seq = seq; sl.step_id = step_id; sl.point_id = point_id; sl.rank_tag = rank_tag;
-                sl.req_index = q; sl.req_id = e[0]; sl.tok_start = e[1]; sl.tok_step = e[2]; sl.n_rows = e[3];
-                sl.row_elems = row_elems; sl.src_dtype = src_dtype; sl.out_dtype = out_dtype;
-                sl.summary_mask = smask; sl.flags = flags;
-                sl.rows = es ? payload + row0 * row_elems * es : nullptr;
-                sl.l2 = arr[0] ? arr[0] + row0 : nullptr;
-                sl.mean = arr[1] ? arr[1] + row0 : nullptr;
-                sl.absmax = arr[2] ? arr[2] + row0 : nullptr;
-                sl.owner = rc;
-                made.push_back(sl);
-                row0 += e[3];
-            }
-            std::lock_guard<std::mutex> lk(r->emu);
-            if (made.empty()) {         // nothing to hand out: the copy goes at once
-                r->exp_bytes -= size;
-                free(rc->bytes);
-                delete rc;
-            } else {
-                rc->refs.store((uint32_t)made.size());
-                for (auto &sl : made) r->slices.push_back(sl);
-                r->ecv_data.notify_all();
-            }
+            r->jcv.notify_one();
         }
     }
 }
@@ -1000,12 +1054,15 @@ dmi_status_t dmi_release_host(dmi_ring_t *r, uint64_t upto)
     return release_host_impl(r, upto);
 }
 
-dmi_status_t dmi_exporter_start(dmi_ring_t *r, uint64_t max_pageable_bytes)
+dmi_status_t dmi_exporter_start(dmi_ring_t *r, uint64_t max_pageable_bytes, uint32_t n_copy_threads)
 {
-    if (!r || !max_pageable_bytes) return fail(DMI_ERR_INVALID_ARG, "bad argument");
+    if (!r || !max_pageable_bytes || n_copy_threads > 16u) return fail(DMI_ERR_INVALID_ARG, "bad argument");
     if (r->exp_running.exchange(true)) return fail(DMI_ERR_INVALID_ARG, "exporter already running");
     r->exp_stop.store(false);
     r->exp_max_bytes = max_pageable_bytes;
+    r->next_emit = 0;
+    const uint32_t n = n_copy_threads ? n_copy_threads : 3u;
+    for (uint32_t i = 0; i < n; i++) r->exp_workers.emplace_back(exporter_worker, r);
     r->exporter = std::thread(exporter_loop, r);
     return DMI_OK;
 }
@@ -1018,6 +1075,30 @@ dmi_status_t dmi_exporter_next(dmi_ring_t *r, dmi_slice_t *out, uint32_t timeout
         return fail(DMI_ERR_AGAIN, "no slice within %u ms", timeout_ms);
     *out = r->slices.front();
     r->slices.pop_front();
+    return DMI_OK;
+}
+
+dmi_status_t dmi_exporter_next_many(dmi_ring_t *r, dmi_slice_t *out, uint32_t max, uint32_t *n, uint32_t timeout_ms)
+{
+    if (!r || !n || (max && !out)) return fail(DMI_ERR_INVALID_ARG, "NULL argument");
+    *n = 0;
+    std::unique_lock<std::mutex> lk(r->emu);
+    if (!r->ecv_data.wait_for(lk, std::chrono::milliseconds(timeout_ms), [&] { return !r->slices.empty(); }))
+        return fail(DMI_ERR_AGAIN, "no slice within %u ms", timeout_ms);
+    while (*n < max && !r->slices.empty()) {
+        out[(*n)++] = r->slices.front();
+        r->slices.pop_front();
+    }
+    return DMI_OK;
+}
+
+dmi_status_t dmi_exporter_release_many(dmi_ring_t *r, const dmi_slice_t *sl, uint32_t n)
+{
+    if (!r || (n && !sl)) return fail(DMI_ERR_INVALID_ARG, "NULL argument");
+    for (uint32_t i = 0; i < n; i++) {
+        dmi_status_t st = dmi_exporter_release(r, &sl[i]);
+        if (st != DMI_OK) return st;
+    }
     return DMI_OK;
 }
 
@@ -1044,8 +1125,20 @@ dmi_status_t dmi_exporter_stop(dmi_ring_t *r)
     r->exp_stop.store(true);
     r->ecv_space.notify_all();
     if (r->exporter.joinable()) r->exporter.join();
+    {
+        std::lock_guard<std::mutex> lk(r->jmu);
+        r->jobs.clear();
+    }
+    r->jcv.notify_all();
+    for (auto &w : r->exp_workers) if (w.joinable()) w.join();
+    r->exp_workers.clear();
     {   // discard what was not handed out
         std::lock_guard<std::mutex> lk(r->emu);
+        for (auto &kv : r->done_jobs) {
+            if (kv.second.slices.empty()) { free(kv.second.rc->bytes); delete kv.second.rc; }
+            else for (auto &sl : kv.second.slices) r->slices.push_back(sl);
+        }
+        r->done_jobs.clear();
         for (auto &sl : r->slices) {
             RecordCopy *rc = static_cast<RecordCopy *>(sl.owner);
             if (rc->refs.fetch_sub(1) == 1) { r->exp_bytes -= rc->size; free(rc->bytes); delete rc; }
