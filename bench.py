@@ -346,6 +346,100 @@ def main():
                              "dropped_records": st.dropped_records,
                              "paper_context": "0.4-6.8 % offline, ~6 % online on H100 (other hardware, real models)"}
         log(f"overhead: {extra['overhead']}")
+
+        # the same comparison with each step captured once into a graph and replayed (how a serving
+        # engine runs decode): 32 x (GEMV + capture launch) per graph, one graph per pool slot
+        r7 = B.Ring(wl.device_ring_bytes, wl.host_ring_bytes, flags=B.BG_THREAD, max_reqs_per_observe=256)
+
+        def capture_graph(slot, with_gemv, with_capture, ring_):
+            step = B.Step(ring_, n_points) if with_capture else None
+            g = torch.cuda.CUDAGraph()
+            if step is not None:
+                step.capture_begin()
+            with torch.cuda.graph(g):
+                h = torch.cuda.current_stream().cuda_stream
+                for l in range(n_points):
+                    if with_gemv:
+                        bench_lib.dmi_bench_stream_gemv(weights[l].data_ptr(), n_w, xvec.data_ptr(), acc.data_ptr(), h)
+                    if step is not None:
+                        c = calls0[slot][l]
+                        step.observe_tensor(c.point_id, c.tensor, c.reqs, stream=h, out_dtype=c.out_dtype,
+                                            summary_mask=c.summary_mask)
+            if step is not None:
+                step.seal()
+            return step, g
+
+        g_base = capture_graph(0, True, False, None)[1]
+        g_cap = [capture_graph(slot, True, True, r7) for slot in range(4)]
+
+        def graph_steps(first, count, capture):
+            for s in range(first, first + count):
+                if capture:
+                    step, g = g_cap[s % 4]
+                    step.begin(s, sh)
+                    g.replay()
+                    step.end(sh)
+                    consume(r7)
+                else:
+                    g_base.replay()
+
+        per_step = {False: [], True: []}
+        graph_steps(0, 5, True)
+        graph_steps(0, 5, False)
+        stream.synchronize()
+        for rep in range(5):
+            for capture in (False, True):
+                torch.cuda.synchronize()
+                t = time.perf_counter()
+                graph_steps(100 + rep * 20, 20, capture)
+                stream.synchronize()
+                if capture:
+                    while r7.get_stats().drained_bytes < r7.get_stats().captured_bytes:
+                        time.sleep(0.00005)
+                    consume(r7)
+                per_step[capture].append((time.perf_counter() - t) * 1e3 / 20)
+        base_g, cap_g = statistics.median(per_step[False]), statistics.median(per_step[True])
+        st = r7.get_stats()
+        assert st.dropped_records == 0 and st.captured_records == st.launched_records
+        extra["overhead_graph_replay"] = {
+            "no_capture_ms_per_step": round(base_g, 4), "capture_ms_per_step": round(cap_g, 4),
+            "overhead_pct": round((cap_g - base_g) / base_g * 100, 3),
+            "what": "each step one graph replay (32 GEMV, or 32 x (GEMV + capture launch) between "
+                    "dmi_step_begin and dmi_step_end)"}
+        log(f"overhead, graph replay: {extra['overhead_graph_replay']}")
+        torch.cuda.synchronize()
+        for step, g in g_cap:
+            del g
+            step.destroy()
+        del g_cap, g_base
+        r7.destroy()
+
+        # capture launches alone inside a graph: 32 per replay, 8 replays back to back behind a sleep
+        r8 = B.Ring(wl.device_ring_bytes, wl.host_ring_bytes, max_reqs_per_observe=256)
+        g_only = [capture_graph(slot, False, True, r8) for slot in range(4)]
+        best = 1e9
+        for rep in range(5):
+            settle(r8)
+            e0, e1 = ev_pair()
+            bench_lib.dmi_bench_sleep(sh, 4000)
+            e0.record(stream)
+            for k in range(8):
+                step, g = g_only[k % 4]
+                step.begin(k, sh)
+                g.replay()
+                step.end(sh)
+            e1.record(stream)
+            e1.synchronize()
+            best = min(best, e0.elapsed_time(e1) * 1e3 / (8 * n_points))
+        settle(r8)
+        extra["capture_us_per_launch_in_graph"] = round(best, 3)
+        log(f"capture launches inside a replayed graph: {best:.2f} us/launch (includes 1/32 of the step-begin launch)")
+        torch.cuda.synchronize()
+        for step, g in g_only:
+            del g
+            step.destroy()
+        del g_only
+        r8.destroy()
         del weights
 
     # ------------------------------------------------------------------ the other configurations end to end

@@ -317,6 +317,81 @@ dmi_status_t dmi_ring_free_bytes(dmi_ring_t *ring, uint64_t *free_bytes /*[host]
 dmi_status_t dmi_set_keep_mask(dmi_ring_t *ring, const uint8_t *keep /*[host]*/, uint32_t n_reqs,
                                void *hip_stream, const uint8_t **keep_mask_dev /*[host]*/);
 
+/*
+ * Replayable steps (section 4.4, policy manager; section 4.1 on graph compatibility).
+ *
+ * Serving engines capture a forward step once into a graph and replay it.  A capture
+ * launch issued by dmi_observe carries its sequence number, step id and policy as kernel
+ * arguments, which a graph would freeze.  A dmi_step_t is a fixed list of capture launches
+ * that read those values from device memory instead, so the launches can be recorded into
+ * the caller's hipGraph together with the caller's own kernels:
+ *
+ *     dmi_step_create(ring, max_observes, &step);
+ *     dmi_step_capture_begin(step);
+ *       hipStreamBeginCapture(stream, ...);               // the caller's capture
+ *         ... forward pass, with dmi_step_observe(step, point, tensor, sel, xf, stream, &node)
+ *             where a HookPoint sits ...
+ *       hipStreamEndCapture(stream, &graph);
+ *     dmi_step_seal(step);
+ *     per step:
+ *         dmi_step_update(step, node, reqs, n_reqs);      // optional: new batch composition
+ *         dmi_step_begin(step, step_id, stream);          // the policy manager's turn
+ *         hipGraphLaunch(graph_exec, stream);             // exactly once per dmi_step_begin
+ *         dmi_step_end(step, stream);
+ *
+ * What stays fixed between replays: the list of launches, their source tensors (address,
+ * shape, strides), transforms, request counts, the addresses of keep vectors and row
+ * indices.  What may change: the contents of source tensors, of keep_mask_dev and
+ * row_index_dev vectors (caller-owned device memory, rewritten on the stream before the
+ * replay; a vector from dmi_set_keep_mask rotates and is not suitable), request tables
+ * (dmi_step_update), step id, backpressure policy and sampling (dmi_set_policy).  Hook
+ * filtering applies when the step is captured: dmi_step_observe of a disabled point
+ * returns DMI_POINT_DISABLED and adds nothing to the graph.
+ *
+ * Records, sequence numbers, drops and counters are the same as if the step's observes
+ * had been issued by dmi_observe in the same order.  dmi_observe may be used between
+ * steps (not between dmi_step_begin and dmi_step_end).  All of these are producer-thread
+ * calls.  Destroy a step after its last replay has finished and before its ring.
+ */
+typedef struct dmi_step dmi_step_t;
+#define DMI_STEP_MAX_OBSERVES 256u
+/* Allocates the step's device-side parameter block and request-table space (not under capture). */
+dmi_status_t dmi_step_create(dmi_ring_t *ring, uint32_t max_observes, dmi_step_t **out /*[host]*/);
+dmi_status_t dmi_step_destroy(dmi_step_t *step);
+/* Opens the step for dmi_step_observe*.  Until dmi_step_seal the library's own threads
+ * (drain thread, exporter) make no HIP call, so a capture in the global capture mode is
+ * not disturbed by them; the caller's other threads must not call into this ring either. */
+dmi_status_t dmi_step_capture_begin(dmi_step_t *step);
+/* As dmi_observe / dmi_observe_paged without step id: validates, appends the launch to the
+ * step and issues it on hip_stream, which must be capturing (DMI_ERR_INVALID_ARG otherwise).
+ * Makes no HIP call besides the capture-status query and the kernel launch.
+ * *node [host, optional] = index of the launch in the step.
+ * Returns DMI_POINT_DISABLED (no launch) for a disabled point. */
+dmi_status_t dmi_step_observe(dmi_step_t *step, uint32_t point_id, const dmi_tensor_t *tensor /*[host]*/,
+                              const dmi_selection_t *sel /*[host]*/, const dmi_transform_t *xf /*[host]*/,
+                              void *hip_stream, uint32_t *node /*[host]*/);
+dmi_status_t dmi_step_observe_paged(dmi_step_t *step, uint32_t point_id, const dmi_paged_kv_t *kv /*[host]*/,
+                                    const dmi_selection_t *sel /*[host]*/, const dmi_transform_t *xf /*[host]*/,
+                                    void *hip_stream, uint32_t *node /*[host]*/);
+/* Closes the step; the library's threads resume. */
+dmi_status_t dmi_step_seal(dmi_step_t *step);
+/* Replace the request table of launch `node` (host side; it reaches the device with the
+ * next dmi_step_begin).  Launches captured with an identical table share it and are
+ * updated together.  n_reqs must be the captured count; rows must lie inside every
+ * tensor concerned; a launch captured with one row per request and no keep vector keeps
+ * that shape (and, where request i sat in row first + i, that placement), otherwise
+ * DMI_ERR_INVALID_ARG: capture again. */
+dmi_status_t dmi_step_update(dmi_step_t *step, uint32_t node, const dmi_req_sel_t *reqs /*[host]*/, uint32_t n_reqs);
+/* Before each replay, on the stream the graph is about to be launched on: sampling
+ * (returns DMI_SAMPLED_OUT: the graph is still launched, its capture kernels then do
+ * nothing and take no sequence numbers), admission (DMI_POLICY_BLOCK: waits on the host,
+ * as dmi_observe does, until all records of the step are sure to fit; DMI_ERR_TOO_LARGE
+ * if they can never fit together; DMI_ERR_AGAIN after block_timeout_ms), upload of
+ * changed tables and of the step's parameters (one small launch on hip_stream). */
+dmi_status_t dmi_step_begin(dmi_step_t *step, uint64_t step_id, void *hip_stream);
+/* After the graph launch, same stream: accounts for the step's launches. */
+dmi_status_t dmi_step_end(dmi_step_t *step, void *hip_stream);
+
 /* Hook filtering (section 4.4): a disabled point launches nothing. */
 dmi_status_t dmi_point_enable(dmi_ring_t *ring, uint32_t point_id, int enabled);
 

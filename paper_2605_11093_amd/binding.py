@@ -184,6 +184,20 @@ def lib():
                                     P(C.c_uint32)]
     L.dmi_ring_free_bytes.argtypes = [C.c_void_p, P(C.c_uint64)]
     L.dmi_set_keep_mask.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, P(C.c_void_p)]
+    L.dmi_step_create.argtypes = [C.c_void_p, C.c_uint32, P(C.c_void_p)]
+    L.dmi_step_destroy.argtypes = [C.c_void_p]
+    L.dmi_step_capture_begin.argtypes = [C.c_void_p]
+    L.dmi_step_observe.argtypes = [C.c_void_p, C.c_uint32, P(Tensor), P(Selection), P(Transform), C.c_void_p,
+                                   P(C.c_uint32)]
+    L.dmi_step_observe_paged.argtypes = [C.c_void_p, C.c_uint32, P(PagedKV), P(Selection), P(Transform),
+                                         C.c_void_p, P(C.c_uint32)]
+    L.dmi_step_seal.argtypes = [C.c_void_p]
+    L.dmi_step_update.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32]
+    L.dmi_step_begin.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p]
+    L.dmi_step_end.argtypes = [C.c_void_p, C.c_void_p]
+    for name in ("dmi_step_create", "dmi_step_destroy", "dmi_step_capture_begin", "dmi_step_observe",
+                 "dmi_step_observe_paged", "dmi_step_seal", "dmi_step_update", "dmi_step_begin", "dmi_step_end"):
+        getattr(L, name).restype = C.c_int32
     for name in ("dmi_ring_create", "dmi_ring_destroy", "dmi_observe", "dmi_observe_paged", "dmi_drain",
                  "dmi_poll_host", "dmi_release_host", "dmi_set_policy", "dmi_point_enable",
                  "dmi_get_stats", "dmi_get_point_drops", "dmi_debug_fill_rings", "dmi_policy_select",
@@ -270,6 +284,67 @@ class PreparedObserve:
 
     def __call__(self, step_id: int, stream: int) -> int:
         return self._fn(self._h, self._point, self._a[0], self._a[1], self._a[2], step_id, stream)
+
+
+class Step:
+    """A replayable step (dmi_step_*): capture launches that can sit in a captured graph."""
+
+    def __init__(self, ring: "Ring", max_observes: int):
+        h = C.c_void_p()
+        _check(lib().dmi_step_create(ring._h, max_observes, C.byref(h)))
+        self._h = h
+        self._ring = ring
+
+    def destroy(self):
+        if self._h:
+            _check(lib().dmi_step_destroy(self._h))
+            self._h = None
+
+    def capture_begin(self):
+        _check(lib().dmi_step_capture_begin(self._h))
+
+    def observe_tensor(self, point_id: int, tensor, reqs, *, stream: int, out_dtype: Optional[int] = None,
+                       summary_mask: int = 0, keep_mask=None, row_index=None, allow: Sequence[int] = ()) -> int:
+        """Returns the node index, or -1 if the point is disabled (nothing launched)."""
+        dt = _torch_dtype_code(tensor)
+        ra = _reqs_buffer(reqs)
+        t = Tensor(tensor.data_ptr(), dt, (C.c_int64 * 2)(*tensor.shape), (C.c_int64 * 2)(*tensor.stride()))
+        sel = Selection(ra.shape[0], ra.ctypes.data, None if keep_mask is None else keep_mask.data_ptr(),
+                        None if row_index is None else row_index.data_ptr())
+        xf = Transform(dt if out_dtype is None else out_dtype, summary_mask)
+        node = C.c_uint32()
+        code = _check(lib().dmi_step_observe(self._h, point_id, C.byref(t), C.byref(sel), C.byref(xf),
+                                             stream or None, C.byref(node)), allow)
+        return int(node.value) if code == OK else -1
+
+    def observe_paged(self, point_id: int, cache, block_table, reqs, *, block_size: int, n_heads: int,
+                      head_dim: int, heads_sel: Sequence[int], stream: int, out_dtype: Optional[int] = None,
+                      summary_mask: int = 0, keep_mask=None, allow: Sequence[int] = ()) -> int:
+        dt = _torch_dtype_code(cache)
+        ra = _reqs_buffer(reqs)
+        kv = PagedKV(cache.data_ptr(), dt, cache.stride(0), cache.stride(1), cache.stride(2),
+                     block_size, n_heads, head_dim, cache.shape[0], block_table.shape[0],
+                     block_table.data_ptr(), block_table.stride(0), len(heads_sel),
+                     (C.c_uint32 * 8)(*heads_sel))
+        sel = Selection(ra.shape[0], ra.ctypes.data, None if keep_mask is None else keep_mask.data_ptr(), None)
+        xf = Transform(dt if out_dtype is None else out_dtype, summary_mask)
+        node = C.c_uint32()
+        code = _check(lib().dmi_step_observe_paged(self._h, point_id, C.byref(kv), C.byref(sel), C.byref(xf),
+                                                   stream or None, C.byref(node)), allow)
+        return int(node.value) if code == OK else -1
+
+    def seal(self):
+        _check(lib().dmi_step_seal(self._h))
+
+    def update(self, node: int, reqs, allow: Sequence[int] = ()) -> int:
+        ra = _reqs_buffer(reqs)
+        return _check(lib().dmi_step_update(self._h, node, ra.ctypes.data, ra.shape[0]), allow)
+
+    def begin(self, step_id: int, stream: int, allow: Sequence[int] = ()) -> int:
+        return _check(lib().dmi_step_begin(self._h, step_id, stream or None), allow)
+
+    def end(self, stream: int) -> int:
+        return _check(lib().dmi_step_end(self._h, stream or None))
 
 
 class Ring:

@@ -102,10 +102,31 @@ struct ExportDone {
     std::vector<dmi_slice_t> slices;
 };
 
+struct Geometry {
+    uint32_t src_dtype, row_elems, n_seg, seg_elems;
+    bool vec16;
+};
+
+// What a capture launch is, apart from when it runs and where its table lives.
+struct Plan {
+    uint64_t listed = 0;        // rows the selection lists
+    uint64_t ub = 0;            // record bytes if every request is kept
+    uint32_t grid = 1;
+    bool decode = false;        // the decode-shaped kernel applies
+};
+
+// What the launches between two probes add when the host can tell without asking the
+// device: completeness policy and no keep vector, so each record has its listed size and
+// none is dropped.
+struct Delta {
+    uint64_t bytes = 0, records = 0, rows = 0;
+};
+
 struct Probe {
-    hipEvent_t ev_user;     // recorded on the producer's stream behind the launches
-    hipEvent_t ev_done;     // recorded on the control stream behind the slot fetch
-    uint64_t covers;        // every launch with seq < covers was enqueued before ev_user
+    hipEvent_t ev;          // recorded on the producer's stream behind the launches (and the slot fetch)
+    uint64_t covers;        // every launch with seq < covers was enqueued before ev
+    bool fetched;           // the commit slot of launch covers-1 was copied to the host mirror
+    Delta delta;            // else: what the launches since the previous probe added
 };
 
 }  // namespace
@@ -139,11 +160,17 @@ struct dmi_ring {
     std::deque<std::pair<uint64_t, uint64_t>> inflight;    // (seq, upper bound of record bytes)
     uint64_t inflight_sum = 0;
     uint64_t unprobed_launches = 0, unprobed_bytes = 0, probe_bytes = 8u << 20;
+    uint32_t chain_par = 0;                                // which copy of head / tail_for the next launch reads
+    bool step_open = false;                                // between dmi_step_begin and dmi_step_end
+    std::atomic<int> quiet{0};                             // a capture is open: library threads make no HIP call
+    std::atomic<bool> bg_parked{false};
 
     // commit discovery: events recorded behind launches ("probes"), queried in order
     std::mutex pmu;
     std::deque<Probe> probes;
     std::vector<hipEvent_t> probe_pool;
+    Delta window;                                          // launches since the last probe (under pmu)
+    bool window_exact = true;
     uint64_t probed_upto = 0;                              // launches with seq < this have a probe behind them
     std::atomic<uint64_t> confirmed{0};                    // launches with seq < this have finished
     std::atomic<uint64_t> committed{0};                    // device head after launch confirmed-1
@@ -180,6 +207,38 @@ struct dmi_ring {
     std::atomic<uint64_t> exp_records{0}, exp_copied_bytes{0};
 };
 
+// A replayable step (section 4.4, policy manager): a fixed list of capture launches that
+// take sequence base, step id, tail floor and policy from device memory.
+struct StepTable {                  // one request table, shared by the nodes captured with the same selection
+    std::vector<uint32_t> words;    // as selection_words() lays them out
+    std::vector<dmi_req_sel_t> reqs;
+    bool paged = false;
+    bool dirty = true;              // staged on the host, not yet on the device
+    uint32_t slot = 0;
+};
+
+struct StepNode {
+    CaptureArgs a;
+    Plan pl;
+    Geometry geo;
+    dmi_transform_t xf;
+    uint32_t point_id = 0;
+    uint32_t table = 0;
+    bool index_mode = false, masked = false;
+    uint32_t n_seqs = 0;            // paged: rows of the block table
+};
+
+struct dmi_step {
+    dmi_ring *r = nullptr;
+    uint32_t max_nodes = 0;
+    std::vector<StepNode> nodes;
+    std::vector<StepTable> tables;
+    StepParams *dparams = nullptr;  // device
+    uint32_t *slab = nullptr;       // device: max_nodes table slots
+    bool open = false, sealed = false, begun = false, skipped = false, drop_newest = false;
+    uint64_t sum_ub = 0, sum_listed = 0, seq_base = 0;
+};
+
 namespace {
 
 void atomic_max(std::atomic<uint64_t> &a, uint64_t v)
@@ -188,24 +247,30 @@ void atomic_max(std::atomic<uint64_t> &a, uint64_t v)
     while (cur < v && !a.compare_exchange_weak(cur, v, std::memory_order_relaxed)) {}
 }
 
-// Record an event behind everything launched so far (no-op if that is already covered)
-// and, behind it on the control stream, the fetch of the newest launch's commit slot.
+// Record an event behind everything launched so far (no-op if that is already covered).
+// If the host cannot tell what those launches added (drop-newest, keep vectors), the
+// newest launch's commit slot is fetched into the pinned mirror in front of the event.
+// Both go onto the producer's own stream: a second hardware queue with work pending slows
+// every dispatch of the first by a microsecond or more, far more than a small launch
+// every sixteenth capture costs in line.
 dmi_status_t record_probe(dmi_ring *r)
 {
     std::lock_guard<std::mutex> lk(r->pmu);
     const uint64_t launched = r->next_seq.load(std::memory_order_acquire);
     if (launched <= r->probed_upto) return DMI_OK;
-    hipEvent_t ev[2];
-    for (int i = 0; i < 2; i++) {
-        if (r->probe_pool.empty()) HIP_TRY(hipEventCreateWithFlags(&ev[i], hipEventDisableTiming));
-        else { ev[i] = r->probe_pool.back(); r->probe_pool.pop_back(); }
+    hipEvent_t ev;
+    if (r->probe_pool.empty()) HIP_TRY(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
+    else { ev = r->probe_pool.back(); r->probe_pool.pop_back(); }
+    hipStream_t us = (hipStream_t)r->last_stream.load(std::memory_order_acquire);
+    const bool fetch = !r->window_exact;
+    if (fetch) {
+        const uint32_t slot = (uint32_t)((launched - 1u) % kCommitSlots);
+        HIP_TRY(launch_fetch_slot(&r->dctrl->slots[slot], r->hslots_dev + slot, us));
     }
-    const uint32_t slot = (uint32_t)((launched - 1u) % kCommitSlots);
-    HIP_TRY(hipEventRecord(ev[0], (hipStream_t)r->last_stream.load(std::memory_order_acquire)));
-    HIP_TRY(hipStreamWaitEvent(r->ctl_stream, ev[0], 0));
-    HIP_TRY(launch_fetch_slot(&r->dctrl->slots[slot], r->hslots_dev + slot, r->ctl_stream));
-    HIP_TRY(hipEventRecord(ev[1], r->ctl_stream));
-    r->probes.push_back({ev[0], ev[1], launched});
+    HIP_TRY(hipEventRecord(ev, us));
+    r->probes.push_back({ev, launched, fetch, r->window});
+    r->window = Delta();
+    r->window_exact = true;
     r->probed_upto = launched;
     return DMI_OK;
 }
@@ -217,21 +282,27 @@ dmi_status_t advance_commits(dmi_ring *r, bool block)
     std::lock_guard<std::mutex> lk(r->pmu);
     while (!r->probes.empty()) {
         Probe &p = r->probes.front();
-        hipError_t e = block ? hipEventSynchronize(p.ev_done) : hipEventQuery(p.ev_done);
+        hipError_t e = block ? hipEventSynchronize(p.ev) : hipEventQuery(p.ev);
         block = false;
         if (e == hipErrorNotReady) break;
         if (e != hipSuccess) return fail(DMI_ERR_HIP, "commit event: %s", hipGetErrorString(e));
-        const volatile CommitSlot &sl = r->hslots[(p.covers - 1u) % kCommitSlots];
-        std::atomic_thread_fence(std::memory_order_acquire);
-        if (sl.seq_plus1 != p.covers)
-            return fail(DMI_ERR_CLOSED, "commit slot of launch %llu holds %llu",
-                        (unsigned long long)(p.covers - 1u), (unsigned long long)sl.seq_plus1);
-        r->snap[0] = sl.captured_records; r->snap[1] = sl.captured_rows; r->snap[2] = sl.captured_bytes;
-        r->snap[3] = sl.dropped_records;  r->snap[4] = sl.dropped_rows;  r->snap[5] = sl.dropped_bytes;
-        r->committed.store(sl.head, std::memory_order_release);
+        if (p.fetched) {
+            const volatile CommitSlot &sl = r->hslots[(p.covers - 1u) % kCommitSlots];
+            std::atomic_thread_fence(std::memory_order_acquire);
+            if (sl.seq_plus1 != p.covers)
+                return fail(DMI_ERR_CLOSED, "commit slot of launch %llu holds %llu",
+                            (unsigned long long)(p.covers - 1u), (unsigned long long)sl.seq_plus1);
+            r->snap[0] = sl.captured_records; r->snap[1] = sl.captured_rows; r->snap[2] = sl.captured_bytes;
+            r->snap[3] = sl.dropped_records;  r->snap[4] = sl.dropped_rows;  r->snap[5] = sl.dropped_bytes;
+            r->committed.store(sl.head, std::memory_order_release);
+        } else {
+            // state after the previous probe is exact, and so is what came since
+            r->snap[0] += p.delta.records; r->snap[1] += p.delta.rows; r->snap[2] += p.delta.bytes;
+            r->committed.store(r->committed.load(std::memory_order_relaxed) + p.delta.bytes,
+                               std::memory_order_release);
+        }
         r->confirmed.store(p.covers, std::memory_order_release);
-        r->probe_pool.push_back(p.ev_user);
-        r->probe_pool.push_back(p.ev_done);
+        r->probe_pool.push_back(p.ev);
         r->probes.pop_front();
     }
     return DMI_OK;
@@ -371,6 +442,35 @@ dmi_status_t wait_for_room(dmi_ring *r, uint64_t ub)
     return DMI_OK;
 }
 
+// A launch's commit slot is reused kCommitSlots launches later: keep fewer than that
+// unconfirmed before issuing `n` more.
+dmi_status_t commit_slot_room(dmi_ring *r, uint32_t n)
+{
+    while (r->next_seq.load(std::memory_order_relaxed) + n - r->confirmed.load(std::memory_order_acquire) >=
+           kCommitSlots) {
+        dmi_status_t st = record_probe(r);
+        if (st == DMI_OK) st = advance_commits(r, true);
+        if (st != DMI_OK) return st;
+    }
+    return DMI_OK;
+}
+
+// Request table as the kernels read it: n x {req_id, tok_start, tok_step, tok_count}, then
+// n x first source row of the request (dense; callers have checked that it fits 32 bits)
+// or its row of the block table (paged).
+void selection_words(const dmi_req_sel_t *reqs, uint32_t n, bool paged, std::vector<uint32_t> &words)
+{
+    words.resize((size_t)n * 5u);
+    for (uint32_t i = 0; i < n; i++) {
+        const dmi_req_sel_t &q = reqs[i];
+        words[4u * i + 0] = q.req_id;
+        words[4u * i + 1] = q.tok_start;
+        words[4u * i + 2] = q.tok_step;
+        words[4u * i + 3] = q.tok_count;
+        words[4u * n + i] = paged ? q.row_base : q.row_base + q.tok_start;
+    }
+}
+
 // Put the request table where the kernel can read it from L2: a slab of slots in
 // device memory, refilled only when the selection differs from recent ones (all
 // hook points of a step share their selection).
@@ -378,8 +478,6 @@ dmi_status_t stage_selection(dmi_ring *r, const dmi_selection_t *sel, bool paged
                              uint32_t *slot_out)
 {
     const uint32_t n = sel->n_reqs;
-    // first source row of the request (dense; the caller has checked that it fits 32 bits),
-    // or its row of the block table (paged)
     auto row0 = [paged](const dmi_req_sel_t &q) { return paged ? q.row_base : q.row_base + q.tok_start; };
     for (auto &c : r->cache) {
         if (!c.valid || c.stream != s || c.paged != paged || c.words.size() != (size_t)n * 5u) continue;
@@ -392,15 +490,8 @@ dmi_status_t stage_selection(dmi_ring *r, const dmi_selection_t *sel, bool paged
         }
         if (same) { *slot_out = c.slot; return DMI_OK; }
     }
-    std::vector<uint32_t> words((size_t)n * 5u);
-    for (uint32_t i = 0; i < n; i++) {
-        const dmi_req_sel_t &q = sel->reqs[i];
-        words[4u * i + 0] = q.req_id;
-        words[4u * i + 1] = q.tok_start;
-        words[4u * i + 2] = q.tok_step;
-        words[4u * i + 3] = q.tok_count;
-        words[4u * n + i] = row0(q);
-    }
+    std::vector<uint32_t> words;
+    selection_words(sel->reqs, n, paged, words);
     const uint32_t slot = r->next_slab++ % kSlabSlots;
     for (auto &c : r->cache) if (c.valid && c.slot == slot) c.valid = false;
     if (n) HIP_TRY(launch_upload(r->slab + (size_t)slot * r->slab_slot_words, words.data(), n * 5u, s));
@@ -410,16 +501,12 @@ dmi_status_t stage_selection(dmi_ring *r, const dmi_selection_t *sel, bool paged
     return DMI_OK;
 }
 
-struct Geometry {
-    uint32_t src_dtype, row_elems, n_seg, seg_elems;
-    bool vec16;
-};
-
-dmi_status_t observe_common(dmi_ring *r, uint32_t point_id, const dmi_selection_t *sel,
-                            const dmi_transform_t *xf, uint64_t step_id, void *hip_stream,
-                            const Geometry &geo, CaptureArgs &a)
+// Fill every kernel argument that depends only on the tensor, the selection's shape and the
+// transform.  Left to the caller: request table location, sequence number, step id, commit
+// slot, tail floor, policy, chain parity.
+dmi_status_t plan_capture(dmi_ring *r, uint32_t point_id, const dmi_selection_t *sel, const dmi_transform_t *xf,
+                          const Geometry &geo, CaptureArgs &a, Plan &pl)
 {
-    hipStream_t s = (hipStream_t)hip_stream;
     const uint32_t es_in = dtype_size(geo.src_dtype);
     uint64_t listed = 0;
     for (uint32_t i = 0; i < sel->n_reqs; i++) listed += sel->reqs[i].tok_count;
@@ -432,36 +519,15 @@ dmi_status_t observe_common(dmi_ring *r, uint32_t point_id, const dmi_selection_
     if (ub > r->dev_cap)
         return fail(DMI_ERR_TOO_LARGE, "record of %llu bytes exceeds the device ring (%llu)",
                     (unsigned long long)ub, (unsigned long long)r->dev_cap);
+    pl.listed = listed;
+    pl.ub = ub;
 
-    const uint32_t mode = r->mode.load(std::memory_order_relaxed);
-    r->last_stream.store(hip_stream, std::memory_order_release);
-    if (mode == DMI_POLICY_BLOCK) {
-        dmi_status_t st = wait_for_room(r, ub);
-        if (st != DMI_OK) return st;
-    } else {
-        head_upper_bound(r);    // keeps the in-flight list short
-    }
-    // a launch's host slot is reused kCommitSlots launches later: keep fewer than that unconfirmed
-    while (r->next_seq.load(std::memory_order_relaxed) - r->confirmed.load(std::memory_order_acquire) >=
-           kCommitSlots - 1u) {
-        dmi_status_t st = record_probe(r);
-        if (st == DMI_OK) st = advance_commits(r, true);
-        if (st != DMI_OK) return st;
-    }
-
-    uint32_t slot = 0;
-    dmi_status_t st = stage_selection(r, sel, a.paged != 0, s, &slot);
-    if (st != DMI_OK) return st;
-
-    const uint64_t seq = r->next_seq.load(std::memory_order_relaxed);
     const bool index_mode = sel->row_index_dev != nullptr;
     bool simple = sel->keep_mask_dev == nullptr;
     for (uint32_t i = 0; simple && i < sel->n_reqs; i++) simple = sel->reqs[i].tok_count == 1u;
     const bool tab_lds = !simple && sel->n_reqs <= kLdsTableMax;
     a.n_seg = geo.n_seg;
     a.seg_units = geo.seg_elems / unit_elems;
-    a.req_table = reinterpret_cast<const uint4 *>(r->slab + (size_t)slot * r->slab_slot_words);
-    a.row0 = r->slab + (size_t)slot * r->slab_slot_words + 4u * (size_t)sel->n_reqs;
     a.keep_mask = sel->keep_mask_dev;
     a.row_index = sel->row_index_dev;
     a.n_reqs = sel->n_reqs;
@@ -477,19 +543,14 @@ dmi_status_t observe_common(dmi_ring *r, uint32_t point_id, const dmi_selection_
     a.rows_per_wg = (upr <= 128u || (upr <= 1024u && listed >= 2048u)) ? 4u : 1u;
     a.point_id = point_id;
     a.rank_tag = r->cfg.rank_tag;
-    a.seq = seq;
-    a.step_id = step_id;
     a.ring = r->dev_ring;
     a.cap = r->dev_cap;
     a.ctrl = r->dctrl;
-    a.cslot = &r->dctrl->slots[seq % kCommitSlots];
-    a.tail_floor = r->drain_done.load(std::memory_order_acquire);
     a.simple = simple ? 1u : 0u;
     auto shift_of = [](uint64_t v) { return v && (v & (v - 1u)) == 0 ? (uint32_t)__builtin_ctzll(v) : 32u; };
     a.upr_shift = shift_of(upr);
     a.bs_shift = shift_of(a.block_size);
     a.seg_shift = shift_of(a.seg_units);
-    a.drop_newest = mode == DMI_POLICY_DROP_NEWEST ? 1u : 0u;
     a.table_in_lds = tab_lds ? 1u : 0u;
     a.lds_bytes = capture_lds_bytes(simple ? 0u : sel->n_reqs, index_mode, tab_lds);
 
@@ -499,11 +560,12 @@ dmi_status_t observe_common(dmi_ring *r, uint32_t point_id, const dmi_selection_
         groups = (listed + 4u * kThreads / upr - 1u) / (4u * kThreads / upr);      // 2 or 4 rows per work item
     else if (upr >= kThreads) groups = listed * ((upr + 4u * kThreads - 1u) / (4u * kThreads));
     else groups = (listed * upr + kThreads - 1u) / kThreads;
-    uint32_t grid = groups < 1u ? 1u : groups > kMaxGrid ? kMaxGrid : (uint32_t)groups;
+    pl.grid = groups < 1u ? 1u : groups > kMaxGrid ? kMaxGrid : (uint32_t)groups;
 
-    hipError_t e;
-    if (decode_kernel_applies(a, geo.vec16)) {
+    pl.decode = decode_kernel_applies(a, geo.vec16);
+    if (pl.decode) {
         // the host knows this record exactly: geometry and header travel as kernel arguments
+        // (the kernel itself puts sequence number and step id into the header)
         const uint64_t table_bytes = pad64((uint64_t)sel->n_reqs * 16u);
         a.payload_bytes = listed * geo.row_elems * dtype_size(xf->out_dtype);
         a.off_payload = DMI_HEADER_BYTES + table_bytes;
@@ -516,19 +578,63 @@ dmi_status_t observe_common(dmi_ring *r, uint32_t point_id, const dmi_selection_
             a.rows_consecutive = sel->reqs[i].row_base + sel->reqs[i].tok_start == a.row_first + i;
         a.hdr[0] = DMI_MAGIC;
         a.hdr[1] = 1u | (DMI_HEADER_BYTES << 16);
-        a.hdr[2] = (uint32_t)seq;            a.hdr[3] = (uint32_t)(seq >> 32);
-        a.hdr[4] = (uint32_t)step_id;        a.hdr[5] = (uint32_t)(step_id >> 32);
         a.hdr[6] = point_id;
         a.hdr[7] = a.src_dtype | (a.out_dtype << 8) | (a.summary_mask << 16) | (a.rec_flags << 24);
         a.hdr[8] = sel->n_reqs;  a.hdr[9] = (uint32_t)listed;  a.hdr[10] = geo.row_elems;  a.hdr[11] = a.rank_tag;
         a.hdr[12] = (uint32_t)ub;               a.hdr[13] = (uint32_t)(ub >> 32);
         a.hdr[14] = (uint32_t)a.payload_bytes;  a.hdr[15] = (uint32_t)(a.payload_bytes >> 32);
-        e = launch_capture_decode(a, s);
-    } else {
-        e = launch_capture(a, grid, geo.vec16, s);
     }
+    return DMI_OK;
+}
+
+dmi_status_t observe_common(dmi_ring *r, uint32_t point_id, const dmi_selection_t *sel,
+                            const dmi_transform_t *xf, uint64_t step_id, void *hip_stream,
+                            const Geometry &geo, CaptureArgs &a)
+{
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (r->step_open)
+        return fail(DMI_ERR_INVALID_ARG, "a replayable step is between dmi_step_begin and dmi_step_end");
+    Plan pl;
+    dmi_status_t st = plan_capture(r, point_id, sel, xf, geo, a, pl);
+    if (st != DMI_OK) return st;
+    const uint64_t ub = pl.ub;
+
+    const uint32_t mode = r->mode.load(std::memory_order_relaxed);
+    r->last_stream.store(hip_stream, std::memory_order_release);
+    if (mode == DMI_POLICY_BLOCK) {
+        if ((st = wait_for_room(r, ub)) != DMI_OK) return st;
+    } else {
+        head_upper_bound(r);    // keeps the in-flight list short
+    }
+    if ((st = commit_slot_room(r, 1u)) != DMI_OK) return st;
+
+    uint32_t slot = 0;
+    if ((st = stage_selection(r, sel, a.paged != 0, s, &slot)) != DMI_OK) return st;
+
+    const uint64_t seq = r->next_seq.load(std::memory_order_relaxed);
+    a.req_table = reinterpret_cast<const uint4 *>(r->slab + (size_t)slot * r->slab_slot_words);
+    a.row0 = r->slab + (size_t)slot * r->slab_slot_words + 4u * (size_t)sel->n_reqs;
+    a.seq = seq;
+    a.step_id = step_id;
+    a.cslot = &r->dctrl->slots[seq % kCommitSlots];
+    a.tail_floor = r->drain_done.load(std::memory_order_acquire);
+    a.drop_newest = mode == DMI_POLICY_DROP_NEWEST ? 1u : 0u;
+    a.par_in = r->chain_par;
+    a.step = nullptr;
+    a.node = 0;
+
+    const hipError_t e = pl.decode ? launch_capture_decode(a, s) : launch_capture(a, pl.grid, geo.vec16, s);
     if (e != hipSuccess) return fail(DMI_ERR_HIP, "capture launch failed: %s", hipGetErrorString(e));
-    r->next_seq.store(seq + 1, std::memory_order_release);
+    r->chain_par ^= 1u;
+    {
+        std::lock_guard<std::mutex> lk(r->pmu);
+        r->next_seq.store(seq + 1, std::memory_order_release);
+        if (mode == DMI_POLICY_BLOCK && !sel->keep_mask_dev) {
+            r->window.bytes += ub; r->window.records += 1; r->window.rows += pl.listed;
+        } else {
+            r->window_exact = false;
+        }
+    }
     r->inflight.emplace_back(seq, ub);
     r->inflight_sum += ub;
     r->unprobed_launches += 1;
@@ -575,6 +681,13 @@ void bg_loop(dmi_ring *r)
     const uint64_t timeout_ns = (uint64_t)(r->cfg.bg_timeout_us ? r->cfg.bg_timeout_us : 200u) * 1000ull;
     uint64_t waiting_since = 0, last_probe = 0;
     while (!r->stop.load(std::memory_order_acquire)) {
+        if (r->quiet.load(std::memory_order_acquire)) {
+            // a stream capture is open on the producer's side: stay away from the HIP API
+            r->bg_parked.store(true, std::memory_order_release);
+            std::this_thread::sleep_for(std::chrono::microseconds(50));
+            continue;
+        }
+        r->bg_parked.store(false, std::memory_order_release);
         bool idle_probes;
         {
             std::lock_guard<std::mutex> lk(r->pmu);
@@ -612,7 +725,7 @@ void free_ring(dmi_ring *r)
     if (r->ctl_stream) { (void)hipStreamSynchronize(r->ctl_stream); (void)hipStreamDestroy(r->ctl_stream); }
     for (auto &p : r->pending) (void)hipEventDestroy(p.ev);
     for (auto ev : r->ev_pool) (void)hipEventDestroy(ev);
-    for (auto &p : r->probes) { (void)hipEventDestroy(p.ev_user); (void)hipEventDestroy(p.ev_done); }
+    for (auto &p : r->probes) (void)hipEventDestroy(p.ev);
     for (auto ev : r->probe_pool) (void)hipEventDestroy(ev);
     if (r->dev_ring) (void)hipFree(r->dev_ring);
     if (r->dctrl) (void)hipFree(r->dctrl);
@@ -690,6 +803,10 @@ void exporter_worker(dmi_ring *r)
         RecordCopy *rc = new RecordCopy;
         rc->size = job.view.n0 + job.view.n1;
         rc->bytes = static_cast<uint8_t *>(malloc(rc->size));
+        while (!rc->bytes) {        // the budget is the caller's promise that this fits; wait for memory
+            std::this_thread::sleep_for(std::chrono::milliseconds(1));
+            rc->bytes = static_cast<uint8_t *>(malloc(rc->size));
+        }
         memcpy(rc->bytes, job.view.p0, job.view.n0);
         if (job.view.n1) memcpy(rc->bytes + job.view.n0, job.view.p1, job.view.n1);
         std::vector<dmi_slice_t> made;
@@ -851,12 +968,44 @@ dmi_status_t dmi_ring_destroy(dmi_ring_t *r)
     return DMI_OK;
 }
 
-dmi_status_t dmi_observe(dmi_ring_t *r, uint32_t point_id, const dmi_tensor_t *t, const dmi_selection_t *sel,
-                         const dmi_transform_t *xf, uint64_t step_id, void *hip_stream)
+}  // extern "C"
+
+namespace {
+
+// Checks of a selection against a dense source of T rows (not in index mode, where the
+// kernel checks every index itself).
+dmi_status_t check_dense_rows(const dmi_req_sel_t *reqs, uint32_t n, int64_t T)
 {
-    if (!t) return fail(DMI_ERR_INVALID_ARG, "tensor is NULL");
-    dmi_status_t g = gate(r, point_id, sel, xf, step_id, t->dtype);
-    if (g != DMI_OK) return g;
+    for (uint32_t i = 0; i < n; i++) {
+        const dmi_req_sel_t &q = reqs[i];
+        if (!q.tok_count) continue;
+        const uint64_t last = (uint64_t)q.row_base + q.tok_start + (uint64_t)(q.tok_count - 1u) * q.tok_step;
+        if (last >= (uint64_t)T)
+            return fail(DMI_ERR_INVALID_ARG, "request %u selects row %llu of a %lld-row tensor", i,
+                        (unsigned long long)last, (long long)T);
+    }
+    return DMI_OK;
+}
+
+// Same for a paged source: block-table row and token positions.
+dmi_status_t check_paged_rows(const dmi_req_sel_t *reqs, uint32_t n, uint32_t n_seqs, uint32_t block_size,
+                              int64_t bt_stride)
+{
+    for (uint32_t i = 0; i < n; i++) {
+        const dmi_req_sel_t &q = reqs[i];
+        if (q.row_base >= n_seqs) return fail(DMI_ERR_INVALID_ARG, "request %u: block-table row out of range", i);
+        if (!q.tok_count) continue;
+        const uint64_t last = (uint64_t)q.tok_start + (uint64_t)(q.tok_count - 1u) * q.tok_step;
+        if (last > 0x7FFFFFFFull || last / block_size >= (uint64_t)bt_stride)
+            return fail(DMI_ERR_INVALID_ARG, "request %u: token %llu is beyond the block table", i,
+                        (unsigned long long)last);
+    }
+    return DMI_OK;
+}
+
+// Validate a dense tensor + selection and fill the source part of the kernel arguments.
+dmi_status_t prep_dense(const dmi_tensor_t *t, const dmi_selection_t *sel, Geometry &geo, CaptureArgs &a)
+{
     const uint32_t es = dtype_size(t->dtype);
     const int64_t T = t->shape[0], E = t->shape[1];
     if (T < 0 || T > 0xFFFFFFFFll || E < 1 || E > 0x7FFFFFFF) return fail(DMI_ERR_INVALID_ARG, "bad tensor shape");
@@ -864,39 +1013,26 @@ dmi_status_t dmi_observe(dmi_ring_t *r, uint32_t point_id, const dmi_tensor_t *t
     if (!t->data && T > 0) return fail(DMI_ERR_INVALID_ARG, "tensor data is NULL");
     if ((uintptr_t)t->data % es) return fail(DMI_ERR_INVALID_ARG, "tensor data is not element aligned");
     if (!sel->row_index_dev) {
-        for (uint32_t i = 0; i < sel->n_reqs; i++) {
-            const dmi_req_sel_t &q = sel->reqs[i];
-            if (!q.tok_count) continue;
-            const uint64_t last = (uint64_t)q.row_base + q.tok_start + (uint64_t)(q.tok_count - 1u) * q.tok_step;
-            if (last >= (uint64_t)T)
-                return fail(DMI_ERR_INVALID_ARG, "request %u selects row %llu of a %lld-row tensor", i,
-                            (unsigned long long)last, (long long)T);
-        }
+        dmi_status_t st = check_dense_rows(sel->reqs, sel->n_reqs, T);
+        if (st != DMI_OK) return st;
     }
-    (void)hipSetDevice(r->dev);
-    Geometry geo;
     geo.src_dtype = t->dtype;
     geo.row_elems = (uint32_t)E;
     geo.n_seg = 1;
     geo.seg_elems = (uint32_t)E;
     geo.vec16 = (uintptr_t)t->data % 16 == 0 && ((uint64_t)t->stride[0] * es) % 16 == 0 && ((uint64_t)E * es) % 16 == 0;
-    CaptureArgs a;
     memset(&a, 0, sizeof a);
     a.src = (const uint8_t *)t->data;
     a.row_stride_b = t->stride[0] * (int64_t)es;
     a.n_src_rows = T;
     a.paged = 0;
     a.block_size = 1;
-    return observe_common(r, point_id, sel, xf, step_id, hip_stream, geo, a);
+    return DMI_OK;
 }
 
-dmi_status_t dmi_observe_paged(dmi_ring_t *r, uint32_t point_id, const dmi_paged_kv_t *kv,
-                               const dmi_selection_t *sel, const dmi_transform_t *xf, uint64_t step_id,
-                               void *hip_stream)
+// Validate a paged KV description + selection and fill the source part of the kernel arguments.
+dmi_status_t prep_paged(const dmi_paged_kv_t *kv, const dmi_selection_t *sel, Geometry &geo, CaptureArgs &a)
 {
-    if (!kv) return fail(DMI_ERR_INVALID_ARG, "kv is NULL");
-    dmi_status_t g = gate(r, point_id, sel, xf, step_id, kv->dtype);
-    if (g != DMI_OK) return g;
     const uint32_t es = dtype_size(kv->dtype);
     if (sel->row_index_dev) return fail(DMI_ERR_INVALID_ARG, "row_index_dev is not valid for paged captures");
     if (!kv->base || !kv->block_table_dev) return fail(DMI_ERR_INVALID_ARG, "kv base / block table is NULL");
@@ -910,17 +1046,10 @@ dmi_status_t dmi_observe_paged(dmi_ring_t *r, uint32_t point_id, const dmi_paged
         return fail(DMI_ERR_INVALID_ARG, "negative kv stride");
     if ((uintptr_t)kv->base % es) return fail(DMI_ERR_INVALID_ARG, "kv base is not element aligned");
     if ((uint64_t)kv->n_heads_sel * kv->head_dim > 0x7FFFFFFFull) return fail(DMI_ERR_INVALID_ARG, "row too long");
-    for (uint32_t i = 0; i < sel->n_reqs; i++) {
-        const dmi_req_sel_t &q = sel->reqs[i];
-        if (q.row_base >= kv->n_seqs) return fail(DMI_ERR_INVALID_ARG, "request %u: block-table row out of range", i);
-        if (!q.tok_count) continue;
-        const uint64_t last = (uint64_t)q.tok_start + (uint64_t)(q.tok_count - 1u) * q.tok_step;
-        if (last > 0x7FFFFFFFull || last / kv->block_size >= (uint64_t)kv->block_table_stride)
-            return fail(DMI_ERR_INVALID_ARG, "request %u: token %llu is beyond the block table", i,
-                        (unsigned long long)last);
+    {
+        dmi_status_t st = check_paged_rows(sel->reqs, sel->n_reqs, kv->n_seqs, kv->block_size, kv->block_table_stride);
+        if (st != DMI_OK) return st;
     }
-    (void)hipSetDevice(r->dev);
-    Geometry geo;
     geo.src_dtype = kv->dtype;
     geo.n_seg = kv->n_heads_sel;
     geo.seg_elems = kv->head_dim;
@@ -928,7 +1057,6 @@ dmi_status_t dmi_observe_paged(dmi_ring_t *r, uint32_t point_id, const dmi_paged
     geo.vec16 = (uintptr_t)kv->base % 16 == 0 && ((uint64_t)kv->block_stride * es) % 16 == 0 &&
                 ((uint64_t)kv->slot_stride * es) % 16 == 0 && ((uint64_t)kv->head_stride * es) % 16 == 0 &&
                 ((uint64_t)kv->head_dim * es) % 16 == 0;
-    CaptureArgs a;
     memset(&a, 0, sizeof a);
     a.src = (const uint8_t *)kv->base;
     a.n_src_rows = kv->n_blocks;
@@ -940,7 +1068,360 @@ dmi_status_t dmi_observe_paged(dmi_ring_t *r, uint32_t point_id, const dmi_paged
     a.block_size = kv->block_size;
     for (uint32_t i = 0; i < kv->n_heads_sel; i++) a.heads_sel[i] = kv->heads_sel[i];
     a.paged = 1;
+    return DMI_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+dmi_status_t dmi_observe(dmi_ring_t *r, uint32_t point_id, const dmi_tensor_t *t, const dmi_selection_t *sel,
+                         const dmi_transform_t *xf, uint64_t step_id, void *hip_stream)
+{
+    if (!t) return fail(DMI_ERR_INVALID_ARG, "tensor is NULL");
+    dmi_status_t g = gate(r, point_id, sel, xf, step_id, t->dtype);
+    if (g != DMI_OK) return g;
+    Geometry geo;
+    CaptureArgs a;
+    if ((g = prep_dense(t, sel, geo, a)) != DMI_OK) return g;
+    (void)hipSetDevice(r->dev);
     return observe_common(r, point_id, sel, xf, step_id, hip_stream, geo, a);
+}
+
+dmi_status_t dmi_observe_paged(dmi_ring_t *r, uint32_t point_id, const dmi_paged_kv_t *kv,
+                               const dmi_selection_t *sel, const dmi_transform_t *xf, uint64_t step_id,
+                               void *hip_stream)
+{
+    if (!kv) return fail(DMI_ERR_INVALID_ARG, "kv is NULL");
+    dmi_status_t g = gate(r, point_id, sel, xf, step_id, kv->dtype);
+    if (g != DMI_OK) return g;
+    Geometry geo;
+    CaptureArgs a;
+    if ((g = prep_paged(kv, sel, geo, a)) != DMI_OK) return g;
+    (void)hipSetDevice(r->dev);
+    return observe_common(r, point_id, sel, xf, step_id, hip_stream, geo, a);
+}
+
+// ------------------------------------------------------------------ replayable steps
+dmi_status_t dmi_step_create(dmi_ring_t *r, uint32_t max_observes, dmi_step_t **out)
+{
+    if (!r || !out) return fail(DMI_ERR_INVALID_ARG, "NULL argument");
+    if (max_observes < 1u || max_observes > DMI_STEP_MAX_OBSERVES)
+        return fail(DMI_ERR_INVALID_ARG, "max_observes must be 1..%u", DMI_STEP_MAX_OBSERVES);
+    (void)hipSetDevice(r->dev);
+    dmi_step *st = new (std::nothrow) dmi_step;
+    if (!st) return fail(DMI_ERR_NOMEM, "out of host memory");
+    st->r = r;
+    st->max_nodes = max_observes;
+    hipError_t e = hipMalloc((void **)&st->dparams, sizeof(StepParams));
+    if (e == hipSuccess) e = hipMalloc((void **)&st->slab, (size_t)max_observes * r->slab_slot_words * 4u);
+    // a first launch out of this library, so that none of its code is loaded under a capture
+    StepParams zero;
+    memset(&zero, 0, sizeof zero);
+    if (e == hipSuccess) e = launch_step_begin(r->dctrl, st->dparams, zero, 0u, 0u, r->ctl_stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(r->ctl_stream);
+    if (e != hipSuccess) {
+        if (st->dparams) (void)hipFree(st->dparams);
+        if (st->slab) (void)hipFree(st->slab);
+        delete st;
+        return fail(DMI_ERR_HIP, "step setup failed: %s", hipGetErrorString(e));
+    }
+    *out = st;
+    return DMI_OK;
+}
+
+dmi_status_t dmi_step_destroy(dmi_step_t *st)
+{
+    if (!st) return fail(DMI_ERR_INVALID_ARG, "step is NULL");
+    if (st->open) st->r->quiet.store(0, std::memory_order_release);
+    if (st->begun) st->r->step_open = false;
+    (void)hipSetDevice(st->r->dev);
+    (void)hipFree(st->dparams);
+    (void)hipFree(st->slab);
+    delete st;
+    return DMI_OK;
+}
+
+dmi_status_t dmi_step_capture_begin(dmi_step_t *st)
+{
+    if (!st) return fail(DMI_ERR_INVALID_ARG, "step is NULL");
+    if (st->open || st->sealed) return fail(DMI_ERR_INVALID_ARG, "the step is already open or sealed");
+    dmi_ring *r = st->r;
+    // the caller is about to capture a stream: the library's own threads must keep away from
+    // the HIP API until dmi_step_seal (some of their calls would invalidate the capture)
+    r->quiet.store(1, std::memory_order_release);
+    if (r->bg.joinable()) {
+        const uint64_t t0 = now_ns();
+        while (!r->bg_parked.load(std::memory_order_acquire)) {
+            if (now_ns() - t0 > 2000000000ull) {
+                r->quiet.store(0, std::memory_order_release);
+                return fail(DMI_ERR_AGAIN, "the drain thread did not pause");
+            }
+            std::this_thread::sleep_for(std::chrono::microseconds(50));
+        }
+    }
+    st->open = true;
+    return DMI_OK;
+}
+
+}  // extern "C"
+
+namespace {
+
+// Add one launch to an open step and issue it on the capturing stream.  The only HIP
+// calls made here are the capture-status query and the kernel launch.
+dmi_status_t step_add(dmi_step *st, uint32_t point_id, const dmi_selection_t *sel, const dmi_transform_t *xf,
+                      const Geometry &geo, CaptureArgs &a, uint32_t n_seqs, void *hip_stream, uint32_t *node_out)
+{
+    dmi_ring *r = st->r;
+    if (st->nodes.size() >= st->max_nodes)
+        return fail(DMI_ERR_INVALID_ARG, "the step holds max_observes (%u) launches already", st->max_nodes);
+    // outside a capture the launch would run at once, with whatever the parameter block holds
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing((hipStream_t)hip_stream, &cs) != hipSuccess || cs != hipStreamCaptureStatusActive)
+        return fail(DMI_ERR_INVALID_ARG, "hip_stream is not capturing");
+    StepNode nd;
+    dmi_status_t rc = plan_capture(r, point_id, sel, xf, geo, a, nd.pl);
+    if (rc != DMI_OK) return rc;
+
+    // nodes captured with the same selection share one table (and are updated together)
+    std::vector<uint32_t> words;
+    selection_words(sel->reqs, sel->n_reqs, a.paged != 0, words);
+    uint32_t ti = 0;
+    for (; ti < st->tables.size(); ti++)
+        if (st->tables[ti].paged == (a.paged != 0) && st->tables[ti].words == words) break;
+    if (ti == st->tables.size()) {
+        StepTable t;
+        t.words.swap(words);
+        t.reqs.assign(sel->reqs, sel->reqs + sel->n_reqs);
+        t.paged = a.paged != 0;
+        t.slot = ti;                // at most one table per node, so slots suffice
+        st->tables.push_back(std::move(t));
+    }
+    const uint32_t node = (uint32_t)st->nodes.size();
+    uint32_t *slot = st->slab + (size_t)st->tables[ti].slot * r->slab_slot_words;
+    a.req_table = reinterpret_cast<const uint4 *>(slot);
+    a.row0 = slot + 4u * (size_t)sel->n_reqs;
+    a.seq = 0;
+    a.step_id = 0;
+    a.cslot = nullptr;
+    a.tail_floor = 0;
+    a.drop_newest = 0;
+    a.par_in = node & 1u;           // dmi_step_begin leaves head and tail in copy 0
+    a.step = st->dparams;
+    a.node = node;
+    const hipError_t e = nd.pl.decode ? launch_capture_decode(a, (hipStream_t)hip_stream)
+                                      : launch_capture(a, nd.pl.grid, geo.vec16, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return fail(DMI_ERR_HIP, "capture launch failed: %s", hipGetErrorString(e));
+    nd.a = a;
+    nd.geo = geo;
+    nd.xf = *xf;
+    nd.point_id = point_id;
+    nd.table = ti;
+    nd.index_mode = sel->row_index_dev != nullptr;
+    nd.masked = sel->keep_mask_dev != nullptr;
+    nd.n_seqs = n_seqs;
+    st->nodes.push_back(nd);
+    if (node_out) *node_out = node;
+    return DMI_OK;
+}
+
+// Front checks of dmi_step_observe*: state, arguments, hook filtering (a disabled point
+// adds no launch to the step: it is not in the graph at all).
+dmi_status_t step_gate(dmi_step *st, uint32_t point_id, const dmi_selection_t *sel, const dmi_transform_t *xf,
+                       uint32_t src_dtype)
+{
+    if (!st) return fail(DMI_ERR_INVALID_ARG, "step is NULL");
+    if (!st->open) return fail(DMI_ERR_INVALID_ARG, "call dmi_step_capture_begin first");
+    dmi_ring *r = st->r;
+    if (!sel || !xf) return fail(DMI_ERR_INVALID_ARG, "selection / transform is NULL");
+    if (point_id >= DMI_MAX_POINTS) return fail(DMI_ERR_INVALID_ARG, "point_id %u >= %u", point_id, DMI_MAX_POINTS);
+    if (sel->n_reqs > r->max_reqs)
+        return fail(DMI_ERR_INVALID_ARG, "n_reqs %u exceeds max_reqs_per_observe %u", sel->n_reqs, r->max_reqs);
+    if (sel->n_reqs && !sel->reqs) return fail(DMI_ERR_INVALID_ARG, "reqs is NULL");
+    if (!transform_ok(src_dtype, xf->out_dtype))
+        return fail(DMI_ERR_INVALID_ARG, "unsupported dtype pair %u -> %u", src_dtype, xf->out_dtype);
+    if (xf->summary_mask & ~7u) return fail(DMI_ERR_INVALID_ARG, "bad summary_mask %u", xf->summary_mask);
+    if (r->point_off[point_id]) return DMI_POINT_DISABLED;
+    return DMI_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+dmi_status_t dmi_step_observe(dmi_step_t *st, uint32_t point_id, const dmi_tensor_t *t, const dmi_selection_t *sel,
+                              const dmi_transform_t *xf, void *hip_stream, uint32_t *node)
+{
+    if (!t) return fail(DMI_ERR_INVALID_ARG, "tensor is NULL");
+    dmi_status_t g = step_gate(st, point_id, sel, xf, t->dtype);
+    if (g != DMI_OK) return g;
+    Geometry geo;
+    CaptureArgs a;
+    if ((g = prep_dense(t, sel, geo, a)) != DMI_OK) return g;
+    return step_add(st, point_id, sel, xf, geo, a, 0u, hip_stream, node);
+}
+
+dmi_status_t dmi_step_observe_paged(dmi_step_t *st, uint32_t point_id, const dmi_paged_kv_t *kv,
+                                    const dmi_selection_t *sel, const dmi_transform_t *xf, void *hip_stream,
+                                    uint32_t *node)
+{
+    if (!kv) return fail(DMI_ERR_INVALID_ARG, "kv is NULL");
+    dmi_status_t g = step_gate(st, point_id, sel, xf, kv->dtype);
+    if (g != DMI_OK) return g;
+    Geometry geo;
+    CaptureArgs a;
+    if ((g = prep_paged(kv, sel, geo, a)) != DMI_OK) return g;
+    return step_add(st, point_id, sel, xf, geo, a, kv->n_seqs, hip_stream, node);
+}
+
+dmi_status_t dmi_step_seal(dmi_step_t *st)
+{
+    if (!st) return fail(DMI_ERR_INVALID_ARG, "step is NULL");
+    if (!st->open) return fail(DMI_ERR_INVALID_ARG, "the step is not open");
+    st->open = false;
+    st->sealed = true;
+    st->sum_ub = st->sum_listed = 0;
+    for (auto &nd : st->nodes) { st->sum_ub += nd.pl.ub; st->sum_listed += nd.pl.listed; }
+    st->r->quiet.store(0, std::memory_order_release);
+    return DMI_OK;
+}
+
+dmi_status_t dmi_step_update(dmi_step_t *st, uint32_t node, const dmi_req_sel_t *reqs, uint32_t n_reqs)
+{
+    if (!st || !reqs) return fail(DMI_ERR_INVALID_ARG, "NULL argument");
+    if (!st->sealed) return fail(DMI_ERR_INVALID_ARG, "the step is not sealed");
+    if (st->begun) return fail(DMI_ERR_INVALID_ARG, "between dmi_step_begin and dmi_step_end");
+    if (node >= st->nodes.size()) return fail(DMI_ERR_INVALID_ARG, "no node %u", node);
+    dmi_ring *r = st->r;
+    const uint32_t ti = st->nodes[node].table;
+    StepTable &tab = st->tables[ti];
+    if (n_reqs != tab.reqs.size())
+        return fail(DMI_ERR_INVALID_ARG, "the node was captured with %zu requests, not %u", tab.reqs.size(), n_reqs);
+    uint64_t listed = 0;
+    bool all_one = true;
+    for (uint32_t i = 0; i < n_reqs; i++) { listed += reqs[i].tok_count; all_one = all_one && reqs[i].tok_count == 1u; }
+    // every launch that reads this table must still be the launch that was captured
+    std::vector<uint64_t> ubs;
+    for (auto &nd : st->nodes) {
+        if (nd.table != ti) continue;
+        const CaptureArgs &a = nd.a;
+        dmi_status_t rc = DMI_OK;
+        if (a.paged) rc = check_paged_rows(reqs, n_reqs, nd.n_seqs, a.block_size, a.bt_stride);
+        else if (!nd.index_mode) rc = check_dense_rows(reqs, n_reqs, a.n_src_rows);
+        if (rc != DMI_OK) return rc;
+        if (a.simple && !all_one)
+            return fail(DMI_ERR_INVALID_ARG, "captured with one row per request: capture the step again to change that");
+        if (nd.pl.decode && a.rows_consecutive)
+            for (uint32_t i = 0; i < n_reqs; i++)
+                if (reqs[i].row_base + reqs[i].tok_start != a.row_first + i)
+                    return fail(DMI_ERR_INVALID_ARG, "captured with request i in row %u + i: capture the step again "
+                                                     "to change that", a.row_first);
+        if (listed > 0xFFFFFFFFull || listed * a.units_per_row > 0xFFFFFFFFull)
+            return fail(DMI_ERR_TOO_LARGE, "selection of %llu rows exceeds one record", (unsigned long long)listed);
+        const uint64_t ub = dmi_record_bytes(n_reqs, listed, nd.geo.row_elems, nd.xf.out_dtype, nd.xf.summary_mask);
+        if (ub > r->dev_cap)
+            return fail(DMI_ERR_TOO_LARGE, "record of %llu bytes exceeds the device ring (%llu)",
+                        (unsigned long long)ub, (unsigned long long)r->dev_cap);
+        ubs.push_back(ub);
+    }
+    size_t k = 0;
+    for (auto &nd : st->nodes) {
+        if (nd.table != ti) continue;
+        st->sum_ub += ubs[k] - nd.pl.ub;
+        st->sum_listed += listed - nd.pl.listed;
+        nd.pl.ub = ubs[k++];
+        nd.pl.listed = listed;
+    }
+    tab.reqs.assign(reqs, reqs + n_reqs);
+    selection_words(reqs, n_reqs, tab.paged, tab.words);
+    tab.dirty = true;
+    return DMI_OK;
+}
+
+dmi_status_t dmi_step_begin(dmi_step_t *st, uint64_t step_id, void *hip_stream)
+{
+    if (!st) return fail(DMI_ERR_INVALID_ARG, "step is NULL");
+    if (!st->sealed) return fail(DMI_ERR_INVALID_ARG, "the step is not sealed");
+    dmi_ring *r = st->r;
+    if (st->begun || r->step_open) return fail(DMI_ERR_INVALID_ARG, "a step is already between begin and end");
+    (void)hipSetDevice(r->dev);
+    hipStream_t s = (hipStream_t)hip_stream;
+    const uint32_t n = (uint32_t)st->nodes.size();
+    const uint32_t mode = r->mode.load(std::memory_order_relaxed);
+    const uint32_t k = r->sample_k.load(std::memory_order_relaxed);
+    const bool skip = step_id % k != r->sample_phase.load(std::memory_order_relaxed);
+    dmi_status_t rc;
+    r->last_stream.store(hip_stream, std::memory_order_release);
+    if (!skip && n) {
+        if (mode == DMI_POLICY_BLOCK) {
+            // the flush before the forward step: the whole step must be sure to fit
+            if (st->sum_ub > r->dev_cap)
+                return fail(DMI_ERR_TOO_LARGE, "the step's records (%llu bytes) exceed the device ring (%llu): "
+                            "launches inside a graph cannot wait for the drain",
+                            (unsigned long long)st->sum_ub, (unsigned long long)r->dev_cap);
+            if ((rc = wait_for_room(r, st->sum_ub)) != DMI_OK) return rc;
+        } else {
+            head_upper_bound(r);
+        }
+        if ((rc = commit_slot_room(r, n)) != DMI_OK) return rc;
+    }
+    for (auto &t : st->tables) {
+        if (!t.dirty) continue;
+        if (!t.words.empty())
+            HIP_TRY(launch_upload(st->slab + (size_t)t.slot * r->slab_slot_words, t.words.data(),
+                                  (uint32_t)t.words.size(), s));
+        t.dirty = false;
+    }
+    StepParams v;
+    v.seq_base = r->next_seq.load(std::memory_order_relaxed);
+    v.step_id = step_id;
+    v.tail_floor = r->drain_done.load(std::memory_order_acquire);
+    v.flags = (mode == DMI_POLICY_DROP_NEWEST ? kStepDropNewest : 0u) | (skip ? kStepSkip : 0u);
+    v.pad = 0;
+    HIP_TRY(launch_step_begin(r->dctrl, st->dparams, v, r->chain_par, 0u, s));
+    r->chain_par = 0;
+    st->seq_base = v.seq_base;
+    st->skipped = skip;
+    st->drop_newest = mode == DMI_POLICY_DROP_NEWEST;
+    st->begun = true;
+    r->step_open = true;
+    r->observed_calls += n;
+    if (skip) {
+        r->sampled_out_calls += n;
+        r->sampled_out_rows += st->sum_listed;
+        return DMI_SAMPLED_OUT;
+    }
+    return DMI_OK;
+}
+
+dmi_status_t dmi_step_end(dmi_step_t *st, void *hip_stream)
+{
+    if (!st) return fail(DMI_ERR_INVALID_ARG, "step is NULL");
+    if (!st->begun) return fail(DMI_ERR_INVALID_ARG, "dmi_step_begin has not been called");
+    dmi_ring *r = st->r;
+    (void)hipSetDevice(r->dev);
+    const uint32_t n = (uint32_t)st->nodes.size();
+    st->begun = false;
+    r->step_open = false;
+    r->chain_par = n & 1u;
+    r->last_stream.store(hip_stream, std::memory_order_release);
+    if (st->skipped || !n) return DMI_OK;
+    for (uint32_t i = 0; i < n; i++) {
+        r->inflight.emplace_back(st->seq_base + i, st->nodes[i].pl.ub);
+        r->inflight_sum += st->nodes[i].pl.ub;
+    }
+    {
+        std::lock_guard<std::mutex> lk(r->pmu);
+        r->next_seq.store(st->seq_base + n, std::memory_order_release);
+        for (auto &nd : st->nodes) {
+            if (st->drop_newest || nd.masked) { r->window_exact = false; break; }
+            r->window.bytes += nd.pl.ub; r->window.records += 1; r->window.rows += nd.pl.listed;
+        }
+    }
+    r->unprobed_launches = 0;
+    r->unprobed_bytes = 0;
+    return record_probe(r);
 }
 
 dmi_status_t dmi_drain(dmi_ring_t *r, uint32_t flags, uint64_t *bytes_moved)
@@ -1003,7 +1484,7 @@ dmi_status_t poll_host_impl(dmi_ring *r, dmi_record_view_t *out, uint32_t max, u
     std::lock_guard<std::mutex> lk(r->mu);
     // with the library's drain thread running, arrivals are noted by that thread; a HIP call
     // on the drain stream's events from here would queue up behind its blocking wait
-    if (!(r->cfg.flags & DMI_BG_THREAD)) {
+    if (!(r->cfg.flags & DMI_BG_THREAD) && !r->quiet.load(std::memory_order_acquire)) {
         dmi_status_t st = reap(r, false);
         if (st != DMI_OK) return st;
     }
@@ -1122,11 +1603,16 @@ dmi_status_t dmi_exporter_stop(dmi_ring_t *r)
 {
     if (!r) return fail(DMI_ERR_INVALID_ARG, "ring is NULL");
     if (!r->exp_running.load()) return DMI_OK;
-    r->exp_stop.store(true);
+    {   // set under the lock the dispatcher evaluates its wait condition under
+        std::lock_guard<std::mutex> lk(r->emu);
+        r->exp_stop.store(true);
+    }
     r->ecv_space.notify_all();
     if (r->exporter.joinable()) r->exporter.join();
+    uint64_t dropped = 0;       // pageable budget booked for records no worker will copy
     {
         std::lock_guard<std::mutex> lk(r->jmu);
+        for (auto &j : r->jobs) dropped += j.view.n0 + j.view.n1;
         r->jobs.clear();
     }
     r->jcv.notify_all();
@@ -1134,9 +1620,15 @@ dmi_status_t dmi_exporter_stop(dmi_ring_t *r)
     r->exp_workers.clear();
     {   // discard what was not handed out
         std::lock_guard<std::mutex> lk(r->emu);
+        r->exp_bytes -= dropped;
         for (auto &kv : r->done_jobs) {
-            if (kv.second.slices.empty()) { free(kv.second.rc->bytes); delete kv.second.rc; }
-            else for (auto &sl : kv.second.slices) r->slices.push_back(sl);
+            if (kv.second.slices.empty()) {
+                r->exp_bytes -= kv.second.rc->size;
+                free(kv.second.rc->bytes);
+                delete kv.second.rc;
+            } else {
+                for (auto &sl : kv.second.slices) r->slices.push_back(sl);
+            }
         }
         r->done_jobs.clear();
         for (auto &sl : r->slices) {

@@ -26,9 +26,9 @@ struct CommitSlot {
 // Control block in device memory.  Offsets are logical stream offsets.
 //
 // Launches of one ring run one after another (stream order), so the head needs no
-// atomic reservation: launch `seq` reads head[seq & 1], which the previous launch
+// atomic reservation: the n-th launch reads head[n & 1], which the previous launch
 // wrote and nobody writes during this one, and its workgroup 0 writes
-// head[(seq + 1) & 1], which nobody reads during this one.  No workgroup has to be
+// head[(n + 1) & 1], which nobody reads during this one.  No workgroup has to be
 // the last one, so the kernel has no completion counter and no fence.  The tail the
 // drop-newest decision uses travels the same way (tail_for), fed from `tail`, which the
 // drain advances at any time.
@@ -42,6 +42,20 @@ struct DevCtrl {
     uint32_t point_drops[4096];
     CommitSlot slots[kCommitSlots];
 };
+
+// Per-step values of a replayable step (device memory, one block per step object).
+// Kernels launched as part of such a step take from here what an ordinary launch gets as
+// kernel arguments, so their launches can sit in a captured graph: the graph is replayed
+// unchanged and only this block (and the request tables) are rewritten between replays,
+// the way the paper's keep/drop vector is (section 4.4).
+struct StepParams {
+    uint64_t seq_base;              // sequence number of the step's first observe
+    uint64_t step_id;
+    uint64_t tail_floor;            // the host's view of the tail when the step was begun
+    uint32_t flags;                 // bit 0: drop-newest policy; bit 1: step sampled out, capture nothing
+    uint32_t pad;
+};
+constexpr uint32_t kStepDropNewest = 1u, kStepSkip = 2u;
 
 struct CaptureArgs {
     // source
@@ -87,6 +101,11 @@ struct CaptureArgs {
     uint64_t off_payload, off_sum, sum_arr, record_bytes, payload_bytes;
     uint32_t rows_consecutive;      // request i's row is row_first + i: no table lookup needed
     uint32_t row_first;
+    // launch chain: which copy of head / tail_for this launch reads (it writes the other)
+    uint32_t par_in;
+    // replayable steps: seq = step->seq_base + node, step id, tail floor and policy from *step
+    uint32_t node;
+    const StepParams *step;
 };
 
 // Launchers (dmi_kernels.hip).  All return the launch's hipError_t.
@@ -97,6 +116,10 @@ bool decode_kernel_applies(const CaptureArgs &a, bool vec16);
 hipError_t launch_capture_decode(const CaptureArgs &a, hipStream_t s);
 hipError_t launch_upload(uint32_t *dst, const uint32_t *words, uint32_t n_words, hipStream_t s);
 hipError_t launch_set_tail(DevCtrl *ctrl, uint64_t tail, hipStream_t s);
+// start of a replayable step: writes *step and, if par_from != par_to, carries head and
+// tail_for over to the copy the step's first launch reads
+hipError_t launch_step_begin(DevCtrl *ctrl, StepParams *step, StepParams v, uint32_t par_from, uint32_t par_to,
+                             hipStream_t s);
 hipError_t launch_fetch_slot(const CommitSlot *src, CommitSlot *dst_host, hipStream_t s);
 hipError_t launch_drain_kernel(const uint8_t *ring, uint64_t cap, uint8_t *host_ring, uint64_t host_cap,
                                uint64_t from, uint64_t nbytes, uint32_t grid, hipStream_t s);

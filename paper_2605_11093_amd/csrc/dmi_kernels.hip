@@ -47,6 +47,17 @@ __device__ __forceinline__ void st_agent(uint64_t *p, uint64_t v)
 }
 
 // ---------------------------------------------------------------- wavefront helpers
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also makes every
+// wavefront wait until all of its global stores have been acknowledged, a round trip to
+// memory of a microsecond or more; values handed over through LDS do not need that, and
+// nothing here reads global memory written by another lane of the same launch.
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v, uint32_t lane)
 {
 #pragma unroll
@@ -179,7 +190,11 @@ __device__ __forceinline__ void ring_store(const RingW &w, uint64_t off, T v)
 {
     uint64_t p = w.base + off;
     if (p >= w.cap) p -= w.cap;
-    __builtin_nontemporal_store(v, reinterpret_cast<T *>(w.ring + p));
+    // streaming stores for the vectors a wavefront lays down as whole lines; small scalars (a
+    // summary value per workgroup, pad bytes) are left to L2 to merge: as streaming stores of a
+    // fraction of a line they cost a launch microseconds
+    if constexpr (sizeof(T) >= 8) __builtin_nontemporal_store(v, reinterpret_cast<T *>(w.ring + p));
+    else *reinterpret_cast<T *>(w.ring + p) = v;
 }
 
 // Per-lane partial row summaries.  Sum of squares and sum are fp32; the largest magnitude is
@@ -318,7 +333,7 @@ __host__ __device__ inline LdsMap lds_map(uint32_t n_reqs, bool index_mode, bool
     m.hdr = p; p += 16;
     m.heads = p; p += 8;
     m.red = p; p += 12;
-    m.bcast = p; p += 8;           // head lo/hi, tail lo/hi, spare
+    m.bcast = p; p += 12;          // head, tail, ring offset of the head, policy flags, seq, step id
     m.pref = p; p += n_reqs + 1;
     m.btot = p; p += nb + 1;
     m.pref_all = p; m.btot_all = p;
@@ -346,15 +361,75 @@ struct RowRef {
 #ifdef DMI_TRACE
 __device__ uint64_t g_trace[256 * 8];
 #define DMI_STAMP(k) do { if (tid == 0 && blockIdx.x < 256) g_trace[blockIdx.x * 8 + (k)] = wall_clock64(); } while (0)
+// decode-shaped kernel: first row workgroup and the extra workgroup of the last 32 launches
+#define DMI_STAMP_D(k) do { if (threadIdx.x == 0 && (blockIdx.x == 0 || blockIdx.x == a.n_reqs)) \
+        g_trace[(a.seq & 31u) * 16u + (blockIdx.x == 0 ? 0u : 8u) + (k)] = wall_clock64(); } while (0)
 #else
 #define DMI_STAMP(k) do { } while (0)
+#define DMI_STAMP_D(k) do { } while (0)
 #endif
+
+// Control words of one launch, fetched by one lane per workgroup.  Every load is issued
+// before any result is used, whether or not this launch needs it: loads issued together
+// cost one trip to memory, loads issued as their conditions become known cost one each.
+struct RawControl {
+    uint64_t head, tail_for, tail_now, sp_seq, sp_step, sp_floor;
+    uint64_t cap[3], drop[3];
+    uint32_t sp_flags;
+};
+struct Control {
+    uint64_t head, tail, seq, step_id;
+    uint32_t flags;
+};
+
+// Issues the loads and touches none of the results, so that the caller can put more
+// loads behind them before the first wait.
+__device__ __forceinline__ RawControl fetch_control(const DevCtrl *c, uint32_t par, const StepParams *step)
+{
+    RawControl r;
+    // a launch outside a replayable step reads (and ignores) the head of the control block instead
+    const StepParams *spp = step ? step : reinterpret_cast<const StepParams *>(c);
+    r.head = c->head[par];
+    r.tail_for = c->tail_for[par];
+    r.sp_seq = spp->seq_base; r.sp_step = spp->step_id; r.sp_floor = spp->tail_floor;
+    r.sp_flags = spp->flags;
+    r.tail_now = ld_agent(&c->tail);
+    r.cap[0] = c->captured_records; r.cap[1] = c->captured_rows; r.cap[2] = c->captured_bytes;
+    r.drop[0] = c->dropped_records; r.drop[1] = c->dropped_rows; r.drop[2] = c->dropped_bytes;
+    return r;
+}
+
+__device__ __forceinline__ Control resolve_control(const RawControl &r, bool in_step, uint32_t node,
+                                                   uint64_t tail_floor, uint64_t seq, uint64_t step_id, uint32_t flags)
+{
+    Control o;
+    o.head = r.head;
+    o.seq = in_step ? r.sp_seq + node : seq;
+    o.step_id = in_step ? r.sp_step : step_id;
+    o.flags = in_step ? r.sp_flags : flags;
+    const uint64_t floor = in_step ? r.sp_floor : tail_floor;
+    o.tail = (o.flags & kStepDropNewest) && r.tail_for > floor ? r.tail_for : floor;
+    return o;
+}
+
+// Fetch every line of a by-value kernel argument block now, together.
+template <typename T>
+__device__ __forceinline__ void touch_argument_lines(const T &a)
+{
+    const uint32_t *p = reinterpret_cast<const uint32_t *>(&a);
+    constexpr uint32_t n = (sizeof(T) + 63u) / 64u;
+    static_assert(n <= 10, "argument block larger than expected");
+    auto at = [p](uint32_t line) { return p[(line < n ? line : n - 1u) * 16u]; };
+    asm volatile("" ::"s"(at(0)), "s"(at(1)), "s"(at(2)), "s"(at(3)), "s"(at(4)), "s"(at(5)), "s"(at(6)), "s"(at(7)),
+                 "s"(at(8)), "s"(at(9)));
+}
 
 // ---------------------------------------------------------------- capture kernel
 template <int ES_IN, int VEC, int OUT, bool SUMM>
 __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
+    touch_argument_lines(a);        // all lines of the argument block in one trip, not one by one
     constexpr uint32_t NB_IN = ES_IN * VEC;
     constexpr uint32_t NB_OUT = out_unit_bytes<ES_IN, VEC, OUT>();
     typedef typename UnitT<NB_IN>::T unit_t;
@@ -369,7 +444,7 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
     uint4 *ltab = reinterpret_cast<uint4 *>(lds + m.tab);
     uint32_t *lrb = lds + m.rb;
     const uint32_t nb = (n_reqs + 63u) / 64u;
-    const uint32_t par = (uint32_t)a.seq & 1u;
+    const uint32_t par = a.par_in;
 
     DMI_STAMP(0);
     // -- control words: lane 0 of the last wavefront fetches the head (under drop-newest
@@ -380,28 +455,29 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
     //    this launch reads what the previous one left and writes the other copy, so the
     //    values are the same for every workgroup with no atomic and no waiting.
     constexpr uint32_t kCtlTid = kThreads - 64u;
-    uint64_t cnt_cap[3] = {0, 0, 0}, cnt_drop[3] = {0, 0, 0}, tail_now = 0;
-    if (tid == kCtlTid) {
-        const DevCtrl *c = a.ctrl;
-        const uint64_t h = c->head[par];
-        uint64_t t = a.tail_floor;
-        if (a.drop_newest) {
-            const uint64_t tp = c->tail_for[par];
-            t = tp > t ? tp : t;
-        }
-        if (blockIdx.x == 0) {
-            cnt_cap[0] = c->captured_records; cnt_cap[1] = c->captured_rows; cnt_cap[2] = c->captured_bytes;
-            cnt_drop[0] = c->dropped_records; cnt_drop[1] = c->dropped_rows; cnt_drop[2] = c->dropped_bytes;
-            tail_now = ld_agent(&c->tail);
-        }
-        const uint64_t base = h % a.cap;
+    uint64_t cnt_cap[3] = {0, 0, 0}, cnt_drop[3] = {0, 0, 0}, tail_now = 0, seq = a.seq;
+    RawControl raw = {};
+    if (tid == kCtlTid)     // issued here, used just before the barrier below
+        raw = fetch_control(a.ctrl, par, a.step);
+    auto publish_control = [&]() {
+        const Control ct = resolve_control(raw, a.step != nullptr, a.node, a.tail_floor, a.seq, a.step_id,
+                                           a.drop_newest);
+        seq = ct.seq;
+        tail_now = raw.tail_now;
+        for (int i = 0; i < 3; i++) { cnt_cap[i] = raw.cap[i]; cnt_drop[i] = raw.drop[i]; }
+        const uint64_t base = ct.head % a.cap;
         lds[m.bcast + 4] = (uint32_t)base;
         lds[m.bcast + 5] = (uint32_t)(base >> 32);
-        lds[m.bcast + 0] = (uint32_t)h;
-        lds[m.bcast + 1] = (uint32_t)(h >> 32);
-        lds[m.bcast + 2] = (uint32_t)t;
-        lds[m.bcast + 3] = (uint32_t)(t >> 32);
-    }
+        lds[m.bcast + 0] = (uint32_t)ct.head;
+        lds[m.bcast + 1] = (uint32_t)(ct.head >> 32);
+        lds[m.bcast + 2] = (uint32_t)ct.tail;
+        lds[m.bcast + 3] = (uint32_t)(ct.tail >> 32);
+        lds[m.bcast + 6] = ct.flags;
+        lds[m.bcast + 8] = (uint32_t)ct.seq;
+        lds[m.bcast + 9] = (uint32_t)(ct.seq >> 32);
+        lds[m.bcast + 10] = (uint32_t)ct.step_id;
+        lds[m.bcast + 11] = (uint32_t)(ct.step_id >> 32);
+    };
     if (tid < 8) lds[m.heads + tid] = a.heads_sel[tid];
     DMI_STAMP(1);
 
@@ -430,7 +506,7 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
                 if (lane == 63u) btot_all[b] = inc_all;
             }
         }
-        __syncthreads();
+        lds_barrier();
         if (wave == 0) {
             uint32_t carry = 0, carry_all = 0;
             for (uint32_t b0 = 0; b0 < nb; b0 += 64u) {
@@ -451,7 +527,7 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
                 if (index_mode) btot_all[nb] = carry_all;
             }
         }
-        __syncthreads();
+        lds_barrier();
         for (uint32_t r = tid; r < n_reqs; r += kThreads) {
             pref[r] += btot[r >> 6];
             if (index_mode) pref_all[r] += btot_all[r >> 6];
@@ -492,7 +568,8 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
             pre = true;
         }
     }
-    __syncthreads();
+    if (tid == kCtlTid) publish_control();
+    lds_barrier();
 
     DMI_STAMP(2);
     // -- record geometry
@@ -507,8 +584,18 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
     const uint64_t record_bytes = off_sum + (uint64_t)n_sum * sum_arr;
 
     const uint64_t head = (uint64_t)lds[m.bcast + 0] | ((uint64_t)lds[m.bcast + 1] << 32);
+    const uint32_t flags = lds[m.bcast + 6];
+    if (flags & kStepSkip) {
+        // a sampled-out replay: no record, no sequence number; the chain of head and tail
+        // copies still has to reach the next launch
+        if (blockIdx.x == 0 && tid == kCtlTid) {
+            a.ctrl->head[par ^ 1u] = head;
+            a.ctrl->tail_for[par ^ 1u] = tail_now;
+        }
+        return;
+    }
     bool dropped = false;
-    if (a.drop_newest) {
+    if (flags & kStepDropNewest) {
         const uint64_t tail = (uint64_t)lds[m.bcast + 2] | ((uint64_t)lds[m.bcast + 3] << 32);
         dropped = head - tail + record_bytes > a.cap;
     }
@@ -530,7 +617,7 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
         }
         c->head[par ^ 1u] = new_head;
         c->tail_for[par ^ 1u] = tail_now;
-        CommitSlot *h = a.cslot;
+        CommitSlot *h = a.step ? &c->slots[seq % kCommitSlots] : a.cslot;
         h->head = new_head;
         h->captured_records = cnt_cap[0];
         h->captured_rows = cnt_cap[1];
@@ -538,7 +625,7 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
         h->dropped_records = cnt_drop[0];
         h->dropped_rows = cnt_drop[1];
         h->dropped_bytes = cnt_drop[2];
-        h->seq_plus1 = a.seq + 1u;
+        h->seq_plus1 = seq + 1u;
     }
 
     RingW w;
@@ -606,15 +693,15 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
                 uint32_t *h = lds + m.hdr;
                 h[0] = 0x32494D44u;
                 h[1] = 1u | (64u << 16);
-                h[2] = (uint32_t)a.seq;          h[3] = (uint32_t)(a.seq >> 32);
-                h[4] = (uint32_t)a.step_id;      h[5] = (uint32_t)(a.step_id >> 32);
+                h[2] = lds[m.bcast + 8];         h[3] = lds[m.bcast + 9];       // seq
+                h[4] = lds[m.bcast + 10];        h[5] = lds[m.bcast + 11];      // step id
                 h[6] = a.point_id;
                 h[7] = a.src_dtype | (a.out_dtype << 8) | (a.summary_mask << 16) | (a.rec_flags << 24);
                 h[8] = n_reqs;  h[9] = n_rows;  h[10] = a.row_elems;  h[11] = a.rank_tag;
                 h[12] = (uint32_t)record_bytes;  h[13] = (uint32_t)(record_bytes >> 32);
                 h[14] = (uint32_t)payload_bytes; h[15] = (uint32_t)(payload_bytes >> 32);
             }
-            __syncthreads();
+            lds_barrier();
             if (tid < 4) {
                 const uint32_t *h = lds + m.hdr + 4 * tid;
                 u32x4 v = {h[0], h[1], h[2], h[3]};
@@ -818,13 +905,13 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
                         uint32_t am = wave_max_u32(fold_am<ES_IN, VEC>(acc.am));
                         DMI_STAMP(6);
                         if (rpw == 1u) {
-                            __syncthreads();        // the previous row's readers are done with red[]
+                            lds_barrier();        // the previous row's readers are done with red[]
                             if (lane == 0) {
                                 red[wave] = acc.ss;
                                 red[4 + wave] = acc.s;
                                 reinterpret_cast<uint32_t *>(red)[8 + wave] = am;
                             }
-                            __syncthreads();
+                            lds_barrier();
                             acc.ss = (red[0] + red[1]) + (red[2] + red[3]);
                             acc.s = (red[4] + red[5]) + (red[6] + red[7]);
                             const uint32_t *ra = reinterpret_cast<const uint32_t *>(red) + 8;
@@ -867,56 +954,105 @@ extern "C" int dmi_trace_read(uint64_t *out)
 // issues its loads at once, an extra workgroup writes header, table and pads and publishes.
 // A small capture is bound by instructions issued and dependent memory trips, not by
 // bytes; the general kernel above executes several times as many instructions per row.
+// Kernel arguments of the decode-shaped kernel.  The scalar cache is cold at every launch,
+// so each 64-byte line of the argument block costs a trip to memory when it is first
+// touched, and the compiler, left alone, puts each argument load next to its first use:
+// a chain of such trips, one after another, that is longer than the copy itself.  What
+// every workgroup needs therefore sits in the first two lines, what only the extra
+// workgroup needs in the third, and all three are fetched together at the top.
+struct DecodeArgs {
+    // line 0
+    const uint8_t *src;
+    int64_t row_stride_b;
+    const int32_t *rows;            // row per request (int32 indices or uint32 first rows), unless consecutive
+    uint8_t *ring;
+    uint64_t cap;
+    DevCtrl *ctrl;
+    const StepParams *step;
+    uint64_t tail_floor;
+    // line 1
+    uint64_t record_bytes, off_payload, off_sum, sum_arr;
+    uint32_t n_src_rows, n_reqs, units_per_row, row_first;
+    uint32_t flags;                 // kDec*
+    uint32_t node, summary_mask, row_elems;
+    // line 2
+    uint64_t seq, step_id;
+    const uint4 *req_table;
+    CommitSlot *cslot;
+    uint64_t payload_bytes;
+    uint32_t point_id, hdr7, rank_tag, pad;
+    uint64_t reserved;
+};
+static_assert(sizeof(DecodeArgs) == 192, "three lines");
+constexpr uint32_t kDecDropNewest = 1u, kDecConsecutive = 2u, kDecIndexed = 4u, kDecParIn = 8u;
+
 template <int OUT, bool SUMM>
-__global__ void __launch_bounds__(kThreads) capture_decode_kernel(const CaptureArgs a)
+__global__ void __launch_bounds__(kThreads) capture_decode_kernel(const DecodeArgs a)
 {
-    __shared__ uint32_t sh[24];
+    __shared__ uint32_t sh[32];
+    DMI_STAMP_D(0);
+    touch_argument_lines(a);
     constexpr uint32_t U = 4;
     constexpr uint32_t NB_OUT = out_unit_bytes<2, 8, OUT>();
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
-    const uint32_t par = (uint32_t)a.seq & 1u;
+    const uint32_t par = (a.flags & kDecParIn) ? 1u : 0u;
     const bool meta_wg = blockIdx.x == a.n_reqs;
     constexpr uint32_t kCtlTid = kThreads - 64u;
+    DMI_STAMP_D(1);
 
+    // control words first (they depend on nothing but the arguments), then the row
+    uint64_t cnt_cap[3] = {0, 0, 0}, cnt_drop[3] = {0, 0, 0}, tail_now = 0, seq = a.seq;
+    RawControl raw = {};
+    if (tid == kCtlTid) raw = fetch_control(a.ctrl, par, a.step);
     u32x4 v[U];
     bool ok = false;
     if (!meta_wg) {
         const uint32_t g = blockIdx.x;
         // the usual decode layout (request i in row first + i) saves the dependent trip to the table
-        const int64_t row = a.rows_consecutive ? (int64_t)a.row_first + g
-                            : a.row_index ? (int64_t)a.row_index[g] : (int64_t)a.row0[g];
-        ok = row >= 0 && row < a.n_src_rows;
+        const int64_t row = (a.flags & kDecConsecutive) ? (int64_t)a.row_first + g
+                            : (a.flags & kDecIndexed) ? (int64_t)a.rows[g]
+                                                      : (int64_t)reinterpret_cast<const uint32_t *>(a.rows)[g];
+        ok = row >= 0 && row < (int64_t)a.n_src_rows;
         const uint8_t *base = a.src + (ok ? row : 0) * a.row_stride_b;
 #pragma unroll
-        for (uint32_t k = 0; k < U; k++) {
-            const uint32_t c = tid + k * kThreads;
-            v[k] = u32x4{0u, 0u, 0u, 0u};
-            if (ok && c < a.units_per_row) v[k] = *reinterpret_cast<const u32x4 *>(base + (uint64_t)c * 16u);
+        for (uint32_t k = 0; k < U; k++) v[k] = u32x4{0u, 0u, 0u, 0u};
+        if (ok) {
+            // straight-line loads: lanes past the end of the row fetch its first unit again and
+            // ignore it (a load under its own condition makes the compiler wait between loads)
+#pragma unroll
+            for (uint32_t k = 0; k < U; k++) {
+                const uint32_t c = tid + k * kThreads;
+                v[k] = *reinterpret_cast<const u32x4 *>(base + (uint64_t)(c < a.units_per_row ? c : 0u) * 16u);
+            }
         }
     }
-    uint64_t cnt_cap[3] = {0, 0, 0}, cnt_drop[3] = {0, 0, 0}, tail_now = 0;
     if (tid == kCtlTid) {
-        const DevCtrl *c = a.ctrl;
-        const uint64_t h = c->head[par];
-        uint64_t t = a.tail_floor;
-        if (a.drop_newest) {
-            const uint64_t tp = c->tail_for[par];
-            t = tp > t ? tp : t;
-        }
-        if (meta_wg) {
-            cnt_cap[0] = c->captured_records; cnt_cap[1] = c->captured_rows; cnt_cap[2] = c->captured_bytes;
-            cnt_drop[0] = c->dropped_records; cnt_drop[1] = c->dropped_rows; cnt_drop[2] = c->dropped_bytes;
-            tail_now = ld_agent(&c->tail);
-        }
-        const uint64_t base = h % a.cap;
-        sh[0] = (uint32_t)h;    sh[1] = (uint32_t)(h >> 32);
-        sh[2] = (uint32_t)t;    sh[3] = (uint32_t)(t >> 32);
-        sh[4] = (uint32_t)base; sh[5] = (uint32_t)(base >> 32);
+        const Control ct = resolve_control(raw, a.step != nullptr, a.node, a.tail_floor, a.seq, a.step_id,
+                                           a.flags & kDecDropNewest);
+        seq = ct.seq;
+        tail_now = raw.tail_now;
+        for (int i = 0; i < 3; i++) { cnt_cap[i] = raw.cap[i]; cnt_drop[i] = raw.drop[i]; }
+        const uint64_t base = ct.head % a.cap;
+        sh[0] = (uint32_t)ct.head;  sh[1] = (uint32_t)(ct.head >> 32);
+        sh[2] = (uint32_t)ct.tail;  sh[3] = (uint32_t)(ct.tail >> 32);
+        sh[4] = (uint32_t)base;     sh[5] = (uint32_t)(base >> 32);
+        sh[6] = ct.flags;
+        sh[24] = (uint32_t)ct.seq;      sh[25] = (uint32_t)(ct.seq >> 32);
+        sh[26] = (uint32_t)ct.step_id;  sh[27] = (uint32_t)(ct.step_id >> 32);
     }
-    __syncthreads();
+    lds_barrier();
+    DMI_STAMP_D(2);
     const uint64_t head = (uint64_t)sh[0] | ((uint64_t)sh[1] << 32);
     const uint64_t tail = (uint64_t)sh[2] | ((uint64_t)sh[3] << 32);
-    const bool dropped = a.drop_newest && head - tail + a.record_bytes > a.cap;
+    const uint32_t flags = sh[6];
+    if (flags & kStepSkip) {    // sampled-out replay: pass head and tail on, capture nothing
+        if (meta_wg && tid == kCtlTid) {
+            a.ctrl->head[par ^ 1u] = head;
+            a.ctrl->tail_for[par ^ 1u] = tail_now;
+        }
+        return;
+    }
+    const bool dropped = (flags & kStepDropNewest) && head - tail + a.record_bytes > a.cap;
     RingW w;
     w.ring = a.ring;
     w.cap = a.cap;
@@ -937,15 +1073,20 @@ __global__ void __launch_bounds__(kThreads) capture_decode_kernel(const CaptureA
             }
             c->head[par ^ 1u] = new_head;
             c->tail_for[par ^ 1u] = tail_now;
-            CommitSlot *h = a.cslot;
+            CommitSlot *h = a.step ? &c->slots[seq % kCommitSlots] : a.cslot;
             h->head = new_head;
             h->captured_records = cnt_cap[0]; h->captured_rows = cnt_cap[1]; h->captured_bytes = cnt_cap[2];
             h->dropped_records = cnt_drop[0]; h->dropped_rows = cnt_drop[1]; h->dropped_bytes = cnt_drop[2];
-            h->seq_plus1 = a.seq + 1u;
+            h->seq_plus1 = seq + 1u;
         }
         if (dropped) return;
         if (tid < 4) {
-            u32x4 hv = {a.hdr[4 * tid], a.hdr[4 * tid + 1], a.hdr[4 * tid + 2], a.hdr[4 * tid + 3]};
+            u32x4 hv;
+            if (tid == 0) hv = u32x4{0x32494D44u, 1u | (64u << 16), sh[24], sh[25]};
+            else if (tid == 1) hv = u32x4{sh[26], sh[27], a.point_id, a.hdr7};
+            else if (tid == 2) hv = u32x4{n_rows, n_rows, a.row_elems, a.rank_tag};
+            else hv = u32x4{(uint32_t)a.record_bytes, (uint32_t)(a.record_bytes >> 32), (uint32_t)a.payload_bytes,
+                            (uint32_t)(a.payload_bytes >> 32)};
             ring_store<u32x4>(w, 16u * tid, hv);
         }
         const uint32_t tab_slots = (uint32_t)((a.off_payload - 64u) / 16u);
@@ -965,6 +1106,7 @@ __global__ void __launch_bounds__(kThreads) capture_decode_kernel(const CaptureA
             const uint32_t arr = k / spad, i = k - arr * spad;
             ring_store<uint32_t>(w, a.off_sum + arr * a.sum_arr + (uint64_t)n_rows * 4u + 4ull * i, 0u);
         }
+        DMI_STAMP_D(4);
         return;
     }
 
@@ -973,12 +1115,22 @@ __global__ void __launch_bounds__(kThreads) capture_decode_kernel(const CaptureA
     if (!ok && tid == 0) atomicAdd((unsigned long long *)&a.ctrl->bad_rows, 1ull);
     Accum acc = {0.f, 0.f, 0u};
     const uint64_t row_off = a.off_payload + (uint64_t)g * a.units_per_row * NB_OUT;
+    // all stores first, then the summaries: the launch cannot end before its stores have been
+    // acknowledged, and the arithmetic fits into that wait
 #pragma unroll
     for (uint32_t k = 0; k < U; k++) {
         const uint32_t c = tid + k * kThreads;
         if (c < a.units_per_row)
-            emit_unit<2, 8, OUT, SUMM>(w, row_off + (uint64_t)c * NB_OUT, v[k], 1u, acc);
+            emit_unit<2, 8, OUT, false>(w, row_off + (uint64_t)c * NB_OUT, v[k], 1u, acc);
     }
+    if constexpr (SUMM) {
+#pragma unroll
+        for (uint32_t k = 0; k < U; k++) {
+            const uint32_t c = tid + k * kThreads;
+            if (c < a.units_per_row) emit_unit<2, 8, OUT_NONE, true>(w, 0, v[k], 1u, acc);
+        }
+    }
+    DMI_STAMP_D(3);
     if constexpr (SUMM) {
         acc.ss = wave_sum(acc.ss);
         acc.s = wave_sum(acc.s);
@@ -989,7 +1141,7 @@ __global__ void __launch_bounds__(kThreads) capture_decode_kernel(const CaptureA
             red[4 + wave] = acc.s;
             sh[16 + wave] = am;
         }
-        __syncthreads();
+        lds_barrier();
         if (tid == 0) {
             const float ss = (red[0] + red[1]) + (red[2] + red[3]);
             const float sm = (red[4] + red[5]) + (red[6] + red[7]);
@@ -1001,6 +1153,7 @@ __global__ void __launch_bounds__(kThreads) capture_decode_kernel(const CaptureA
             if (a.summary_mask & 4u) { ring_store<float>(w, o, __uint_as_float(am << 16)); }
         }
     }
+    DMI_STAMP_D(5);
 }
 
 // ---------------------------------------------------------------- small kernels
@@ -1016,6 +1169,19 @@ __global__ void __launch_bounds__(kThreads) upload_kernel(uint32_t *dst, const U
 __global__ void set_tail_kernel(DevCtrl *ctrl, uint64_t tail)
 {
     st_agent(&ctrl->tail, tail);
+}
+
+// Start of a replayable step (an ordinary launch in front of the graph's): the step's
+// parameter block, and head / tail_for carried over to the copy its first launch reads.
+__global__ void step_begin_kernel(DevCtrl *ctrl, StepParams *step, const StepParams v, uint32_t par_from,
+                                  uint32_t par_to)
+{
+    if (threadIdx.x != 0) return;
+    *step = v;
+    if (par_from != par_to) {
+        ctrl->head[par_to] = ctrl->head[par_from];
+        ctrl->tail_for[par_to] = ctrl->tail_for[par_from];
+    }
 }
 
 // Fetch one commit slot into pinned host memory (runs on the library's control stream
@@ -1085,23 +1251,56 @@ bool decode_kernel_applies(const CaptureArgs &a, bool vec16)
 }
 
 template <int OUT>
-static hipError_t launch_decode_t(const CaptureArgs &a, hipStream_t s)
+static hipError_t launch_decode_t(const DecodeArgs &d, bool summaries, hipStream_t s)
 {
-    const dim3 grid(a.n_reqs + 1u);
-    if (a.summary_mask)
-        hipLaunchKernelGGL((capture_decode_kernel<OUT, true>), grid, dim3(kThreads), 0, s, a);
+    const dim3 grid(d.n_reqs + 1u);
+    if (summaries)
+        hipLaunchKernelGGL((capture_decode_kernel<OUT, true>), grid, dim3(kThreads), 0, s, d);
     else
-        hipLaunchKernelGGL((capture_decode_kernel<OUT, false>), grid, dim3(kThreads), 0, s, a);
+        hipLaunchKernelGGL((capture_decode_kernel<OUT, false>), grid, dim3(kThreads), 0, s, d);
     return hipGetLastError();
 }
 
 hipError_t launch_capture_decode(const CaptureArgs &a, hipStream_t s)
 {
+    if (a.n_src_rows < 0 || a.n_src_rows > 0xFFFFFFFFll) return hipErrorInvalidValue;
+    DecodeArgs d;
+    std::memset(&d, 0, sizeof d);
+    d.src = a.src;
+    d.row_stride_b = a.row_stride_b;
+    d.rows = a.row_index ? a.row_index : reinterpret_cast<const int32_t *>(a.row0);
+    d.ring = a.ring;
+    d.cap = a.cap;
+    d.ctrl = a.ctrl;
+    d.step = a.step;
+    d.tail_floor = a.tail_floor;
+    d.record_bytes = a.record_bytes;
+    d.off_payload = a.off_payload;
+    d.off_sum = a.off_sum;
+    d.sum_arr = a.sum_arr;
+    d.n_src_rows = (uint32_t)a.n_src_rows;
+    d.n_reqs = a.n_reqs;
+    d.units_per_row = a.units_per_row;
+    d.row_first = a.row_first;
+    d.flags = (a.drop_newest ? kDecDropNewest : 0u) | (a.rows_consecutive ? kDecConsecutive : 0u) |
+              (a.row_index ? kDecIndexed : 0u) | (a.par_in ? kDecParIn : 0u);
+    d.node = a.node;
+    d.summary_mask = a.summary_mask;
+    d.row_elems = a.row_elems;
+    d.seq = a.seq;
+    d.step_id = a.step_id;
+    d.req_table = a.req_table;
+    d.cslot = a.cslot;
+    d.payload_bytes = a.payload_bytes;
+    d.point_id = a.point_id;
+    d.hdr7 = a.hdr[7];
+    d.rank_tag = a.rank_tag;
+    const bool summ = a.summary_mask != 0;
     switch (a.out_dtype) {
-    case 0: return launch_decode_t<OUT_NONE>(a, s);
-    case 1: return launch_decode_t<OUT_RAW>(a, s);
-    case 2: return launch_decode_t<OUT_FP16>(a, s);
-    case 4: return launch_decode_t<OUT_FP8>(a, s);
+    case 0: return launch_decode_t<OUT_NONE>(d, summ, s);
+    case 1: return launch_decode_t<OUT_RAW>(d, summ, s);
+    case 2: return launch_decode_t<OUT_FP16>(d, summ, s);
+    case 4: return launch_decode_t<OUT_FP8>(d, summ, s);
     default: return hipErrorInvalidValue;
     }
 }
@@ -1122,6 +1321,13 @@ hipError_t launch_upload(uint32_t *dst, const uint32_t *words, uint32_t n_words,
 hipError_t launch_fetch_slot(const CommitSlot *src, CommitSlot *dst_host, hipStream_t s)
 {
     hipLaunchKernelGGL(fetch_slot_kernel, dim3(1), dim3(64), 0, s, src, dst_host);
+    return hipGetLastError();
+}
+
+hipError_t launch_step_begin(DevCtrl *ctrl, StepParams *step, StepParams v, uint32_t par_from, uint32_t par_to,
+                             hipStream_t s)
+{
+    hipLaunchKernelGGL(step_begin_kernel, dim3(1), dim3(64), 0, s, ctrl, step, v, par_from, par_to);
     return hipGetLastError();
 }
 

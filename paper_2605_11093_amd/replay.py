@@ -136,3 +136,135 @@ def run_workload_gpu(wl, *, drain_every: int = 1, release: bool = True, collect:
             s.synchronize()
             ring.destroy()
     return run
+
+
+def run_workload_graph(wl, *, n_graph: Optional[int] = None, drain_every: int = 1, release: bool = True,
+                       flags: int = 0, device_ring_bytes=None, host_ring_bytes=None, lockstep: bool = True,
+                       block_timeout_ms: int = 1, bg_min_bytes: int = 0, replays_per_capture: int = 0) -> GpuRun:
+    """Feed a host-side workload whose steps repeat a fixed list of observes through
+    a captured graph: the first `n_graph` calls of step 0 are captured once
+    (torch.cuda.graph over dmi_step_observe launches on static device buffers); every
+    step copies its tensor contents, keep vectors, row indices and block tables into
+    those buffers, hands changed request tables to dmi_step_update, and replays the
+    graph between dmi_step_begin and dmi_step_end.  Calls beyond the first n_graph of
+    a step go through dmi_observe.  replays_per_capture > 0 re-captures the graph
+    (a new step object) after that many replays."""
+    dev = "cuda:0"
+    n_graph = wl.notes["n_graph"] if n_graph is None else n_graph
+    ring = B.Ring(device_ring_bytes or wl.device_ring_bytes, host_ring_bytes or wl.host_ring_bytes,
+                  flags=flags, max_reqs_per_observe=wl.max_reqs, block_timeout_ms=block_timeout_ms,
+                  bg_min_bytes=bg_min_bytes)
+    ring.set_policy(wl.policy_mode, wl.sample_k, 0)
+    run = GpuRun()
+    s = torch.cuda.current_stream()
+    calls0 = wl.step_calls(0)[:n_graph]
+
+    class Static:                       # device buffers of one fixed launch
+        def __init__(self, c):
+            self.tensor = c.tensor.to(dev)
+            self.keep = None if c.keep_mask is None else torch.zeros(len(c.keep_mask), dtype=torch.uint8, device=dev)
+            self.rows = None if c.row_index is None else torch.zeros(len(c.row_index), dtype=torch.int32, device=dev)
+            self.table = None if c.paged is None else c.paged.block_table.to(dev)
+            self.reqs = None
+
+        def load(self, c):
+            self.tensor.copy_(c.tensor)
+            if self.keep is not None:
+                self.keep.copy_(torch.from_numpy(np.ascontiguousarray(c.keep_mask, dtype=np.uint8)))
+            if self.rows is not None:
+                self.rows.copy_(torch.from_numpy(np.ascontiguousarray(c.row_index, dtype=np.int32)))
+            if self.table is not None:
+                self.table.copy_(c.paged.block_table)
+
+    statics = [Static(c) for c in calls0]
+
+    def capture():
+        step = B.Step(ring, max(1, n_graph))
+        graph = torch.cuda.CUDAGraph()
+        step.capture_begin()
+        with torch.cuda.graph(graph):
+            h = torch.cuda.current_stream().cuda_stream
+            for c, st in zip(calls0, statics):
+                if c.paged is None:
+                    node = step.observe_tensor(c.point_id, st.tensor, c.reqs, stream=h, out_dtype=c.out_dtype,
+                                               summary_mask=c.summary_mask, keep_mask=st.keep, row_index=st.rows)
+                else:
+                    p = c.paged
+                    node = step.observe_paged(c.point_id, st.tensor, st.table, c.reqs, block_size=p.block_size,
+                                              n_heads=p.n_heads, head_dim=p.head_dim, heads_sel=p.heads_sel,
+                                              stream=h, out_dtype=c.out_dtype, summary_mask=c.summary_mask,
+                                              keep_mask=st.keep)
+                st.node = node
+                st.reqs = np.array(c.reqs, copy=True)
+        step.seal()
+        return step, graph
+
+    step, graph = capture()
+    old = []
+    replays = 0
+    keep_alive: list = []
+    try:
+        for sidx, calls in wl.steps():
+            if replays_per_capture and replays == replays_per_capture:
+                old.append((step, graph))           # destroyed once its replays have finished
+                step, graph = capture()
+                replays = 0
+            for c, st in zip(calls[:n_graph], statics):
+                st.load(c)
+                if st.node >= 0 and not np.array_equal(st.reqs, c.reqs):
+                    step.update(st.node, c.reqs)
+                    # launches captured with the same table follow it
+                    for other in statics:
+                        if other is not st and other.reqs is not None and np.array_equal(other.reqs, st.reqs):
+                            other.reqs = np.array(c.reqs, copy=True)
+                    st.reqs = np.array(c.reqs, copy=True)
+            rc = step.begin(sidx, s.cuda_stream, allow=(B.ERR_AGAIN,))
+            tries = 0
+            while rc == B.ERR_AGAIN:
+                consume(ring, run, True, release)
+                tries += 1
+                rc = step.begin(sidx, s.cuda_stream, allow=(B.ERR_AGAIN,) if tries < 200000 else ())
+            graph.replay()
+            step.end(s.cuda_stream)
+            replays += 1
+            if rc == B.OK:
+                run.launched.extend(c for c, st in zip(calls[:n_graph], statics) if st.node >= 0)
+            for c in calls[n_graph:]:
+                c_dev = type(c)(**{**c.__dict__, "tensor": c.tensor.to(dev)})
+                keep_alive.append(c_dev.tensor)
+                rc = observe_call(ring, c_dev, s.cuda_stream, keep_alive, allow=(B.ERR_AGAIN,))
+                tries = 0
+                while rc == B.ERR_AGAIN:
+                    consume(ring, run, True, release)
+                    tries += 1
+                    rc = observe_call(ring, c_dev, s.cuda_stream, keep_alive,
+                                      allow=(B.ERR_AGAIN,) if tries < 200000 else ())
+                if rc == B.OK:
+                    run.launched.append(c)
+            if (sidx + 1) % drain_every == 0:
+                if lockstep:
+                    s.synchronize()
+                ring.drain(B.DRAIN_FLUSH if lockstep else 0, allow=(B.ERR_AGAIN,))
+                consume(ring, run, True, release)
+            else:
+                s.synchronize()     # the next step overwrites the static buffers
+        s.synchronize()
+        deadline = time.monotonic() + 60.0
+        while True:
+            if time.monotonic() > deadline:
+                raise RuntimeError("final drain made no progress for 60 s")
+            ring.drain(B.DRAIN_FLUSH, allow=(B.ERR_AGAIN,))
+            before = run.n_records
+            consume(ring, run, True, release)
+            if ring.last_drain_status == B.OK:
+                break
+            if run.n_records == before and not release:
+                break
+        run.stats = ring.get_stats()
+    finally:
+        s.synchronize()
+        for st_, g_ in old + [(step, graph)]:
+            del g_
+            st_.destroy()
+        ring.destroy()
+    return run

@@ -1,0 +1,174 @@
+"""Replayable steps: capture launches recorded once into a graph (torch.cuda.graph
+over dmi_step_observe) and replayed with new tensor contents, batch composition,
+keep vectors, row indices, block tables, step ids and policies.  The stream must be
+the one the oracle builds for the same observes issued one by one."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import replay as oreplay
+from oracle.decode import decode_record, record_offsets
+from oracle.stream import POLICY_BLOCK, POLICY_DROP_NEWEST
+from workloads import configs, prng
+
+from _util import compare_record, compare_streams
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def B():
+    assert torch.cuda.is_available()
+    from paper_2605_11093_amd import binding
+    binding.lib()
+    return binding
+
+
+@pytest.fixture(scope="module")
+def G():
+    from paper_2605_11093_amd import replay
+    return replay
+
+
+def _check_stats(run, ref):
+    for k in ("observed_calls", "captured_records", "captured_rows", "captured_bytes", "dropped_records",
+              "dropped_rows", "dropped_bytes", "sampled_out_calls", "sampled_out_rows"):
+        assert getattr(run.stats, k) == getattr(ref.stats, k), k
+
+
+@pytest.mark.parametrize("n_graph,extra", [(6, 0), (6, 2), (5, 2), (1, 1), (3, 0)])
+def test_replayed_step_equals_the_oracle_stream(B, G, n_graph, extra):
+    # odd launch counts and ordinary observes between replays exercise the hand-over of
+    # head and tail between the two copies of the control words
+    wl = configs.replayed_step(n_steps=6, n_graph=n_graph, eager_extra_every=extra)
+    ref = oreplay.run_workload(wl)
+    run = G.run_workload_graph(wl)
+    compare_streams(run.stream, ref.stream())
+    _check_stats(run, ref)
+    assert run.stats.bad_rows == 0
+
+
+def test_sampled_out_replays_capture_nothing_and_take_no_sequence_numbers(B, G):
+    wl = configs.replayed_step(n_steps=7, n_graph=5, eager_extra_every=3, sample_k=2)
+    ref = oreplay.run_workload(wl)
+    run = G.run_workload_graph(wl)
+    compare_streams(run.stream, ref.stream())
+    _check_stats(run, ref)
+    steps = sorted({decode_record(b).step_id for _, b in run.records})
+    assert steps == [0, 2, 4, 6]
+
+
+def test_drop_newest_in_lockstep_drops_the_same_records(B, G):
+    # device ring holds about one and a half steps; drains every second step
+    wl = configs.replayed_step(n_steps=8, n_graph=6, eager_extra_every=2, policy_mode=POLICY_DROP_NEWEST,
+                               device_ring_bytes=640 << 10)
+    ref = oreplay.run_workload(wl, drain_every=2)
+    assert ref.stats.dropped_records > 0 and ref.stats.captured_records > 0
+    run = G.run_workload_graph(wl, drain_every=2)
+    compare_streams(run.stream, ref.stream())
+    _check_stats(run, ref)
+
+
+def test_small_rings_wrap_and_block_waits_for_the_whole_step(B, G):
+    # one step is ~390 KB; the device ring holds one step, the host ring two
+    wl = configs.replayed_step(n_steps=6, n_graph=6, device_ring_bytes=448 << 10, host_ring_bytes=896 << 10)
+    ref = oreplay.run_workload(wl)
+    run = G.run_workload_graph(wl)
+    compare_streams(run.stream, ref.stream())
+    assert run.stats.dropped_records == 0
+
+
+def test_recapture_and_library_drain_thread(B, G):
+    # a new step object every second replay; the drain thread is paused during each capture
+    wl = configs.replayed_step(n_steps=6, n_graph=6, eager_extra_every=2)
+    ref = oreplay.run_workload(wl)
+    run = G.run_workload_graph(wl, flags=B.BG_THREAD | B.DRAIN_KERNEL, lockstep=False, replays_per_capture=2,
+                               bg_min_bytes=4096)
+    compare_streams(run.stream, ref.stream())
+    _check_stats(run, ref)
+
+
+def _t(rows=64, E=256, seed=1):
+    return prng.randn_bf16(prng.sub_seed(23, seed), rows * E, DEV).view(rows, E)
+
+
+def _reqs(n, rows_each=1):
+    return np.array([(100 + i, i * rows_each, 0, rows_each, 1) for i in range(n)], dtype=np.uint32)
+
+
+def test_step_protocol_errors(B):
+    t = _t()
+    s = torch.cuda.current_stream().cuda_stream
+    with B.Ring(1 << 20, 1 << 20) as ring:
+        step = B.Step(ring, 4)
+        with pytest.raises(B.DmiError):             # not open yet
+            step.observe_tensor(0, t, _reqs(4), stream=s)
+        with pytest.raises(B.DmiError):             # not sealed yet
+            step.begin(0, s)
+        step.capture_begin()
+        with pytest.raises(B.DmiError) as e:        # the stream is not capturing
+            step.observe_tensor(0, t, _reqs(4), stream=s)
+        assert e.value.code == B.ERR_INVALID_ARG
+        ring.point_enable(3, False)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            h = torch.cuda.current_stream().cuda_stream
+            assert step.observe_tensor(3, t, _reqs(4), stream=h) == -1      # disabled: not part of the step
+            n0 = step.observe_tensor(0, t, _reqs(4), stream=h)
+            n1 = step.observe_tensor(1, t, _reqs(4, 2), stream=h, summary_mask=1)
+        assert (n0, n1) == (0, 1)
+        step.seal()
+        with pytest.raises(B.DmiError):
+            step.observe_tensor(0, t, _reqs(4), stream=s)
+        for bad in (_reqs(5), _reqs(4, 2), np.array([(1, 0, 0, 1, 1), (2, 1, 0, 1, 1), (3, 2, 0, 1, 1), (4, 64, 0, 1, 1)])):
+            with pytest.raises(B.DmiError) as e:
+                step.update(n0, bad)
+            assert e.value.code == B.ERR_INVALID_ARG
+        with pytest.raises(B.DmiError) as e:        # rows would leave the tensor
+            step.update(n1, _reqs(4, 17))
+        assert e.value.code == B.ERR_INVALID_ARG
+        step.update(n1, _reqs(4, 16))               # ragged launches may change their row counts
+        assert step.begin(0, s) == B.OK
+        with pytest.raises(B.DmiError) as e:        # no ordinary observe inside a step
+            ring.observe_tensor(0, t, _reqs(4), step_id=0, stream=s)
+        assert e.value.code == B.ERR_INVALID_ARG
+        with pytest.raises(B.DmiError):
+            step.begin(1, s)
+        graph.replay()
+        step.end(s)
+        with pytest.raises(B.DmiError):
+            step.end(s)
+        ring.drain(B.DRAIN_FLUSH)
+        recs = [decode_record(v.bytes()) for v in ring.poll_host()]
+        assert [(r.seq, r.point_id, r.n_rows) for r in recs] == [(0, 0, 4), (1, 1, 64)]
+        torch.cuda.synchronize()
+        step.destroy()
+
+
+def test_block_policy_refuses_a_step_that_can_never_fit(B):
+    t = _t(64, 256)
+    s = torch.cuda.current_stream().cuda_stream
+    with B.Ring(16384, 1 << 20) as ring:
+        step = B.Step(ring, 4)
+        step.capture_begin()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            h = torch.cuda.current_stream().cuda_stream
+            for p in range(3):
+                step.observe_tensor(p, t, _reqs(15), stream=h)      # 3 x 8000 bytes > 16384
+        step.seal()
+        with pytest.raises(B.DmiError) as e:
+            step.begin(0, s)
+        assert e.value.code == B.ERR_TOO_LARGE
+        ring.set_policy(B.POLICY_DROP_NEWEST)
+        assert step.begin(0, s) == B.OK             # best effort: the third record is dropped on the device
+        graph.replay()
+        step.end(s)
+        ring.drain(B.DRAIN_FLUSH)
+        assert [v.seq for v in ring.poll_host()] == [0, 1]
+        st = ring.get_stats()
+        assert (st.captured_records, st.dropped_records, st.dropped_bytes) == (2, 1, 8000)
+        assert ring.get_point_drops(2) == 1
+        torch.cuda.synchronize()
+        step.destroy()

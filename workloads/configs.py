@@ -210,3 +210,73 @@ def config4_paged_kv(device="cpu", n_layers_cap=4, n_blocks=65536, block_size=16
     return Workload("paged_kv", device_ring_bytes, host_ring_bytes, POLICY_BLOCK, 1,
                     n_steps, step_calls, max_reqs=max(64, reqs_per_step),
                     notes={"ctx0": ctx0, "layers": [0, 10, 21, 31][:n_layers_cap]})
+
+
+# --------------------------------------------------------------------------
+# replayed step: the same list of observes every step (fixed tensor shapes, request
+# counts and transforms, as a captured graph has them), while tensor contents, batch
+# composition, keep vectors, row indices and block tables change from step to step
+# --------------------------------------------------------------------------
+def replayed_step(n_steps=6, n_graph=6, eager_extra_every=0, policy_mode=POLICY_BLOCK, sample_k=1,
+                  device_ring_bytes=4 << 20, host_ring_bytes=16 << 20) -> Workload:
+    """Host-side workload (tensors on the CPU; a harness copies each step's contents
+    into its static device buffers).  The first `n_graph` calls of every step are the
+    step's fixed launches, in a fixed order:
+      0  bf16 [64, 1024]   one row per request in rows 0..63, raw + L2 + absmax
+      1  bf16 [64, 1024]   same selection, fp8 out
+      2  bf16 [300, 256]   ragged token ranges + keep vector, fp16 out, mean
+      3  fp32 [40, 101]    explicit row indices (rows not 16-byte movable), raw
+      4  bf16 paged [48, 16, 4, 64], heads {1, 3}, token ranges that grow, raw + absmax
+      5  bf16 [64, 1024]   one row per request, rows permuted per step, raw
+    With eager_extra_every = m > 0 every m-th step ends with one more observe that
+    is not part of the fixed list (issued the ordinary way between replays)."""
+    assert 1 <= n_graph <= 6
+    n_r = 64
+
+    def t_bf16(tag, step, shape):
+        return prng.randn_bf16(prng.sub_seed(9, tag, step), int(np.prod(shape))).view(*shape)
+
+    block_size, n_heads, head_dim, n_blocks, n_seqs, max_blocks = 16, 4, 64, 48, 6, 8
+
+    def step_calls(step):
+        calls = []
+        # 0, 1: decode-shaped, request ids change with the step
+        reqs01 = make_reqs((100 * step + r, r, 0, 1, 1) for r in range(n_r))
+        x0 = t_bf16(0, step, (n_r, 1024))
+        calls.append(ObserveCall(point_id=0, step_id=step, tensor=x0, reqs=reqs01, out_dtype=DT_BF16,
+                                 summary_mask=SUM_L2 | SUM_ABSMAX))
+        calls.append(ObserveCall(point_id=1, step_id=step, tensor=t_bf16(1, step, (n_r, 1024)), reqs=reqs01,
+                                 out_dtype=DT_FP8))
+        # 2: ragged ranges inside 5 requests of 60 rows each, keep vector
+        lens = prng.randint(prng.sub_seed(9, 20, step), 5, 0, 12)
+        starts = prng.randint(prng.sub_seed(9, 21, step), 5, 0, 20)
+        reqs2 = make_reqs((7 * step + r, 60 * r, int(starts[r]), int(lens[r]), 1 + (r + step) % 3)
+                          for r in range(5))
+        keep2 = (prng.randint(prng.sub_seed(9, 22, step), 5, 0, 3) > 0).astype(np.uint8)
+        calls.append(ObserveCall(point_id=2, step_id=step, tensor=t_bf16(2, step, (300, 256)), reqs=reqs2,
+                                 out_dtype=DT_FP16, summary_mask=SUM_MEAN, keep_mask=keep2))
+        # 3: fp32, explicit rows (3 requests x 4 rows)
+        rows3 = prng.randint(prng.sub_seed(9, 30, step), 12, 0, 39).astype(np.int32)
+        reqs3 = make_reqs((50 + r, 0, 10 * step + r, 4, 2) for r in range(3))
+        calls.append(ObserveCall(point_id=3, step_id=step, tensor=t_bf16(3, step, (40, 101)).float(),
+                                 reqs=reqs3, out_dtype=DT_FP32, row_index=rows3))
+        # 4: paged cache, contexts grow by one token per step, block table reshuffled per step
+        table = prng.permutation(prng.sub_seed(9, 40, step), n_blocks).astype(np.int32).reshape(n_seqs, max_blocks)
+        spec = PagedSpec(block_size, n_heads, head_dim, [1, 3], torch.from_numpy(np.ascontiguousarray(table)))
+        reqs4 = make_reqs((900 + r, r + 1, 0, 20 + 9 * r + step, 1) for r in range(4))
+        calls.append(ObserveCall(point_id=4, step_id=step,
+                                 tensor=t_bf16(4, step, (n_blocks, block_size, n_heads, head_dim)),
+                                 reqs=reqs4, out_dtype=DT_BF16, summary_mask=SUM_ABSMAX, paged=spec))
+        # 5: one row per request, rows permuted
+        perm = prng.permutation(prng.sub_seed(9, 50, step), n_r)
+        reqs5 = make_reqs((3000 + r, int(perm[r]), 0, 1, 1) for r in range(n_r))
+        calls.append(ObserveCall(point_id=5, step_id=step, tensor=t_bf16(5, step, (n_r, 1024)), reqs=reqs5,
+                                 out_dtype=DT_BF16))
+        calls = calls[:n_graph]
+        if eager_extra_every and step % eager_extra_every == eager_extra_every - 1:
+            reqs6 = make_reqs([(1, 2, 0, 3, 1)])
+            calls.append(ObserveCall(point_id=6, step_id=step, tensor=x0, reqs=reqs6, out_dtype=DT_BF16))
+        return calls
+
+    return Workload("replayed_step", device_ring_bytes, host_ring_bytes, policy_mode, sample_k, n_steps,
+                    step_calls, max_reqs=64, notes={"n_graph": n_graph})
