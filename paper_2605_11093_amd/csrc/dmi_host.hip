@@ -554,12 +554,28 @@ dmi_status_t plan_capture(dmi_ring *r, uint32_t point_id, const dmi_selection_t 
     a.table_in_lds = tab_lds ? 1u : 0u;
     a.lds_bytes = capture_lds_bytes(simple ? 0u : sel->n_reqs, index_mode, tab_lds);
 
+    // Work items per launch path, and a grid that gives every workgroup the same number of them:
+    // with a fixed grid of "as many as fit" the last round is run by a fraction of the
+    // workgroups while the rest idle (up to half the launch for 1 < items/grid < 2).
+    // kResident is what stays resident at the register budget of the widest variants.
+    constexpr uint64_t kResident = 5u * 256u;
+    auto balanced = [](uint64_t items) -> uint64_t {
+        if (items <= kResident) return items;
+        const uint64_t rounds = (items + kResident - 1u) / kResident;
+        return (items + rounds - 1u) / rounds;
+    };
     uint64_t groups;
-    if (xf->summary_mask) groups = (listed + a.rows_per_wg - 1u) / a.rows_per_wg;
-    else if (upr >= kThreads && upr < 4u * kThreads && (4u * kThreads) % upr == 0)
-        groups = (listed + 4u * kThreads / upr - 1u) / (4u * kThreads / upr);      // 2 or 4 rows per work item
-    else if (upr >= kThreads) groups = listed * ((upr + 4u * kThreads - 1u) / (4u * kThreads));
-    else groups = (listed * upr + kThreads - 1u) / kThreads;
+    if (xf->summary_mask) {
+        groups = balanced((listed + a.rows_per_wg - 1u) / a.rows_per_wg);
+    } else if (upr >= kThreads && upr < 4u * kThreads && (4u * kThreads) % upr == 0) {
+        groups = balanced((listed + 4u * kThreads / upr - 1u) / (4u * kThreads / upr));      // 2 or 4 rows per work item
+    } else if (upr >= kThreads) {
+        groups = balanced(listed * ((upr + 4u * kThreads - 1u) / (4u * kThreads)));
+    } else {
+        // short rows: slices of 256 units; a workgroup takes 4 per round once there are enough
+        const uint64_t slices = (listed * upr + kThreads - 1u) / kThreads;
+        groups = slices <= kResident ? slices : balanced((slices + 3u) / 4u);
+    }
     pl.grid = groups < 1u ? 1u : groups > kMaxGrid ? kMaxGrid : (uint32_t)groups;
 
     pl.decode = decode_kernel_applies(a, geo.vec16);

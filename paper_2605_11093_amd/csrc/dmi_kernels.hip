@@ -810,30 +810,69 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
                     }
                 } else {
                     // ---- short rows: the n_rows x units_per_row units are dealt to lanes in order,
-                    //      so stores stay fully coalesced; 4 loads in flight per lane
-                    const uint64_t total = (uint64_t)n_rows * a.units_per_row;
-                    for (uint64_t t0 = (uint64_t)blockIdx.x * kThreads; t0 < total;
-                         t0 += (uint64_t)gridDim.x * U * kThreads) {
+                    //      so stores stay fully coalesced; 4 loads in flight per lane.
+                    //      A wavefront's 64 units of one slice lie in at most 64/upr + 2 rows.  When
+                    //      the rows of its four slices fit the 64 lanes, each lane locates one row
+                    //      (all of them in a single pass) and every unit picks up its row's place by
+                    //      shuffle: locating a row costs on the order of a hundred instructions, and
+                    //      done per unit that, not memory, is what the launch spends its time on.
+                    const uint32_t total = (uint32_t)((uint64_t)n_rows * a.units_per_row);  // host keeps it below 2^32
+                    const uint32_t upr = a.units_per_row;
+                    auto row_of = [&](uint32_t u) { return a.upr_shift < 32u ? u >> a.upr_shift : u / upr; };
+                    const bool shared_locate = 64u / upr + 2u <= 16u;
+                    const uint32_t slice_stride = gridDim.x * kThreads;
+                    for (uint64_t t0 = (uint64_t)blockIdx.x * kThreads; t0 < total; t0 += (uint64_t)slice_stride * U) {
                         unit_t v[U];
                         bool live[U];
-#pragma unroll
-                        for (uint32_t k = 0; k < U; k++) {
-                            const uint64_t u = t0 + (uint64_t)k * gridDim.x * kThreads + tid;
-                            live[k] = u < total;
-                            v[k] = unit_t{};
-                            if (live[k]) {
-                                const uint32_t u32 = (uint32_t)u;       // host keeps total below 2^32
-                                const uint32_t g = a.upr_shift < 32u ? u32 >> a.upr_shift : u32 / a.units_per_row;
-                                const uint32_t c = u32 - g * a.units_per_row;
-                                const RowRef ref = locate(g);
-                                if (!ref.ok && c == 0)
-                                    atomicAdd((unsigned long long *)&a.ctrl->bad_rows, 1ull);
-                                v[k] = load_unit(ref, c);
+                        uint32_t my_lo = 0, my_hi = 0, my_ok = 0, my_first = 0;
+                        if (shared_locate) {
+                            const uint32_t sl = lane >> 4, j = lane & 15u;
+                            const uint64_t us = t0 + (uint64_t)sl * slice_stride + wave * 64u;
+                            if (us < total) {
+                                const uint32_t ue = us + 63u < total ? (uint32_t)us + 63u : total - 1u;
+                                my_first = row_of((uint32_t)us);
+                                const uint32_t g = my_first + j;
+                                if (g <= row_of(ue)) {
+                                    const RowRef ref = locate(g);
+                                    my_lo = (uint32_t)(uintptr_t)ref.base;
+                                    my_hi = (uint32_t)((uintptr_t)ref.base >> 32);
+                                    my_ok = ref.ok ? 1u : 0u;
+                                    // a bad row is counted where its first unit lies
+                                    const uint64_t fu = (uint64_t)g * upr;
+                                    if (!ref.ok && fu >= us && fu <= ue)
+                                        atomicAdd((unsigned long long *)&a.ctrl->bad_rows, 1ull);
+                                }
                             }
                         }
 #pragma unroll
                         for (uint32_t k = 0; k < U; k++) {
-                            const uint64_t u = t0 + (uint64_t)k * gridDim.x * kThreads + tid;
+                            const uint64_t u = t0 + (uint64_t)k * slice_stride + tid;
+                            live[k] = u < total;
+                            const uint32_t u32 = live[k] ? (uint32_t)u : total - 1u;
+                            const uint32_t g = row_of(u32);
+                            const uint32_t c = u32 - g * upr;
+                            RowRef ref;
+                            if (shared_locate) {
+                                // executed by all 64 lanes: a shuffle reads nothing useful from a lane that is off
+                                const uint32_t first_k = __shfl(my_first, (int)(k << 4), 64);
+                                const int src = (int)(((k << 4) + (g - first_k)) & 63u);
+                                const uint32_t lo = __shfl(my_lo, src, 64), hi = __shfl(my_hi, src, 64);
+                                ref.ok = __shfl(my_ok, src, 64);
+                                ref.base = reinterpret_cast<const uint8_t *>(((uint64_t)hi << 32) | lo);
+                                if (!live[k]) ref.ok = 0;
+                            } else {
+                                ref.base = nullptr;
+                                ref.ok = 0;
+                                if (live[k]) {
+                                    ref = locate(g);
+                                    if (!ref.ok && c == 0) atomicAdd((unsigned long long *)&a.ctrl->bad_rows, 1ull);
+                                }
+                            }
+                            v[k] = load_unit(ref, c);
+                        }
+#pragma unroll
+                        for (uint32_t k = 0; k < U; k++) {
+                            const uint64_t u = t0 + (uint64_t)k * slice_stride + tid;
                             if (live[k])
                                 emit_unit<ES_IN, VEC, OUT, false>(w, off_payload + u * NB_OUT, v[k],
                                                                   a.src_dtype, dummy);
