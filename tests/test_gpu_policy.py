@@ -210,3 +210,55 @@ def test_record_straddling_the_host_ring_end_comes_back_in_two_spans(B):
         for step, (_, b) in enumerate(out):
             assert np.array_equal(b, orc.build_record(t.cpu(), _reqs(16), seq=step, step_id=step, point_id=0,
                                                       out_dtype=1))
+
+
+@pytest.mark.parametrize("flags_name", ["none", "bg"])
+def test_commit_accounting_across_policy_and_mask_changes(B, flags_name):
+    """How the host learns what was committed differs by launch kind (sizes known on the
+    host under the completeness policy without a keep vector; read back from the device
+    otherwise).  A sequence that keeps switching kinds, with drains in between, must
+    still add up: same stream, same counters as the oracle."""
+    from workloads import prng as P
+    t = _t(64, 256, seed=9)
+    tc = t.cpu()
+    flags = B.BG_THREAD if flags_name == "bg" else 0
+    ref = OracleRing(8 << 20, 32 << 20, POLICY_BLOCK)
+    kinds = P.randint(P.sub_seed(77, 1), 150, 0, 2)
+    sizes = P.randint(P.sub_seed(77, 2), 150, 1, 20)
+    drains = P.randint(P.sub_seed(77, 3), 150, 0, 6)
+    keep_alive = []
+    with B.Ring(8 << 20, 32 << 20, flags=flags, bg_min_bytes=4096) as ring:
+        s = torch.cuda.current_stream()
+        got = []
+        for i in range(150):
+            kind, n = int(kinds[i]), int(sizes[i])
+            reqs = np.array([(i * 100 + r, 3 * r, 0, 1 + (r + i) % 3, 1) for r in range(n)], dtype=np.uint32)
+            keep = None
+            if kind == 1:       # completeness policy, keep vector: sizes decided on the device
+                keep = (P.randint(P.sub_seed(77, 4, i), n, 0, 1)).astype(np.uint8)
+            mode = B.POLICY_DROP_NEWEST if kind == 2 else B.POLICY_BLOCK
+            ring.set_policy(mode)
+            ref.mode = POLICY_DROP_NEWEST if kind == 2 else POLICY_BLOCK
+            km = None
+            if keep is not None:
+                km = torch.from_numpy(keep).to(DEV)
+                keep_alive.append(km)
+            assert ring.observe_tensor(i % 7, t, reqs, step_id=i, stream=s.cuda_stream, keep_mask=km,
+                                       summary_mask=i % 8) == B.OK
+            assert ref.observe(tc, reqs, point_id=i % 7, step_id=i, out_dtype=1, summary_mask=i % 8,
+                               keep_mask=keep) == 0
+            if drains[i] == 0:
+                ring.drain(0)               # moves what has committed by now, whatever that is
+                for v in ring.poll_host():
+                    got.append(v.bytes())
+                    ring.release_host(v.seq)
+        s.synchronize()
+        ring.drain(B.DRAIN_FLUSH)
+        for v in ring.poll_host():
+            got.append(v.bytes())
+        ref.drain()
+        from _util import compare_streams
+        compare_streams(np.concatenate(got), ref.stream())
+        st = ring.get_stats()
+        assert (st.captured_records, st.captured_rows, st.captured_bytes, st.dropped_records) == \
+            (ref.stats.captured_records, ref.stats.captured_rows, ref.stats.captured_bytes, 0)
