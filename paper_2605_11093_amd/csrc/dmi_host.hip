@@ -79,10 +79,6 @@ struct SelCache {
     std::vector<uint32_t> words;
 };
 
-struct Pending {
-    hipEvent_t ev;
-    uint64_t upto;
-};
 
 // One record copied out of the pinned ring (exporter stage 2) and shared by its slices.
 struct RecordCopy {
@@ -157,6 +153,7 @@ struct dmi_ring {
     // producer side
     std::atomic<uint64_t> next_seq{0};                     // launches issued so far
     std::atomic<void *> last_stream{nullptr};
+    std::atomic<uint64_t> last_launch_ns{0};
     std::deque<std::pair<uint64_t, uint64_t>> inflight;    // (seq, upper bound of record bytes)
     uint64_t inflight_sum = 0;
     uint64_t unprobed_launches = 0, unprobed_bytes = 0, probe_bytes = 8u << 20;
@@ -180,8 +177,13 @@ struct dmi_ring {
     std::mutex mu;
     uint64_t drain_issued = 0;
     std::atomic<uint64_t> drain_done{0};
-    std::deque<Pending> pending;
-    std::vector<hipEvent_t> ev_pool;
+    // The drain stream carries the batch copies only (no launch, no event, no small copy: any
+    // of these is a packet on a second compute queue, and a second queue with packets pending
+    // slows every dispatch of the producer's queue by microseconds).  A batch is known to be
+    // done when the whole stream is idle; the drained-up-to mark reaches the kernels through a
+    // pinned host word that they read themselves.
+    volatile uint64_t *htail = nullptr;                    // pinned, coherent
+    const uint64_t *htail_dev = nullptr;                   // its device address
     uint64_t poll_cursor = 0, released = 0;
     std::deque<std::pair<uint64_t, uint64_t>> polled;      // (seq, end offset)
 
@@ -310,18 +312,15 @@ dmi_status_t advance_commits(dmi_ring *r, bool block)
 
 uint64_t read_committed(const dmi_ring *r) { return r->committed.load(std::memory_order_acquire); }
 
-// Retire finished copies.  Caller holds r->mu.
+// Retire finished copies (all of them at once: the drain stream is idle).  Caller holds r->mu.
 dmi_status_t reap(dmi_ring *r, bool wait)
 {
-    while (!r->pending.empty()) {
-        Pending &p = r->pending.front();
-        hipError_t e = wait ? hipEventSynchronize(p.ev) : hipEventQuery(p.ev);
-        if (e == hipErrorNotReady) break;
-        if (e != hipSuccess) return fail(DMI_ERR_HIP, "drain event: %s", hipGetErrorString(e));
-        r->drain_done.store(p.upto, std::memory_order_release);
-        r->ev_pool.push_back(p.ev);
-        r->pending.pop_front();
-    }
+    if (r->drain_done.load(std::memory_order_relaxed) == r->drain_issued) return DMI_OK;
+    hipError_t e = wait ? hipStreamSynchronize(r->drain_stream) : hipStreamQuery(r->drain_stream);
+    if (e == hipErrorNotReady) return DMI_OK;
+    if (e != hipSuccess) return fail(DMI_ERR_HIP, "drain stream: %s", hipGetErrorString(e));
+    r->drain_done.store(r->drain_issued, std::memory_order_release);
+    *r->htail = r->drain_issued;
     return DMI_OK;
 }
 
@@ -360,13 +359,6 @@ dmi_status_t drain_issue_locked(dmi_ring *r, uint64_t *moved)
                 left -= len;
             }
         }
-        // the device may reuse the span only after the copies before this have run
-        HIP_TRY(launch_set_tail(r->dctrl, from + n, r->drain_stream));
-        hipEvent_t ev;
-        if (r->ev_pool.empty()) HIP_TRY(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
-        else { ev = r->ev_pool.back(); r->ev_pool.pop_back(); }
-        HIP_TRY(hipEventRecord(ev, r->drain_stream));
-        r->pending.push_back({ev, from + n});
         r->drain_issued = from + n;
         r->drained_bytes += n;
         r->drain_batches += 1;
@@ -381,19 +373,23 @@ dmi_status_t drain_issue_locked(dmi_ring *r, uint64_t *moved)
 // producer asks for room, while a copy is in flight.
 dmi_status_t drain(dmi_ring *r, bool wait, uint64_t *moved)
 {
-    hipEvent_t last = nullptr;
+    uint64_t mark;
     {
         std::lock_guard<std::mutex> lk(r->mu);
         dmi_status_t st = drain_issue_locked(r, moved);
         if (st != DMI_OK) return st;
-        if (!r->pending.empty()) last = r->pending.back().ev;
+        mark = r->drain_issued;
+        if (!wait || r->drain_done.load(std::memory_order_relaxed) == mark) return DMI_OK;
     }
-    if (!wait || !last) return DMI_OK;
-    // an event that another thread retires meanwhile has completed, so this returns at once
-    hipError_t e = hipEventSynchronize(last);
-    if (e != hipSuccess) return fail(DMI_ERR_HIP, "drain event: %s", hipGetErrorString(e));
+    // everything issued up to `mark` was on the stream before this call
+    hipError_t e = hipStreamSynchronize(r->drain_stream);
+    if (e != hipSuccess) return fail(DMI_ERR_HIP, "drain stream: %s", hipGetErrorString(e));
     std::lock_guard<std::mutex> lk(r->mu);
-    return reap(r, false);
+    if (r->drain_done.load(std::memory_order_relaxed) < mark) {
+        r->drain_done.store(mark, std::memory_order_release);
+        *r->htail = mark;       // the span may be reused only now that its copies have run
+    }
+    return DMI_OK;
 }
 
 // Pop launches known to have finished; returns an upper bound of the device head once
@@ -635,6 +631,9 @@ dmi_status_t observe_common(dmi_ring *r, uint32_t point_id, const dmi_selection_
     a.cslot = &r->dctrl->slots[seq % kCommitSlots];
     a.tail_floor = r->drain_done.load(std::memory_order_acquire);
     a.drop_newest = mode == DMI_POLICY_DROP_NEWEST ? 1u : 0u;
+    // best effort: every fourth launch refreshes the drained-up-to mark from the host's word
+    // (a read across the host link by one lane); in between, the launch-time floor stands
+    a.tail_src = (a.drop_newest && (seq & 3u) == 0) ? r->htail_dev : nullptr;
     a.par_in = r->chain_par;
     a.step = nullptr;
     a.node = 0;
@@ -642,6 +641,7 @@ dmi_status_t observe_common(dmi_ring *r, uint32_t point_id, const dmi_selection_
     const hipError_t e = pl.decode ? launch_capture_decode(a, s) : launch_capture(a, pl.grid, geo.vec16, s);
     if (e != hipSuccess) return fail(DMI_ERR_HIP, "capture launch failed: %s", hipGetErrorString(e));
     r->chain_par ^= 1u;
+    r->last_launch_ns.store(now_ns(), std::memory_order_relaxed);
     {
         std::lock_guard<std::mutex> lk(r->pmu);
         r->next_seq.store(seq + 1, std::memory_order_release);
@@ -709,9 +709,10 @@ void bg_loop(dmi_ring *r)
             std::lock_guard<std::mutex> lk(r->pmu);
             idle_probes = r->probes.empty();
         }
-        // cover launches the producer left unprobed, but rarely: every event recorded on the
-        // producer's stream is a barrier in the inference queue
-        if (idle_probes && now_ns() - last_probe >= timeout_ns) {
+        // cover launches the producer left unprobed once it has paused (while it keeps launching it
+        // probes by itself): every probe is a barrier, or a small launch, in the inference queue
+        if (idle_probes && now_ns() - last_probe >= timeout_ns &&
+            now_ns() - r->last_launch_ns.load(std::memory_order_relaxed) >= timeout_ns) {
             (void)record_probe(r);
             last_probe = now_ns();
         }
@@ -739,8 +740,7 @@ void free_ring(dmi_ring *r)
     if (!r) return;
     if (r->drain_stream) { (void)hipStreamSynchronize(r->drain_stream); (void)hipStreamDestroy(r->drain_stream); }
     if (r->ctl_stream) { (void)hipStreamSynchronize(r->ctl_stream); (void)hipStreamDestroy(r->ctl_stream); }
-    for (auto &p : r->pending) (void)hipEventDestroy(p.ev);
-    for (auto ev : r->ev_pool) (void)hipEventDestroy(ev);
+    if (r->htail) (void)hipHostFree((void *)r->htail);
     for (auto &p : r->probes) (void)hipEventDestroy(p.ev);
     for (auto ev : r->probe_pool) (void)hipEventDestroy(ev);
     if (r->dev_ring) (void)hipFree(r->dev_ring);
@@ -930,6 +930,9 @@ dmi_status_t dmi_ring_create(const dmi_ring_config_t *cfg, dmi_ring_t **out)
     r->block_timeout_ms = cfg->block_timeout_ms ? cfg->block_timeout_ms : 2000u;
     r->point_off.assign(DMI_MAX_POINTS, 0);
     r->slab_slot_words = (max_reqs * 5u + 63u) & ~63u;
+    // a probe at least every 16 launches, or every 1/32 of the ring (not under 8 MiB): often enough
+    // for the drain to follow closely, rare enough that its cost in the producer's stream stays small
+    r->probe_bytes = r->dev_cap / 32u > (8u << 20) ? r->dev_cap / 32u : (8u << 20);
 
     auto bail = [&](hipError_t err, const char *what) {
         fail(DMI_ERR_HIP, "%s failed: %s", what, hipGetErrorString(err));
@@ -963,6 +966,11 @@ dmi_status_t dmi_ring_create(const dmi_ring_config_t *cfg, dmi_ring_t **out)
         delete init;
         if (e != hipSuccess) return bail(e, "hipMemcpy(ctrl)");
     }
+    if ((e = hipHostMalloc((void **)&r->htail, 64, hipHostMallocMapped | hipHostMallocCoherent)) != hipSuccess)
+        return bail(e, "hipHostMalloc(tail word)");
+    if ((e = hipHostGetDevicePointer((void **)&r->htail_dev, (void *)r->htail, 0)) != hipSuccess)
+        return bail(e, "hipHostGetDevicePointer(tail word)");
+    *r->htail = 0;
     if ((e = hipStreamCreateWithFlags(&r->drain_stream, hipStreamNonBlocking)) != hipSuccess)
         return bail(e, "hipStreamCreate");
     if ((e = hipStreamCreateWithFlags(&r->ctl_stream, hipStreamNonBlocking)) != hipSuccess)
@@ -1134,7 +1142,7 @@ dmi_status_t dmi_step_create(dmi_ring_t *r, uint32_t max_observes, dmi_step_t **
     // a first launch out of this library, so that none of its code is loaded under a capture
     StepParams zero;
     memset(&zero, 0, sizeof zero);
-    if (e == hipSuccess) e = launch_step_begin(r->dctrl, st->dparams, zero, 0u, 0u, r->ctl_stream);
+    if (e == hipSuccess) e = launch_step_begin(r->dctrl, st->dparams, zero, 0u, 0u, nullptr, r->ctl_stream);
     if (e == hipSuccess) e = hipStreamSynchronize(r->ctl_stream);
     if (e != hipSuccess) {
         if (st->dparams) (void)hipFree(st->dparams);
@@ -1223,6 +1231,7 @@ dmi_status_t step_add(dmi_step *st, uint32_t point_id, const dmi_selection_t *se
     a.cslot = nullptr;
     a.tail_floor = 0;
     a.drop_newest = 0;
+    a.tail_src = nullptr;           // the device copy that the step's begin launch refreshes
     a.par_in = node & 1u;           // dmi_step_begin leaves head and tail in copy 0
     a.step = st->dparams;
     a.node = node;
@@ -1395,7 +1404,8 @@ dmi_status_t dmi_step_begin(dmi_step_t *st, uint64_t step_id, void *hip_stream)
     v.tail_floor = r->drain_done.load(std::memory_order_acquire);
     v.flags = (mode == DMI_POLICY_DROP_NEWEST ? kStepDropNewest : 0u) | (skip ? kStepSkip : 0u);
     v.pad = 0;
-    HIP_TRY(launch_step_begin(r->dctrl, st->dparams, v, r->chain_par, 0u, s));
+    HIP_TRY(launch_step_begin(r->dctrl, st->dparams, v, r->chain_par, 0u,
+                              mode == DMI_POLICY_DROP_NEWEST ? r->htail_dev : nullptr, s));
     r->chain_par = 0;
     st->seq_base = v.seq_base;
     st->skipped = skip;
@@ -1421,6 +1431,7 @@ dmi_status_t dmi_step_end(dmi_step_t *st, void *hip_stream)
     st->begun = false;
     r->step_open = false;
     r->chain_par = n & 1u;
+    r->last_launch_ns.store(now_ns(), std::memory_order_relaxed);
     r->last_stream.store(hip_stream, std::memory_order_release);
     if (st->skipped || !n) return DMI_OK;
     for (uint32_t i = 0; i < n; i++) {

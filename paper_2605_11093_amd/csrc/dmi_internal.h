@@ -30,12 +30,14 @@ struct CommitSlot {
 // wrote and nobody writes during this one, and its workgroup 0 writes
 // head[(n + 1) & 1], which nobody reads during this one.  No workgroup has to be
 // the last one, so the kernel has no completion counter and no fence.  The tail the
-// drop-newest decision uses travels the same way (tail_for), fed from `tail`, which the
-// drain advances at any time.
+// drop-newest decision uses travels the same way (tail_for): one lane of a launch reads the
+// drained-up-to mark from a word in pinned host memory that the drain side keeps current
+// with plain CPU stores (no copy, launch or event of the drain ever enters a GPU queue
+// for it) and leaves it for the next launch.
 struct DevCtrl {
     uint64_t head[2];               // next free stream byte, double buffered by launch parity
     uint64_t tail_for[2];           // the tail as the previous launch saw it, same scheme
-    uint64_t tail;                  // stream bytes below this have been drained (set by the drain)
+    uint64_t tail;                  // drained-up-to mark as the last replayable step's begin launch read it
     uint64_t captured_records, captured_rows, captured_bytes;
     uint64_t dropped_records, dropped_rows, dropped_bytes;
     uint64_t bad_rows;              // rows whose device-side index left the tensor (stored as zeros)
@@ -89,6 +91,7 @@ struct CaptureArgs {
     DevCtrl *ctrl;
     CommitSlot *cslot;              // this launch's commit slot (device memory)
     uint64_t tail_floor;            // the host's view of the tail when the launch was issued
+    const uint64_t *tail_src;       // pinned host word holding the drained-up-to mark (NULL: not read)
     uint32_t simple;                // no keep mask and every request contributes exactly one row
     uint32_t upr_shift;             // log2(units_per_row) if that is a power of two, else 32
     uint32_t bs_shift, seg_shift;   // same for block_size and seg_units
@@ -115,11 +118,10 @@ hipError_t launch_capture(const CaptureArgs &a, uint32_t grid, bool vec16, hipSt
 bool decode_kernel_applies(const CaptureArgs &a, bool vec16);
 hipError_t launch_capture_decode(const CaptureArgs &a, hipStream_t s);
 hipError_t launch_upload(uint32_t *dst, const uint32_t *words, uint32_t n_words, hipStream_t s);
-hipError_t launch_set_tail(DevCtrl *ctrl, uint64_t tail, hipStream_t s);
 // start of a replayable step: writes *step and, if par_from != par_to, carries head and
 // tail_for over to the copy the step's first launch reads
 hipError_t launch_step_begin(DevCtrl *ctrl, StepParams *step, StepParams v, uint32_t par_from, uint32_t par_to,
-                             hipStream_t s);
+                             const uint64_t *host_tail, hipStream_t s);
 hipError_t launch_fetch_slot(const CommitSlot *src, CommitSlot *dst_host, hipStream_t s);
 hipError_t launch_drain_kernel(const uint8_t *ring, uint64_t cap, uint8_t *host_ring, uint64_t host_cap,
                                uint64_t from, uint64_t nbytes, uint32_t grid, hipStream_t s);

@@ -41,6 +41,11 @@ __device__ __forceinline__ uint64_t ld_agent(const uint64_t *p)
 {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+// a word the host writes (pinned host memory): every read crosses the host link
+__device__ __forceinline__ uint64_t ld_system(const uint64_t *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
 __device__ __forceinline__ void st_agent(uint64_t *p, uint64_t v)
 {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -373,7 +378,7 @@ __device__ uint64_t g_trace[256 * 8];
 // before any result is used, whether or not this launch needs it: loads issued together
 // cost one trip to memory, loads issued as their conditions become known cost one each.
 struct RawControl {
-    uint64_t head, tail_for, tail_now, sp_seq, sp_step, sp_floor;
+    uint64_t head, tail_for, sp_seq, sp_step, sp_floor;
     uint64_t cap[3], drop[3];
     uint32_t sp_flags;
 };
@@ -393,7 +398,6 @@ __device__ __forceinline__ RawControl fetch_control(const DevCtrl *c, uint32_t p
     r.tail_for = c->tail_for[par];
     r.sp_seq = spp->seq_base; r.sp_step = spp->step_id; r.sp_floor = spp->tail_floor;
     r.sp_flags = spp->flags;
-    r.tail_now = ld_agent(&c->tail);
     r.cap[0] = c->captured_records; r.cap[1] = c->captured_rows; r.cap[2] = c->captured_bytes;
     r.drop[0] = c->dropped_records; r.drop[1] = c->dropped_rows; r.drop[2] = c->dropped_bytes;
     return r;
@@ -463,7 +467,6 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
         const Control ct = resolve_control(raw, a.step != nullptr, a.node, a.tail_floor, a.seq, a.step_id,
                                            a.drop_newest);
         seq = ct.seq;
-        tail_now = raw.tail_now;
         for (int i = 0; i < 3; i++) { cnt_cap[i] = raw.cap[i]; cnt_drop[i] = raw.drop[i]; }
         const uint64_t base = ct.head % a.cap;
         lds[m.bcast + 4] = (uint32_t)base;
@@ -568,7 +571,15 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
             pre = true;
         }
     }
-    if (tid == kCtlTid) publish_control();
+    if (tid == kCtlTid) {
+        // the drained-up-to mark for the next launch's drop decision: workgroup 0 reads it where
+        // the host keeps it (a read across the host link, issued after every other load of this
+        // lane so that none of them queues behind it; nothing in this launch waits for it but
+        // the closing stores of this one lane)
+        const uint64_t *ts = blockIdx.x == 0 && a.tail_src ? a.tail_src : &a.ctrl->tail;
+        tail_now = ld_system(ts);
+        publish_control();
+    }
     lds_barrier();
 
     DMI_STAMP(2);
@@ -590,7 +601,7 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
         // copies still has to reach the next launch
         if (blockIdx.x == 0 && tid == kCtlTid) {
             a.ctrl->head[par ^ 1u] = head;
-            a.ctrl->tail_for[par ^ 1u] = tail_now;
+            a.ctrl->tail_for[par ^ 1u] = tail_now > raw.tail_for ? tail_now : raw.tail_for;
         }
         return;
     }
@@ -616,7 +627,7 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
             c->captured_records = cnt_cap[0]; c->captured_rows = cnt_cap[1]; c->captured_bytes = cnt_cap[2];
         }
         c->head[par ^ 1u] = new_head;
-        c->tail_for[par ^ 1u] = tail_now;
+        c->tail_for[par ^ 1u] = tail_now > raw.tail_for ? tail_now : raw.tail_for;
         CommitSlot *h = a.step ? &c->slots[seq % kCommitSlots] : a.cslot;
         h->head = new_head;
         h->captured_records = cnt_cap[0];
@@ -1020,7 +1031,7 @@ struct DecodeArgs {
     CommitSlot *cslot;
     uint64_t payload_bytes;
     uint32_t point_id, hdr7, rank_tag, pad;
-    uint64_t reserved;
+    const uint64_t *tail_src;       // where the extra workgroup reads the drained-up-to mark (may be NULL)
 };
 static_assert(sizeof(DecodeArgs) == 192, "three lines");
 constexpr uint32_t kDecDropNewest = 1u, kDecConsecutive = 2u, kDecIndexed = 4u, kDecParIn = 8u;
@@ -1066,10 +1077,13 @@ __global__ void __launch_bounds__(kThreads) capture_decode_kernel(const DecodeAr
         }
     }
     if (tid == kCtlTid) {
+        // the drained-up-to mark for the next launch's drop decision, read where the host keeps
+        // it by the extra workgroup's lane, after every other load of that lane
+        const uint64_t *ts = meta_wg && a.tail_src ? a.tail_src : &a.ctrl->tail;
+        tail_now = ld_system(ts);
         const Control ct = resolve_control(raw, a.step != nullptr, a.node, a.tail_floor, a.seq, a.step_id,
                                            a.flags & kDecDropNewest);
         seq = ct.seq;
-        tail_now = raw.tail_now;
         for (int i = 0; i < 3; i++) { cnt_cap[i] = raw.cap[i]; cnt_drop[i] = raw.drop[i]; }
         const uint64_t base = ct.head % a.cap;
         sh[0] = (uint32_t)ct.head;  sh[1] = (uint32_t)(ct.head >> 32);
@@ -1087,7 +1101,7 @@ __global__ void __launch_bounds__(kThreads) capture_decode_kernel(const DecodeAr
     if (flags & kStepSkip) {    // sampled-out replay: pass head and tail on, capture nothing
         if (meta_wg && tid == kCtlTid) {
             a.ctrl->head[par ^ 1u] = head;
-            a.ctrl->tail_for[par ^ 1u] = tail_now;
+            a.ctrl->tail_for[par ^ 1u] = tail_now > raw.tail_for ? tail_now : raw.tail_for;
         }
         return;
     }
@@ -1111,7 +1125,7 @@ __global__ void __launch_bounds__(kThreads) capture_decode_kernel(const DecodeAr
                 c->captured_records = cnt_cap[0]; c->captured_rows = cnt_cap[1]; c->captured_bytes = cnt_cap[2];
             }
             c->head[par ^ 1u] = new_head;
-            c->tail_for[par ^ 1u] = tail_now;
+            c->tail_for[par ^ 1u] = tail_now > raw.tail_for ? tail_now : raw.tail_for;
             CommitSlot *h = a.step ? &c->slots[seq % kCommitSlots] : a.cslot;
             h->head = new_head;
             h->captured_records = cnt_cap[0]; h->captured_rows = cnt_cap[1]; h->captured_bytes = cnt_cap[2];
@@ -1205,18 +1219,14 @@ __global__ void __launch_bounds__(kThreads) upload_kernel(uint32_t *dst, const U
     for (uint32_t i = threadIdx.x; i < n; i += kThreads) dst[i] = c.w[i];
 }
 
-__global__ void set_tail_kernel(DevCtrl *ctrl, uint64_t tail)
-{
-    st_agent(&ctrl->tail, tail);
-}
-
 // Start of a replayable step (an ordinary launch in front of the graph's): the step's
 // parameter block, and head / tail_for carried over to the copy its first launch reads.
 __global__ void step_begin_kernel(DevCtrl *ctrl, StepParams *step, const StepParams v, uint32_t par_from,
-                                  uint32_t par_to)
+                                  uint32_t par_to, const uint64_t *host_tail)
 {
     if (threadIdx.x != 0) return;
     *step = v;
+    if (host_tail) ctrl->tail = ld_system(host_tail);    // the step's launches read this copy
     if (par_from != par_to) {
         ctrl->head[par_to] = ctrl->head[par_from];
         ctrl->tail_for[par_to] = ctrl->tail_for[par_from];
@@ -1334,6 +1344,7 @@ hipError_t launch_capture_decode(const CaptureArgs &a, hipStream_t s)
     d.point_id = a.point_id;
     d.hdr7 = a.hdr[7];
     d.rank_tag = a.rank_tag;
+    d.tail_src = a.tail_src;
     const bool summ = a.summary_mask != 0;
     switch (a.out_dtype) {
     case 0: return launch_decode_t<OUT_NONE>(d, summ, s);
@@ -1364,15 +1375,9 @@ hipError_t launch_fetch_slot(const CommitSlot *src, CommitSlot *dst_host, hipStr
 }
 
 hipError_t launch_step_begin(DevCtrl *ctrl, StepParams *step, StepParams v, uint32_t par_from, uint32_t par_to,
-                             hipStream_t s)
+                             const uint64_t *host_tail, hipStream_t s)
 {
-    hipLaunchKernelGGL(step_begin_kernel, dim3(1), dim3(64), 0, s, ctrl, step, v, par_from, par_to);
-    return hipGetLastError();
-}
-
-hipError_t launch_set_tail(DevCtrl *ctrl, uint64_t tail, hipStream_t s)
-{
-    hipLaunchKernelGGL(set_tail_kernel, dim3(1), dim3(1), 0, s, ctrl, tail);
+    hipLaunchKernelGGL(step_begin_kernel, dim3(1), dim3(64), 0, s, ctrl, step, v, par_from, par_to, host_tail);
     return hipGetLastError();
 }
 
