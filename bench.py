@@ -29,8 +29,8 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0           # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the config-2 capture kernel, from the two rocprofv3 --pmc runs
 # summarised in profiles/capture_kernel_config2_config3mlp.md (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000,
-# factors from a plain 256 MiB copy): 0.627 MB read + 0.530 MB written.
-TRAFFIC_CONFIG2_BYTES = 1157000
+# factors from a plain 256 MiB copy): 0.613 MB read + 0.530 MB written.
+TRAFFIC_CONFIG2_BYTES = 1143000
 SEED_NOTE = "synthetic (seeded ~N(0,1) bf16, shapes of the paper's LLM workloads)"
 
 

@@ -182,6 +182,11 @@ typedef struct {
  * block_timeout_ms, then DMI_ERR_AGAIN; DMI_POLICY_DROP_NEWEST never waits: the
  * kernel discards the record if it does not fit when it runs, and counts it.
  * A sequence number is consumed only when a kernel is launched.
+ * Besides the capture kernel the library puts small operations of its own on the stream
+ * most recently passed here: an event every 16 launches or so, in best-effort mode (or with
+ * keep vectors) also a one-workgroup launch that copies 64 bytes to pinned memory; dmi_drain
+ * and the library's drain thread may add one when the producer has paused.  Do not capture
+ * that stream into a graph by hand while captures are outstanding: use dmi_step_t.
  */
 dmi_status_t dmi_observe(dmi_ring_t *ring, uint32_t point_id, const dmi_tensor_t *tensor /*[host]*/,
                          const dmi_selection_t *sel /*[host]*/, const dmi_transform_t *xf /*[host]*/,
@@ -411,7 +416,7 @@ typedef struct {
  * library has observed: after dmi_drain(DMI_DRAIN_FLUSH) that is all of them. */
 dmi_status_t dmi_get_stats(dmi_ring_t *ring, dmi_stats_t *out /*[host]*/);
 /* Records of one point discarded by drop-newest (synchronises the library's
- * own control stream only). */
+ * own stream only). */
 dmi_status_t dmi_get_point_drops(dmi_ring_t *ring, uint32_t point_id, uint64_t *n /*[host]*/);
 
 /* Test hook: fill both rings with one byte value (synchronous).  Lets a test see

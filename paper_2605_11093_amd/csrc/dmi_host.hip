@@ -136,7 +136,7 @@ struct dmi_ring {
     uint64_t host_cap = 0;
     DevCtrl *dctrl = nullptr;
     CommitSlot *hslots = nullptr, *hslots_dev = nullptr;   // pinned mirror of DevCtrl::slots
-    hipStream_t ctl_stream = nullptr;                      // fetches commit slots
+    hipStream_t ctl_stream = nullptr;                      // statistics reads, set-up launches
     uint8_t *mask_buf = nullptr;                           // 4 rotating keep vectors of max_reqs bytes
     uint32_t mask_rr = 0, mask_stride = 0;
     uint32_t *slab = nullptr;

@@ -1233,10 +1233,10 @@ __global__ void step_begin_kernel(DevCtrl *ctrl, StepParams *step, const StepPar
     }
 }
 
-// Fetch one commit slot into pinned host memory (runs on the library's control stream
-// behind an event of the producer's stream, so the capture kernel itself never writes
-// across PCIe: such a store is acknowledged only after some 4-5 microseconds, and a
-// kernel cannot retire before its stores have been).
+// Fetch one commit slot into pinned host memory: a small launch of its own on the producer's
+// stream, so the capture kernel itself never writes across PCIe (such a store is
+// acknowledged only after some 4-5 microseconds, and a kernel cannot retire before its
+// stores have been).
 __global__ void fetch_slot_kernel(const CommitSlot *src, CommitSlot *dst_host)
 {
     const uint32_t i = threadIdx.x;
@@ -1245,7 +1245,7 @@ __global__ void fetch_slot_kernel(const CommitSlot *src, CommitSlot *dst_host)
 }
 
 // Drain by kernel: 16-byte loads from the device ring, 16-byte stores into the pinned
-// host ring (posted PCIe writes).  The tail is advanced by set_tail_kernel behind it.
+// host ring (posted PCIe writes).
 __global__ void __launch_bounds__(kThreads) drain_kernel(const uint8_t *ring, uint64_t cap, uint8_t *host,
                                                          uint64_t host_cap, uint64_t from, uint64_t nbytes)
 {
