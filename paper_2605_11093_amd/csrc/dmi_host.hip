@@ -519,8 +519,10 @@ dmi_status_t plan_capture(dmi_ring *r, uint32_t point_id, const dmi_selection_t 
     pl.ub = ub;
 
     const bool index_mode = sel->row_index_dev != nullptr;
-    bool simple = sel->keep_mask_dev == nullptr;
-    for (uint32_t i = 0; simple && i < sel->n_reqs; i++) simple = sel->reqs[i].tok_count == 1u;
+    bool one_row_each = true;
+    for (uint32_t i = 0; one_row_each && i < sel->n_reqs; i++) one_row_each = sel->reqs[i].tok_count == 1u;
+    const bool simple = one_row_each && sel->keep_mask_dev == nullptr;
+    a.one_row_each = one_row_each ? 1u : 0u;
     const bool tab_lds = !simple && sel->n_reqs <= kLdsTableMax;
     a.n_seg = geo.n_seg;
     a.seg_units = geo.seg_elems / unit_elems;
@@ -1335,7 +1337,7 @@ dmi_status_t dmi_step_update(dmi_step_t *st, uint32_t node, const dmi_req_sel_t 
         if (a.paged) rc = check_paged_rows(reqs, n_reqs, nd.n_seqs, a.block_size, a.bt_stride);
         else if (!nd.index_mode) rc = check_dense_rows(reqs, n_reqs, a.n_src_rows);
         if (rc != DMI_OK) return rc;
-        if (a.simple && !all_one)
+        if ((a.simple || nd.pl.decode) && !all_one)
             return fail(DMI_ERR_INVALID_ARG, "captured with one row per request: capture the step again to change that");
         if (nd.pl.decode && a.rows_consecutive)
             for (uint32_t i = 0; i < n_reqs; i++)

@@ -93,6 +93,7 @@ struct CaptureArgs {
     uint64_t tail_floor;            // the host's view of the tail when the launch was issued
     const uint64_t *tail_src;       // pinned host word holding the drained-up-to mark (NULL: not read)
     uint32_t simple;                // no keep mask and every request contributes exactly one row
+    uint32_t one_row_each;          // every request lists exactly one row (a keep vector may still drop some)
     uint32_t upr_shift;             // log2(units_per_row) if that is a power of two, else 32
     uint32_t bs_shift, seg_shift;   // same for block_size and seg_units
     uint32_t drop_newest;
@@ -113,8 +114,9 @@ struct CaptureArgs {
 
 // Launchers (dmi_kernels.hip).  All return the launch's hipError_t.
 hipError_t launch_capture(const CaptureArgs &a, uint32_t grid, bool vec16, hipStream_t s);
-// decode-shaped captures: bf16 source, dense, one row per request, no mask, 16-byte movable
-// rows of at most 1024 units; grid is n_reqs + 1
+// decode-shaped captures: bf16 source, dense, one row per request (with or without a keep
+// vector; with one, at most 1024 requests), 16-byte movable rows of at most 1024 units;
+// grid is n_reqs + 1
 bool decode_kernel_applies(const CaptureArgs &a, bool vec16);
 hipError_t launch_capture_decode(const CaptureArgs &a, hipStream_t s);
 hipError_t launch_upload(uint32_t *dst, const uint32_t *words, uint32_t n_words, hipStream_t s);

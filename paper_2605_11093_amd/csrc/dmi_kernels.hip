@@ -1032,14 +1032,23 @@ struct DecodeArgs {
     uint64_t payload_bytes;
     uint32_t point_id, hdr7, rank_tag, pad;
     const uint64_t *tail_src;       // where the extra workgroup reads the drained-up-to mark (may be NULL)
+    // line 3
+    const uint8_t *keep_mask;       // keep vector (MASK variants): request r is captured iff keep_mask[r] != 0
+    uint64_t spare[7];
 };
-static_assert(sizeof(DecodeArgs) == 192, "three lines");
+static_assert(sizeof(DecodeArgs) == 256, "four lines");
 constexpr uint32_t kDecDropNewest = 1u, kDecConsecutive = 2u, kDecIndexed = 4u, kDecParIn = 8u;
 
-template <int OUT, bool SUMM>
+// MASK: the paper's best-effort path (section 4.4): a batch-aligned keep vector, read when the
+// kernel runs, decides per request.  Every workgroup reads the whole vector (at most 1024
+// bytes) together with its other loads, the wavefronts ballot it into 16 words of LDS, and
+// each workgroup derives from those the record's row count and its own row's place.  The
+// row itself is loaded before the vector is known and thrown away if the request is out.
+template <int OUT, bool SUMM, bool MASK>
 __global__ void __launch_bounds__(kThreads) capture_decode_kernel(const DecodeArgs a)
 {
     __shared__ uint32_t sh[32];
+    __shared__ uint64_t kept_bits[16];      // MASK: bit i of word q = request 64 q + i is kept
     DMI_STAMP_D(0);
     touch_argument_lines(a);
     constexpr uint32_t U = 4;
@@ -1054,6 +1063,14 @@ __global__ void __launch_bounds__(kThreads) capture_decode_kernel(const DecodeAr
     uint64_t cnt_cap[3] = {0, 0, 0}, cnt_drop[3] = {0, 0, 0}, tail_now = 0, seq = a.seq;
     RawControl raw = {};
     if (tid == kCtlTid) raw = fetch_control(a.ctrl, par, a.step);
+    uint32_t kb[4] = {0u, 0u, 0u, 0u};
+    if constexpr (MASK) {
+#pragma unroll
+        for (uint32_t k = 0; k < 4; k++) {
+            const uint32_t r = tid + k * kThreads;
+            kb[k] = a.keep_mask[r < a.n_reqs ? r : 0u];
+        }
+    }
     u32x4 v[U];
     bool ok = false;
     if (!meta_wg) {
@@ -1074,6 +1091,14 @@ __global__ void __launch_bounds__(kThreads) capture_decode_kernel(const DecodeAr
                 const uint32_t c = tid + k * kThreads;
                 v[k] = *reinterpret_cast<const u32x4 *>(base + (uint64_t)(c < a.units_per_row ? c : 0u) * 16u);
             }
+        }
+    }
+    if constexpr (MASK) {
+#pragma unroll
+        for (uint32_t k = 0; k < 4; k++) {
+            const uint32_t r = tid + k * kThreads;
+            const uint64_t b = __ballot(r < a.n_reqs && kb[k] != 0u);
+            if (lane == 0) kept_bits[k * 4u + wave] = b;
         }
     }
     if (tid == kCtlTid) {
@@ -1105,23 +1130,46 @@ __global__ void __launch_bounds__(kThreads) capture_decode_kernel(const DecodeAr
         }
         return;
     }
-    const bool dropped = (flags & kStepDropNewest) && head - tail + a.record_bytes > a.cap;
+    // record geometry: known on the host, or from the keep vector
+    uint32_t n_rows = a.n_reqs, my_row = blockIdx.x;
+    bool kept = true;
+    uint64_t record_bytes = a.record_bytes, payload_bytes = a.payload_bytes, off_sum = a.off_sum, sum_arr = a.sum_arr;
+    if constexpr (MASK) {
+        const uint32_t q_me = blockIdx.x >> 6;
+        n_rows = 0;
+        my_row = 0;
+#pragma unroll
+        for (uint32_t q = 0; q < 16; q++) {
+            const uint32_t pc = (uint32_t)__popcll(kept_bits[q]);
+            n_rows += pc;
+            if (q < q_me) my_row += pc;
+        }
+        if (!meta_wg) {
+            const uint64_t mine = kept_bits[q_me & 15u], bit = 1ull << (blockIdx.x & 63u);
+            kept = (mine & bit) != 0;
+            my_row += (uint32_t)__popcll(mine & (bit - 1u));
+        }
+        payload_bytes = (uint64_t)n_rows * a.units_per_row * NB_OUT;
+        off_sum = a.off_payload + ((payload_bytes + 63u) & ~63ull);
+        sum_arr = ((uint64_t)n_rows * 4u + 63u) & ~63ull;
+        record_bytes = off_sum + (uint64_t)__popc(a.summary_mask & 7u) * sum_arr;
+    }
+    const bool dropped = (flags & kStepDropNewest) && head - tail + record_bytes > a.cap;
     RingW w;
     w.ring = a.ring;
     w.cap = a.cap;
     w.base = (uint64_t)sh[4] | ((uint64_t)sh[5] << 32);
-    const uint32_t n_rows = a.n_reqs;
 
     if (meta_wg) {
         if (tid == kCtlTid) {
             DevCtrl *c = a.ctrl;
-            const uint64_t new_head = dropped ? head : head + a.record_bytes;
+            const uint64_t new_head = dropped ? head : head + record_bytes;
             if (dropped) {
-                cnt_drop[0] += 1; cnt_drop[1] += n_rows; cnt_drop[2] += a.record_bytes;
+                cnt_drop[0] += 1; cnt_drop[1] += n_rows; cnt_drop[2] += record_bytes;
                 c->dropped_records = cnt_drop[0]; c->dropped_rows = cnt_drop[1]; c->dropped_bytes = cnt_drop[2];
                 c->point_drops[a.point_id & 4095u] += 1;
             } else {
-                cnt_cap[0] += 1; cnt_cap[1] += n_rows; cnt_cap[2] += a.record_bytes;
+                cnt_cap[0] += 1; cnt_cap[1] += n_rows; cnt_cap[2] += record_bytes;
                 c->captured_records = cnt_cap[0]; c->captured_rows = cnt_cap[1]; c->captured_bytes = cnt_cap[2];
             }
             c->head[par ^ 1u] = new_head;
@@ -1137,34 +1185,35 @@ __global__ void __launch_bounds__(kThreads) capture_decode_kernel(const DecodeAr
             u32x4 hv;
             if (tid == 0) hv = u32x4{0x32494D44u, 1u | (64u << 16), sh[24], sh[25]};
             else if (tid == 1) hv = u32x4{sh[26], sh[27], a.point_id, a.hdr7};
-            else if (tid == 2) hv = u32x4{n_rows, n_rows, a.row_elems, a.rank_tag};
-            else hv = u32x4{(uint32_t)a.record_bytes, (uint32_t)(a.record_bytes >> 32), (uint32_t)a.payload_bytes,
-                            (uint32_t)(a.payload_bytes >> 32)};
+            else if (tid == 2) hv = u32x4{a.n_reqs, n_rows, a.row_elems, a.rank_tag};
+            else hv = u32x4{(uint32_t)record_bytes, (uint32_t)(record_bytes >> 32), (uint32_t)payload_bytes,
+                            (uint32_t)(payload_bytes >> 32)};
             ring_store<u32x4>(w, 16u * tid, hv);
         }
         const uint32_t tab_slots = (uint32_t)((a.off_payload - 64u) / 16u);
         for (uint32_t r = tid; r < tab_slots; r += kThreads) {
             u32x4 tv = {0u, 0u, 0u, 0u};
-            if (r < n_rows) {
+            if (r < a.n_reqs) {
                 const uint4 e = a.req_table[r];
                 tv.x = e.x; tv.y = e.y; tv.z = e.z; tv.w = e.w;
+                if constexpr (MASK) tv.w = (uint32_t)((kept_bits[(r >> 6) & 15u] >> (r & 63u)) & 1ull);
             }
             ring_store<u32x4>(w, 64u + 16ull * r, tv);
         }
-        const uint32_t pad = (uint32_t)(a.off_sum - a.off_payload - a.payload_bytes);
-        if (tid < pad) ring_store<uint8_t>(w, a.off_payload + a.payload_bytes + tid, (uint8_t)0);
+        const uint32_t pad = (uint32_t)(off_sum - a.off_payload - payload_bytes);
+        if (tid < pad) ring_store<uint8_t>(w, a.off_payload + payload_bytes + tid, (uint8_t)0);
         const uint32_t n_sum = __popc(a.summary_mask & 7u);
-        const uint32_t spad = (uint32_t)(a.sum_arr - (uint64_t)n_rows * 4u) / 4u;
+        const uint32_t spad = (uint32_t)(sum_arr - (uint64_t)n_rows * 4u) / 4u;
         for (uint32_t k = tid; k < n_sum * spad; k += kThreads) {
             const uint32_t arr = k / spad, i = k - arr * spad;
-            ring_store<uint32_t>(w, a.off_sum + arr * a.sum_arr + (uint64_t)n_rows * 4u + 4ull * i, 0u);
+            ring_store<uint32_t>(w, off_sum + arr * sum_arr + (uint64_t)n_rows * 4u + 4ull * i, 0u);
         }
         DMI_STAMP_D(4);
         return;
     }
 
-    if (dropped) return;
-    const uint32_t g = blockIdx.x;
+    if (dropped || !kept) return;
+    const uint32_t g = my_row;
     if (!ok && tid == 0) atomicAdd((unsigned long long *)&a.ctrl->bad_rows, 1ull);
     Accum acc = {0.f, 0.f, 0u};
     const uint64_t row_off = a.off_payload + (uint64_t)g * a.units_per_row * NB_OUT;
@@ -1200,9 +1249,9 @@ __global__ void __launch_bounds__(kThreads) capture_decode_kernel(const DecodeAr
             const float sm = (red[4] + red[5]) + (red[6] + red[7]);
             const uint32_t m01 = sh[16] > sh[17] ? sh[16] : sh[17], m23 = sh[18] > sh[19] ? sh[18] : sh[19];
             am = m01 > m23 ? m01 : m23;
-            uint64_t o = a.off_sum + (uint64_t)g * 4u;
-            if (a.summary_mask & 1u) { ring_store<float>(w, o, sqrtf(ss)); o += a.sum_arr; }
-            if (a.summary_mask & 2u) { ring_store<float>(w, o, sm / (float)a.row_elems); o += a.sum_arr; }
+            uint64_t o = off_sum + (uint64_t)g * 4u;
+            if (a.summary_mask & 1u) { ring_store<float>(w, o, sqrtf(ss)); o += sum_arr; }
+            if (a.summary_mask & 2u) { ring_store<float>(w, o, sm / (float)a.row_elems); o += sum_arr; }
             if (a.summary_mask & 4u) { ring_store<float>(w, o, __uint_as_float(am << 16)); }
         }
     }
@@ -1295,18 +1344,25 @@ hipError_t launch_capture(const CaptureArgs &a, uint32_t grid, bool vec16, hipSt
 
 bool decode_kernel_applies(const CaptureArgs &a, bool vec16)
 {
-    return a.simple && !a.paged && vec16 && a.src_dtype == 1u && a.units_per_row <= 4u * kThreads &&
-           a.n_reqs >= 1u;
+    const bool shape = a.simple || (a.one_row_each && a.keep_mask && a.n_reqs <= 1024u);
+    return shape && !a.paged && vec16 && a.src_dtype == 1u && a.units_per_row <= 4u * kThreads && a.n_reqs >= 1u;
 }
 
 template <int OUT>
 static hipError_t launch_decode_t(const DecodeArgs &d, bool summaries, hipStream_t s)
 {
     const dim3 grid(d.n_reqs + 1u);
-    if (summaries)
-        hipLaunchKernelGGL((capture_decode_kernel<OUT, true>), grid, dim3(kThreads), 0, s, d);
-    else
-        hipLaunchKernelGGL((capture_decode_kernel<OUT, false>), grid, dim3(kThreads), 0, s, d);
+    if (d.keep_mask) {
+        if (summaries)
+            hipLaunchKernelGGL((capture_decode_kernel<OUT, true, true>), grid, dim3(kThreads), 0, s, d);
+        else
+            hipLaunchKernelGGL((capture_decode_kernel<OUT, false, true>), grid, dim3(kThreads), 0, s, d);
+    } else {
+        if (summaries)
+            hipLaunchKernelGGL((capture_decode_kernel<OUT, true, false>), grid, dim3(kThreads), 0, s, d);
+        else
+            hipLaunchKernelGGL((capture_decode_kernel<OUT, false, false>), grid, dim3(kThreads), 0, s, d);
+    }
     return hipGetLastError();
 }
 
@@ -1345,6 +1401,8 @@ hipError_t launch_capture_decode(const CaptureArgs &a, hipStream_t s)
     d.hdr7 = a.hdr[7];
     d.rank_tag = a.rank_tag;
     d.tail_src = a.tail_src;
+    d.keep_mask = a.keep_mask;
+    if (a.keep_mask && a.n_reqs > 1024u) return hipErrorInvalidValue;
     const bool summ = a.summary_mask != 0;
     switch (a.out_dtype) {
     case 0: return launch_decode_t<OUT_NONE>(d, summ, s);

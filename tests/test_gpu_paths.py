@@ -205,3 +205,59 @@ def test_out_of_range_device_indices_give_zero_rows_and_are_counted(B):
             else:
                 assert not r.payload[tkn].any()
         assert ring.get_stats().bad_rows == 16
+
+
+MASKED_DECODE = {
+    # name: (n_reqs, E, out_dtype, summary_mask, mask kind, row placement)
+    "c2_shape": (64, 4096, 1, 5, "mod4", "consecutive"),
+    "fp8_1000_reqs": (1000, 512, 4, 0, "random", "consecutive"),
+    "fp16_permuted_rows": (300, 1024, 2, 7, "random", "permuted"),
+    "all_out": (70, 256, 1, 7, "none", "consecutive"),
+    "all_in_indexed": (129, 8192, 1, 1, "all", "indexed"),
+    "summary_only": (257, 2048, 0, 7, "random", "consecutive"),
+    "one_request": (1, 4096, 1, 5, "all", "consecutive"),
+    "one_request_out": (1, 4096, 4, 0, "none", "consecutive"),
+}
+
+
+@pytest.mark.parametrize("name", sorted(MASKED_DECODE))
+def test_keep_vector_on_decode_shapes_through_a_wrapping_ring(B, name):
+    """One row per request with a keep vector (the best-effort path of a decode step)."""
+    n, E, out_dtype, sm, mkind, place = MASKED_DECODE[name]
+    T = n + 3
+    pool = [prng.randn_bf16(prng.sub_seed(34, len(name), k), T * E, DEV).view(T, E) for k in range(2)]
+    if place == "permuted":
+        rows = prng.permutation(prng.sub_seed(34, 7), T)[:n]
+    else:
+        rows = np.arange(n) + 2
+    reqs = np.array([(9000 + i, int(rows[i]), 0, 1, 1) for i in range(n)], dtype=np.uint32)
+    idx = None
+    if place == "indexed":
+        idx = ((np.arange(n) * 31) % T).astype(np.int32)
+    masks = []
+    for k in range(3):
+        if mkind == "mod4":
+            m = ((np.arange(n) + k) % 4 != 1)
+        elif mkind == "random":
+            m = prng.randint(prng.sub_seed(34, 8, k), n, 0, 2) > 0
+        elif mkind == "none":
+            m = np.zeros(n, bool)
+        else:
+            m = np.ones(n, bool)
+        masks.append(m.astype(np.uint8))
+    dev_masks = [torch.from_numpy(m).to(DEV) for m in masks]
+    dev_idx = None if idx is None else torch.from_numpy(idx).to(DEV)
+    rec = orc.record_bytes(n, n, E, out_dtype, sm)
+
+    def args(i):
+        kw = dict(out_dtype=out_dtype, summary_mask=sm, keep_mask=dev_masks[i % 3])
+        okw = dict(out_dtype=out_dtype, summary_mask=sm, keep_mask=masks[i % 3])
+        if idx is not None:
+            kw["row_index"] = dev_idx
+            okw["row_index"] = idx
+        return pool[i % 2], reqs, kw, okw
+
+    got, ref = _stream_through_small_ring(B, args, 9, rec)
+    compare_streams(got, ref)
+    for rbytes in (decode_record(got[:0 + int.from_bytes(got[48:56].tobytes(), "little")]),):
+        assert rbytes.flags & 2
