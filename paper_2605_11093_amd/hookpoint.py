@@ -6,6 +6,10 @@ synchronisation happens, the tensor is neither modified nor retained.
 The work is the C ABI's dmi_observe; this file only finds the arguments: the ring, the
 point id, and the step context (request selection, step id) that the serving loop sets
 once per forward step (the paper's prepare_step).
+
+Under graph capture (StepContext.capture) a HookPoint adds its launch to a replayable
+step (dmi_step_observe) instead, so the captures sit in the same graph as the model's own
+kernels; StepContext.begin_replay / end_replay bracket each replay of that graph.
 """
 from __future__ import annotations
 
@@ -26,11 +30,60 @@ class StepContext:
         self.reqs: Optional[np.ndarray] = None
         self.step_id = 0
         self.keep_mask_dev = 0
+        self.step: Optional[B.Step] = None          # set while / after a graph capture
+        self._capturing = False
+        self._nodes: list = []
+        self._keep_tensor = None
 
     def prepare_step(self, step_id: int, reqs, keep_mask_dev: int = 0):
         self.reqs = np.ascontiguousarray(np.asarray(reqs, dtype=np.uint32).reshape(-1, 5))
         self.step_id = int(step_id)
         self.keep_mask_dev = int(keep_mask_dev)
+
+    # -- graph capture and replay ------------------------------------------
+    def capture(self, ring: B.Ring, reqs, *, max_observes: int = 64, keep_mask=None):
+        """Context manager around the caller's graph capture of one forward step:
+
+            with ctx.capture(ring, reqs, keep_mask=mask_tensor):
+                with torch.cuda.graph(g):
+                    y = model(static_x)
+
+        reqs is the selection the step is captured with (its shape stays; contents may be
+        replaced per replay); keep_mask an optional uint8 device tensor that the caller
+        rewrites between replays."""
+        ctx = self
+
+        class _Capture:
+            def __enter__(self_inner):
+                ctx.step = B.Step(ring, max_observes)
+                ctx.reqs = np.ascontiguousarray(np.asarray(reqs, dtype=np.uint32).reshape(-1, 5))
+                ctx.keep_mask_dev = 0 if keep_mask is None else keep_mask.data_ptr()
+                ctx._keep_tensor = keep_mask
+                ctx._nodes = []
+                ctx.step.capture_begin()
+                ctx._capturing = True
+                return ctx.step
+
+            def __exit__(self_inner, *exc):
+                ctx._capturing = False
+                ctx.step.seal()
+                return False
+
+        return _Capture()
+
+    def begin_replay(self, step_id: int, stream: int, reqs=None, allow=()) -> int:
+        """Before replaying the captured graph on `stream`: optional new batch composition
+        (same number of requests), then the step's policy gate and parameter upload."""
+        if reqs is not None:
+            ra = np.ascontiguousarray(np.asarray(reqs, dtype=np.uint32).reshape(-1, 5))
+            if not np.array_equal(ra, self.reqs):
+                if self._nodes:
+                    self.step.update(self._nodes[0], ra)    # all hook points share the step's one table
+                self.reqs = ra
+        return self.step.begin(step_id, stream, allow=allow)
+
+    def end_replay(self, stream: int):
+        self.step.end(stream)
 
 
 class HookPoint(nn.Module):
@@ -50,6 +103,14 @@ class HookPoint(nn.Module):
         if t.stride(-1) != 1 or t.data_ptr() != x.data_ptr():
             raise ValueError("HookPoint needs a tensor whose rows are contiguous in memory")
         dt = B._torch_dtype_code(t)
+        if self.ctx._capturing:
+            node = self.ctx.step.observe_tensor(self.point_id, t, self.ctx.reqs,
+                                                stream=torch.cuda.current_stream(x.device).cuda_stream,
+                                                out_dtype=dt if self.out_dtype is None else self.out_dtype,
+                                                summary_mask=self.summary_mask, keep_mask=self.ctx._keep_tensor)
+            if node >= 0:
+                self.ctx._nodes.append(node)
+            return x
         self.ring.observe(self.point_id, t.data_ptr(), dt, tuple(t.shape), tuple(t.stride()), self.ctx.reqs,
                           step_id=self.ctx.step_id, stream=torch.cuda.current_stream(x.device).cuda_stream,
                           out_dtype=dt if self.out_dtype is None else self.out_dtype,

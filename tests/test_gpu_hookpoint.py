@@ -54,3 +54,59 @@ def test_hookpoints_capture_without_changing_the_forward():
             t = captured[name].reshape(-1, captured[name].shape[-1]).cpu()
             ref = orc.build_record(t, reqs, seq=v.seq, step_id=5, point_id=pid, out_dtype=1, summary_mask=5)
             compare_record(v.bytes(), ref)
+
+
+def test_hookpoints_inside_a_captured_graph():
+    """The model's forward, HookPoints included, captured once and replayed: every replay's
+    records equal the oracle's records of the tensors that replay produced."""
+    from paper_2605_11093_amd import binding as B
+    from paper_2605_11093_amd.hookpoint import StepContext, install_hookpoints
+    from _util import compare_record
+    torch.manual_seed(1)
+    d, T = 256, 16
+    model = nn.Sequential(*[Block(d) for _ in range(3)]).to(DEV).to(torch.bfloat16).eval()
+    static_x = torch.zeros(T, d, device=DEV, dtype=torch.bfloat16)
+    keep = torch.ones(T, dtype=torch.uint8, device=DEV)
+    live = {}
+    with B.Ring(1 << 20, 1 << 20) as ring:
+        ctx = StepContext()
+        hooks = install_hookpoints(model, ring, ctx, {"0": 10, "1.up": 11, "2": 12}, enabled=["0", "1.up", "2"],
+                                   summary_mask=5)
+        ring.point_enable(12, False)                # filtered out: not part of the graph
+        # the tensors that reach the hooks live in the graph's memory pool; holding them keeps
+        # their memory from being reused inside the graph, so they can be read after a replay
+        for name, hp in hooks.items():
+            hp.register_forward_pre_hook(lambda m, a, n=name: live.__setitem__(n, a[0]))
+        reqs0 = [(100 + i, i, 0, 1, 1) for i in range(T)]
+        with torch.no_grad():
+            model(static_x)                         # warm-up outside the capture (library set-up, no hooks fire:
+            torch.cuda.synchronize()                # no step prepared yet)
+        assert ring.get_stats().launched_records == 0
+        g = torch.cuda.CUDAGraph()
+        with ctx.capture(ring, reqs0, keep_mask=keep):
+            with torch.cuda.graph(g), torch.no_grad():
+                model(static_x)
+        s = torch.cuda.current_stream()
+        seq = 0
+        for step in range(5):
+            x = torch.randn(T, d, device=DEV).to(torch.bfloat16)
+            static_x.copy_(x)
+            mask = (np.arange(T) % 3 != step % 3).astype(np.uint8) if step else np.ones(T, np.uint8)
+            keep.copy_(torch.from_numpy(mask))
+            reqs = [(1000 * step + i, i, 0, 1, 1) for i in range(T)]
+            assert ctx.begin_replay(step, s.cuda_stream, reqs=reqs) == B.OK
+            g.replay()
+            ctx.end_replay(s.cuda_stream)
+            s.synchronize()
+            ring.drain(B.DRAIN_FLUSH)
+            views = ring.poll_host()
+            assert [v.seq for v in views] == [seq, seq + 1]
+            for v, (name, pid) in zip(views, (("0", 10), ("1.up", 11))):
+                t = live[name].reshape(-1, live[name].shape[-1]).cpu()
+                ref = orc.build_record(t, reqs, seq=v.seq, step_id=step, point_id=pid, out_dtype=1, summary_mask=5,
+                                       keep_mask=mask)
+                compare_record(v.bytes(), ref)
+            ring.release_host(views[-1].seq)
+            seq += 2
+        torch.cuda.synchronize()
+        ctx.step.destroy()
