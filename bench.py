@@ -271,6 +271,14 @@ def main():
                              "GBs": round(alg / best / 1e3, 1), "frac_hbm_peak": round(alg / best / 1e3 / HBM_PEAK_GBS, 4)}
             log(f"kernel {name}: {kernels[name]}")
 
+        # config 2's record with a keep vector (the best-effort path of a decode step: 3 of 4 requests kept)
+        km2 = torch.from_numpy((np.arange(n_reqs) % 4 != 1).astype(np.uint8)).to(dev)
+        c2 = calls0[0][0]
+        kept = int((np.arange(n_reqs) % 4 != 1).sum())
+        time_shape("config2_keep_vector",
+                   lambda r: dmi.PreparedObserve(r, c2.point_id, c2.tensor, c2.reqs, out_dtype=c2.out_dtype,
+                                                 summary_mask=c2.summary_mask, keep_mask=km2),
+                   kept * hidden * 4 + n_reqs * 37 + 64 + kept * 8, 256, rec_bytes * 256 + (1 << 20))
         # config 3: ragged prefill, every 4th token, bf16 -> fp8
         w3 = configs.config3_prefill(device=dev, n_steps=1, n_resid=1, n_mlp=1)
         c_res, c_mlp = [c for c in w3.step_calls(0) if c.point_id < 100][0], [c for c in w3.step_calls(0) if c.point_id >= 100][0]
