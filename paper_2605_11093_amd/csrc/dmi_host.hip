@@ -109,6 +109,7 @@ struct Plan {
     uint64_t ub = 0;            // record bytes if every request is kept
     uint32_t grid = 1;
     bool decode = false;        // the decode-shaped kernel applies
+    bool row_map = false;       // ... and wants the source row of every listed row behind the table
 };
 
 // What the launches between two probes add when the host can tell without asking the
@@ -142,6 +143,7 @@ struct dmi_ring {
     uint32_t *slab = nullptr;
     uint32_t slab_slot_words = 0, next_slab = 0, max_reqs = 0;
     SelCache cache[kSelCache];
+    std::vector<uint32_t> sel_scratch;
     uint32_t cache_rr = 0;
     hipStream_t drain_stream = nullptr;
     uint32_t block_timeout_ms = 2000;
@@ -215,6 +217,7 @@ struct StepTable {                  // one request table, shared by the nodes ca
     std::vector<uint32_t> words;    // as selection_words() lays them out
     std::vector<dmi_req_sel_t> reqs;
     bool paged = false;
+    bool row_map = false;           // carries the source row of every listed row behind the table
     bool dirty = true;              // staged on the host, not yet on the device
     uint32_t slot = 0;
 };
@@ -453,8 +456,9 @@ dmi_status_t commit_slot_room(dmi_ring *r, uint32_t n)
 
 // Request table as the kernels read it: n x {req_id, tok_start, tok_step, tok_count}, then
 // n x first source row of the request (dense; callers have checked that it fits 32 bits)
-// or its row of the block table (paged).
-void selection_words(const dmi_req_sel_t *reqs, uint32_t n, bool paged, std::vector<uint32_t> &words)
+// or its row of the block table (paged); with row_map, then the source row of every listed
+// row in output order (for the decode-shaped kernel when requests list several rows).
+void selection_words(const dmi_req_sel_t *reqs, uint32_t n, bool paged, bool row_map, std::vector<uint32_t> &words)
 {
     words.resize((size_t)n * 5u);
     for (uint32_t i = 0; i < n; i++) {
@@ -465,34 +469,33 @@ void selection_words(const dmi_req_sel_t *reqs, uint32_t n, bool paged, std::vec
         words[4u * i + 3] = q.tok_count;
         words[4u * n + i] = paged ? q.row_base : q.row_base + q.tok_start;
     }
+    if (row_map)
+        for (uint32_t i = 0; i < n; i++)
+            for (uint32_t j = 0; j < reqs[i].tok_count; j++)
+                words.push_back(reqs[i].row_base + reqs[i].tok_start + j * reqs[i].tok_step);
 }
 
 // Put the request table where the kernel can read it from L2: a slab of slots in
 // device memory, refilled only when the selection differs from recent ones (all
 // hook points of a step share their selection).
-dmi_status_t stage_selection(dmi_ring *r, const dmi_selection_t *sel, bool paged, hipStream_t s,
+dmi_status_t stage_selection(dmi_ring *r, const dmi_selection_t *sel, bool paged, bool row_map, hipStream_t s,
                              uint32_t *slot_out)
 {
-    const uint32_t n = sel->n_reqs;
-    auto row0 = [paged](const dmi_req_sel_t &q) { return paged ? q.row_base : q.row_base + q.tok_start; };
+    std::vector<uint32_t> &words = r->sel_scratch;
+    selection_words(sel->reqs, sel->n_reqs, paged, row_map, words);
     for (auto &c : r->cache) {
-        if (!c.valid || c.stream != s || c.paged != paged || c.words.size() != (size_t)n * 5u) continue;
-        const uint32_t *w = c.words.data();
-        bool same = true;
-        for (uint32_t i = 0; same && i < n; i++) {
-            const dmi_req_sel_t &q = sel->reqs[i];
-            same = w[4u * i] == q.req_id && w[4u * i + 1] == q.tok_start && w[4u * i + 2] == q.tok_step &&
-                   w[4u * i + 3] == q.tok_count && w[4u * n + i] == row0(q);
+        if (!c.valid || c.stream != s || c.paged != paged || c.words.size() != words.size()) continue;
+        if (words.empty() || memcmp(c.words.data(), words.data(), words.size() * 4u) == 0) {
+            *slot_out = c.slot;
+            return DMI_OK;
         }
-        if (same) { *slot_out = c.slot; return DMI_OK; }
     }
-    std::vector<uint32_t> words;
-    selection_words(sel->reqs, n, paged, words);
     const uint32_t slot = r->next_slab++ % kSlabSlots;
     for (auto &c : r->cache) if (c.valid && c.slot == slot) c.valid = false;
-    if (n) HIP_TRY(launch_upload(r->slab + (size_t)slot * r->slab_slot_words, words.data(), n * 5u, s));
+    if (!words.empty())
+        HIP_TRY(launch_upload(r->slab + (size_t)slot * r->slab_slot_words, words.data(), (uint32_t)words.size(), s));
     SelCache &c = r->cache[r->cache_rr++ % kSelCache];
-    c.valid = true; c.paged = paged; c.stream = s; c.slot = slot; c.words.swap(words);
+    c.valid = true; c.paged = paged; c.stream = s; c.slot = slot; c.words = words;
     *slot_out = slot;
     return DMI_OK;
 }
@@ -501,7 +504,7 @@ dmi_status_t stage_selection(dmi_ring *r, const dmi_selection_t *sel, bool paged
 // transform.  Left to the caller: request table location, sequence number, step id, commit
 // slot, tail floor, policy, chain parity.
 dmi_status_t plan_capture(dmi_ring *r, uint32_t point_id, const dmi_selection_t *sel, const dmi_transform_t *xf,
-                          const Geometry &geo, CaptureArgs &a, Plan &pl)
+                          const Geometry &geo, CaptureArgs &a, Plan &pl, bool fixed_row_count_ok)
 {
     const uint32_t es_in = dtype_size(geo.src_dtype);
     uint64_t listed = 0;
@@ -523,6 +526,7 @@ dmi_status_t plan_capture(dmi_ring *r, uint32_t point_id, const dmi_selection_t 
     for (uint32_t i = 0; one_row_each && i < sel->n_reqs; i++) one_row_each = sel->reqs[i].tok_count == 1u;
     const bool simple = one_row_each && sel->keep_mask_dev == nullptr;
     a.one_row_each = one_row_each ? 1u : 0u;
+    a.listed_rows = (uint32_t)listed;
     const bool tab_lds = !simple && sel->n_reqs <= kLdsTableMax;
     a.n_seg = geo.n_seg;
     a.seg_units = geo.seg_elems / unit_elems;
@@ -576,7 +580,10 @@ dmi_status_t plan_capture(dmi_ring *r, uint32_t point_id, const dmi_selection_t 
     }
     pl.grid = groups < 1u ? 1u : groups > kMaxGrid ? kMaxGrid : (uint32_t)groups;
 
-    pl.decode = decode_kernel_applies(a, geo.vec16);
+    // requests listing several rows take the decode-shaped kernel with one workgroup per listed
+    // row: a launch whose row count must be able to change later (a replayable step) does not
+    pl.decode = decode_kernel_applies(a, geo.vec16) && (one_row_each || fixed_row_count_ok);
+    pl.row_map = pl.decode && !one_row_each && !index_mode;
     if (pl.decode) {
         // the host knows this record exactly: geometry and header travel as kernel arguments
         // (the kernel itself puts sequence number and step id into the header)
@@ -586,7 +593,7 @@ dmi_status_t plan_capture(dmi_ring *r, uint32_t point_id, const dmi_selection_t 
         a.off_sum = a.off_payload + pad64(a.payload_bytes);
         a.sum_arr = pad64(listed * 4u);
         a.record_bytes = ub;
-        a.rows_consecutive = sel->row_index_dev == nullptr;
+        a.rows_consecutive = sel->row_index_dev == nullptr && one_row_each;
         a.row_first = sel->reqs[0].row_base + sel->reqs[0].tok_start;
         for (uint32_t i = 1; a.rows_consecutive && i < sel->n_reqs; i++)
             a.rows_consecutive = sel->reqs[i].row_base + sel->reqs[i].tok_start == a.row_first + i;
@@ -609,7 +616,7 @@ dmi_status_t observe_common(dmi_ring *r, uint32_t point_id, const dmi_selection_
     if (r->step_open)
         return fail(DMI_ERR_INVALID_ARG, "a replayable step is between dmi_step_begin and dmi_step_end");
     Plan pl;
-    dmi_status_t st = plan_capture(r, point_id, sel, xf, geo, a, pl);
+    dmi_status_t st = plan_capture(r, point_id, sel, xf, geo, a, pl, true);
     if (st != DMI_OK) return st;
     const uint64_t ub = pl.ub;
 
@@ -623,11 +630,12 @@ dmi_status_t observe_common(dmi_ring *r, uint32_t point_id, const dmi_selection_
     if ((st = commit_slot_room(r, 1u)) != DMI_OK) return st;
 
     uint32_t slot = 0;
-    if ((st = stage_selection(r, sel, a.paged != 0, s, &slot)) != DMI_OK) return st;
+    if ((st = stage_selection(r, sel, a.paged != 0, pl.row_map, s, &slot)) != DMI_OK) return st;
 
     const uint64_t seq = r->next_seq.load(std::memory_order_relaxed);
     a.req_table = reinterpret_cast<const uint4 *>(r->slab + (size_t)slot * r->slab_slot_words);
     a.row0 = r->slab + (size_t)slot * r->slab_slot_words + 4u * (size_t)sel->n_reqs;
+    a.row_map = pl.row_map ? a.row0 + sel->n_reqs : nullptr;
     a.seq = seq;
     a.step_id = step_id;
     a.cslot = &r->dctrl->slots[seq % kCommitSlots];
@@ -931,7 +939,7 @@ dmi_status_t dmi_ring_create(const dmi_ring_config_t *cfg, dmi_ring_t **out)
     r->max_reqs = max_reqs;
     r->block_timeout_ms = cfg->block_timeout_ms ? cfg->block_timeout_ms : 2000u;
     r->point_off.assign(DMI_MAX_POINTS, 0);
-    r->slab_slot_words = (max_reqs * 5u + 63u) & ~63u;
+    r->slab_slot_words = (max_reqs * 5u + kDecodeMaxListed + 63u) & ~63u;
     // a probe at least every 16 launches, or every 1/32 of the ring (not under 8 MiB): often enough
     // for the drain to follow closely, rare enough that its cost in the producer's stream stays small
     r->probe_bytes = r->dev_cap / 32u > (8u << 20) ? r->dev_cap / 32u : (8u << 20);
@@ -1207,20 +1215,22 @@ dmi_status_t step_add(dmi_step *st, uint32_t point_id, const dmi_selection_t *se
     if (hipStreamIsCapturing((hipStream_t)hip_stream, &cs) != hipSuccess || cs != hipStreamCaptureStatusActive)
         return fail(DMI_ERR_INVALID_ARG, "hip_stream is not capturing");
     StepNode nd;
-    dmi_status_t rc = plan_capture(r, point_id, sel, xf, geo, a, nd.pl);
+    dmi_status_t rc = plan_capture(r, point_id, sel, xf, geo, a, nd.pl, false);
     if (rc != DMI_OK) return rc;
 
     // nodes captured with the same selection share one table (and are updated together)
     std::vector<uint32_t> words;
-    selection_words(sel->reqs, sel->n_reqs, a.paged != 0, words);
+    selection_words(sel->reqs, sel->n_reqs, a.paged != 0, nd.pl.row_map, words);
     uint32_t ti = 0;
     for (; ti < st->tables.size(); ti++)
-        if (st->tables[ti].paged == (a.paged != 0) && st->tables[ti].words == words) break;
+        if (st->tables[ti].paged == (a.paged != 0) && st->tables[ti].row_map == nd.pl.row_map &&
+            st->tables[ti].words == words) break;
     if (ti == st->tables.size()) {
         StepTable t;
         t.words.swap(words);
         t.reqs.assign(sel->reqs, sel->reqs + sel->n_reqs);
         t.paged = a.paged != 0;
+        t.row_map = nd.pl.row_map;
         t.slot = ti;                // at most one table per node, so slots suffice
         st->tables.push_back(std::move(t));
     }
@@ -1228,6 +1238,7 @@ dmi_status_t step_add(dmi_step *st, uint32_t point_id, const dmi_selection_t *se
     uint32_t *slot = st->slab + (size_t)st->tables[ti].slot * r->slab_slot_words;
     a.req_table = reinterpret_cast<const uint4 *>(slot);
     a.row0 = slot + 4u * (size_t)sel->n_reqs;
+    a.row_map = nd.pl.row_map ? a.row0 + sel->n_reqs : nullptr;
     a.seq = 0;
     a.step_id = 0;
     a.cslot = nullptr;
@@ -1361,7 +1372,7 @@ dmi_status_t dmi_step_update(dmi_step_t *st, uint32_t node, const dmi_req_sel_t 
         nd.pl.listed = listed;
     }
     tab.reqs.assign(reqs, reqs + n_reqs);
-    selection_words(reqs, n_reqs, tab.paged, tab.words);
+    selection_words(reqs, n_reqs, tab.paged, tab.row_map, tab.words);
     tab.dirty = true;
     return DMI_OK;
 }

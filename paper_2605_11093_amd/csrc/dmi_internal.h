@@ -9,6 +9,7 @@ namespace dmi {
 constexpr uint32_t kThreads = 256;          // 4 wavefronts of 64 lanes per workgroup
 constexpr uint32_t kMaxGrid = 2048;         // 256 CUs x 8 resident workgroups
 constexpr uint32_t kLdsTableMax = 1024;     // request tables up to this size are cached in LDS
+constexpr uint32_t kDecodeMaxListed = 1024; // most rows a ragged selection may list to take the decode-shaped kernel
 
 // One slot per launch, written by workgroup 0 of the launch: where the head stands
 // after it, and the running counters.  Slot seq % kCommitSlots lives in device memory;
@@ -94,6 +95,9 @@ struct CaptureArgs {
     const uint64_t *tail_src;       // pinned host word holding the drained-up-to mark (NULL: not read)
     uint32_t simple;                // no keep mask and every request contributes exactly one row
     uint32_t one_row_each;          // every request lists exactly one row (a keep vector may still drop some)
+    uint32_t listed_rows;           // rows the selection lists (all requests kept)
+    const uint32_t *row_map;        // decode-shaped kernel, requests listing several rows: source row of every
+                                    // output row, written by the host behind the request table
     uint32_t upr_shift;             // log2(units_per_row) if that is a power of two, else 32
     uint32_t bs_shift, seg_shift;   // same for block_size and seg_units
     uint32_t drop_newest;

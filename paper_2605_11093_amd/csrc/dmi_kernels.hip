@@ -367,7 +367,7 @@ struct RowRef {
 __device__ uint64_t g_trace[256 * 8];
 #define DMI_STAMP(k) do { if (tid == 0 && blockIdx.x < 256) g_trace[blockIdx.x * 8 + (k)] = wall_clock64(); } while (0)
 // decode-shaped kernel: first row workgroup and the extra workgroup of the last 32 launches
-#define DMI_STAMP_D(k) do { if (threadIdx.x == 0 && (blockIdx.x == 0 || blockIdx.x == a.n_reqs)) \
+#define DMI_STAMP_D(k) do { if (threadIdx.x == 0 && (blockIdx.x == 0 || blockIdx.x == a.n_wg_rows)) \
         g_trace[(a.seq & 31u) * 16u + (blockIdx.x == 0 ? 0u : 8u) + (k)] = wall_clock64(); } while (0)
 #else
 #define DMI_STAMP(k) do { } while (0)
@@ -564,9 +564,9 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
 #pragma unroll
             for (uint32_t k = 0; k < U; k++) {
                 const uint32_t c = c_begin + k * stride;
-                pre_v[k] = unit_t{};
-                if (pre_ref.ok && c < a.units_per_row)
-                    pre_v[k] = *reinterpret_cast<const unit_t *>(pre_ref.base + (uint64_t)c * NB_IN);
+                const bool want = pre_ref.ok && c < a.units_per_row;
+                const uint8_t *p = want ? pre_ref.base + (uint64_t)c * NB_IN : reinterpret_cast<const uint8_t *>(a.ctrl);
+                pre_v[k] = *reinterpret_cast<const unit_t *>(p);     // zeroed where it is used if not wanted
             }
             pre = true;
         }
@@ -646,24 +646,29 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
 
     // row g -> request r (largest r with pref[r] <= g; requests with no rows are skipped
     // because their successor shares the same prefix) -> source location
+    // (LDS is read through a pointer that says so: where the table may live either in LDS or
+    // in global memory the compiler otherwise merges the two reads into one untyped load,
+    // which counts as a global one and makes every wait for it a wait for the row loads too)
+    typedef __attribute__((address_space(3))) uint32_t lds_u32;
+    const lds_u32 *const L = (const lds_u32 *)lds;
     auto locate = [&](uint32_t g) -> RowRef {
         uint32_t r = g, j = 0;
         if (!simple) {
             uint32_t lo = 0, hi = n_reqs;
             while (hi - lo > 1u) {
                 const uint32_t mid = (lo + hi) >> 1;
-                if (pref[mid] <= g) lo = mid; else hi = mid;
+                if (L[m.pref + mid] <= g) lo = mid; else hi = mid;
             }
             r = lo;
-            j = g - pref[r];
+            j = g - L[m.pref + r];
         }
         RowRef ref;
         if (!a.paged) {
             int64_t row;
             if (index_mode) {
-                row = (int64_t)a.row_index[simple ? g : pref_all[r] + j];
+                row = (int64_t)a.row_index[simple ? g : L[m.pref_all + r] + j];
             } else if (a.table_in_lds) {
-                row = (int64_t)lrb[r] + (int64_t)j * (int64_t)ltab[r].z;
+                row = (int64_t)L[m.rb + r] + (int64_t)j * (int64_t)L[m.tab + 4u * r + 2u];
             } else {
                 row = (int64_t)a.row0[r];
                 if (j) row += (int64_t)j * (int64_t)a.req_table[r].z;
@@ -671,11 +676,14 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
             ref.ok = row >= 0 && row < a.n_src_rows;
             ref.base = a.src + (ref.ok ? row : 0) * a.row_stride_b;
         } else {
-            uint4 e;
-            uint32_t seq_row;
-            if (a.table_in_lds) { e = ltab[r]; seq_row = lrb[r]; }
-            else { e = a.req_table[r]; seq_row = a.row0[r]; }
-            const uint32_t t = e.y + j * e.z;               // host keeps token positions below 2^31
+            uint32_t tok0, tstep, seq_row;
+            if (a.table_in_lds) {
+                tok0 = L[m.tab + 4u * r + 1u]; tstep = L[m.tab + 4u * r + 2u]; seq_row = L[m.rb + r];
+            } else {
+                const uint4 e = a.req_table[r];
+                tok0 = e.y; tstep = e.z; seq_row = a.row0[r];
+            }
+            const uint32_t t = tok0 + j * tstep;            // host keeps token positions below 2^31
             const uint32_t lb = a.bs_shift < 32u ? t >> a.bs_shift : t / a.block_size;
             const uint32_t slot = t - lb * a.block_size;
             const int64_t blk = (int64_t)a.block_table[(int64_t)seq_row * a.bt_stride + (int64_t)lb];
@@ -688,13 +696,21 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
         if (!a.paged) return ref.base + (uint64_t)c * NB_IN;
         const uint32_t seg = a.seg_shift < 32u ? c >> a.seg_shift : c / a.seg_units;
         const uint32_t cc = c - seg * a.seg_units;
-        return ref.base + (int64_t)lds[m.heads + seg] * a.head_stride_b + (uint64_t)cc * NB_IN;
+        return ref.base + (int64_t)L[m.heads + seg] * a.head_stride_b + (uint64_t)cc * NB_IN;
     };
-    auto load_unit = [&](const RowRef &ref, uint32_t c) -> unit_t {
-        unit_t v = {};
-        if (ref.ok) v = *reinterpret_cast<const unit_t *>(unit_ptr(ref, c));
-        return v;
+    // Loads are never put under a condition of their own: the compiler then waits for each
+    // one before it issues the next (a register copy where the branches join), and four
+    // loads in flight become four trips to memory.  A unit that is not wanted (past the
+    // end, or of a row whose index left the source) is read from the control block instead
+    // and replaced by zeros, or skipped, when it is stored.
+    const uint8_t *const safe_src = reinterpret_cast<const uint8_t *>(a.ctrl);
+    auto load_unit = [&](const RowRef &ref, uint32_t c, bool want) -> unit_t {
+        const uint8_t *p = want ? unit_ptr(ref, want ? c : 0u) : safe_src;
+        // both are device memory; said explicitly, or the choice between two pointers costs the load its type
+        typedef __attribute__((address_space(1))) const unit_t global_unit_t;
+        return *(global_unit_t *)p;
     };
+    auto zero_unless = [](bool keep, unit_t v) -> unit_t { return keep ? v : unit_t{}; };
 
     if (!dropped) {
         // ---- header, request table and all pad bytes: workgroup 0.  The header is put
@@ -754,9 +770,12 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
                     const uint64_t n_items = rpi > 1u ? ((uint64_t)n_rows + rpi - 1u) / rpi
                                                       : (uint64_t)n_rows * cpr;
                     // unit k of this lane in item `it`: its flat position in the payload, loaded value
-                    auto fetch = [&](uint64_t it, unit_t (&v)[U], uint64_t (&pos)[U], bool (&live)[U]) {
-                        RowRef ref = {nullptr, 0};
-                        uint32_t g_prev = 0xFFFFFFFFu;
+                    auto fetch = [&](uint64_t it, unit_t (&v)[U], uint64_t (&pos)[U], bool (&live)[U], uint32_t &okm) {
+                        RowRef ref = {nullptr, 0}, refs[U];
+                        uint32_t g_prev = 0xFFFFFFFFu, cs[U];
+                        okm = 0;
+                        // first where every unit comes from (a row's place may take a load of its own to
+                        // find), then all the unit loads together
 #pragma unroll
                         for (uint32_t k = 0; k < U; k++) {
                             uint32_t g, c;
@@ -771,15 +790,20 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
                             }
                             live[k] = g < n_rows && c < a.units_per_row;
                             pos[k] = (uint64_t)g * a.units_per_row + c;
-                            v[k] = unit_t{};
-                            if (live[k]) {
-                                if (g != g_prev) {
-                                    ref = locate(g);
-                                    g_prev = g;
-                                    if (!ref.ok && c == 0) atomicAdd((unsigned long long *)&a.ctrl->bad_rows, 1ull);
-                                }
-                                v[k] = load_unit(ref, c);
+                            if (live[k] && g != g_prev) {
+                                ref = locate(g);
+                                g_prev = g;
+                                if (!ref.ok && c == 0) atomicAdd((unsigned long long *)&a.ctrl->bad_rows, 1ull);
                             }
+                            refs[k] = ref;
+                            cs[k] = c;
+                        }
+                        asm volatile("" ::: "memory");      // keep the two phases apart
+#pragma unroll
+                        for (uint32_t k = 0; k < U; k++) {
+                            const bool want = live[k] && refs[k].ok != 0;
+                            okm |= want ? 1u << k : 0u;
+                            v[k] = load_unit(refs[k], cs[k], want);
                         }
                     };
                     uint64_t it = blockIdx.x;
@@ -787,6 +811,7 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
                         unit_t v[U];
                         uint64_t pos[U];
                         bool live[U];
+                        uint32_t okm = 0;
                         if (pre) {      // decode-shaped, rows of >= 1024 units handled one per item
                             const uint32_t g = cpr == 1u ? (uint32_t)it : (uint32_t)(it / cpr);
                             const uint32_t c0 = (uint32_t)(it - (uint64_t)g * cpr) * CH + tid;
@@ -795,11 +820,12 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
                                 const uint32_t c = c0 + k * kThreads;
                                 v[k] = pre_v[k];
                                 live[k] = c < a.units_per_row;
+                                okm |= live[k] && pre_ref.ok ? 1u << k : 0u;
                                 pos[k] = (uint64_t)g * a.units_per_row + c;
                             }
                             if (!pre_ref.ok && c0 == 0) atomicAdd((unsigned long long *)&a.ctrl->bad_rows, 1ull);
                         } else {
-                            fetch(it, v, pos, live);
+                            fetch(it, v, pos, live, okm);
                         }
                         for (;;) {
                             const uint64_t nxt = it + gridDim.x;
@@ -807,14 +833,16 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
                             unit_t v_n[U];
                             uint64_t pos_n[U];
                             bool live_n[U];
-                            if (more) fetch(nxt, v_n, pos_n, live_n);
+                            uint32_t okm_n = 0;
+                            if (more) fetch(nxt, v_n, pos_n, live_n, okm_n);
 #pragma unroll
                             for (uint32_t k = 0; k < U; k++)
                                 if (live[k])
-                                    emit_unit<ES_IN, VEC, OUT, false>(w, off_payload + pos[k] * NB_OUT, v[k],
-                                                                      a.src_dtype, dummy);
+                                    emit_unit<ES_IN, VEC, OUT, false>(w, off_payload + pos[k] * NB_OUT,
+                                                                      zero_unless((okm >> k) & 1u, v[k]), a.src_dtype, dummy);
                             if (!more) break;
                             it = nxt;
+                            okm = okm_n;
 #pragma unroll
                             for (uint32_t k = 0; k < U; k++) { v[k] = v_n[k]; pos[k] = pos_n[k]; live[k] = live_n[k]; }
                         }
@@ -834,7 +862,7 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
                     const uint32_t slice_stride = gridDim.x * kThreads;
                     for (uint64_t t0 = (uint64_t)blockIdx.x * kThreads; t0 < total; t0 += (uint64_t)slice_stride * U) {
                         unit_t v[U];
-                        bool live[U];
+                        bool live[U], okk[U];
                         uint32_t my_lo = 0, my_hi = 0, my_ok = 0, my_first = 0;
                         if (shared_locate) {
                             const uint32_t sl = lane >> 4, j = lane & 15u;
@@ -879,13 +907,14 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
                                     if (!ref.ok && c == 0) atomicAdd((unsigned long long *)&a.ctrl->bad_rows, 1ull);
                                 }
                             }
-                            v[k] = load_unit(ref, c);
+                            okk[k] = live[k] && ref.ok != 0;
+                            v[k] = load_unit(ref, c, okk[k]);
                         }
 #pragma unroll
                         for (uint32_t k = 0; k < U; k++) {
                             const uint64_t u = t0 + (uint64_t)k * slice_stride + tid;
                             if (live[k])
-                                emit_unit<ES_IN, VEC, OUT, false>(w, off_payload + u * NB_OUT, v[k],
+                                emit_unit<ES_IN, VEC, OUT, false>(w, off_payload + u * NB_OUT, zero_unless(okk[k], v[k]),
                                                                   a.src_dtype, dummy);
                         }
                     }
@@ -902,17 +931,15 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
             // a step = (g0: first row of the workgroup's current group, pass)
             auto fetch = [&](uint64_t st_g0, uint32_t st_pass, RowRef &ref, unit_t (&v)[U]) {
                 const uint64_t g = st_g0 + sub;
-                if (g < n_rows) {
-                    if (st_pass == 0) {
-                        ref = locate((uint32_t)g);
-                        if (!ref.ok && l == 0) atomicAdd((unsigned long long *)&a.ctrl->bad_rows, 1ull);
-                    }
+                const bool row_live = g < n_rows;
+                if (row_live && st_pass == 0) {
+                    ref = locate((uint32_t)g);
+                    if (!ref.ok && l == 0) atomicAdd((unsigned long long *)&a.ctrl->bad_rows, 1ull);
+                }
 #pragma unroll
-                    for (uint32_t k = 0; k < U; k++) {
-                        const uint32_t c = l + (st_pass * U + k) * gsz;
-                        v[k] = unit_t{};
-                        if (c < a.units_per_row) v[k] = load_unit(ref, c);
-                    }
+                for (uint32_t k = 0; k < U; k++) {
+                    const uint32_t c = l + (st_pass * U + k) * gsz;
+                    v[k] = load_unit(ref, c, row_live && ref.ok != 0 && c < a.units_per_row);
                 }
             };
             uint64_t cur_g0 = (uint64_t)blockIdx.x * rpw;
@@ -944,8 +971,8 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
                         for (uint32_t k = 0; k < U; k++) {
                             const uint32_t c = l + (cur_pass * U + k) * gsz;
                             if (c < a.units_per_row)
-                                emit_unit<ES_IN, VEC, OUT, true>(w, row_off + (uint64_t)c * NB_OUT, v[k],
-                                                                 a.src_dtype, acc);
+                                emit_unit<ES_IN, VEC, OUT, true>(w, row_off + (uint64_t)c * NB_OUT,
+                                                                 zero_unless(ref.ok != 0, v[k]), a.src_dtype, acc);
                         }
                     }
                     if (cur_pass == spr - 1u) {     // the row is complete: reduce and store its summaries
@@ -1034,7 +1061,9 @@ struct DecodeArgs {
     const uint64_t *tail_src;       // where the extra workgroup reads the drained-up-to mark (may be NULL)
     // line 3
     const uint8_t *keep_mask;       // keep vector (MASK variants): request r is captured iff keep_mask[r] != 0
-    uint64_t spare[7];
+    uint32_t n_wg_rows;             // row workgroups = rows listed (= n_reqs unless requests list several rows)
+    uint32_t spare32;
+    uint64_t spare[6];
 };
 static_assert(sizeof(DecodeArgs) == 256, "four lines");
 constexpr uint32_t kDecDropNewest = 1u, kDecConsecutive = 2u, kDecIndexed = 4u, kDecParIn = 8u;
@@ -1055,7 +1084,7 @@ __global__ void __launch_bounds__(kThreads) capture_decode_kernel(const DecodeAr
     constexpr uint32_t NB_OUT = out_unit_bytes<2, 8, OUT>();
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const uint32_t par = (a.flags & kDecParIn) ? 1u : 0u;
-    const bool meta_wg = blockIdx.x == a.n_reqs;
+    const bool meta_wg = blockIdx.x == a.n_wg_rows;
     constexpr uint32_t kCtlTid = kThreads - 64u;
     DMI_STAMP_D(1);
 
@@ -1131,7 +1160,7 @@ __global__ void __launch_bounds__(kThreads) capture_decode_kernel(const DecodeAr
         return;
     }
     // record geometry: known on the host, or from the keep vector
-    uint32_t n_rows = a.n_reqs, my_row = blockIdx.x;
+    uint32_t n_rows = a.n_wg_rows, my_row = blockIdx.x;
     bool kept = true;
     uint64_t record_bytes = a.record_bytes, payload_bytes = a.payload_bytes, off_sum = a.off_sum, sum_arr = a.sum_arr;
     if constexpr (MASK) {
@@ -1344,14 +1373,17 @@ hipError_t launch_capture(const CaptureArgs &a, uint32_t grid, bool vec16, hipSt
 
 bool decode_kernel_applies(const CaptureArgs &a, bool vec16)
 {
-    const bool shape = a.simple || (a.one_row_each && a.keep_mask && a.n_reqs <= 1024u);
+    // one row per request (with a keep vector: up to 1024 requests), or, without a keep vector, any
+    // selection of at most 1024 rows (the host then lists the source row of every output row)
+    const bool shape = a.simple || (a.one_row_each && a.keep_mask && a.n_reqs <= 1024u) ||
+                       (!a.keep_mask && a.listed_rows >= 1u && a.listed_rows <= kDecodeMaxListed);
     return shape && !a.paged && vec16 && a.src_dtype == 1u && a.units_per_row <= 4u * kThreads && a.n_reqs >= 1u;
 }
 
 template <int OUT>
 static hipError_t launch_decode_t(const DecodeArgs &d, bool summaries, hipStream_t s)
 {
-    const dim3 grid(d.n_reqs + 1u);
+    const dim3 grid(d.n_wg_rows + 1u);
     if (d.keep_mask) {
         if (summaries)
             hipLaunchKernelGGL((capture_decode_kernel<OUT, true, true>), grid, dim3(kThreads), 0, s, d);
@@ -1373,7 +1405,8 @@ hipError_t launch_capture_decode(const CaptureArgs &a, hipStream_t s)
     std::memset(&d, 0, sizeof d);
     d.src = a.src;
     d.row_stride_b = a.row_stride_b;
-    d.rows = a.row_index ? a.row_index : reinterpret_cast<const int32_t *>(a.row0);
+    d.rows = a.row_index ? a.row_index : reinterpret_cast<const int32_t *>(a.row_map ? a.row_map : a.row0);
+    d.n_wg_rows = a.hdr[9];         // rows listed
     d.ring = a.ring;
     d.cap = a.cap;
     d.ctrl = a.ctrl;

@@ -103,6 +103,11 @@ CASES = {
     "short_rows_flat": (3000, 256, torch.bfloat16, "ragged", 1, 0),
     "elementwise_odd": (120, 1001, torch.bfloat16, "ragged", 4, 7),
     "summary_only_long": (2100, 8192, torch.bfloat16, "ragged", 0, 7),
+    # few rows in all: the decode-shaped kernel with the host's row list
+    "ragged_small_raw_sum": (220, 4096, torch.bfloat16, "ragged", 1, 5),
+    "ragged_small_fp8": (220, 1024, torch.bfloat16, "ragged", 4, 0),
+    "ragged_small_fp16_sum": (75, 8192, torch.bfloat16, "ragged", 2, 7),
+    "ragged_small_summary_only": (1000, 256, torch.bfloat16, "ragged", 0, 3),
 }
 
 
