@@ -1147,6 +1147,29 @@ __global__ void __launch_bounds__(kThreads) capture_decode_kernel(const DecodeAr
         sh[24] = (uint32_t)ct.seq;      sh[25] = (uint32_t)(ct.seq >> 32);
         sh[26] = (uint32_t)ct.step_id;  sh[27] = (uint32_t)(ct.step_id >> 32);
     }
+    // Summaries are taken before the one barrier of this kernel, which then hands over both
+    // the control words and the wavefronts' partial sums: the rows arrive later than the
+    // control words anyway, and a second barrier behind the stores would put the summary
+    // stores a good half microsecond behind the row stores.
+    if constexpr (SUMM) {
+        Accum acc = {0.f, 0.f, 0u};
+        if (!meta_wg) {
+#pragma unroll
+            for (uint32_t k = 0; k < U; k++) {
+                const uint32_t c = tid + k * kThreads;
+                if (c < a.units_per_row) emit_unit<2, 8, OUT_NONE, true>(RingW{}, 0, v[k], 1u, acc);
+            }
+            acc.ss = wave_sum(acc.ss);
+            acc.s = wave_sum(acc.s);
+            const uint32_t am = wave_max_u32(fold_am<2, 8>(acc.am));
+            float *red = reinterpret_cast<float *>(sh + 8);
+            if (lane == 0) {
+                red[wave] = acc.ss;
+                red[4 + wave] = acc.s;
+                sh[16 + wave] = am;
+            }
+        }
+    }
     lds_barrier();
     DMI_STAMP_D(2);
     const uint64_t head = (uint64_t)sh[0] | ((uint64_t)sh[1] << 32);
@@ -1246,38 +1269,20 @@ __global__ void __launch_bounds__(kThreads) capture_decode_kernel(const DecodeAr
     if (!ok && tid == 0) atomicAdd((unsigned long long *)&a.ctrl->bad_rows, 1ull);
     Accum acc = {0.f, 0.f, 0u};
     const uint64_t row_off = a.off_payload + (uint64_t)g * a.units_per_row * NB_OUT;
-    // all stores first, then the summaries: the launch cannot end before its stores have been
-    // acknowledged, and the arithmetic fits into that wait
 #pragma unroll
     for (uint32_t k = 0; k < U; k++) {
         const uint32_t c = tid + k * kThreads;
         if (c < a.units_per_row)
             emit_unit<2, 8, OUT, false>(w, row_off + (uint64_t)c * NB_OUT, v[k], 1u, acc);
     }
-    if constexpr (SUMM) {
-#pragma unroll
-        for (uint32_t k = 0; k < U; k++) {
-            const uint32_t c = tid + k * kThreads;
-            if (c < a.units_per_row) emit_unit<2, 8, OUT_NONE, true>(w, 0, v[k], 1u, acc);
-        }
-    }
     DMI_STAMP_D(3);
     if constexpr (SUMM) {
-        acc.ss = wave_sum(acc.ss);
-        acc.s = wave_sum(acc.s);
-        uint32_t am = wave_max_u32(fold_am<2, 8>(acc.am));
-        float *red = reinterpret_cast<float *>(sh + 8);
-        if (lane == 0) {
-            red[wave] = acc.ss;
-            red[4 + wave] = acc.s;
-            sh[16 + wave] = am;
-        }
-        lds_barrier();
         if (tid == 0) {
+            const float *red = reinterpret_cast<const float *>(sh + 8);
             const float ss = (red[0] + red[1]) + (red[2] + red[3]);
             const float sm = (red[4] + red[5]) + (red[6] + red[7]);
             const uint32_t m01 = sh[16] > sh[17] ? sh[16] : sh[17], m23 = sh[18] > sh[19] ? sh[18] : sh[19];
-            am = m01 > m23 ? m01 : m23;
+            const uint32_t am = m01 > m23 ? m01 : m23;
             uint64_t o = off_sum + (uint64_t)g * 4u;
             if (a.summary_mask & 1u) { ring_store<float>(w, o, sqrtf(ss)); o += sum_arr; }
             if (a.summary_mask & 2u) { ring_store<float>(w, o, sm / (float)a.row_elems); o += sum_arr; }
