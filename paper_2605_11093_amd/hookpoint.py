@@ -86,6 +86,26 @@ class StepContext:
         self.step.end(stream)
 
 
+# The custom-operator layer (paper section 4.1): reaching a HookPoint is one call of the
+# operator dmi::observe(x, hook), so a traced / compiled model carries the capture as an
+# ordinary node of its graph instead of breaking at a Python callback.  The operator is
+# declared as writing its input (it writes nothing): that keeps compilers from dropping a
+# call whose result nobody uses, and from moving it across other uses of the tensor.
+_HOOKS: Dict[int, "HookPoint"] = {}
+_op_registered = False
+
+
+def _register_op():
+    global _op_registered
+    if _op_registered:
+        return
+    _op_registered = True
+
+    @torch.library.custom_op("dmi::observe", mutates_args=("x",))
+    def _observe(x: torch.Tensor, hook: int) -> None:
+        _HOOKS[hook]._launch(x)
+
+
 class HookPoint(nn.Module):
     """Identity module that observes its input.  `enabled=False` makes it a plain
     identity: nothing is launched (hook filtering)."""
@@ -95,10 +115,19 @@ class HookPoint(nn.Module):
         super().__init__()
         self.ring, self.point_id, self.ctx = ring, int(point_id), ctx
         self.out_dtype, self.summary_mask, self.enabled, self.hook_name = out_dtype, summary_mask, enabled, name
+        _register_op()
+        self._hook_id = len(_HOOKS) + 1
+        _HOOKS[self._hook_id] = self
 
     def forward(self, x: torch.Tensor) -> torch.Tensor:
-        if not self.enabled or self.ctx.reqs is None:
+        if not self.enabled:            # hook filtering: a disabled hook is not in the graph at all
             return x
+        torch.ops.dmi.observe(x, self._hook_id)
+        return x
+
+    def _launch(self, x: torch.Tensor) -> None:
+        if self.ctx.reqs is None:
+            return
         t = x if x.dim() == 2 else x.reshape(-1, x.shape[-1])      # [tokens, features] view, no copy
         if t.stride(-1) != 1 or t.data_ptr() != x.data_ptr():
             raise ValueError("HookPoint needs a tensor whose rows are contiguous in memory")
@@ -110,13 +139,12 @@ class HookPoint(nn.Module):
                                                 summary_mask=self.summary_mask, keep_mask=self.ctx._keep_tensor)
             if node >= 0:
                 self.ctx._nodes.append(node)
-            return x
+            return
         self.ring.observe(self.point_id, t.data_ptr(), dt, tuple(t.shape), tuple(t.stride()), self.ctx.reqs,
                           step_id=self.ctx.step_id, stream=torch.cuda.current_stream(x.device).cuda_stream,
                           out_dtype=dt if self.out_dtype is None else self.out_dtype,
                           summary_mask=self.summary_mask, keep_mask_dev=self.ctx.keep_mask_dev,
                           allow=())
-        return x
 
 
 def install_hookpoints(model: nn.Module, ring: B.Ring, ctx: StepContext, where: Dict[str, int],

@@ -110,3 +110,39 @@ def test_hookpoints_inside_a_captured_graph():
             seq += 2
         torch.cuda.synchronize()
         ctx.step.destroy()
+
+
+def test_hookpoints_survive_compilation_as_graph_nodes():
+    """torch.compile traces the model into one graph (no break at the hooks); the captures
+    are nodes of that graph and still fire once per forward."""
+    from paper_2605_11093_amd import binding as B
+    from paper_2605_11093_amd.hookpoint import StepContext, install_hookpoints
+    from _util import compare_record
+    torch.manual_seed(2)
+    d, T = 256, 12
+    model = nn.Sequential(*[Block(d) for _ in range(2)]).to(DEV).to(torch.bfloat16).eval()
+    live = {}
+    with B.Ring(1 << 20, 1 << 20) as ring:
+        ctx = StepContext()
+        hooks = install_hookpoints(model, ring, ctx, {"0": 3, "1": 4})
+        for name, hp in hooks.items():
+            hp.register_forward_pre_hook(lambda m, a, n=name: live.__setitem__(n, a[0].detach().clone()))
+        compiled = torch.compile(model, backend="aot_eager", fullgraph=True)
+        reqs = [(5, 0, 2, 3, 4)]                        # rows 2, 6, 10
+        seq = 0
+        for step in range(3):
+            x = torch.randn(T, d, device=DEV).to(torch.bfloat16)
+            ctx.prepare_step(step, reqs)
+            with torch.no_grad():
+                y = compiled(x)
+                ctx.reqs = None                         # the reference forward below must not capture
+                ref_y = model(x)
+            assert torch.equal(y, ref_y)
+            ring.drain(B.DRAIN_FLUSH)
+            views = ring.poll_host()
+            assert [v.seq for v in views] == [seq, seq + 1]
+            for v, (name, pid) in zip(views, (("0", 3), ("1", 4))):
+                t = live[name].reshape(-1, d).cpu()
+                compare_record(v.bytes(), orc.build_record(t, reqs, seq=v.seq, step_id=step, point_id=pid, out_dtype=1))
+            ring.release_host(views[-1].seq)
+            seq += 2
