@@ -28,9 +28,9 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0           # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the config-2 capture kernel, from the two rocprofv3 --pmc runs
-# summarised in profiles/capture_kernel_config2_config3mlp.md (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000,
-# factors from a plain 256 MiB copy): 0.613 MB read + 0.530 MB written.
-TRAFFIC_CONFIG2_BYTES = 1143000
+# summarised in profiles/capture_kernels_all_configs.md (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000,
+# factors from a plain 256 MiB copy): 0.625 MB read + 0.530 MB written.
+TRAFFIC_CONFIG2_BYTES = 1154000
 SEED_NOTE = "synthetic (seeded ~N(0,1) bf16, shapes of the paper's LLM workloads)"
 
 
@@ -159,6 +159,52 @@ def main():
         stream.synchronize()
         log(f"large launch: config 3 MLP point, {rows3} rows x 14336, fp8: "
             f"{rows3 * 14336 * 3} algorithmic bytes per launch; plain copy: 268435456 B read + 268435456 B written")
+        r3.destroy()
+        # the other shapes, a few launches each, so that one profile covers every kernel variant in use
+        cr = [c for c in w3.step_calls(0) if c.point_id < 100][0]
+        r3 = B.Ring(dmi.record_bytes(32, rows3, 4096, B.DT_FP8, 0) * 6, 1 << 26, max_reqs_per_observe=256)
+        r3.set_policy(B.POLICY_DROP_NEWEST)
+        po = dmi.PreparedObserve(r3, cr.point_id, cr.tensor, cr.reqs, out_dtype=B.DT_FP8)
+        for i in range(5):
+            observe_checked(po, i)
+        stream.synchronize()
+        log(f"config 3 residual point, {rows3} rows x 4096, fp8: {rows3 * 4096 * 3} algorithmic bytes per launch")
+        r3.destroy()
+        del w3, c, cr, po
+        torch.cuda.empty_cache()
+        w4 = configs.config4_paged_kv(device=dev, n_layers_cap=1, n_steps=1)
+        c4 = w4.step_calls(0)[0]
+        rows4 = int(c4.reqs[:, 3].sum())
+        r3 = B.Ring(dmi.record_bytes(16, rows4, 256, B.DT_BF16, 0) * 6, 1 << 26, max_reqs_per_observe=256)
+        r3.set_policy(B.POLICY_DROP_NEWEST)
+        po = dmi.PreparedObserve(r3, c4.point_id, c4.tensor, c4.reqs, paged=c4.paged)
+        for i in range(5):
+            observe_checked(po, i)
+        stream.synchronize()
+        log(f"config 4 K slice, {rows4} rows x 256 (2 heads x 128), raw: {rows4 * 256 * 4} algorithmic bytes per launch")
+        r3.destroy()
+        del w4, c4, po
+        torch.cuda.empty_cache()
+        w5 = configs.config5_saturation(device=dev, n_points=1, n_steps=1)
+        c5 = w5.step_calls(0)[0]
+        r3 = B.Ring(dmi.record_bytes(256, 256, 8192, B.DT_BF16, 0) * 40, 1 << 26, max_reqs_per_observe=256)
+        r3.set_policy(B.POLICY_DROP_NEWEST)
+        po = dmi.PreparedObserve(r3, c5.point_id, c5.tensor, c5.reqs)
+        for i in range(32):
+            observe_checked(po, i)
+        stream.synchronize()
+        log(f"config 5 record, 256 rows x 8192, raw: {256 * 8192 * 4} algorithmic bytes per launch")
+        r3.destroy()
+        km = torch.from_numpy((np.arange(n_reqs) % 4 != 1).astype(np.uint8)).to(dev)
+        c2 = calls0[0][0]
+        r3 = B.Ring(rec_bytes * 40, 1 << 26, max_reqs_per_observe=256)
+        r3.set_policy(B.POLICY_DROP_NEWEST)
+        po = dmi.PreparedObserve(r3, c2.point_id, c2.tensor, c2.reqs, out_dtype=c2.out_dtype,
+                                 summary_mask=c2.summary_mask, keep_mask=km)
+        for i in range(32):
+            observe_checked(po, i)
+        stream.synchronize()
+        log("config 2 record with a keep vector (48 of 64 requests kept)")
         r3.destroy()
         return
 
