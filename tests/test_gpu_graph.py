@@ -172,3 +172,62 @@ def test_block_policy_refuses_a_step_that_can_never_fit(B):
         assert ring.get_point_drops(2) == 1
         torch.cuda.synchronize()
         step.destroy()
+
+
+def test_policy_and_keep_vector_change_between_replays(B):
+    """One captured step (decode-shaped launches with a keep vector), replayed under the
+    completeness policy, then best effort with a ring that is too small, then 1-in-2
+    sampling: flags come from the step's parameter block, not from the graph."""
+    from oracle.stream import OracleRing
+    n, E = 48, 512
+    ts = [prng.randn_bf16(prng.sub_seed(24, p), n * E, DEV).view(n, E) for p in range(3)]
+    keep = torch.ones(n, dtype=torch.uint8, device=DEV)
+    reqs = _reqs(n)
+    rec = 64 + 768 + n * E * 2           # all kept: 49,984 bytes
+    cap = rec * 4 + 64                   # four records; a step makes three
+    ref = OracleRing(cap, 1 << 22, POLICY_BLOCK)
+    with B.Ring(cap, 1 << 22, block_timeout_ms=1) as ring:
+        s = torch.cuda.current_stream()
+        step = B.Step(ring, 3)
+        g = torch.cuda.CUDAGraph()
+        step.capture_begin()
+        with torch.cuda.graph(g):
+            h = torch.cuda.current_stream().cuda_stream
+            for p in range(3):
+                step.observe_tensor(p, ts[p], reqs, stream=h, keep_mask=keep, summary_mask=4)
+        step.seal()
+        got = []
+        plan = [(POLICY_BLOCK, 1, True), (POLICY_BLOCK, 1, True), (POLICY_DROP_NEWEST, 1, False),
+                (POLICY_DROP_NEWEST, 1, False), (POLICY_DROP_NEWEST, 1, True), (POLICY_BLOCK, 2, True),
+                (POLICY_BLOCK, 2, True), (POLICY_DROP_NEWEST, 2, True)]
+        for i, (mode, k, drain_after) in enumerate(plan):
+            mask = (np.arange(n) % 5 != i % 5).astype(np.uint8)
+            keep.copy_(torch.from_numpy(mask))
+            ring.set_policy(mode, k, 0)
+            ref.set_policy(mode, k, 0)
+            rc = step.begin(i, s.cuda_stream, allow=(B.ERR_AGAIN,))
+            assert rc in (B.OK, B.SAMPLED_OUT), rc
+            g.replay()
+            step.end(s.cuda_stream)
+            for p in range(3):
+                ref.observe(ts[p].cpu(), reqs, point_id=p, step_id=i, out_dtype=1, summary_mask=4, keep_mask=mask)
+            if drain_after:
+                s.synchronize()
+                ring.drain(B.DRAIN_FLUSH)
+                for v in ring.poll_host():
+                    got.append(v.bytes())
+                    ring.release_host(v.seq)
+                ref.drain()
+                seqs = ref.polled_seqs()
+                if seqs:
+                    ref.release(seqs[-1])
+            else:
+                s.synchronize()
+        assert ref.stats.dropped_records > 0 and ref.stats.sampled_out_calls == 6
+        compare_streams(np.concatenate(got), ref.stream())
+        st = ring.get_stats()
+        for kf in ("captured_records", "captured_rows", "dropped_records", "dropped_rows", "dropped_bytes",
+                   "sampled_out_calls", "sampled_out_rows"):
+            assert getattr(st, kf) == getattr(ref.stats, kf), kf
+        torch.cuda.synchronize()
+        step.destroy()

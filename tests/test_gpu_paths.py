@@ -266,3 +266,27 @@ def test_keep_vector_on_decode_shapes_through_a_wrapping_ring(B, name):
     compare_streams(got, ref)
     for rbytes in (decode_record(got[:0 + int.from_bytes(got[48:56].tobytes(), "little")]),):
         assert rbytes.flags & 2
+
+
+@pytest.mark.parametrize("n,rows_each,masked", [(1024, 1, True), (1025, 1, True), (512, 2, False), (513, 2, False),
+                                                 (341, 3, False), (342, 3, False)])
+def test_kernel_choice_boundaries(B, n, rows_each, masked):
+    """Just inside and just outside what the decode-shaped kernel takes (1024 requests with
+    a keep vector; 1024 listed rows without): both sides must give the oracle's record."""
+    E = 256
+    T = n * rows_each + 5
+    t = prng.randn_bf16(prng.sub_seed(35, n, rows_each), T * E, DEV).view(T, E)
+    reqs = np.array([(i, 2 + i * rows_each, 0, rows_each, 1) for i in range(n)], dtype=np.uint32)
+    mask = (prng.randint(prng.sub_seed(35, 9, n), n, 0, 3) > 0).astype(np.uint8) if masked else None
+    with B.Ring(8 << 20, 8 << 20, max_reqs_per_observe=2048) as ring:
+        s = torch.cuda.current_stream()
+        km = None if mask is None else torch.from_numpy(mask).to(DEV)
+        ring.observe_tensor(3, t, reqs, step_id=11, stream=s.cuda_stream, keep_mask=km, summary_mask=5)
+        ring.observe_tensor(4, t, reqs, step_id=11, stream=s.cuda_stream, keep_mask=km, out_dtype=4)
+        ring.drain(B.DRAIN_FLUSH)
+        v = ring.poll_host()
+        tc = t.cpu()
+        compare_record(v[0].bytes(), orc.build_record(tc, reqs, seq=0, step_id=11, point_id=3, out_dtype=1,
+                                                      summary_mask=5, keep_mask=mask))
+        compare_record(v[1].bytes(), orc.build_record(tc, reqs, seq=1, step_id=11, point_id=4, out_dtype=4,
+                                                      keep_mask=mask))
