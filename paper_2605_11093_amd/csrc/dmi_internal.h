@@ -60,7 +60,8 @@ struct StepParams {
 };
 constexpr uint32_t kStepDropNewest = 1u, kStepSkip = 2u;
 
-struct CaptureArgs {
+// What the general capture kernel reads (its argument block: five 64-byte lines).
+struct CaptureKernelArgs {
     // source
     const uint8_t *src;
     int64_t row_stride_b;           // dense: bytes between rows
@@ -94,26 +95,31 @@ struct CaptureArgs {
     uint64_t tail_floor;            // the host's view of the tail when the launch was issued
     const uint64_t *tail_src;       // pinned host word holding the drained-up-to mark (NULL: not read)
     uint32_t simple;                // no keep mask and every request contributes exactly one row
-    uint32_t one_row_each;          // every request lists exactly one row (a keep vector may still drop some)
-    uint32_t listed_rows;           // rows the selection lists (all requests kept)
-    const uint32_t *row_map;        // decode-shaped kernel, requests listing several rows: source row of every
-                                    // output row, written by the host behind the request table
     uint32_t upr_shift;             // log2(units_per_row) if that is a power of two, else 32
     uint32_t bs_shift, seg_shift;   // same for block_size and seg_units
     uint32_t drop_newest;
     uint32_t table_in_lds;
-    uint32_t lds_bytes;
-    // record geometry and header, filled by the host when it knows them exactly (no keep
-    // mask: the row count is the listed one); used by the decode-shaped kernel
-    uint32_t hdr[16];
-    uint64_t off_payload, off_sum, sum_arr, record_bytes, payload_bytes;
-    uint32_t rows_consecutive;      // request i's row is row_first + i: no table lookup needed
-    uint32_t row_first;
     // launch chain: which copy of head / tail_for this launch reads (it writes the other)
     uint32_t par_in;
     // replayable steps: seq = step->seq_base + node, step id, tail floor and policy from *step
     uint32_t node;
     const StepParams *step;
+};
+
+// The host's plan of one launch: the kernel's arguments plus what only the launchers need
+// (the decode-shaped kernel gets its own, smaller block made from this).
+struct CaptureArgs : CaptureKernelArgs {
+    uint32_t one_row_each;          // every request lists exactly one row (a keep vector may still drop some)
+    uint32_t listed_rows;           // rows the selection lists (all requests kept)
+    const uint32_t *row_map;        // decode-shaped kernel, requests listing several rows: source row of every
+                                    // output row, written by the host behind the request table
+    uint32_t lds_bytes;
+    // record geometry and header words, filled by the host when it knows them exactly (no keep
+    // mask: the row count is the listed one); used by the decode-shaped kernel
+    uint32_t hdr[16];
+    uint64_t off_payload, off_sum, sum_arr, record_bytes, payload_bytes;
+    uint32_t rows_consecutive;      // request i's row is row_first + i: no table lookup needed
+    uint32_t row_first;
 };
 
 // Launchers (dmi_kernels.hip).  All return the launch's hipError_t.

@@ -430,7 +430,7 @@ __device__ __forceinline__ void touch_argument_lines(const T &a)
 
 // ---------------------------------------------------------------- capture kernel
 template <int ES_IN, int VEC, int OUT, bool SUMM>
-__global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
+__global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureKernelArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
     touch_argument_lines(a);        // all lines of the argument block in one trip, not one by one
@@ -502,13 +502,16 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
             }
             const uint32_t inc = wave_incl_scan(cnt, lane);
             if (r < n_reqs) pref[r] = inc - cnt;
-            if (lane == 63u) btot[b] = inc;
+            if (lane == 63u) { btot[b] = inc; if (nb == 1u) pref[n_reqs] = inc; }
             if (index_mode) {
                 const uint32_t inc_all = wave_incl_scan(cnt_all, lane);
                 if (r < n_reqs) pref_all[r] = inc_all - cnt_all;
-                if (lane == 63u) btot_all[b] = inc_all;
+                if (lane == 63u) { btot_all[b] = inc_all; if (nb == 1u) pref_all[n_reqs] = inc_all; }
             }
         }
+        // up to 64 requests: one wavefront has done it all, and the barrier in front of the
+        // geometry below is the only one needed
+        if (nb != 1u) {
         lds_barrier();
         if (wave == 0) {
             uint32_t carry = 0, carry_all = 0;
@@ -538,6 +541,7 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureArgs a)
         if (tid == 0) {
             pref[n_reqs] = btot[nb];
             if (index_mode) pref_all[n_reqs] = btot_all[nb];
+        }
         }
     }
     // -- decode-shaped selections (no mask, one row per request, dense): the first work
@@ -1349,9 +1353,11 @@ template <int ES_IN, int VEC, int OUT>
 static hipError_t launch_t(const CaptureArgs &a, uint32_t grid, hipStream_t s)
 {
     if (a.summary_mask)
-        hipLaunchKernelGGL((capture_kernel<ES_IN, VEC, OUT, true>), dim3(grid), dim3(kThreads), a.lds_bytes, s, a);
+        hipLaunchKernelGGL((capture_kernel<ES_IN, VEC, OUT, true>), dim3(grid), dim3(kThreads), a.lds_bytes, s,
+                           static_cast<const CaptureKernelArgs &>(a));
     else
-        hipLaunchKernelGGL((capture_kernel<ES_IN, VEC, OUT, false>), dim3(grid), dim3(kThreads), a.lds_bytes, s, a);
+        hipLaunchKernelGGL((capture_kernel<ES_IN, VEC, OUT, false>), dim3(grid), dim3(kThreads), a.lds_bytes, s,
+                           static_cast<const CaptureKernelArgs &>(a));
     return hipGetLastError();
 }
 
