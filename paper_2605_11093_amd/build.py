@@ -43,6 +43,22 @@ def build(force: bool = True) -> str:
     return SO
 
 
+C_CLIENT_SRC = os.path.join(ROOT, "examples", "c_client.c")
+C_CLIENT = os.path.join(ROOT, "examples", "c_client")
+
+
+def build_c_client() -> str:
+    """The plain-C example client of the ABI (gcc; links libdmi.so and the HIP runtime)."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = ["gcc", "-std=c11", "-O2", "-Wall", "-D__HIP_PLATFORM_AMD__", "-I", os.path.join(ROOT, "include"),
+           "-I", os.path.join(rocm, "include"), C_CLIENT_SRC, "-o", C_CLIENT,
+           "-L", HERE, "-ldmi", "-L", os.path.join(rocm, "lib"), "-lamdhip64",
+           "-Wl,-rpath,$ORIGIN/../paper_2605_11093_amd", "-Wl,-rpath," + os.path.join(rocm, "lib")]
+    subprocess.check_call(cmd)
+    return C_CLIENT
+
+
 if __name__ == "__main__":
     print(build())
     print(build_bench())
+    print(build_c_client())
