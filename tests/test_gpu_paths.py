@@ -290,3 +290,41 @@ def test_kernel_choice_boundaries(B, n, rows_each, masked):
                                                       summary_mask=5, keep_mask=mask))
         compare_record(v[1].bytes(), orc.build_record(tc, reqs, seq=1, step_id=11, point_id=4, out_dtype=4,
                                                       keep_mask=mask))
+
+
+PAGED_RANGES = {
+    # name: (cache dtype, out_dtype, heads, requests (id, table row, first token, tokens, step), keep vector?)
+    "mid_block_starts": (torch.bfloat16, 1, [1, 5], [(1, 0, 5, 300, 1), (2, 3, 0, 16, 1), (3, 7, 15, 2, 1),
+                                                     (4, 2, 31, 97, 1)], False),
+    "fp8_with_empty_requests": (torch.bfloat16, 4, [0, 7], [(1, 1, 0, 0, 1), (2, 2, 3, 250, 1), (3, 3, 9, 0, 1),
+                                                            (4, 4, 100, 1, 1), (5, 5, 0, 0, 1)], False),
+    "fp16_keep_vector": (torch.bfloat16, 2, [2], [(10 + i, i % 8, 3 * i, 40 + 7 * i, 1) for i in range(9)], True),
+    "fp32_cache": (torch.float32, 3, [3, 4], [(1, 6, 2, 77, 1), (2, 5, 16, 48, 1)], False),
+    "seventy_requests": (torch.bfloat16, 1, [6], [(i, i % 8, (5 * i) % 64, 1 + (11 * i) % 50, 1) for i in range(70)], True),
+}
+
+
+@pytest.mark.parametrize("name", sorted(PAGED_RANGES))
+def test_paged_token_ranges_through_a_wrapping_ring(B, name):
+    """Contiguous token ranges out of a paged cache: ranges that start and end inside
+    blocks, empty requests, keep vectors, an fp32 cache."""
+    dt, out_dtype, heads, req_list, masked = PAGED_RANGES[name]
+    NB, BS, NH, HD = 256, 16, 8, 128 if dt != torch.float32 else 64
+    cache = prng.randn_bf16(prng.sub_seed(36, len(name)), NB * BS * NH * HD, DEV).view(NB, BS, NH, HD).to(dt)
+    table = torch.from_numpy(prng.permutation(prng.sub_seed(36, 2), NB).astype(np.int32).reshape(8, 32)).to(DEV)
+    spec = configs.PagedSpec(BS, NH, HD, heads, table)
+    reqs = np.array(req_list, dtype=np.uint32)
+    n = len(req_list)
+    rows = int(reqs[:, 3].sum())
+    rec = orc.record_bytes(n, rows, len(heads) * HD, out_dtype, 0)
+    masks = [(prng.randint(prng.sub_seed(36, 3, k), n, 0, 2) > 0).astype(np.uint8) for k in range(3)]
+    dev_masks = [torch.from_numpy(m).to(DEV) for m in masks]
+
+    def args(i):
+        kw, okw = dict(out_dtype=out_dtype, summary_mask=0), dict(out_dtype=out_dtype, summary_mask=0)
+        if masked:
+            kw["keep_mask"], okw["keep_mask"] = dev_masks[i % 3], masks[i % 3]
+        return cache, reqs, kw, okw
+
+    got, ref = _stream_through_small_ring(B, args, 8, rec, paged=spec)
+    compare_streams(got, ref)
