@@ -187,6 +187,8 @@ typedef struct {
  * keep vectors) also a one-workgroup launch that copies 64 bytes to pinned memory; dmi_drain
  * and the library's drain thread may add one when the producer has paused.  Do not capture
  * that stream into a graph by hand while captures are outstanding: use dmi_step_t.
+ * Keep the stream alive until dmi_drain(DMI_DRAIN_FLUSH) has returned DMI_OK (or the ring
+ * is destroyed) after the last observe on it.
  */
 dmi_status_t dmi_observe(dmi_ring_t *ring, uint32_t point_id, const dmi_tensor_t *tensor /*[host]*/,
                          const dmi_selection_t *sel /*[host]*/, const dmi_transform_t *xf /*[host]*/,
