@@ -1,29 +1,16 @@
 // Host runtime of the capture-and-stage library: ring ownership, policy gate and
 // admission (paper section 4.4), kernel launches for dmi_observe (section 4.2), the
-// drain stage and pinned host ring (section 4.3), and the C ABI of include/dmi.h.
-#include "dmi.h"
-#include "dmi_internal.h"
-
-#include <algorithm>
-#include <atomic>
-#include <chrono>
-#include <condition_variable>
-#include <cstdarg>
-#include <cstdio>
-#include <cstring>
-#include <deque>
-#include <map>
-#include <mutex>
-#include <new>
-#include <string>
-#include <thread>
-#include <vector>
+// drain stage and pinned host ring (section 4.3), and the core of the C ABI of include/dmi.h
+// (replayable steps: dmi_step.hip; exporter: dmi_exporter.hip).
+#include "dmi_ring.h"
 
 using namespace dmi;
+using namespace dmi::host;
 
-namespace {
+namespace dmi {
+namespace host {
 
-thread_local std::string g_err;
+static thread_local std::string g_err;
 
 dmi_status_t fail(dmi_status_t code, const char *fmt, ...)
 {
@@ -36,215 +23,13 @@ dmi_status_t fail(dmi_status_t code, const char *fmt, ...)
     return code;
 }
 
-#define HIP_TRY(expr)                                                                     \
-    do {                                                                                  \
-        hipError_t e_ = (expr);                                                           \
-        if (e_ != hipSuccess)                                                             \
-            return fail(DMI_ERR_HIP, "%s failed: %s", #expr, hipGetErrorString(e_));      \
-    } while (0)
+const char *last_error_cstr() { return g_err.c_str(); }
 
-uint64_t now_ns()
-{
-    return (uint64_t)std::chrono::duration_cast<std::chrono::nanoseconds>(
-               std::chrono::steady_clock::now().time_since_epoch()).count();
-}
+}  // namespace host
+}  // namespace dmi
 
-inline uint64_t pad64(uint64_t n) { return (n + 63u) & ~63ull; }
-
-uint32_t dtype_size(uint32_t dt)
-{
-    switch (dt) {
-    case DMI_DTYPE_BF16: case DMI_DTYPE_FP16: return 2;
-    case DMI_DTYPE_FP32: return 4;
-    case DMI_DTYPE_FP8_E4M3FN: return 1;
-    default: return 0;
-    }
-}
-
-bool transform_ok(uint32_t src, uint32_t out)
-{
-    if (src != DMI_DTYPE_BF16 && src != DMI_DTYPE_FP16 && src != DMI_DTYPE_FP32) return false;
-    if (out == DMI_DTYPE_NONE || out == src) return true;
-    return src == DMI_DTYPE_BF16 && (out == DMI_DTYPE_FP16 || out == DMI_DTYPE_FP8_E4M3FN);
-}
-
-constexpr uint32_t kSlabSlots = 64;
-constexpr uint32_t kSelCache = 4;
-
-struct SelCache {
-    bool valid = false;
-    bool paged = false;
-    hipStream_t stream = nullptr;
-    uint32_t slot = 0;
-    std::vector<uint32_t> words;
-};
-
-
-// One record copied out of the pinned ring (exporter stage 2) and shared by its slices.
-struct RecordCopy {
-    uint8_t *bytes;
-    uint64_t size;
-    std::atomic<uint32_t> refs;
-};
-
-struct ExportJob {
-    dmi_record_view_t view;
-    uint64_t ticket;
-};
-
-struct ExportDone {
-    uint64_t seq;
-    RecordCopy *rc;
-    std::vector<dmi_slice_t> slices;
-};
-
-struct Geometry {
-    uint32_t src_dtype, row_elems, n_seg, seg_elems;
-    bool vec16;
-};
-
-// What a capture launch is, apart from when it runs and where its table lives.
-struct Plan {
-    uint64_t listed = 0;        // rows the selection lists
-    uint64_t ub = 0;            // record bytes if every request is kept
-    uint32_t grid = 1;
-    bool decode = false;        // the decode-shaped kernel applies
-    bool row_map = false;       // ... and wants the source row of every listed row behind the table
-};
-
-// What the launches between two probes add when the host can tell without asking the
-// device: completeness policy and no keep vector, so each record has its listed size and
-// none is dropped.
-struct Delta {
-    uint64_t bytes = 0, records = 0, rows = 0;
-};
-
-struct Probe {
-    hipEvent_t ev;          // recorded on the producer's stream behind the launches (and the slot fetch)
-    uint64_t covers;        // every launch with seq < covers was enqueued before ev
-    bool fetched;           // the commit slot of launch covers-1 was copied to the host mirror
-    Delta delta;            // else: what the launches since the previous probe added
-};
-
-}  // namespace
-
-struct dmi_ring {
-    dmi_ring_config_t cfg{};
-    int dev = 0;
-    uint8_t *dev_ring = nullptr;
-    uint64_t dev_cap = 0;
-    uint8_t *host_ring = nullptr, *host_ring_dev = nullptr;
-    uint64_t host_cap = 0;
-    DevCtrl *dctrl = nullptr;
-    CommitSlot *hslots = nullptr, *hslots_dev = nullptr;   // pinned mirror of DevCtrl::slots
-    hipStream_t ctl_stream = nullptr;                      // statistics reads, set-up launches
-    uint8_t *mask_buf = nullptr;                           // 4 rotating keep vectors of max_reqs bytes
-    uint32_t mask_rr = 0, mask_stride = 0;
-    uint32_t *slab = nullptr;
-    uint32_t slab_slot_words = 0, next_slab = 0, max_reqs = 0;
-    SelCache cache[kSelCache];
-    std::vector<uint32_t> sel_scratch;
-    uint32_t cache_rr = 0;
-    hipStream_t drain_stream = nullptr;
-    uint32_t block_timeout_ms = 2000;
-
-    // policy (set by the producer thread or between steps)
-    std::atomic<uint32_t> mode{DMI_POLICY_BLOCK}, sample_k{1}, sample_phase{0};
-    std::vector<uint8_t> point_off;
-
-    // producer side
-    std::atomic<uint64_t> next_seq{0};                     // launches issued so far
-    std::atomic<void *> last_stream{nullptr};
-    std::atomic<uint64_t> last_launch_ns{0};
-    std::deque<std::pair<uint64_t, uint64_t>> inflight;    // (seq, upper bound of record bytes)
-    uint64_t inflight_sum = 0;
-    uint64_t unprobed_launches = 0, unprobed_bytes = 0, probe_bytes = 8u << 20;
-    uint32_t chain_par = 0;                                // which copy of head / tail_for the next launch reads
-    bool step_open = false;                                // between dmi_step_begin and dmi_step_end
-    std::atomic<int> quiet{0};                             // a capture is open: library threads make no HIP call
-    std::atomic<bool> bg_parked{false};
-
-    // commit discovery: events recorded behind launches ("probes"), queried in order
-    std::mutex pmu;
-    std::deque<Probe> probes;
-    std::vector<hipEvent_t> probe_pool;
-    Delta window;                                          // launches since the last probe (under pmu)
-    bool window_exact = true;
-    uint64_t probed_upto = 0;                              // launches with seq < this have a probe behind them
-    std::atomic<uint64_t> confirmed{0};                    // launches with seq < this have finished
-    std::atomic<uint64_t> committed{0};                    // device head after launch confirmed-1
-    uint64_t snap[6] = {0, 0, 0, 0, 0, 0};                 // counters of the last confirmed slot
-
-    // drain / host ring state
-    std::mutex mu;
-    uint64_t drain_issued = 0;
-    std::atomic<uint64_t> drain_done{0};
-    // The drain stream carries the batch copies only (no launch, no event, no small copy: any
-    // of these is a packet on a second compute queue, and a second queue with packets pending
-    // slows every dispatch of the producer's queue by microseconds).  A batch is known to be
-    // done when the whole stream is idle; the drained-up-to mark reaches the kernels through a
-    // pinned host word that they read themselves.
-    volatile uint64_t *htail = nullptr;                    // pinned, coherent
-    const uint64_t *htail_dev = nullptr;                   // its device address
-    uint64_t poll_cursor = 0, released = 0;
-    std::deque<std::pair<uint64_t, uint64_t>> polled;      // (seq, end offset)
-
-    // statistics kept on the host
-    std::atomic<uint64_t> observed_calls{0}, sampled_out_calls{0}, sampled_out_rows{0}, disabled_calls{0},
-        drained_bytes{0}, released_bytes{0}, drain_batches{0}, block_wait_ns{0}, dev_high{0}, host_high{0};
-
-    std::thread bg;
-    std::atomic<bool> stop{false};
-
-    // exporter stages 2-3
-    std::thread exporter;
-    std::atomic<bool> exp_stop{false}, exp_running{false};
-    std::mutex emu;
-    std::condition_variable ecv_data, ecv_space;
-    std::deque<dmi_slice_t> slices;
-    uint64_t exp_bytes = 0, exp_max_bytes = 0, next_emit = 0;
-    std::vector<std::thread> exp_workers;
-    std::mutex jmu;
-    std::condition_variable jcv;
-    std::deque<ExportJob> jobs;
-    std::map<uint64_t, ExportDone> done_jobs;
-    std::atomic<uint64_t> exp_records{0}, exp_copied_bytes{0};
-};
-
-// A replayable step (section 4.4, policy manager): a fixed list of capture launches that
-// take sequence base, step id, tail floor and policy from device memory.
-struct StepTable {                  // one request table, shared by the nodes captured with the same selection
-    std::vector<uint32_t> words;    // as selection_words() lays them out
-    std::vector<dmi_req_sel_t> reqs;
-    bool paged = false;
-    bool row_map = false;           // carries the source row of every listed row behind the table
-    bool dirty = true;              // staged on the host, not yet on the device
-    uint32_t slot = 0;
-};
-
-struct StepNode {
-    CaptureArgs a;
-    Plan pl;
-    Geometry geo;
-    dmi_transform_t xf;
-    uint32_t point_id = 0;
-    uint32_t table = 0;
-    bool index_mode = false, masked = false;
-    uint32_t n_seqs = 0;            // paged: rows of the block table
-};
-
-struct dmi_step {
-    dmi_ring *r = nullptr;
-    uint32_t max_nodes = 0;
-    std::vector<StepNode> nodes;
-    std::vector<StepTable> tables;
-    StepParams *dparams = nullptr;  // device
-    uint32_t *slab = nullptr;       // device: max_nodes table slots
-    bool open = false, sealed = false, begun = false, skipped = false, drop_newest = false;
-    uint64_t sum_ub = 0, sum_listed = 0, seq_base = 0;
-};
-
-namespace {
+namespace dmi {
+namespace host {
 
 void atomic_max(std::atomic<uint64_t> &a, uint64_t v)
 {
@@ -762,145 +547,14 @@ void free_ring(dmi_ring *r)
     delete r;
 }
 
-dmi_status_t poll_host_impl(dmi_ring *r, dmi_record_view_t *out, uint32_t max, uint32_t *n);
-dmi_status_t release_host_impl(dmi_ring *r, uint64_t upto);
 
-// Exporter stage 3 for one record copy: shape / dtype from the header, one slice per request with rows.
-void slice_record(RecordCopy *rc, std::vector<dmi_slice_t> &made)
-{
-    const uint8_t *b = rc->bytes;
-    uint32_t n_reqs, n_rows, row_elems, point_id, rank_tag;
-    uint64_t seq, step_id, payload_bytes;
-    memcpy(&seq, b + 8, 8);
-    memcpy(&step_id, b + 16, 8);
-    memcpy(&point_id, b + 24, 4);
-    memcpy(&n_reqs, b + 32, 4);
-    memcpy(&n_rows, b + 36, 4);
-    memcpy(&row_elems, b + 40, 4);
-    memcpy(&rank_tag, b + 44, 4);
-    memcpy(&payload_bytes, b + 56, 8);
-    const uint32_t src_dtype = b[28], out_dtype = b[29], smask = b[30], flags = b[31];
-    const uint64_t es = dtype_size(out_dtype);
-    const uint8_t *table = b + DMI_HEADER_BYTES;
-    const uint8_t *payload = table + pad64((uint64_t)n_reqs * 16u);
-    const uint8_t *sums = payload + pad64(payload_bytes);
-    const uint64_t sum_arr = pad64((uint64_t)n_rows * 4u);
-    const float *arr[3] = {nullptr, nullptr, nullptr};
-    {
-        const uint8_t *p = sums;
-        for (int bit = 0; bit < 3; bit++)
-            if (smask & (1u << bit)) { arr[bit] = reinterpret_cast<const float *>(p); p += sum_arr; }
-    }
-    uint64_t row0 = 0;
-    for (uint32_t q = 0; q < n_reqs; q++) {
-        uint32_t e[4];
-        memcpy(e, table + 16ull * q, 16);
-        if (e[3] == 0) continue;
-        dmi_slice_t sl;
-        memset(&sl, 0, sizeof sl);
-        sl.seq = seq; sl.step_id = step_id; sl.point_id = point_id; sl.rank_tag = rank_tag;
-        sl.req_index = q; sl.req_id = e[0]; sl.tok_start = e[1]; sl.tok_step = e[2]; sl.n_rows = e[3];
-        sl.row_elems = row_elems; sl.src_dtype = src_dtype; sl.out_dtype = out_dtype;
-        sl.summary_mask = smask; sl.flags = flags;
-        sl.rows = es ? payload + row0 * row_elems * es : nullptr;
-        sl.l2 = arr[0] ? arr[0] + row0 : nullptr;
-        sl.mean = arr[1] ? arr[1] + row0 : nullptr;
-        sl.absmax = arr[2] ? arr[2] + row0 : nullptr;
-        sl.owner = rc;
-        made.push_back(sl);
-        row0 += e[3];
-    }
-}
-
-// Exporter copy worker: takes records (with a ticket in ring order) from the dispatcher,
-// copies each into pageable memory, slices it, and commits the results in ticket order
-// (the pinned space is given back in that order too).
-void exporter_worker(dmi_ring *r)
-{
-    for (;;) {
-        ExportJob job;
-        {
-            std::unique_lock<std::mutex> lk(r->jmu);
-            r->jcv.wait(lk, [&] { return r->exp_stop.load() || !r->jobs.empty(); });
-            if (r->jobs.empty()) return;        // stopping
-            job = r->jobs.front();
-            r->jobs.pop_front();
-        }
-        RecordCopy *rc = new RecordCopy;
-        rc->size = job.view.n0 + job.view.n1;
-        rc->bytes = static_cast<uint8_t *>(malloc(rc->size));
-        while (!rc->bytes) {        // the budget is the caller's promise that this fits; wait for memory
-            std::this_thread::sleep_for(std::chrono::milliseconds(1));
-            rc->bytes = static_cast<uint8_t *>(malloc(rc->size));
-        }
-        memcpy(rc->bytes, job.view.p0, job.view.n0);
-        if (job.view.n1) memcpy(rc->bytes + job.view.n0, job.view.p1, job.view.n1);
-        std::vector<dmi_slice_t> made;
-        slice_record(rc, made);
-        rc->refs.store((uint32_t)made.size());
-        r->exp_records++;
-        r->exp_copied_bytes += rc->size;
-
-        std::lock_guard<std::mutex> lk(r->emu);
-        r->done_jobs.emplace(job.ticket, ExportDone{job.view.seq, rc, std::move(made)});
-        bool any = false;
-        while (!r->done_jobs.empty() && r->done_jobs.begin()->first == r->next_emit) {
-            ExportDone &d = r->done_jobs.begin()->second;
-            (void)release_host_impl(r, d.seq);      // pinned space is free again, in ring order
-            if (d.slices.empty()) {                 // nothing to hand out: the copy goes at once
-                r->exp_bytes -= d.rc->size;
-                free(d.rc->bytes);
-                delete d.rc;
-                r->ecv_space.notify_all();
-            } else {
-                for (auto &sl : d.slices) r->slices.push_back(sl);
-                any = true;
-            }
-            r->done_jobs.erase(r->done_jobs.begin());
-            r->next_emit++;
-        }
-        if (any) r->ecv_data.notify_all();
-    }
-}
-
-// Exporter dispatcher: polls whole records out of the pinned ring and hands them to the
-// copy workers, bounded by the pageable budget (this is where back-pressure starts).
-void exporter_loop(dmi_ring *r)
-{
-    (void)hipSetDevice(r->dev);
-    dmi_record_view_t views[64];
-    uint64_t ticket = 0;
-    while (!r->exp_stop.load(std::memory_order_acquire)) {
-        uint32_t n = 0;
-        if (poll_host_impl(r, views, 64, &n) != DMI_OK || n == 0) {
-            std::this_thread::sleep_for(std::chrono::microseconds(50));
-            continue;
-        }
-        for (uint32_t i = 0; i < n; i++) {
-            const uint64_t size = views[i].n0 + views[i].n1;
-            {
-                std::unique_lock<std::mutex> lk(r->emu);
-                r->ecv_space.wait(lk, [&] {
-                    return r->exp_stop.load() || r->exp_bytes == 0 || r->exp_bytes + size <= r->exp_max_bytes;
-                });
-                if (r->exp_stop.load()) return;
-                r->exp_bytes += size;
-            }
-            {
-                std::lock_guard<std::mutex> lk(r->jmu);
-                r->jobs.push_back(ExportJob{views[i], ticket++});
-            }
-            r->jcv.notify_one();
-        }
-    }
-}
-
-}  // namespace
+}  // namespace host
+}  // namespace dmi
 
 // =========================================================================== C ABI
 extern "C" {
 
-const char *dmi_last_error(void) { return g_err.c_str(); }
+const char *dmi_last_error(void) { return last_error_cstr(); }
 const char *dmi_version(void) { return "dmi-ring 0.1 (gfx950)"; }
 
 uint64_t dmi_record_bytes(uint32_t n_reqs, uint64_t n_rows, uint32_t row_elems, uint32_t out_dtype,
@@ -1004,7 +658,8 @@ dmi_status_t dmi_ring_destroy(dmi_ring_t *r)
 
 }  // extern "C"
 
-namespace {
+namespace dmi {
+namespace host {
 
 // Checks of a selection against a dense source of T rows (not in index mode, where the
 // kernel checks every index itself).
@@ -1105,7 +760,8 @@ dmi_status_t prep_paged(const dmi_paged_kv_t *kv, const dmi_selection_t *sel, Ge
     return DMI_OK;
 }
 
-}  // namespace
+}  // namespace host
+}  // namespace dmi
 
 extern "C" {
 
@@ -1134,334 +790,6 @@ dmi_status_t dmi_observe_paged(dmi_ring_t *r, uint32_t point_id, const dmi_paged
     if ((g = prep_paged(kv, sel, geo, a)) != DMI_OK) return g;
     (void)hipSetDevice(r->dev);
     return observe_common(r, point_id, sel, xf, step_id, hip_stream, geo, a);
-}
-
-// ------------------------------------------------------------------ replayable steps
-dmi_status_t dmi_step_create(dmi_ring_t *r, uint32_t max_observes, dmi_step_t **out)
-{
-    if (!r || !out) return fail(DMI_ERR_INVALID_ARG, "NULL argument");
-    if (max_observes < 1u || max_observes > DMI_STEP_MAX_OBSERVES)
-        return fail(DMI_ERR_INVALID_ARG, "max_observes must be 1..%u", DMI_STEP_MAX_OBSERVES);
-    (void)hipSetDevice(r->dev);
-    dmi_step *st = new (std::nothrow) dmi_step;
-    if (!st) return fail(DMI_ERR_NOMEM, "out of host memory");
-    st->r = r;
-    st->max_nodes = max_observes;
-    hipError_t e = hipMalloc((void **)&st->dparams, sizeof(StepParams));
-    if (e == hipSuccess) e = hipMalloc((void **)&st->slab, (size_t)max_observes * r->slab_slot_words * 4u);
-    // a first launch out of this library, so that none of its code is loaded under a capture
-    StepParams zero;
-    memset(&zero, 0, sizeof zero);
-    if (e == hipSuccess) e = launch_step_begin(r->dctrl, st->dparams, zero, 0u, 0u, nullptr, r->ctl_stream);
-    if (e == hipSuccess) e = hipStreamSynchronize(r->ctl_stream);
-    if (e != hipSuccess) {
-        if (st->dparams) (void)hipFree(st->dparams);
-        if (st->slab) (void)hipFree(st->slab);
-        delete st;
-        return fail(DMI_ERR_HIP, "step setup failed: %s", hipGetErrorString(e));
-    }
-    *out = st;
-    return DMI_OK;
-}
-
-dmi_status_t dmi_step_destroy(dmi_step_t *st)
-{
-    if (!st) return fail(DMI_ERR_INVALID_ARG, "step is NULL");
-    if (st->open) st->r->quiet.store(0, std::memory_order_release);
-    if (st->begun) st->r->step_open = false;
-    (void)hipSetDevice(st->r->dev);
-    (void)hipFree(st->dparams);
-    (void)hipFree(st->slab);
-    delete st;
-    return DMI_OK;
-}
-
-dmi_status_t dmi_step_capture_begin(dmi_step_t *st)
-{
-    if (!st) return fail(DMI_ERR_INVALID_ARG, "step is NULL");
-    if (st->open || st->sealed) return fail(DMI_ERR_INVALID_ARG, "the step is already open or sealed");
-    dmi_ring *r = st->r;
-    // the caller is about to capture a stream: the library's own threads must keep away from
-    // the HIP API until dmi_step_seal (some of their calls would invalidate the capture)
-    r->quiet.store(1, std::memory_order_release);
-    if (r->bg.joinable()) {
-        const uint64_t t0 = now_ns();
-        while (!r->bg_parked.load(std::memory_order_acquire)) {
-            if (now_ns() - t0 > 2000000000ull) {
-                r->quiet.store(0, std::memory_order_release);
-                return fail(DMI_ERR_AGAIN, "the drain thread did not pause");
-            }
-            std::this_thread::sleep_for(std::chrono::microseconds(50));
-        }
-    }
-    st->open = true;
-    return DMI_OK;
-}
-
-}  // extern "C"
-
-namespace {
-
-// Add one launch to an open step and issue it on the capturing stream.  The only HIP
-// calls made here are the capture-status query and the kernel launch.
-dmi_status_t step_add(dmi_step *st, uint32_t point_id, const dmi_selection_t *sel, const dmi_transform_t *xf,
-                      const Geometry &geo, CaptureArgs &a, uint32_t n_seqs, void *hip_stream, uint32_t *node_out)
-{
-    dmi_ring *r = st->r;
-    if (st->nodes.size() >= st->max_nodes)
-        return fail(DMI_ERR_INVALID_ARG, "the step holds max_observes (%u) launches already", st->max_nodes);
-    // outside a capture the launch would run at once, with whatever the parameter block holds
-    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
-    if (hipStreamIsCapturing((hipStream_t)hip_stream, &cs) != hipSuccess || cs != hipStreamCaptureStatusActive)
-        return fail(DMI_ERR_INVALID_ARG, "hip_stream is not capturing");
-    StepNode nd;
-    dmi_status_t rc = plan_capture(r, point_id, sel, xf, geo, a, nd.pl, false);
-    if (rc != DMI_OK) return rc;
-
-    // nodes captured with the same selection share one table (and are updated together)
-    std::vector<uint32_t> words;
-    selection_words(sel->reqs, sel->n_reqs, a.paged != 0, nd.pl.row_map, words);
-    uint32_t ti = 0;
-    for (; ti < st->tables.size(); ti++)
-        if (st->tables[ti].paged == (a.paged != 0) && st->tables[ti].row_map == nd.pl.row_map &&
-            st->tables[ti].words == words) break;
-    if (ti == st->tables.size()) {
-        StepTable t;
-        t.words.swap(words);
-        t.reqs.assign(sel->reqs, sel->reqs + sel->n_reqs);
-        t.paged = a.paged != 0;
-        t.row_map = nd.pl.row_map;
-        t.slot = ti;                // at most one table per node, so slots suffice
-        st->tables.push_back(std::move(t));
-    }
-    const uint32_t node = (uint32_t)st->nodes.size();
-    uint32_t *slot = st->slab + (size_t)st->tables[ti].slot * r->slab_slot_words;
-    a.req_table = reinterpret_cast<const uint4 *>(slot);
-    a.row0 = slot + 4u * (size_t)sel->n_reqs;
-    a.row_map = nd.pl.row_map ? a.row0 + sel->n_reqs : nullptr;
-    a.seq = 0;
-    a.step_id = 0;
-    a.cslot = nullptr;
-    a.tail_floor = 0;
-    a.drop_newest = 0;
-    a.tail_src = nullptr;           // the device copy that the step's begin launch refreshes
-    a.par_in = node & 1u;           // dmi_step_begin leaves head and tail in copy 0
-    a.step = st->dparams;
-    a.node = node;
-    const hipError_t e = nd.pl.decode ? launch_capture_decode(a, (hipStream_t)hip_stream)
-                                      : launch_capture(a, nd.pl.grid, geo.vec16, (hipStream_t)hip_stream);
-    if (e != hipSuccess) return fail(DMI_ERR_HIP, "capture launch failed: %s", hipGetErrorString(e));
-    nd.a = a;
-    nd.geo = geo;
-    nd.xf = *xf;
-    nd.point_id = point_id;
-    nd.table = ti;
-    nd.index_mode = sel->row_index_dev != nullptr;
-    nd.masked = sel->keep_mask_dev != nullptr;
-    nd.n_seqs = n_seqs;
-    st->nodes.push_back(nd);
-    if (node_out) *node_out = node;
-    return DMI_OK;
-}
-
-// Front checks of dmi_step_observe*: state, arguments, hook filtering (a disabled point
-// adds no launch to the step: it is not in the graph at all).
-dmi_status_t step_gate(dmi_step *st, uint32_t point_id, const dmi_selection_t *sel, const dmi_transform_t *xf,
-                       uint32_t src_dtype)
-{
-    if (!st) return fail(DMI_ERR_INVALID_ARG, "step is NULL");
-    if (!st->open) return fail(DMI_ERR_INVALID_ARG, "call dmi_step_capture_begin first");
-    dmi_ring *r = st->r;
-    if (!sel || !xf) return fail(DMI_ERR_INVALID_ARG, "selection / transform is NULL");
-    if (point_id >= DMI_MAX_POINTS) return fail(DMI_ERR_INVALID_ARG, "point_id %u >= %u", point_id, DMI_MAX_POINTS);
-    if (sel->n_reqs > r->max_reqs)
-        return fail(DMI_ERR_INVALID_ARG, "n_reqs %u exceeds max_reqs_per_observe %u", sel->n_reqs, r->max_reqs);
-    if (sel->n_reqs && !sel->reqs) return fail(DMI_ERR_INVALID_ARG, "reqs is NULL");
-    if (!transform_ok(src_dtype, xf->out_dtype))
-        return fail(DMI_ERR_INVALID_ARG, "unsupported dtype pair %u -> %u", src_dtype, xf->out_dtype);
-    if (xf->summary_mask & ~7u) return fail(DMI_ERR_INVALID_ARG, "bad summary_mask %u", xf->summary_mask);
-    if (r->point_off[point_id]) return DMI_POINT_DISABLED;
-    return DMI_OK;
-}
-
-}  // namespace
-
-extern "C" {
-
-dmi_status_t dmi_step_observe(dmi_step_t *st, uint32_t point_id, const dmi_tensor_t *t, const dmi_selection_t *sel,
-                              const dmi_transform_t *xf, void *hip_stream, uint32_t *node)
-{
-    if (!t) return fail(DMI_ERR_INVALID_ARG, "tensor is NULL");
-    dmi_status_t g = step_gate(st, point_id, sel, xf, t->dtype);
-    if (g != DMI_OK) return g;
-    Geometry geo;
-    CaptureArgs a;
-    if ((g = prep_dense(t, sel, geo, a)) != DMI_OK) return g;
-    return step_add(st, point_id, sel, xf, geo, a, 0u, hip_stream, node);
-}
-
-dmi_status_t dmi_step_observe_paged(dmi_step_t *st, uint32_t point_id, const dmi_paged_kv_t *kv,
-                                    const dmi_selection_t *sel, const dmi_transform_t *xf, void *hip_stream,
-                                    uint32_t *node)
-{
-    if (!kv) return fail(DMI_ERR_INVALID_ARG, "kv is NULL");
-    dmi_status_t g = step_gate(st, point_id, sel, xf, kv->dtype);
-    if (g != DMI_OK) return g;
-    Geometry geo;
-    CaptureArgs a;
-    if ((g = prep_paged(kv, sel, geo, a)) != DMI_OK) return g;
-    return step_add(st, point_id, sel, xf, geo, a, kv->n_seqs, hip_stream, node);
-}
-
-dmi_status_t dmi_step_seal(dmi_step_t *st)
-{
-    if (!st) return fail(DMI_ERR_INVALID_ARG, "step is NULL");
-    if (!st->open) return fail(DMI_ERR_INVALID_ARG, "the step is not open");
-    st->open = false;
-    st->sealed = true;
-    st->sum_ub = st->sum_listed = 0;
-    for (auto &nd : st->nodes) { st->sum_ub += nd.pl.ub; st->sum_listed += nd.pl.listed; }
-    st->r->quiet.store(0, std::memory_order_release);
-    return DMI_OK;
-}
-
-dmi_status_t dmi_step_update(dmi_step_t *st, uint32_t node, const dmi_req_sel_t *reqs, uint32_t n_reqs)
-{
-    if (!st || !reqs) return fail(DMI_ERR_INVALID_ARG, "NULL argument");
-    if (!st->sealed) return fail(DMI_ERR_INVALID_ARG, "the step is not sealed");
-    if (st->begun) return fail(DMI_ERR_INVALID_ARG, "between dmi_step_begin and dmi_step_end");
-    if (node >= st->nodes.size()) return fail(DMI_ERR_INVALID_ARG, "no node %u", node);
-    dmi_ring *r = st->r;
-    const uint32_t ti = st->nodes[node].table;
-    StepTable &tab = st->tables[ti];
-    if (n_reqs != tab.reqs.size())
-        return fail(DMI_ERR_INVALID_ARG, "the node was captured with %zu requests, not %u", tab.reqs.size(), n_reqs);
-    uint64_t listed = 0;
-    bool all_one = true;
-    for (uint32_t i = 0; i < n_reqs; i++) { listed += reqs[i].tok_count; all_one = all_one && reqs[i].tok_count == 1u; }
-    // every launch that reads this table must still be the launch that was captured
-    std::vector<uint64_t> ubs;
-    for (auto &nd : st->nodes) {
-        if (nd.table != ti) continue;
-        const CaptureArgs &a = nd.a;
-        dmi_status_t rc = DMI_OK;
-        if (a.paged) rc = check_paged_rows(reqs, n_reqs, nd.n_seqs, a.block_size, a.bt_stride);
-        else if (!nd.index_mode) rc = check_dense_rows(reqs, n_reqs, a.n_src_rows);
-        if (rc != DMI_OK) return rc;
-        if ((a.simple || nd.pl.decode) && !all_one)
-            return fail(DMI_ERR_INVALID_ARG, "captured with one row per request: capture the step again to change that");
-        if (nd.pl.decode && a.rows_consecutive)
-            for (uint32_t i = 0; i < n_reqs; i++)
-                if (reqs[i].row_base + reqs[i].tok_start != a.row_first + i)
-                    return fail(DMI_ERR_INVALID_ARG, "captured with request i in row %u + i: capture the step again "
-                                                     "to change that", a.row_first);
-        if (listed > 0xFFFFFFFFull || listed * a.units_per_row > 0xFFFFFFFFull)
-            return fail(DMI_ERR_TOO_LARGE, "selection of %llu rows exceeds one record", (unsigned long long)listed);
-        const uint64_t ub = dmi_record_bytes(n_reqs, listed, nd.geo.row_elems, nd.xf.out_dtype, nd.xf.summary_mask);
-        if (ub > r->dev_cap)
-            return fail(DMI_ERR_TOO_LARGE, "record of %llu bytes exceeds the device ring (%llu)",
-                        (unsigned long long)ub, (unsigned long long)r->dev_cap);
-        ubs.push_back(ub);
-    }
-    size_t k = 0;
-    for (auto &nd : st->nodes) {
-        if (nd.table != ti) continue;
-        st->sum_ub += ubs[k] - nd.pl.ub;
-        st->sum_listed += listed - nd.pl.listed;
-        nd.pl.ub = ubs[k++];
-        nd.pl.listed = listed;
-    }
-    tab.reqs.assign(reqs, reqs + n_reqs);
-    selection_words(reqs, n_reqs, tab.paged, tab.row_map, tab.words);
-    tab.dirty = true;
-    return DMI_OK;
-}
-
-dmi_status_t dmi_step_begin(dmi_step_t *st, uint64_t step_id, void *hip_stream)
-{
-    if (!st) return fail(DMI_ERR_INVALID_ARG, "step is NULL");
-    if (!st->sealed) return fail(DMI_ERR_INVALID_ARG, "the step is not sealed");
-    dmi_ring *r = st->r;
-    if (st->begun || r->step_open) return fail(DMI_ERR_INVALID_ARG, "a step is already between begin and end");
-    (void)hipSetDevice(r->dev);
-    hipStream_t s = (hipStream_t)hip_stream;
-    const uint32_t n = (uint32_t)st->nodes.size();
-    const uint32_t mode = r->mode.load(std::memory_order_relaxed);
-    const uint32_t k = r->sample_k.load(std::memory_order_relaxed);
-    const bool skip = step_id % k != r->sample_phase.load(std::memory_order_relaxed);
-    dmi_status_t rc;
-    r->last_stream.store(hip_stream, std::memory_order_release);
-    if (!skip && n) {
-        if (mode == DMI_POLICY_BLOCK) {
-            // the flush before the forward step: the whole step must be sure to fit
-            if (st->sum_ub > r->dev_cap)
-                return fail(DMI_ERR_TOO_LARGE, "the step's records (%llu bytes) exceed the device ring (%llu): "
-                            "launches inside a graph cannot wait for the drain",
-                            (unsigned long long)st->sum_ub, (unsigned long long)r->dev_cap);
-            if ((rc = wait_for_room(r, st->sum_ub)) != DMI_OK) return rc;
-        } else {
-            head_upper_bound(r);
-        }
-        if ((rc = commit_slot_room(r, n)) != DMI_OK) return rc;
-    }
-    for (auto &t : st->tables) {
-        if (!t.dirty) continue;
-        if (!t.words.empty())
-            HIP_TRY(launch_upload(st->slab + (size_t)t.slot * r->slab_slot_words, t.words.data(),
-                                  (uint32_t)t.words.size(), s));
-        t.dirty = false;
-    }
-    StepParams v;
-    v.seq_base = r->next_seq.load(std::memory_order_relaxed);
-    v.step_id = step_id;
-    v.tail_floor = r->drain_done.load(std::memory_order_acquire);
-    v.flags = (mode == DMI_POLICY_DROP_NEWEST ? kStepDropNewest : 0u) | (skip ? kStepSkip : 0u);
-    v.pad = 0;
-    HIP_TRY(launch_step_begin(r->dctrl, st->dparams, v, r->chain_par, 0u,
-                              mode == DMI_POLICY_DROP_NEWEST ? r->htail_dev : nullptr, s));
-    r->chain_par = 0;
-    st->seq_base = v.seq_base;
-    st->skipped = skip;
-    st->drop_newest = mode == DMI_POLICY_DROP_NEWEST;
-    st->begun = true;
-    r->step_open = true;
-    r->observed_calls += n;
-    if (skip) {
-        r->sampled_out_calls += n;
-        r->sampled_out_rows += st->sum_listed;
-        return DMI_SAMPLED_OUT;
-    }
-    return DMI_OK;
-}
-
-dmi_status_t dmi_step_end(dmi_step_t *st, void *hip_stream)
-{
-    if (!st) return fail(DMI_ERR_INVALID_ARG, "step is NULL");
-    if (!st->begun) return fail(DMI_ERR_INVALID_ARG, "dmi_step_begin has not been called");
-    dmi_ring *r = st->r;
-    (void)hipSetDevice(r->dev);
-    const uint32_t n = (uint32_t)st->nodes.size();
-    st->begun = false;
-    r->step_open = false;
-    r->chain_par = n & 1u;
-    r->last_launch_ns.store(now_ns(), std::memory_order_relaxed);
-    r->last_stream.store(hip_stream, std::memory_order_release);
-    if (st->skipped || !n) return DMI_OK;
-    for (uint32_t i = 0; i < n; i++) {
-        r->inflight.emplace_back(st->seq_base + i, st->nodes[i].pl.ub);
-        r->inflight_sum += st->nodes[i].pl.ub;
-    }
-    {
-        std::lock_guard<std::mutex> lk(r->pmu);
-        r->next_seq.store(st->seq_base + n, std::memory_order_release);
-        for (auto &nd : st->nodes) {
-            if (st->drop_newest || nd.masked) { r->window_exact = false; break; }
-            r->window.bytes += nd.pl.ub; r->window.records += 1; r->window.rows += nd.pl.listed;
-        }
-    }
-    r->unprobed_launches = 0;
-    r->unprobed_bytes = 0;
-    return record_probe(r);
 }
 
 dmi_status_t dmi_drain(dmi_ring_t *r, uint32_t flags, uint64_t *bytes_moved)
@@ -1517,7 +845,8 @@ dmi_status_t dmi_poll_host(dmi_ring_t *r, dmi_record_view_t *out, uint32_t max, 
 
 }  // extern "C"
 
-namespace {
+namespace dmi {
+namespace host {
 dmi_status_t poll_host_impl(dmi_ring *r, dmi_record_view_t *out, uint32_t max, uint32_t *n)
 {
     *n = 0;
@@ -1564,7 +893,8 @@ dmi_status_t release_host_impl(dmi_ring *r, uint64_t upto)
     }
     return DMI_OK;
 }
-}  // namespace
+}  // namespace host
+}  // namespace dmi
 
 extern "C" {
 
@@ -1573,112 +903,6 @@ dmi_status_t dmi_release_host(dmi_ring_t *r, uint64_t upto)
     if (!r) return fail(DMI_ERR_INVALID_ARG, "ring is NULL");
     if (r->exp_running.load()) return fail(DMI_ERR_INVALID_ARG, "the exporter is this ring's consumer");
     return release_host_impl(r, upto);
-}
-
-dmi_status_t dmi_exporter_start(dmi_ring_t *r, uint64_t max_pageable_bytes, uint32_t n_copy_threads)
-{
-    if (!r || !max_pageable_bytes || n_copy_threads > 16u) return fail(DMI_ERR_INVALID_ARG, "bad argument");
-    if (r->exp_running.exchange(true)) return fail(DMI_ERR_INVALID_ARG, "exporter already running");
-    r->exp_stop.store(false);
-    r->exp_max_bytes = max_pageable_bytes;
-    r->next_emit = 0;
-    const uint32_t n = n_copy_threads ? n_copy_threads : 3u;
-    for (uint32_t i = 0; i < n; i++) r->exp_workers.emplace_back(exporter_worker, r);
-    r->exporter = std::thread(exporter_loop, r);
-    return DMI_OK;
-}
-
-dmi_status_t dmi_exporter_next(dmi_ring_t *r, dmi_slice_t *out, uint32_t timeout_ms)
-{
-    if (!r || !out) return fail(DMI_ERR_INVALID_ARG, "NULL argument");
-    std::unique_lock<std::mutex> lk(r->emu);
-    if (!r->ecv_data.wait_for(lk, std::chrono::milliseconds(timeout_ms), [&] { return !r->slices.empty(); }))
-        return fail(DMI_ERR_AGAIN, "no slice within %u ms", timeout_ms);
-    *out = r->slices.front();
-    r->slices.pop_front();
-    return DMI_OK;
-}
-
-dmi_status_t dmi_exporter_next_many(dmi_ring_t *r, dmi_slice_t *out, uint32_t max, uint32_t *n, uint32_t timeout_ms)
-{
-    if (!r || !n || (max && !out)) return fail(DMI_ERR_INVALID_ARG, "NULL argument");
-    *n = 0;
-    std::unique_lock<std::mutex> lk(r->emu);
-    if (!r->ecv_data.wait_for(lk, std::chrono::milliseconds(timeout_ms), [&] { return !r->slices.empty(); }))
-        return fail(DMI_ERR_AGAIN, "no slice within %u ms", timeout_ms);
-    while (*n < max && !r->slices.empty()) {
-        out[(*n)++] = r->slices.front();
-        r->slices.pop_front();
-    }
-    return DMI_OK;
-}
-
-dmi_status_t dmi_exporter_release_many(dmi_ring_t *r, const dmi_slice_t *sl, uint32_t n)
-{
-    if (!r || (n && !sl)) return fail(DMI_ERR_INVALID_ARG, "NULL argument");
-    for (uint32_t i = 0; i < n; i++) {
-        dmi_status_t st = dmi_exporter_release(r, &sl[i]);
-        if (st != DMI_OK) return st;
-    }
-    return DMI_OK;
-}
-
-dmi_status_t dmi_exporter_release(dmi_ring_t *r, const dmi_slice_t *sl)
-{
-    if (!r || !sl || !sl->owner) return fail(DMI_ERR_INVALID_ARG, "NULL argument");
-    RecordCopy *rc = static_cast<RecordCopy *>(sl->owner);
-    if (rc->refs.fetch_sub(1) == 1) {
-        {
-            std::lock_guard<std::mutex> lk(r->emu);
-            r->exp_bytes -= rc->size;
-        }
-        r->ecv_space.notify_all();
-        free(rc->bytes);
-        delete rc;
-    }
-    return DMI_OK;
-}
-
-dmi_status_t dmi_exporter_stop(dmi_ring_t *r)
-{
-    if (!r) return fail(DMI_ERR_INVALID_ARG, "ring is NULL");
-    if (!r->exp_running.load()) return DMI_OK;
-    {   // set under the lock the dispatcher evaluates its wait condition under
-        std::lock_guard<std::mutex> lk(r->emu);
-        r->exp_stop.store(true);
-    }
-    r->ecv_space.notify_all();
-    if (r->exporter.joinable()) r->exporter.join();
-    uint64_t dropped = 0;       // pageable budget booked for records no worker will copy
-    {
-        std::lock_guard<std::mutex> lk(r->jmu);
-        for (auto &j : r->jobs) dropped += j.view.n0 + j.view.n1;
-        r->jobs.clear();
-    }
-    r->jcv.notify_all();
-    for (auto &w : r->exp_workers) if (w.joinable()) w.join();
-    r->exp_workers.clear();
-    {   // discard what was not handed out
-        std::lock_guard<std::mutex> lk(r->emu);
-        r->exp_bytes -= dropped;
-        for (auto &kv : r->done_jobs) {
-            if (kv.second.slices.empty()) {
-                r->exp_bytes -= kv.second.rc->size;
-                free(kv.second.rc->bytes);
-                delete kv.second.rc;
-            } else {
-                for (auto &sl : kv.second.slices) r->slices.push_back(sl);
-            }
-        }
-        r->done_jobs.clear();
-        for (auto &sl : r->slices) {
-            RecordCopy *rc = static_cast<RecordCopy *>(sl.owner);
-            if (rc->refs.fetch_sub(1) == 1) { r->exp_bytes -= rc->size; free(rc->bytes); delete rc; }
-        }
-        r->slices.clear();
-    }
-    r->exp_running.store(false);
-    return DMI_OK;
 }
 
 dmi_status_t dmi_set_policy(dmi_ring_t *r, const dmi_policy_t *p)
