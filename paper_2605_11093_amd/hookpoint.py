@@ -13,6 +13,7 @@ kernels; StepContext.begin_replay / end_replay bracket each replay of that graph
 """
 from __future__ import annotations
 
+import weakref
 from typing import Dict, Iterable, Optional
 
 import numpy as np
@@ -91,7 +92,8 @@ class StepContext:
 # ordinary node of its graph instead of breaking at a Python callback.  The operator is
 # declared as writing its input (it writes nothing): that keeps compilers from dropping a
 # call whose result nobody uses, and from moving it across other uses of the tensor.
-_HOOKS: Dict[int, "HookPoint"] = {}
+_HOOKS: "weakref.WeakValueDictionary[int, HookPoint]" = weakref.WeakValueDictionary()
+_next_hook_id = 0
 _op_registered = False
 
 
@@ -116,7 +118,9 @@ class HookPoint(nn.Module):
         self.ring, self.point_id, self.ctx = ring, int(point_id), ctx
         self.out_dtype, self.summary_mask, self.enabled, self.hook_name = out_dtype, summary_mask, enabled, name
         _register_op()
-        self._hook_id = len(_HOOKS) + 1
+        global _next_hook_id
+        _next_hook_id += 1
+        self._hook_id = _next_hook_id
         _HOOKS[self._hook_id] = self
 
     def forward(self, x: torch.Tensor) -> torch.Tensor:
