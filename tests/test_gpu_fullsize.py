@@ -1,4 +1,4 @@
-"""Parity at the benchmark's full shapes, ring sizes and policies, in the launch
+"""Parity at the full shapes, ring sizes and policies of the five benchmark configurations, in the launch
 configuration bench.py times (asynchronous: non-blocking drains issued by the
 producer thread, or the library's drain thread).  The oracle cannot build these
 streams whole in seconds, so: every record's header is checked against what the
