@@ -13,16 +13,22 @@
 //   * downcasts and fp32 row summaries happen in the same pass, summaries by
 //     wavefront shuffles (no matrix cores: nothing here is a contraction);
 //   * the record's place in the ring comes from a device-resident head, and the
-//     drop-newest decision from a device-resident tail, both double buffered by
-//     launch parity: every workgroup reads the same values with no atomic and no
-//     workgroup has to be "the last one" (a compare-and-swap on one word from a
-//     thousand workgroups measured 7 us here);
+//     drop-newest decision from the drained mark as an earlier launch read it from a
+//     word the host keeps current, both double buffered along the chain of launches:
+//     every workgroup reads the same values with no atomic and no workgroup has to be
+//     "the last one" (a compare-and-swap on one word from a thousand workgroups
+//     measured 7 us here);
 //   * there is no fence and no completion counter in the kernel: on this GPU a
 //     device-scope fence writes back a whole L2, once per wavefront that issues it
 //     (measured: 19 us for a 64-workgroup capture, 300 us for 2048 workgroups).
 //     Workgroup 0 writes where the head stands into this launch's commit slot in
 //     device memory, and the host fetches a slot only behind an event recorded after
-//     the launch (the kernel-end release makes payload and slot visible).
+//     the launch (the kernel-end release makes payload and slot visible);
+//   * a small capture is a chain of dependent trips to memory and little else, so every
+//     kernel here fetches its argument lines, its control words and its first rows in
+//     as few trips as their dependencies allow (see touch_argument_lines, fetch_control,
+//     lds_barrier), and the common small shapes have a short straight-line kernel of
+//     their own (capture_decode_kernel).
 #include "dmi_internal.h"
 
 #include <hip/hip_fp16.h>
