@@ -817,15 +817,18 @@ dmi_status_t dmi_drain(dmi_ring_t *r, uint32_t flags, uint64_t *bytes_moved)
     for (;;) {
         if ((st = advance_commits(r, false)) != DMI_OK) return st;
         const uint64_t done = r->confirmed.load(std::memory_order_acquire);
-        uint64_t moved = 0, left;
+        uint64_t moved = 0, left, in_flight;
         if ((st = drain(r, true, &moved)) != DMI_OK) return st;
         {
             std::lock_guard<std::mutex> lk(r->mu);
             left = read_committed(r) - r->drain_issued;
+            // the drain thread may have issued a batch after the wait above began
+            in_flight = r->drain_issued - r->drain_done.load(std::memory_order_relaxed);
         }
         total += moved;
         if (bytes_moved) *bytes_moved = total;
-        if (done >= want_seq && left == 0) return DMI_OK;
+        if (done >= want_seq && left == 0 && in_flight == 0) return DMI_OK;
+        if (done >= want_seq && left == 0) continue;        // wait for that batch too
         if (done >= want_seq && moved == 0)
             return fail(DMI_ERR_AGAIN, "host ring is full: release records and drain again");
         if (moved == 0) {

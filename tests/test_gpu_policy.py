@@ -262,3 +262,37 @@ def test_commit_accounting_across_policy_and_mask_changes(B, flags_name):
         st = ring.get_stats()
         assert (st.captured_records, st.captured_rows, st.captured_bytes, st.dropped_records) == \
             (ref.stats.captured_records, ref.stats.captured_rows, ref.stats.captured_bytes, 0)
+
+
+def test_flush_waits_for_batches_the_drain_thread_issued(B):
+    """dmi_drain(FLUSH) returning DMI_OK means every record captured so far can be polled,
+    also when the library's drain thread issued the last copy while the flush was waiting
+    for an earlier one."""
+    wl = configs.config2_decode8b(device=DEV, n_points=16, n_steps=4)
+    calls = [wl.step_calls(s) for s in range(4)]
+    from paper_2605_11093_amd import PreparedObserve
+    with B.Ring(256 << 20, 1 << 30, flags=B.BG_THREAD, max_reqs_per_observe=256, block_timeout_ms=2000) as ring:
+        s = torch.cuda.current_stream()
+        pos = [[PreparedObserve(ring, c.point_id, c.tensor, c.reqs, out_dtype=c.out_dtype, summary_mask=c.summary_mask)
+                for c in calls[k]] for k in range(4)]
+
+        def consume():
+            while True:
+                k, views = ring.poll_host_raw()
+                if not k:
+                    return
+                ring.release_host(views[k - 1].seq)
+
+        for trial in range(12):
+            for step in range(48):
+                for po in pos[step % 4]:
+                    assert po(step, s.cuda_stream) == B.OK
+                consume()
+            s.synchronize()
+            while True:
+                ring.drain(B.DRAIN_FLUSH, allow=(B.ERR_AGAIN,))
+                consume()
+                if ring.last_drain_status == B.OK:
+                    break
+            st = ring.get_stats()
+            assert st.released_bytes == st.captured_bytes == st.drained_bytes, (trial, st)
