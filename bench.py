@@ -633,15 +633,26 @@ def main():
                              "overhead_pct": round((dt / n_steps5 - base5) / base5 * 100, 2)}
             log(f"config 5 saturation k={k}: {sat[f'k={k}']}")
         # The same overload met request by request (the paper's best-effort policy, drop-recent):
-        # before every step a policy manager on the host sizes a keep vector to what the ring can
-        # take (an eighth of the room it is sure to have), most recently admitted requests out first;
+        # before every step a policy manager on the host sizes a keep vector to what the host link
+        # takes in one step (95 % of the measured pinned D2H rate over the step time; halved while
+        # the ring's guaranteed room is under a quarter), most recently admitted requests out first;
         # the capture kernels gather only the kept requests.  Whole records should no longer drop.
         r5.set_policy(B.POLICY_DROP_NEWEST, 1, 0)
         settle(r5)
         n_r5 = calls5[0][0].reqs.shape[0]
-        keep_bufs = [torch.ones(n_r5, dtype=torch.uint8, device=dev) for _ in range(4)]
-        p5m = [[[dmi.PreparedObserve(r5, c.point_id, c.tensor, c.reqs, keep_mask=kb) for c in calls5[slot]]
-                for slot in range(4)] for kb in keep_bufs]
+        class _Ptr:                     # a device address where PreparedObserve expects a tensor
+            def __init__(self, p):
+                self.p = p
+
+            def data_ptr(self):
+                return self.p
+
+        ones5 = np.ones(n_r5, dtype=np.uint8)
+        p5m = {}
+        for _ in range(4):              # the library rotates over four keep-vector buffers
+            ptr = r5.set_keep_mask(ones5, sh)
+            p5m[ptr] = [[dmi.PreparedObserve(r5, c.point_id, c.tensor, c.reqs, keep_mask=_Ptr(ptr))
+                         for c in calls5[slot]] for slot in range(4)]
         req_info = [(int(q[0]), 1, i, 0) for i, q in enumerate(calls5[0][0].reqs)]
         row_bytes5 = 8192 * 2
         a0 = r5.get_stats()
@@ -649,13 +660,15 @@ def main():
         torch.cuda.synchronize()
         t = time.perf_counter()
         for s5 in range(n_steps5):
-            budget = r5.free_bytes() // 8 // n_l
+            budget = int(0.95 * d2h_peak * 1e9 * base5 * 1.08) // n_l
+            if r5.free_bytes() < w5.device_ring_bytes // 4:
+                budget //= 2
             keep = B.policy_select(B.SELECT_DROP_RECENT, req_info, row_bytes5, max(0, budget - 4160))
             kept_sum += int(keep.sum())
-            keep_bufs[s5 % 4].copy_(torch.from_numpy(keep), non_blocking=True)
+            step_obs = p5m[r5.set_keep_mask(keep, sh)][s5 % 4]
             for l5 in range(n_l):
                 bench_lib.dmi_bench_stream_gemv(weights5[l5].data_ptr(), n_w5, xv.data_ptr(), ac.data_ptr(), sh)
-                rc = p5m[s5 % 4][s5 % 4][l5](5000 + s5, sh)
+                rc = step_obs[l5](5000 + s5, sh)
                 if rc < 0:
                     raise dmi.DmiError(rc, dmi.lib().dmi_last_error().decode())
             consume(r5)
@@ -672,7 +685,7 @@ def main():
             "overhead_pct": round((dt / n_steps5 - base5) / base5 * 100, 2)}
         log(f"config 5 saturation, request-granular best effort: {sat['request_granular_drop_recent']}")
         r5.destroy()
-        del weights5, p5m, keep_bufs
+        del weights5, p5m
         torch.cuda.empty_cache()
         extra["config5_saturation"] = {"no_capture_ms_per_step": round(base5 * 1e3, 3), "steps": n_steps5,
                                        "interfering_workload": "80 x 219 MB bf16 weight-streaming GEMV per step",

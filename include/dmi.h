@@ -319,8 +319,12 @@ dmi_status_t dmi_ring_free_bytes(dmi_ring_t *ring, uint64_t *free_bytes /*[host]
 /* Copy a keep vector into a library-owned device buffer, ordered on hip_stream before any
  * later work of that stream.  *keep_mask_dev [device] may be passed as
  * dmi_selection_t::keep_mask_dev by observes issued on the same stream; it stays valid for
- * the next three calls of this function.  Updating the vector between steps does not
- * change what is launched, only what the launches copy (section 4.4). */
+ * the next three calls of this function (an observe that passes an older address gets
+ * undefined results).  The library keeps a host copy of each vector it uploaded: observes that
+ * use one are admitted and accounted with the record's real size, so dmi_ring_free_bytes stays
+ * meaningful under masking; for a caller-owned keep vector every listed request counts.
+ * Updating the vector between steps does not change what is launched, only what the
+ * launches copy (section 4.4). */
 dmi_status_t dmi_set_keep_mask(dmi_ring_t *ring, const uint8_t *keep /*[host]*/, uint32_t n_reqs,
                                void *hip_stream, const uint8_t **keep_mask_dev /*[host]*/);
 

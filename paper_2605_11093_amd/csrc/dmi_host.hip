@@ -305,6 +305,21 @@ dmi_status_t plan_capture(dmi_ring *r, uint32_t point_id, const dmi_selection_t 
                     (unsigned long long)ub, (unsigned long long)r->dev_cap);
     pl.listed = listed;
     pl.ub = ub;
+    pl.rows_known = listed;
+    pl.size_known = sel->keep_mask_dev == nullptr;
+    if (sel->keep_mask_dev && sel->keep_mask_dev >= r->mask_buf && sel->keep_mask_dev < r->mask_buf + 4u * r->mask_stride &&
+        (size_t)(sel->keep_mask_dev - r->mask_buf) % r->mask_stride == 0) {
+        // a keep vector that came through dmi_set_keep_mask: the host knows what it holds, so
+        // admission and accounting work with the record's real size instead of the bound
+        const std::vector<uint8_t> &hm = r->mask_host[(size_t)(sel->keep_mask_dev - r->mask_buf) / r->mask_stride];
+        if (hm.size() == sel->n_reqs) {
+            uint64_t kept = 0;
+            for (uint32_t i = 0; i < sel->n_reqs; i++) kept += hm[i] ? sel->reqs[i].tok_count : 0u;
+            pl.ub = dmi_record_bytes(sel->n_reqs, kept, geo.row_elems, xf->out_dtype, xf->summary_mask);
+            pl.rows_known = kept;
+            pl.size_known = true;
+        }
+    }
 
     const bool index_mode = sel->row_index_dev != nullptr;
     bool one_row_each = true;
@@ -440,8 +455,8 @@ dmi_status_t observe_common(dmi_ring *r, uint32_t point_id, const dmi_selection_
     {
         std::lock_guard<std::mutex> lk(r->pmu);
         r->next_seq.store(seq + 1, std::memory_order_release);
-        if (mode == DMI_POLICY_BLOCK && !sel->keep_mask_dev) {
-            r->window.bytes += ub; r->window.records += 1; r->window.rows += pl.listed;
+        if (mode == DMI_POLICY_BLOCK && pl.size_known) {
+            r->window.bytes += ub; r->window.records += 1; r->window.rows += pl.rows_known;
         } else {
             r->window_exact = false;
         }
@@ -970,7 +985,9 @@ dmi_status_t dmi_set_keep_mask(dmi_ring_t *r, const uint8_t *keep, uint32_t n, v
     if (!r || !keep_mask_dev || (n && !keep)) return fail(DMI_ERR_INVALID_ARG, "NULL argument");
     if (n > r->max_reqs) return fail(DMI_ERR_INVALID_ARG, "n_reqs %u exceeds max_reqs_per_observe %u", n, r->max_reqs);
     (void)hipSetDevice(r->dev);
-    uint8_t *dst = r->mask_buf + (size_t)(r->mask_rr++ % 4u) * r->mask_stride;
+    const uint32_t which = r->mask_rr++ % 4u;
+    uint8_t *dst = r->mask_buf + (size_t)which * r->mask_stride;
+    r->mask_host[which].assign(keep, keep + n);
     std::vector<uint32_t> words((n + 3u) / 4u, 0u);
     if (n) memcpy(words.data(), keep, n);
     if (n) HIP_TRY(launch_upload(reinterpret_cast<uint32_t *>(dst), words.data(), (uint32_t)words.size(),

@@ -96,7 +96,9 @@ struct Geometry {
 // What a capture launch is, apart from when it runs and where its table lives.
 struct Plan {
     uint64_t listed = 0;        // rows the selection lists
-    uint64_t ub = 0;            // record bytes if every request is kept
+    uint64_t ub = 0;            // record bytes if every request is kept (or exactly, see size_known)
+    uint64_t rows_known = 0;    // rows of the record when size_known
+    bool size_known = false;    // no keep vector, or one the host has a copy of: ub is the record's size
     uint32_t grid = 1;
     bool decode = false;        // the decode-shaped kernel applies
     bool row_map = false;       // ... and wants the source row of every listed row behind the table
@@ -134,6 +136,7 @@ struct dmi_ring {
     hipStream_t ctl_stream = nullptr;                      // statistics reads, set-up launches
     uint8_t *mask_buf = nullptr;                           // 4 rotating keep vectors of max_reqs bytes
     uint32_t mask_rr = 0, mask_stride = 0;
+    std::vector<uint8_t> mask_host[4];                     // what dmi_set_keep_mask last put into each of them
     uint32_t *slab = nullptr;
     uint32_t slab_slot_words = 0, next_slab = 0, max_reqs = 0;
     SelCache cache[kSelCache];

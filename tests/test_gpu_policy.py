@@ -240,9 +240,16 @@ def test_commit_accounting_across_policy_and_mask_changes(B, flags_name):
             ring.set_policy(mode)
             ref.mode = POLICY_DROP_NEWEST if kind == 2 else POLICY_BLOCK
             km = None
-            if keep is not None:
-                km = torch.from_numpy(keep).to(DEV)
+            if keep is not None and i % 2:
+                km = torch.from_numpy(keep).to(DEV)     # caller-owned: the host cannot tell the record's size
                 keep_alive.append(km)
+            elif keep is not None:
+                class _Ptr:                             # library-owned: the host kept a copy and can
+                    p = ring.set_keep_mask(keep, s.cuda_stream)
+
+                    def data_ptr(self):
+                        return self.p
+                km = _Ptr()
             assert ring.observe_tensor(i % 7, t, reqs, step_id=i, stream=s.cuda_stream, keep_mask=km,
                                        summary_mask=i % 8) == B.OK
             assert ref.observe(tc, reqs, point_id=i % 7, step_id=i, out_dtype=1, summary_mask=i % 8,
