@@ -25,17 +25,18 @@ class CpuView:
     def tensor(self, t: torch.Tensor) -> torch.Tensor:
         if t.device.type == "cpu":
             return t
+        # the cache keeps the original alive: a key made of an address must not outlive its object
         key = (t.data_ptr(), tuple(t.shape), tuple(t.stride()))
         if key not in self._t:
-            self._t[key] = t.cpu()
-        return self._t[key]
+            self._t[key] = (t, t.cpu())
+        return self._t[key][1]
 
     def paged(self, p):
         if p is None:
             return None
         if id(p) not in self._p:
-            self._p[id(p)] = _CpuPaged(p)
-        return self._p[id(p)]
+            self._p[id(p)] = (p, _CpuPaged(p))
+        return self._p[id(p)][1]
 
 
 def observe_call(ring: OracleRing, call, view: CpuView) -> int:

@@ -16,13 +16,16 @@ def compare_record(got: np.ndarray, ref: np.ndarray, what=""):
     assert got.size == ref.size, f"{what}: size {got.size} != {ref.size}"
     g, r = decode_record(got), decode_record(ref)
     if not r.summary_mask:
-        assert np.array_equal(got, ref), f"{what}: bytes differ at {np.flatnonzero(got != ref)[:8]}"
+        if not np.array_equal(got, ref):
+            d = np.flatnonzero(got != ref)
+            raise AssertionError(f"{what}: {d.size} bytes differ, first {d[:8]}, last {d[-3:]} of {ref.size}")
         return
     n_sum = bin(r.summary_mask).count("1")
     sum_bytes = n_sum * ((r.n_rows * 4 + 63) // 64 * 64)
     head = r.record_bytes - sum_bytes
-    assert np.array_equal(got[:head], ref[:head]), \
-        f"{what}: non-summary bytes differ at {np.flatnonzero(got[:head] != ref[:head])[:8]}"
+    if not np.array_equal(got[:head], ref[:head]):
+        d = np.flatnonzero(got[:head] != ref[:head])
+        raise AssertionError(f"{what}: {d.size} non-summary bytes differ, first {d[:8]}, last {d[-3:]} of {head}")
     if 4 in r.summaries:
         a, b = g.summaries[4], r.summaries[4]
         nan = np.isnan(b)

@@ -176,3 +176,19 @@ def test_host_ring_image_wraps_bytewise(oracle):
     assert s.size == 6 * 2176 > 4096
     for b in range(s.size - 4096, s.size):
         assert img[b % 4096] == s[b]
+
+
+def test_replay_cache_never_hands_out_another_objects_host_copy():
+    """The replay driver caches host copies per object; a short-lived object's address may
+    be reused by the next one, which must not get the earlier one's copy."""
+    import gc
+    import torch
+    from oracle.replay import CpuView
+    from workloads.configs import PagedSpec
+    view = CpuView()
+    for k in range(50):
+        table = torch.full((2, 3), k, dtype=torch.int32)
+        spec = PagedSpec(16, 4, 64, [1], table)
+        assert int(view.paged(spec).block_table[0, 0]) == k
+        del spec, table
+        gc.collect()
