@@ -124,7 +124,7 @@ struct CaptureArgs : CaptureKernelArgs {
 
 // Launchers (dmi_kernels.hip).  All return the launch's hipError_t.
 hipError_t launch_capture(const CaptureArgs &a, uint32_t grid, bool vec16, hipStream_t s);
-// decode-shaped captures: bf16 source, dense, one row per request (with or without a keep
+// decode-shaped captures: bf16 source (fp16 if stored as it is), dense, one row per request (with or without a keep
 // vector; with one, at most 1024 requests), 16-byte movable rows of at most 1024 units;
 // grid is n_reqs + 1
 bool decode_kernel_applies(const CaptureArgs &a, bool vec16);

@@ -1167,7 +1167,7 @@ __global__ void __launch_bounds__(kThreads) capture_decode_kernel(const DecodeAr
 #pragma unroll
             for (uint32_t k = 0; k < U; k++) {
                 const uint32_t c = tid + k * kThreads;
-                if (c < a.units_per_row) emit_unit<2, 8, OUT_NONE, true>(RingW{}, 0, v[k], 1u, acc);
+                if (c < a.units_per_row) emit_unit<2, 8, OUT_NONE, true>(RingW{}, 0, v[k], a.hdr7 & 0xFFu, acc);
             }
             acc.ss = wave_sum(acc.ss);
             acc.s = wave_sum(acc.s);
@@ -1283,7 +1283,7 @@ __global__ void __launch_bounds__(kThreads) capture_decode_kernel(const DecodeAr
     for (uint32_t k = 0; k < U; k++) {
         const uint32_t c = tid + k * kThreads;
         if (c < a.units_per_row)
-            emit_unit<2, 8, OUT, false>(w, row_off + (uint64_t)c * NB_OUT, v[k], 1u, acc);
+            emit_unit<2, 8, OUT, false>(w, row_off + (uint64_t)c * NB_OUT, v[k], a.hdr7 & 0xFFu, acc);
     }
     DMI_STAMP_D(3);
     if constexpr (SUMM) {
@@ -1296,7 +1296,7 @@ __global__ void __launch_bounds__(kThreads) capture_decode_kernel(const DecodeAr
             uint64_t o = off_sum + (uint64_t)g * 4u;
             if (a.summary_mask & 1u) { ring_store<float>(w, o, sqrtf(ss)); o += sum_arr; }
             if (a.summary_mask & 2u) { ring_store<float>(w, o, sm / (float)a.row_elems); o += sum_arr; }
-            if (a.summary_mask & 4u) { ring_store<float>(w, o, __uint_as_float(am << 16)); }
+            if (a.summary_mask & 4u) { ring_store<float>(w, o, am_value(am, a.hdr7 & 0xFFu)); }
         }
     }
     DMI_STAMP_D(5);
@@ -1394,7 +1394,9 @@ bool decode_kernel_applies(const CaptureArgs &a, bool vec16)
     // selection of at most 1024 rows (the host then lists the source row of every output row)
     const bool shape = a.simple || (a.one_row_each && a.keep_mask && a.n_reqs <= 1024u) ||
                        (!a.keep_mask && a.listed_rows >= 1u && a.listed_rows <= kDecodeMaxListed);
-    return shape && !a.paged && vec16 && a.src_dtype == 1u && a.units_per_row <= 4u * kThreads && a.n_reqs >= 1u;
+    // 16-bit sources: bf16 with any supported output, fp16 as it is (or summaries only)
+    const bool types = a.src_dtype == 1u || (a.src_dtype == 2u && (a.out_dtype == 2u || a.out_dtype == 0u));
+    return shape && !a.paged && vec16 && types && a.units_per_row <= 4u * kThreads && a.n_reqs >= 1u;
 }
 
 template <int OUT>
@@ -1454,9 +1456,9 @@ hipError_t launch_capture_decode(const CaptureArgs &a, hipStream_t s)
     d.keep_mask = a.keep_mask;
     if (a.keep_mask && a.n_reqs > 1024u) return hipErrorInvalidValue;
     const bool summ = a.summary_mask != 0;
+    if (a.out_dtype == a.src_dtype) return launch_decode_t<OUT_RAW>(d, summ, s);
     switch (a.out_dtype) {
     case 0: return launch_decode_t<OUT_NONE>(d, summ, s);
-    case 1: return launch_decode_t<OUT_RAW>(d, summ, s);
     case 2: return launch_decode_t<OUT_FP16>(d, summ, s);
     case 4: return launch_decode_t<OUT_FP8>(d, summ, s);
     default: return hipErrorInvalidValue;

@@ -328,3 +328,22 @@ def test_paged_token_ranges_through_a_wrapping_ring(B, name):
 
     got, ref = _stream_through_small_ring(B, args, 8, rec, paged=spec)
     compare_streams(got, ref)
+
+
+@pytest.mark.parametrize("out_dtype,sm,masked", [(2, 7, False), (2, 0, True), (0, 5, True), (2, 3, True)])
+def test_fp16_source_on_decode_shapes(B, out_dtype, sm, masked):
+    n, E = 130, 2048
+    pool = [prng.randn_bf16(prng.sub_seed(37, k), (n + 1) * E, DEV).view(n + 1, E).to(torch.float16) for k in range(2)]
+    reqs = np.array([(i, i + 1, 0, 1, 1) for i in range(n)], dtype=np.uint32)
+    masks = [(prng.randint(prng.sub_seed(37, 5, k), n, 0, 3) > 0).astype(np.uint8) for k in range(2)]
+    dev_masks = [torch.from_numpy(m).to(DEV) for m in masks]
+    rec = orc.record_bytes(n, n, E, out_dtype, sm)
+
+    def args(i):
+        kw, okw = dict(out_dtype=out_dtype, summary_mask=sm), dict(out_dtype=out_dtype, summary_mask=sm)
+        if masked:
+            kw["keep_mask"], okw["keep_mask"] = dev_masks[i % 2], masks[i % 2]
+        return pool[i % 2], reqs, kw, okw
+
+    got, ref = _stream_through_small_ring(B, args, 7, rec)
+    compare_streams(got, ref)
