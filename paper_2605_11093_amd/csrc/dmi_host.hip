@@ -307,7 +307,8 @@ dmi_status_t plan_capture(dmi_ring *r, uint32_t point_id, const dmi_selection_t 
     pl.ub = ub;
     pl.rows_known = listed;
     pl.size_known = sel->keep_mask_dev == nullptr;
-    if (sel->keep_mask_dev && sel->keep_mask_dev >= r->mask_buf && sel->keep_mask_dev < r->mask_buf + 4u * r->mask_stride &&
+    if (fixed_row_count_ok &&       // (not for a replayable step: its keep vector changes between replays)
+        sel->keep_mask_dev && sel->keep_mask_dev >= r->mask_buf && sel->keep_mask_dev < r->mask_buf + 4u * r->mask_stride &&
         (size_t)(sel->keep_mask_dev - r->mask_buf) % r->mask_stride == 0) {
         // a keep vector that came through dmi_set_keep_mask: the host knows what it holds, so
         // admission and accounting work with the record's real size instead of the bound
