@@ -120,6 +120,7 @@ typedef struct {
     uint32_t block_timeout_ms;
 } dmi_ring_config_t;
 
+/* The environment variable DMI_DRAIN_MODE ("copy" or "kernel") overrides the drain engine chosen in flags. */
 dmi_status_t dmi_ring_create(const dmi_ring_config_t *cfg /*[host]*/, dmi_ring_t **out /*[host]*/);
 
 /* Stops the drain thread, waits for the library's own streams, frees both

@@ -591,6 +591,14 @@ dmi_status_t dmi_ring_create(const dmi_ring_config_t *cfg, dmi_ring_t **out)
         return fail(DMI_ERR_INVALID_ARG, "ring sizes must be multiples of 64 and at least 4096");
     if ((cfg->flags & DMI_DRAIN_COPY_ENGINE) && (cfg->flags & DMI_DRAIN_KERNEL))
         return fail(DMI_ERR_INVALID_ARG, "choose one drain mode");
+    // DMI_DRAIN_MODE=kernel|copy in the environment overrides the drain engine (for comparisons
+    // without touching the caller's code)
+    uint32_t flags = cfg->flags;
+    if (const char *m = getenv("DMI_DRAIN_MODE")) {
+        if (!strcmp(m, "kernel")) flags = (flags & ~(uint32_t)DMI_DRAIN_COPY_ENGINE) | DMI_DRAIN_KERNEL;
+        else if (!strcmp(m, "copy")) flags = (flags & ~(uint32_t)DMI_DRAIN_KERNEL) | DMI_DRAIN_COPY_ENGINE;
+        else return fail(DMI_ERR_INVALID_ARG, "DMI_DRAIN_MODE must be 'kernel' or 'copy'");
+    }
     const uint32_t max_reqs = cfg->max_reqs_per_observe ? cfg->max_reqs_per_observe : 1024u;
     if (max_reqs > 4096u) return fail(DMI_ERR_INVALID_ARG, "max_reqs_per_observe > 4096");
     int n_dev = 0;
@@ -603,6 +611,7 @@ dmi_status_t dmi_ring_create(const dmi_ring_config_t *cfg, dmi_ring_t **out)
     dmi_ring *r = new (std::nothrow) dmi_ring;
     if (!r) return fail(DMI_ERR_NOMEM, "out of host memory");
     r->cfg = *cfg;
+    r->cfg.flags = flags;
     r->dev = cfg->device_id;
     r->dev_cap = cfg->device_ring_bytes;
     r->host_cap = cfg->host_ring_bytes;
@@ -656,7 +665,7 @@ dmi_status_t dmi_ring_create(const dmi_ring_config_t *cfg, dmi_ring_t **out)
     if ((e = hipStreamCreateWithFlags(&r->ctl_stream, hipStreamNonBlocking)) != hipSuccess)
         return bail(e, "hipStreamCreate");
     if ((e = hipDeviceSynchronize()) != hipSuccess) return bail(e, "hipDeviceSynchronize");
-    if (cfg->flags & DMI_BG_THREAD) r->bg = std::thread(bg_loop, r);
+    if (flags & DMI_BG_THREAD) r->bg = std::thread(bg_loop, r);
     *out = r;
     return DMI_OK;
 }
