@@ -328,6 +328,11 @@ def main():
                    lambda r: dmi.PreparedObserve(r, c2.point_id, c2.tensor, c2.reqs, out_dtype=c2.out_dtype,
                                                  summary_mask=c2.summary_mask, keep_mask=km2),
                    kept * hidden * 4 + n_reqs * 37 + 64 + kept * 8, 256, rec_bytes * 256 + (1 << 20))
+        # config 1's record: 4 requests x 1 row x 256 bf16 (2,176 bytes)
+        w1 = configs.config1_tiny(device=dev, n_steps=1)
+        c1 = w1.step_calls(0)[0]
+        time_shape("config1_tiny", lambda r: dmi.PreparedObserve(r, c1.point_id, c1.tensor, c1.reqs),
+                   4 * 256 * 4 + 4 * 36 + 64, 256, 2176 * 256 + (1 << 20))
         # config 3: ragged prefill, every 4th token, bf16 -> fp8
         w3 = configs.config3_prefill(device=dev, n_steps=1, n_resid=1, n_mlp=1)
         c_res, c_mlp = [c for c in w3.step_calls(0) if c.point_id < 100][0], [c for c in w3.step_calls(0) if c.point_id >= 100][0]
