@@ -293,9 +293,10 @@ def main():
         kernels = {}
 
         def time_shape(name, make_call, alg, n_launch, ring_bytes):
-            # drop-newest: no admission waits on the host (the ring is sized to hold every launch)
+            # the ring is sized to hold every launch, so the completeness policy never waits; under it
+            # the commit probes are events only (no slot-fetch launches between the timed ones)
             r3 = B.Ring(ring_bytes, 1 << 26, max_reqs_per_observe=256)
-            r3.set_policy(B.POLICY_DROP_NEWEST)
+            r3.set_policy(B.POLICY_BLOCK)
             po = make_call(r3)
             for i in range(3):
                 observe_checked(po, i)
@@ -304,7 +305,7 @@ def main():
             for rep in range(3):
                 r3.destroy()
                 r3 = B.Ring(ring_bytes, 1 << 26, max_reqs_per_observe=256)
-                r3.set_policy(B.POLICY_DROP_NEWEST)
+                r3.set_policy(B.POLICY_BLOCK)
                 po = make_call(r3)
                 e0, e1 = ev_pair()
                 bench_lib.dmi_bench_sleep(sh, 300 + 10 * n_launch)
