@@ -243,6 +243,22 @@ def test_downcast_of_every_bf16_bit_pattern(B, out_dtype, width):
     assert np.array_equal(got, ref)
 
 
+@pytest.mark.parametrize("out_dtype", [DT_FP16, DT_FP8])
+@pytest.mark.parametrize("shape", [(2048, 32), (16, 4096)])
+def test_downcast_of_every_bf16_bit_pattern_general_kernel(B, out_dtype, shape):
+    """The same exhaustive check through the general kernel's short-row and long-row paths
+    (more than 1024 rows, or a keep vector with several rows per request, keep it off the
+    decode-shaped kernel)."""
+    bits = torch.arange(65536, dtype=torch.int32).to(torch.int16)
+    t = bits.view(torch.bfloat16).view(*shape).to(DEV)
+    if shape[0] > 1024:
+        got, ref = _one(B, t, [(1, 0, 0, shape[0], 1)], out_dtype=out_dtype, ring_bytes=1 << 20)
+    else:
+        got, ref = _one(B, t, [(1, 0, 0, 9, 1), (2, 9, 0, 7, 1)], out_dtype=out_dtype, keep_mask=[1, 1],
+                        ring_bytes=1 << 20)
+    assert np.array_equal(got, ref)
+
+
 def test_summaries_closed_forms_and_non_finite(B):
     E = 4096
     x = torch.zeros(8, E, dtype=torch.bfloat16, device=DEV)
