@@ -457,11 +457,11 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureKernelAr
     const uint32_t par = a.par_in;
 
     DMI_STAMP(0);
-    // -- control words: lane 0 of the last wavefront fetches the head (under drop-newest
-    //    also the tail, in workgroup 0 also the running counters) while the first
-    //    wavefronts start on the request table.  All these loads are in flight together:
-    //    every dependent trip to memory costs most of a microsecond, and a small capture
-    //    is made of little else.  Head and tail are double buffered by launch parity:
+    // -- control words: lane 0 of the last wavefront fetches head, tail copy, running counters
+    //    and (for a replayable step) the step's parameters, all at once and whether or not this
+    //    workgroup will need them, while the first wavefronts start on the request table.
+    //    Every dependent trip to memory costs most of a microsecond, and a small capture is
+    //    made of little else.  Head and tail are double buffered along the chain of launches:
     //    this launch reads what the previous one left and writes the other copy, so the
     //    values are the same for every workgroup with no atomic and no waiting.
     constexpr uint32_t kCtlTid = kThreads - 64u;
