@@ -223,7 +223,9 @@ dmi_status_t dmi_observe_paged(dmi_ring_t *ring, uint32_t point_id, const dmi_pa
 /* Move committed bytes from the device ring to the host ring (section 4.3, drain
  * stage).  Copies what is committed and fits the host ring's free space, then
  * lets the device reuse the drained span.  *bytes_moved [host, optional] = bytes
- * whose copy this call issued.  With DMI_DRAIN_FLUSH returns DMI_ERR_AGAIN if
+ * whose copy this call issued.  With DMI_DRAIN_FLUSH: DMI_OK means that every record of
+ * every observe issued before the call has arrived in the host ring and can be polled,
+ * whoever issued its copy (this call or the library's drain thread); DMI_ERR_AGAIN if
  * the host ring filled up before everything was moved (release and call again)
  * or the observes did not commit within block_timeout_ms. */
 dmi_status_t dmi_drain(dmi_ring_t *ring, uint32_t flags, uint64_t *bytes_moved);
