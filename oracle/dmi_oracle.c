@@ -33,6 +33,24 @@
  *                 token-ascending, tightly packed, pad to 64 (absent if out_dtype NONE)
  *   summaries   : for each set bit of summary_mask, ascending (1 L2, 2 mean,
  *                 4 absmax): f32[n_rows], each array padded to 64
+ *
+ * What pins this file to something other than itself (tests/test_oracle_*.py, no GPU):
+ *   - gathers: the all-rows case equals a memcpy of the tensor; ragged selections equal
+ *     torch.index_select on the same bytes; a paged cache whose elements encode
+ *     (block, slot, head, dim) decodes to exactly the rows asked for, and an identity
+ *     block table reduces the paged gather to the dense one;
+ *   - bf16 -> fp16: all 65,536 inputs against torch's CPU cast (a library routine), and
+ *     closed-form values (overflow to inf, ties, subnormals, NaN payload);
+ *   - bf16 -> fp8: all inputs with |x| <= 464 against torch's CPU float8_e4m3fn cast, all
+ *     65,536 against a separate linear scan over the 254 finite codes, and closed-form
+ *     values (448, 464, 1.0, 2^-9, 2^-10, -0, saturation, NaN);
+ *   - summaries: constant, one-hot and alternating rows (closed forms), numpy float64 as a
+ *     second route, NaN / inf rows;
+ *   - layout: an independent decoder (decode.py) recomputes every size and checks every
+ *     pad byte over random shapes.
+ * Parity unpinned: the record layout itself.  The paper prints no byte values (it speaks of
+ * a 64-byte descriptor with offset, length and ready flag); the layout above is this
+ * build's, checked for self-consistency only.
  */
 #include <math.h>
 #include <stdint.h>

@@ -18,6 +18,15 @@ Policies (paper section 4.4, plus this build's readings):
 
 This model is *lockstep*: every call completes before the next one starts, and
 bytes move from the device ring to the host ring only inside drain().
+
+Pins (tests/test_oracle_stream.py): a separate byte-level brute-force simulation of
+the drop policy on small random schedules; ring-capacity independence of the stream
+under the completeness policy; row conservation (captured + dropped + sampled-out =
+listed); per-point step order; the configuration-1 stream's size and SHA-256
+(tests/golden, written by make_golden.py from this package alone).  Parity unpinned:
+the readings themselves (what drop-newest discards, where block waits, what 1-in-k
+counts) are this build's where the paper is silent; the tests pin the model to those
+readings, not the readings to the paper.
 """
 from __future__ import annotations
 
