@@ -65,7 +65,11 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     dmi.lib()
-    bench_lib = C.CDLL(os.path.join(ROOT, "paper_2605_11093_amd", "libdmi_bench.so"))
+    bench_so = os.path.join(ROOT, "paper_2605_11093_amd", "libdmi_bench.so")
+    if not os.path.exists(bench_so):        # normally built beforehand by __graft_entry__.build()
+        from paper_2605_11093_amd import build as _b
+        _b.build_bench()
+    bench_lib = C.CDLL(bench_so)
     bench_lib.dmi_bench_sleep.argtypes = [C.c_void_p, C.c_uint32]
     bench_lib.dmi_bench_stream_gemv.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p]
     bench_lib.dmi_bench_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]
