@@ -276,6 +276,36 @@ def main():
     extra["hbm_copy_probe_GBs"] = round(d2d, 1)
     extra["pinned_d2h_peak_GBs"] = round(d2h_peak, 2)
 
+    # ------------------------------------------------------------------ what a second busy queue costs
+    # (the reason why nothing of the library runs on a second compute queue while captures are in
+    # flight): 256 plain 512 KiB copy kernels back to back on this stream, alone, and while a launch
+    # on another stream waits for an event of this one (what a commit probe on a control stream did)
+    if not args.skip_extra:
+        src_q = torch.empty(512 << 10, dtype=torch.uint8, device=dev)
+        dst_q = torch.empty(512 << 10, dtype=torch.uint8, device=dev)
+        side = torch.cuda.Stream()
+        q = {}
+        for name, busy in (("alone", False), ("second_queue_waiting", True)):
+            best = 1e9
+            for rep in range(4):
+                torch.cuda.synchronize()
+                e0, e1 = ev_pair()
+                bench_lib.dmi_bench_sleep(sh, 3000)
+                e0.record(stream)
+                for i in range(256):
+                    bench_lib.dmi_bench_copy(dst_q.data_ptr(), src_q.data_ptr(), 512 << 10, sh)
+                e1.record(stream)
+                if busy:                    # the other queue waits for this stream's last event the whole time
+                    side.wait_event(e1)
+                    bench_lib.dmi_bench_sleep(side.cuda_stream, 1)
+                e1.synchronize()
+                best = min(best, e0.elapsed_time(e1) * 1e3 / 256)
+                torch.cuda.synchronize()
+            q[name] = round(best, 3)
+        extra["dispatch_us_per_512KiB_copy_kernel"] = q
+        log(f"512 KiB copy kernels back to back: {q} us per launch")
+        del src_q, dst_q
+
     # ------------------------------------------------------------------ drain alone, both engines
     drain = {}
     for name, fl in (("copy_engine", B.DRAIN_COPY_ENGINE), ("kernel", B.DRAIN_KERNEL)):

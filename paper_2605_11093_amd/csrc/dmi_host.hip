@@ -40,9 +40,9 @@ void atomic_max(std::atomic<uint64_t> &a, uint64_t v)
 // Record an event behind everything launched so far (no-op if that is already covered).
 // If the host cannot tell what those launches added (drop-newest, keep vectors), the
 // newest launch's commit slot is fetched into the pinned mirror in front of the event.
-// Both go onto the producer's own stream: a second hardware queue with work pending slows
-// every dispatch of the first by a microsecond or more, far more than a small launch
-// every sixteenth capture costs in line.
+// Both go onto the producer's own stream: a launch on a second hardware queue that waits
+// for an event of this one slows every dispatch here by a microsecond or so while it
+// waits, far more than a small launch every sixteenth capture costs in line.
 dmi_status_t record_probe(dmi_ring *r)
 {
     std::lock_guard<std::mutex> lk(r->pmu);

@@ -177,8 +177,8 @@ struct dmi_ring {
     uint64_t drain_issued = 0;
     std::atomic<uint64_t> drain_done{0};
     // The drain stream carries the batch copies only (no launch, no event, no small copy: any
-    // of these is a packet on a second compute queue, and a second queue with packets pending
-    // slows every dispatch of the producer's queue by microseconds).  A batch is known to be
+    // of these is a packet on a second compute queue that waits for the copy in front of it, and
+    // a waiting packet there slows every dispatch of the producer's queue by a microsecond or so).  A batch is known to be
     // done when the whole stream is idle; the drained-up-to mark reaches the kernels through a
     // pinned host word that they read themselves.
     volatile uint64_t *htail = nullptr;                    // pinned, coherent
