@@ -220,6 +220,31 @@ dmi_status_t dmi_observe_paged(dmi_ring_t *ring, uint32_t point_id, const dmi_pa
                                const dmi_selection_t *sel /*[host]*/, const dmi_transform_t *xf /*[host]*/,
                                uint64_t step_id, void *hip_stream);
 
+/*
+ * dmi_observe for callers that cannot allocate: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  It needs no ring object and calls no allocating
+ * routine: the device memory a capture needs besides its input and output (control words,
+ * counters, the staged request table) is a 128 KiB array that the library's code object holds
+ * on every GPU for the life of the process.
+ * Runs on the calling thread's current HIP device.  Launches, on hip_stream, two one-workgroup
+ * launches that reset the control words and stage the request table, then the capture kernel
+ * dmi_observe would launch, and returns.  The record, byte for byte the one dmi_observe would
+ * produce with sequence number `seq` and this rank_tag, is written at out[0 ..) [device,
+ * 64-byte aligned]; its size is in its header (bytes 48..55) and, when the selection has no
+ * keep vector, in *record_bytes [host, optional] (with one: an upper bound).  Bytes of `out`
+ * behind the record are not touched.  No policy applies: nothing is sampled, dropped or waited for.
+ * Limits: at most 1024 requests; the record's upper bound (dmi_record_bytes with every listed
+ * row kept) must fit out_bytes (a multiple of 64): otherwise DMI_ERR_TOO_LARGE and nothing is
+ * launched.  Every call on a GPU uses that GPU's one array, so calls whose kernels may overlap
+ * there (different streams with no ordering between them) race; calls on one stream do not.
+ * Under a stream capture, call it once outside first: the first call on a device looks the
+ * array up and loads the kernels.
+ */
+dmi_status_t dmi_observe_into(uint32_t point_id, const dmi_tensor_t *tensor /*[host]*/,
+                              const dmi_selection_t *sel /*[host]*/, const dmi_transform_t *xf /*[host]*/,
+                              uint64_t seq, uint64_t step_id, uint32_t rank_tag, void *out /*[device]*/,
+                              uint64_t out_bytes, uint64_t *record_bytes /*[host]*/, void *hip_stream);
+
 /* Move committed bytes from the device ring to the host ring (section 4.3, drain
  * stage).  Copies what is committed and fits the host ring's free space, then
  * lets the device reuse the drained span.  *bytes_moved [host, optional] = bytes

@@ -166,6 +166,9 @@ def lib():
                               C.c_uint64, C.c_void_p]
     L.dmi_observe_paged.argtypes = [C.c_void_p, C.c_uint32, P(PagedKV), P(Selection), P(Transform),
                                     C.c_uint64, C.c_void_p]
+    L.dmi_observe_into.argtypes = [C.c_uint32, P(Tensor), P(Selection), P(Transform), C.c_uint64, C.c_uint64,
+                                   C.c_uint32, C.c_void_p, C.c_uint64, P(C.c_uint64), C.c_void_p]
+    L.dmi_observe_into.restype = C.c_int32
     L.dmi_drain.argtypes = [C.c_void_p, C.c_uint32, P(C.c_uint64)]
     L.dmi_poll_host.argtypes = [C.c_void_p, P(RecordViewC), C.c_uint32, P(C.c_uint32)]
     L.dmi_release_host.argtypes = [C.c_void_p, C.c_uint64]
@@ -252,6 +255,24 @@ def _torch_dtype_code(t) -> int:
 def _reqs_buffer(reqs):
     a = np.ascontiguousarray(np.asarray(reqs, dtype=np.uint32).reshape(-1, 5))
     return a
+
+
+def observe_into(point_id: int, tensor, reqs, out, *, seq: int, step_id: int, rank_tag: int = 0,
+                 out_dtype: Optional[int] = None, summary_mask: int = 0, keep_mask=None, row_index=None,
+                 stream: int = 0, allow: Sequence[int] = ()) -> int:
+    """dmi_observe_into: one record into `out` (a uint8 device tensor), no ring, no allocation.
+    Returns the record's size (an upper bound if a keep vector is given)."""
+    dt = _torch_dtype_code(tensor)
+    ra = _reqs_buffer(reqs)
+    t = Tensor(tensor.data_ptr(), dt, (C.c_int64 * 2)(*tensor.shape), (C.c_int64 * 2)(*tensor.stride()))
+    sel = Selection(ra.shape[0], ra.ctypes.data, None if keep_mask is None else keep_mask.data_ptr(),
+                    None if row_index is None else row_index.data_ptr())
+    xf = Transform(dt if out_dtype is None else out_dtype, summary_mask)
+    n = C.c_uint64()
+    _check(lib().dmi_observe_into(point_id, C.byref(t), C.byref(sel), C.byref(xf), seq, step_id, rank_tag,
+                                  out.data_ptr(), out.numel() * out.element_size(), C.byref(n), stream or None),
+           allow)
+    return int(n.value)
 
 
 class PreparedObserve:

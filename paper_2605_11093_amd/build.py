@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 SO = os.path.join(HERE, "libdmi.so")
 SOURCES = [os.path.join(HERE, "csrc", f) for f in ("dmi_kernels.hip", "dmi_host.hip", "dmi_step.hip",
-                                                     "dmi_exporter.hip")]
+                                                     "dmi_exporter.hip", "dmi_noalloc.hip")]
 HEADERS = [os.path.join(HERE, "csrc", "dmi_internal.h"), os.path.join(HERE, "csrc", "dmi_ring.h"),
            os.path.join(ROOT, "include", "dmi.h")]
 

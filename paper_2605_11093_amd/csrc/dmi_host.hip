@@ -288,9 +288,12 @@ dmi_status_t stage_selection(dmi_ring *r, const dmi_selection_t *sel, bool paged
 // Fill every kernel argument that depends only on the tensor, the selection's shape and the
 // transform.  Left to the caller: request table location, sequence number, step id, commit
 // slot, tail floor, policy, chain parity.
-dmi_status_t plan_capture(dmi_ring *r, uint32_t point_id, const dmi_selection_t *sel, const dmi_transform_t *xf,
+PlanEnv plan_env(const dmi_ring *r) { return PlanEnv{r->dev_ring, r->dev_cap, r->dctrl, r->cfg.rank_tag, r}; }
+
+dmi_status_t plan_capture(const PlanEnv &env, uint32_t point_id, const dmi_selection_t *sel, const dmi_transform_t *xf,
                           const Geometry &geo, CaptureArgs &a, Plan &pl, bool fixed_row_count_ok)
 {
+    const dmi_ring *r = env.masks;
     const uint32_t es_in = dtype_size(geo.src_dtype);
     uint64_t listed = 0;
     for (uint32_t i = 0; i < sel->n_reqs; i++) listed += sel->reqs[i].tok_count;
@@ -300,14 +303,14 @@ dmi_status_t plan_capture(dmi_ring *r, uint32_t point_id, const dmi_selection_t 
         return fail(DMI_ERR_TOO_LARGE, "selection of %llu rows x %llu units exceeds one record",
                     (unsigned long long)listed, (unsigned long long)upr);
     const uint64_t ub = dmi_record_bytes(sel->n_reqs, listed, geo.row_elems, xf->out_dtype, xf->summary_mask);
-    if (ub > r->dev_cap)
+    if (ub > env.cap)
         return fail(DMI_ERR_TOO_LARGE, "record of %llu bytes exceeds the device ring (%llu)",
-                    (unsigned long long)ub, (unsigned long long)r->dev_cap);
+                    (unsigned long long)ub, (unsigned long long)env.cap);
     pl.listed = listed;
     pl.ub = ub;
     pl.rows_known = listed;
     pl.size_known = sel->keep_mask_dev == nullptr;
-    if (fixed_row_count_ok &&       // (not for a replayable step: its keep vector changes between replays)
+    if (fixed_row_count_ok && r &&  // (not for a replayable step: its keep vector changes between replays)
         sel->keep_mask_dev && sel->keep_mask_dev >= r->mask_buf && sel->keep_mask_dev < r->mask_buf + 4u * r->mask_stride &&
         (size_t)(sel->keep_mask_dev - r->mask_buf) % r->mask_stride == 0) {
         // a keep vector that came through dmi_set_keep_mask: the host knows what it holds, so
@@ -345,10 +348,10 @@ dmi_status_t plan_capture(dmi_ring *r, uint32_t point_id, const dmi_selection_t 
     // reduction, four rows in flight per workgroup); otherwise a workgroup per row
     a.rows_per_wg = (upr <= 128u || (upr <= 1024u && listed >= 2048u)) ? 4u : 1u;
     a.point_id = point_id;
-    a.rank_tag = r->cfg.rank_tag;
-    a.ring = r->dev_ring;
-    a.cap = r->dev_cap;
-    a.ctrl = r->dctrl;
+    a.rank_tag = env.rank_tag;
+    a.ring = env.ring;
+    a.cap = env.cap;
+    a.ctrl = env.ctrl;
     a.simple = simple ? 1u : 0u;
     auto shift_of = [](uint64_t v) { return v && (v & (v - 1u)) == 0 ? (uint32_t)__builtin_ctzll(v) : 32u; };
     a.upr_shift = shift_of(upr);
@@ -417,7 +420,7 @@ dmi_status_t observe_common(dmi_ring *r, uint32_t point_id, const dmi_selection_
     if (r->step_open)
         return fail(DMI_ERR_INVALID_ARG, "a replayable step is between dmi_step_begin and dmi_step_end");
     Plan pl;
-    dmi_status_t st = plan_capture(r, point_id, sel, xf, geo, a, pl, true);
+    dmi_status_t st = plan_capture(plan_env(r), point_id, sel, xf, geo, a, pl, true);
     if (st != DMI_OK) return st;
     const uint64_t ub = pl.ub;
 

@@ -134,6 +134,8 @@ hipError_t launch_upload(uint32_t *dst, const uint32_t *words, uint32_t n_words,
 // tail_for over to the copy the step's first launch reads
 hipError_t launch_step_begin(DevCtrl *ctrl, StepParams *step, StepParams v, uint32_t par_from, uint32_t par_to,
                              const uint64_t *host_tail, hipStream_t s);
+// zeroes head / tail copies and the running counters of a control block
+hipError_t launch_ctrl_reset(DevCtrl *ctrl, hipStream_t s);
 hipError_t launch_fetch_slot(const CommitSlot *src, CommitSlot *dst_host, hipStream_t s);
 hipError_t launch_drain_kernel(const uint8_t *ring, uint64_t cap, uint8_t *host_ring, uint64_t host_cap,
                                uint64_t from, uint64_t nbytes, uint32_t grid, hipStream_t s);

@@ -1326,6 +1326,19 @@ __global__ void step_begin_kernel(DevCtrl *ctrl, StepParams *step, const StepPar
     }
 }
 
+// Put a control block back to "empty stream, nothing counted": the chain words and the running
+// counters (a fill kernel, so that a caller under graph capture records a kernel node).
+__global__ void ctrl_reset_kernel(DevCtrl *ctrl)
+{
+    if (threadIdx.x != 0) return;
+    ctrl->head[0] = ctrl->head[1] = 0;
+    ctrl->tail_for[0] = ctrl->tail_for[1] = 0;
+    ctrl->tail = 0;
+    ctrl->captured_records = ctrl->captured_rows = ctrl->captured_bytes = 0;
+    ctrl->dropped_records = ctrl->dropped_rows = ctrl->dropped_bytes = 0;
+    ctrl->bad_rows = 0;
+}
+
 // Fetch one commit slot into pinned host memory: a small launch of its own on the producer's
 // stream, so the capture kernel itself never writes across PCIe (such a store is
 // acknowledged only after some 4-5 microseconds, and a kernel cannot retire before its
@@ -1476,6 +1489,12 @@ hipError_t launch_upload(uint32_t *dst, const uint32_t *words, uint32_t n_words,
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
+}
+
+hipError_t launch_ctrl_reset(DevCtrl *ctrl, hipStream_t s)
+{
+    hipLaunchKernelGGL(ctrl_reset_kernel, dim3(1), dim3(64), 0, s, ctrl);
+    return hipGetLastError();
 }
 
 hipError_t launch_fetch_slot(const CommitSlot *src, CommitSlot *dst_host, hipStream_t s)

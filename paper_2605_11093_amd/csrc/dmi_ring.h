@@ -104,6 +104,16 @@ struct Plan {
     bool row_map = false;       // ... and wants the source row of every listed row behind the table
 };
 
+// Where a planned launch writes and what it stamps into its header.  `masks`, when given, is the
+// ring whose dmi_set_keep_mask buffers the plan may recognise (the host knows their contents).
+struct PlanEnv {
+    uint8_t *ring;
+    uint64_t cap;
+    DevCtrl *ctrl;
+    uint32_t rank_tag;
+    const dmi_ring *masks;
+};
+
 // What the launches between two probes add when the host can tell without asking the
 // device: completeness policy and no keep vector, so each record has its listed size and
 // none is dropped.
@@ -251,7 +261,8 @@ uint64_t head_upper_bound(dmi_ring *r);
 dmi_status_t wait_for_room(dmi_ring *r, uint64_t ub);
 dmi_status_t commit_slot_room(dmi_ring *r, uint32_t n);
 void selection_words(const dmi_req_sel_t *reqs, uint32_t n, bool paged, bool row_map, std::vector<uint32_t> &words);
-dmi_status_t plan_capture(dmi_ring *r, uint32_t point_id, const dmi_selection_t *sel, const dmi_transform_t *xf,
+PlanEnv plan_env(const dmi_ring *r);
+dmi_status_t plan_capture(const PlanEnv &env, uint32_t point_id, const dmi_selection_t *sel, const dmi_transform_t *xf,
                           const Geometry &geo, CaptureArgs &a, Plan &pl, bool fixed_row_count_ok);
 dmi_status_t check_dense_rows(const dmi_req_sel_t *reqs, uint32_t n, int64_t T);
 dmi_status_t check_paged_rows(const dmi_req_sel_t *reqs, uint32_t n, uint32_t n_seqs, uint32_t block_size,

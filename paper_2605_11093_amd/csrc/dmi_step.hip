@@ -86,7 +86,7 @@ dmi_status_t step_add(dmi_step *st, uint32_t point_id, const dmi_selection_t *se
     if (hipStreamIsCapturing((hipStream_t)hip_stream, &cs) != hipSuccess || cs != hipStreamCaptureStatusActive)
         return fail(DMI_ERR_INVALID_ARG, "hip_stream is not capturing");
     StepNode nd;
-    dmi_status_t rc = plan_capture(r, point_id, sel, xf, geo, a, nd.pl, false);
+    dmi_status_t rc = plan_capture(plan_env(r), point_id, sel, xf, geo, a, nd.pl, false);
     if (rc != DMI_OK) return rc;
 
     // nodes captured with the same selection share one table (and are updated together)
