@@ -221,6 +221,37 @@ dmi_status_t dmi_observe_paged(dmi_ring_t *ring, uint32_t point_id, const dmi_pa
                                uint64_t step_id, void *hip_stream);
 
 /*
+ * Several observation points in one launch (paper section 5, "Device-to-device kernel": one
+ * launch per observed tensor; a launch has a fixed cost of a few microseconds on the GPU, which
+ * a decode step's small tensors cannot amortise one by one).  When n tensors of one dtype, shape
+ * and stride are alive together and share selection and transform -- the residual stream of
+ * every layer kept until the end of a decode step, K and V slices of several layers -- one
+ * call captures them all:
+ *   point_ids [host]  n observation points, one per tensor
+ *   data      [host]  n [device] pointers: the tensors' data (dense) / the caches' bases (paged)
+ *   like      [host]  dtype, shape and stride (dense) or the cache geometry, block table and
+ *                     selected heads (paged) common to all of them; its data / base field is ignored
+ * The result is, byte for byte and counter for counter, what n calls of dmi_observe /
+ * dmi_observe_paged in array order would give with nothing happening between them: n records
+ * with consecutive sequence numbers in array order (section 4.2: ring order is hook order), each
+ * tensor passing hook filtering on its own (a disabled point is skipped and counted), sampling
+ * applied to the step, drop-newest deciding per record (the records that still fit are kept, the
+ * rest of the batch is dropped and counted per point).  Under DMI_POLICY_BLOCK the batch is
+ * issued in as few launches as the device ring's size allows, each waiting for its room.
+ * *n_done [host, optional]: how many positions of the arrays have been dealt with (captured or
+ * skipped) when the call returns: n unless it fails; after DMI_ERR_AGAIN call again from there.
+ * Returns DMI_OK if anything was launched, else DMI_SAMPLED_OUT or DMI_POINT_DISABLED.
+ */
+dmi_status_t dmi_observe_batch(dmi_ring_t *ring, uint32_t n, const uint32_t *point_ids /*[host]*/,
+                               const void *const *data /*[host]*/, const dmi_tensor_t *like /*[host]*/,
+                               const dmi_selection_t *sel /*[host]*/, const dmi_transform_t *xf /*[host]*/,
+                               uint64_t step_id, void *hip_stream, uint32_t *n_done /*[host]*/);
+dmi_status_t dmi_observe_paged_batch(dmi_ring_t *ring, uint32_t n, const uint32_t *point_ids /*[host]*/,
+                                     const void *const *bases /*[host]*/, const dmi_paged_kv_t *like /*[host]*/,
+                                     const dmi_selection_t *sel /*[host]*/, const dmi_transform_t *xf /*[host]*/,
+                                     uint64_t step_id, void *hip_stream, uint32_t *n_done /*[host]*/);
+
+/*
  * dmi_observe for callers that cannot allocate: code under HIP graph capture, tight serving
  * loops, harnesses that forbid hipMalloc.  It needs no ring object and calls no allocating
  * routine: the device memory a capture needs besides its input and output (control words,
@@ -393,7 +424,7 @@ dmi_status_t dmi_set_keep_mask(dmi_ring_t *ring, const uint8_t *keep /*[host]*/,
  * calls.  Destroy a step after its last replay has finished and before its ring.
  */
 typedef struct dmi_step dmi_step_t;
-#define DMI_STEP_MAX_OBSERVES 256u
+#define DMI_STEP_MAX_OBSERVES 256u   /* records per step */
 /* Allocates the step's device-side parameter block and request-table space (not under capture). */
 dmi_status_t dmi_step_create(dmi_ring_t *ring, uint32_t max_observes, dmi_step_t **out /*[host]*/);
 dmi_status_t dmi_step_destroy(dmi_step_t *step);
@@ -404,7 +435,7 @@ dmi_status_t dmi_step_capture_begin(dmi_step_t *step);
 /* As dmi_observe / dmi_observe_paged without step id: validates, appends the launch to the
  * step and issues it on hip_stream, which must be capturing (DMI_ERR_INVALID_ARG otherwise).
  * Makes no HIP call besides the capture-status query and the kernel launch.
- * *node [host, optional] = index of the launch in the step.
+ * *node [host, optional] = index of the record in the step (what dmi_step_update takes).
  * Returns DMI_POINT_DISABLED (no launch) for a disabled point. */
 dmi_status_t dmi_step_observe(dmi_step_t *step, uint32_t point_id, const dmi_tensor_t *tensor /*[host]*/,
                               const dmi_selection_t *sel /*[host]*/, const dmi_transform_t *xf /*[host]*/,
@@ -412,9 +443,20 @@ dmi_status_t dmi_step_observe(dmi_step_t *step, uint32_t point_id, const dmi_ten
 dmi_status_t dmi_step_observe_paged(dmi_step_t *step, uint32_t point_id, const dmi_paged_kv_t *kv /*[host]*/,
                                     const dmi_selection_t *sel /*[host]*/, const dmi_transform_t *xf /*[host]*/,
                                     void *hip_stream, uint32_t *node /*[host]*/);
+/* As dmi_observe_batch / dmi_observe_paged_batch inside a step: the n tensors become n
+ * consecutive records of the step, written by one launch (two beyond 128 tensors).
+ * *node = index of the first of them.  Disabled points are left out; DMI_POINT_DISABLED if all are. */
+dmi_status_t dmi_step_observe_batch(dmi_step_t *step, uint32_t n, const uint32_t *point_ids /*[host]*/,
+                                    const void *const *data /*[host]*/, const dmi_tensor_t *like /*[host]*/,
+                                    const dmi_selection_t *sel /*[host]*/, const dmi_transform_t *xf /*[host]*/,
+                                    void *hip_stream, uint32_t *node /*[host]*/);
+dmi_status_t dmi_step_observe_paged_batch(dmi_step_t *step, uint32_t n, const uint32_t *point_ids /*[host]*/,
+                                          const void *const *bases /*[host]*/, const dmi_paged_kv_t *like /*[host]*/,
+                                          const dmi_selection_t *sel /*[host]*/, const dmi_transform_t *xf /*[host]*/,
+                                          void *hip_stream, uint32_t *node /*[host]*/);
 /* Closes the step; the library's threads resume. */
 dmi_status_t dmi_step_seal(dmi_step_t *step);
-/* Replace the request table of launch `node` (host side; it reaches the device with the
+/* Replace the request table of record `node` of the step (host side; it reaches the device with the
  * next dmi_step_begin).  Launches captured with an identical table share it and are
  * updated together.  n_reqs must be the captured count; rows must lie inside every
  * tensor concerned; a launch captured with one row per request and no keep vector keeps

@@ -3,6 +3,6 @@
 The product is libdmi.so (HIP kernels + C ABI, see include/dmi.h); this package
 only marshals arguments for it.
 """
-from .binding import (DmiError, PreparedObserve, Ring, Step, Stats, RecordView, lib, library_path,  # noqa: F401
+from .binding import (DmiError, PreparedBatch, PreparedObserve, Ring, Step, Stats, RecordView, lib, library_path,  # noqa: F401
                       record_bytes, version)
 from . import binding  # noqa: F401

@@ -166,6 +166,17 @@ def lib():
                               C.c_uint64, C.c_void_p]
     L.dmi_observe_paged.argtypes = [C.c_void_p, C.c_uint32, P(PagedKV), P(Selection), P(Transform),
                                     C.c_uint64, C.c_void_p]
+    L.dmi_observe_batch.argtypes = [C.c_void_p, C.c_uint32, P(C.c_uint32), P(C.c_void_p), P(Tensor), P(Selection),
+                                    P(Transform), C.c_uint64, C.c_void_p, P(C.c_uint32)]
+    L.dmi_observe_paged_batch.argtypes = [C.c_void_p, C.c_uint32, P(C.c_uint32), P(C.c_void_p), P(PagedKV),
+                                          P(Selection), P(Transform), C.c_uint64, C.c_void_p, P(C.c_uint32)]
+    L.dmi_step_observe_batch.argtypes = [C.c_void_p, C.c_uint32, P(C.c_uint32), P(C.c_void_p), P(Tensor),
+                                         P(Selection), P(Transform), C.c_void_p, P(C.c_uint32)]
+    L.dmi_step_observe_paged_batch.argtypes = [C.c_void_p, C.c_uint32, P(C.c_uint32), P(C.c_void_p), P(PagedKV),
+                                               P(Selection), P(Transform), C.c_void_p, P(C.c_uint32)]
+    for name in ("dmi_observe_batch", "dmi_observe_paged_batch", "dmi_step_observe_batch",
+                 "dmi_step_observe_paged_batch"):
+        getattr(L, name).restype = C.c_int32
     L.dmi_observe_into.argtypes = [C.c_uint32, P(Tensor), P(Selection), P(Transform), C.c_uint64, C.c_uint64,
                                    C.c_uint32, C.c_void_p, C.c_uint64, P(C.c_uint64), C.c_void_p]
     L.dmi_observe_into.restype = C.c_int32
@@ -307,6 +318,59 @@ class PreparedObserve:
         return self._fn(self._h, self._point, self._a[0], self._a[1], self._a[2], step_id, stream)
 
 
+def _paged_struct(cache, paged_or_table, *, block_size=None, n_heads=None, head_dim=None, heads_sel=None):
+    """dmi_paged_kv_t for a cache tensor [blocks, slots, heads, dim]."""
+    if block_size is None:
+        p = paged_or_table
+        bt, block_size, n_heads, head_dim, heads_sel = p.block_table, p.block_size, p.n_heads, p.head_dim, p.heads_sel
+    else:
+        bt = paged_or_table
+    return PagedKV(cache.data_ptr(), _torch_dtype_code(cache), cache.stride(0), cache.stride(1), cache.stride(2),
+                   block_size, n_heads, head_dim, cache.shape[0], bt.shape[0], bt.data_ptr(), bt.stride(0),
+                   len(heads_sel), (C.c_uint32 * 8)(*heads_sel))
+
+
+def _same_layout(tensors):
+    t0 = tensors[0]
+    for t in tensors[1:]:
+        if t.dtype != t0.dtype or tuple(t.shape) != tuple(t0.shape) or tuple(t.stride()) != tuple(t0.stride()):
+            raise ValueError("the tensors of a batch must share dtype, shape and strides")
+
+
+class PreparedBatch:
+    """The argument structs of one dmi_observe_batch / dmi_observe_paged_batch call, built once.
+    Calling it returns (status, n_done)."""
+
+    def __init__(self, ring: "Ring", point_ids, tensors, reqs, *, out_dtype: Optional[int] = None,
+                 summary_mask: int = 0, keep_mask=None, row_index=None, paged=None):
+        tensors = list(tensors)
+        _same_layout(tensors)
+        dt = _torch_dtype_code(tensors[0])
+        self._keep = (tensors, keep_mask, row_index, paged)
+        self._n = len(tensors)
+        self._points = (C.c_uint32 * self._n)(*[int(p) for p in point_ids])
+        self._data = (C.c_void_p * self._n)(*[t.data_ptr() for t in tensors])
+        self._ra = _reqs_buffer(reqs)
+        self._sel = Selection(self._ra.shape[0], self._ra.ctypes.data,
+                              None if keep_mask is None else keep_mask.data_ptr(),
+                              None if row_index is None else row_index.data_ptr())
+        self._xf = Transform(dt if out_dtype is None else out_dtype, summary_mask)
+        self._h = ring._h
+        t0 = tensors[0]
+        if paged is None:
+            self._like = Tensor(t0.data_ptr(), dt, (C.c_int64 * 2)(*t0.shape), (C.c_int64 * 2)(*t0.stride()))
+            self._fn = lib().dmi_observe_batch
+        else:
+            self._like = _paged_struct(t0, paged)
+            self._fn = lib().dmi_observe_paged_batch
+        self._done = C.c_uint32()
+
+    def __call__(self, step_id: int, stream: int):
+        rc = self._fn(self._h, self._n, self._points, self._data, C.byref(self._like), C.byref(self._sel),
+                      C.byref(self._xf), step_id, stream, C.byref(self._done))
+        return rc, self._done.value
+
+
 class Step:
     """A replayable step (dmi_step_*): capture launches that can sit in a captured graph."""
 
@@ -352,6 +416,33 @@ class Step:
         node = C.c_uint32()
         code = _check(lib().dmi_step_observe_paged(self._h, point_id, C.byref(kv), C.byref(sel), C.byref(xf),
                                                    stream or None, C.byref(node)), allow)
+        return int(node.value) if code == OK else -1
+
+    def observe_batch(self, point_ids, tensors, reqs, *, stream: int, out_dtype: Optional[int] = None,
+                      summary_mask: int = 0, keep_mask=None, row_index=None, paged=None,
+                      allow: Sequence[int] = ()) -> int:
+        """n tensors of one layout -> n consecutive records of the step, one launch.
+        Returns the index of the first record, or -1 if every point is disabled."""
+        tensors = list(tensors)
+        _same_layout(tensors)
+        n, t0 = len(tensors), tensors[0]
+        dt = _torch_dtype_code(t0)
+        ra = _reqs_buffer(reqs)
+        pts = (C.c_uint32 * n)(*[int(p) for p in point_ids])
+        data = (C.c_void_p * n)(*[t.data_ptr() for t in tensors])
+        sel = Selection(ra.shape[0], ra.ctypes.data, None if keep_mask is None else keep_mask.data_ptr(),
+                        None if row_index is None else row_index.data_ptr())
+        xf = Transform(dt if out_dtype is None else out_dtype, summary_mask)
+        node = C.c_uint32()
+        if paged is None:
+            like = Tensor(t0.data_ptr(), dt, (C.c_int64 * 2)(*t0.shape), (C.c_int64 * 2)(*t0.stride()))
+            code = lib().dmi_step_observe_batch(self._h, n, pts, data, C.byref(like), C.byref(sel), C.byref(xf),
+                                                stream or None, C.byref(node))
+        else:
+            like = _paged_struct(t0, paged)
+            code = lib().dmi_step_observe_paged_batch(self._h, n, pts, data, C.byref(like), C.byref(sel),
+                                                      C.byref(xf), stream or None, C.byref(node))
+        _check(code, allow)
         return int(node.value) if code == OK else -1
 
     def seal(self):
@@ -439,6 +530,17 @@ class Ring:
         xf = Transform(dt if out_dtype is None else out_dtype, summary_mask)
         return _check(lib().dmi_observe_paged(self._h, point_id, C.byref(kv), C.byref(sel),
                                               C.byref(xf), step_id, stream or None), allow)
+
+    def observe_batch(self, point_ids, tensors, reqs, *, step_id: int, stream: int = 0,
+                      out_dtype: Optional[int] = None, summary_mask: int = 0, keep_mask=None, row_index=None,
+                      paged=None, allow: Sequence[int] = ()):
+        """dmi_observe_batch / dmi_observe_paged_batch (paged: an object with block_table, block_size,
+        n_heads, head_dim, heads_sel; tensors are then the caches).  Returns (status, n_done)."""
+        po = PreparedBatch(self, point_ids, tensors, reqs, out_dtype=out_dtype, summary_mask=summary_mask,
+                           keep_mask=keep_mask, row_index=row_index, paged=paged)
+        rc, done = po(step_id, stream or None)
+        _check(rc, allow)
+        return rc, done
 
     # -- consumer --------------------------------------------------------
     def drain(self, flags: int = 0, allow: Sequence[int] = ()) -> int:

@@ -7,9 +7,10 @@
 namespace dmi {
 
 constexpr uint32_t kThreads = 256;          // 4 wavefronts of 64 lanes per workgroup
-constexpr uint32_t kMaxGrid = 2048;         // 256 CUs x 8 resident workgroups
+constexpr uint32_t kMaxGrid = 1u << 22;     // workgroups per tensor of one launch
 constexpr uint32_t kLdsTableMax = 1024;     // request tables up to this size are cached in LDS
 constexpr uint32_t kDecodeMaxListed = 1024; // most rows a ragged selection may list to take the decode-shaped kernel
+constexpr uint32_t kMaxBatch = 128;         // most tensors one batched launch captures
 
 // One slot per launch, written by workgroup 0 of the launch: where the head stands
 // after it, and the running counters.  Slot seq % kCommitSlots lives in device memory;
@@ -60,10 +61,19 @@ struct StepParams {
 };
 constexpr uint32_t kStepDropNewest = 1u, kStepSkip = 2u;
 
+// A batched launch captures several tensors that share shape, selection and transform: one
+// record each, at consecutive sequence numbers, laid down one behind the other exactly as
+// consecutive single launches would.  Workgroups with blockIdx.y = i work on tensor i; what
+// differs between the tensors travels in this second argument block (a single launch is a
+// batch of one).
+struct BatchArgs {
+    const uint8_t *src[kMaxBatch];  // dense: the tensor's data; paged: the cache's base
+    uint32_t point[kMaxBatch];      // observation point of each record
+};
+
 // What the general capture kernel reads (its argument block: five 64-byte lines).
 struct CaptureKernelArgs {
-    // source
-    const uint8_t *src;
+    // source (the data pointer itself is in BatchArgs)
     int64_t row_stride_b;           // dense: bytes between rows
     int64_t n_src_rows;             // dense: rows in the tensor; paged: physical blocks
     int64_t block_stride_b, slot_stride_b, head_stride_b;
@@ -85,8 +95,8 @@ struct CaptureKernelArgs {
     uint32_t row_elems;
     uint32_t units_per_row;
     uint32_t rows_per_wg;           // summary kernels: 1 (a workgroup per row) or 4 (a wavefront per row)
-    uint32_t point_id, rank_tag;
-    uint64_t seq, step_id;
+    uint32_t n_batch, rank_tag;     // n_batch = gridDim.y
+    uint64_t seq, step_id;          // seq: of the launch's first record
     // ring
     uint8_t *ring;
     uint64_t cap;
@@ -109,6 +119,8 @@ struct CaptureKernelArgs {
 // The host's plan of one launch: the kernel's arguments plus what only the launchers need
 // (the decode-shaped kernel gets its own, smaller block made from this).
 struct CaptureArgs : CaptureKernelArgs {
+    const uint8_t *src;             // the tensor (the first one of a batch); goes into BatchArgs::src
+    uint32_t point_id;              // same, BatchArgs::point
     uint32_t one_row_each;          // every request lists exactly one row (a keep vector may still drop some)
     uint32_t listed_rows;           // rows the selection lists (all requests kept)
     const uint32_t *row_map;        // decode-shaped kernel, requests listing several rows: source row of every
@@ -123,12 +135,12 @@ struct CaptureArgs : CaptureKernelArgs {
 };
 
 // Launchers (dmi_kernels.hip).  All return the launch's hipError_t.
-hipError_t launch_capture(const CaptureArgs &a, uint32_t grid, bool vec16, hipStream_t s);
+hipError_t launch_capture(const CaptureArgs &a, const BatchArgs &b, uint32_t grid, bool vec16, hipStream_t s);
 // decode-shaped captures: bf16 source (fp16 if stored as it is), dense, one row per request (with or without a keep
 // vector; with one, at most 1024 requests), 16-byte movable rows of at most 1024 units;
 // grid is n_reqs + 1
 bool decode_kernel_applies(const CaptureArgs &a, bool vec16);
-hipError_t launch_capture_decode(const CaptureArgs &a, hipStream_t s);
+hipError_t launch_capture_decode(const CaptureArgs &a, const BatchArgs &b, hipStream_t s);
 hipError_t launch_upload(uint32_t *dst, const uint32_t *words, uint32_t n_words, hipStream_t s);
 // start of a replayable step: writes *step and, if par_from != par_to, carries head and
 // tail_for over to the copy the step's first launch reads

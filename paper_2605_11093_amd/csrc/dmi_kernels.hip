@@ -422,24 +422,28 @@ __device__ __forceinline__ Control resolve_control(const RawControl &r, bool in_
     return o;
 }
 
-// Fetch every line of a by-value kernel argument block now, together.
+// Fetch every line of a by-value kernel argument block now, together, along with this
+// workgroup's entry of the batch block (its tensor and observation point).
 template <typename T>
-__device__ __forceinline__ void touch_argument_lines(const T &a)
+__device__ __forceinline__ void touch_argument_lines(const T &a, const uint8_t *src, uint32_t point)
 {
     const uint32_t *p = reinterpret_cast<const uint32_t *>(&a);
     constexpr uint32_t n = (sizeof(T) + 63u) / 64u;
     static_assert(n <= 10, "argument block larger than expected");
     auto at = [p](uint32_t line) { return p[(line < n ? line : n - 1u) * 16u]; };
     asm volatile("" ::"s"(at(0)), "s"(at(1)), "s"(at(2)), "s"(at(3)), "s"(at(4)), "s"(at(5)), "s"(at(6)), "s"(at(7)),
-                 "s"(at(8)), "s"(at(9)));
+                 "s"(at(8)), "s"(at(9)), "s"((uint32_t)(uintptr_t)src), "s"((uint32_t)((uintptr_t)src >> 32)), "s"(point));
 }
 
 // ---------------------------------------------------------------- capture kernel
 template <int ES_IN, int VEC, int OUT, bool SUMM>
-__global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureKernelArgs a)
+__global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureKernelArgs a, const BatchArgs b)
 {
     extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
-    touch_argument_lines(a);        // all lines of the argument block in one trip, not one by one
+    const uint32_t y = blockIdx.y;                  // which tensor of the batch this workgroup works on
+    const uint8_t *const src = b.src[y];
+    const uint32_t point_id = b.point[y];
+    touch_argument_lines(a, src, point_id);         // all of it in one trip, not one by one
     constexpr uint32_t NB_IN = ES_IN * VEC;
     constexpr uint32_t NB_OUT = out_unit_bytes<ES_IN, VEC, OUT>();
     typedef typename UnitT<NB_IN>::T unit_t;
@@ -570,7 +574,7 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureKernelAr
         if (g < n_reqs) {
             const int64_t row = index_mode ? (int64_t)a.row_index[g] : (int64_t)a.row0[g];
             pre_ref.ok = row >= 0 && row < a.n_src_rows;
-            pre_ref.base = a.src + (pre_ref.ok ? row : 0) * a.row_stride_b;
+            pre_ref.base = src + (pre_ref.ok ? row : 0) * a.row_stride_b;
 #pragma unroll
             for (uint32_t k = 0; k < U; k++) {
                 const uint32_t c = c_begin + k * stride;
@@ -586,7 +590,7 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureKernelAr
         // the host keeps it (a read across the host link, issued after every other load of this
         // lane so that none of them queues behind it; nothing in this launch waits for it but
         // the closing stores of this one lane)
-        const uint64_t *ts = blockIdx.x == 0 && a.tail_src ? a.tail_src : &a.ctrl->tail;
+        const uint64_t *ts = blockIdx.x == 0 && y == 0 && a.tail_src ? a.tail_src : &a.ctrl->tail;
         tail_now = ld_system(ts);
         publish_control();
     }
@@ -604,41 +608,52 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureKernelAr
     const uint32_t n_sum = __popc(a.summary_mask & 7u);
     const uint64_t record_bytes = off_sum + (uint64_t)n_sum * sum_arr;
 
-    const uint64_t head = (uint64_t)lds[m.bcast + 0] | ((uint64_t)lds[m.bcast + 1] << 32);
+    // Record y of the launch lies y records behind the head the launch found: all records of a
+    // batch have the same size, so record y fits iff the y before it did, and then they were kept.
+    const uint64_t head0 = (uint64_t)lds[m.bcast + 0] | ((uint64_t)lds[m.bcast + 1] << 32);
+    const uint64_t head = head0 + (uint64_t)y * record_bytes;
     const uint32_t flags = lds[m.bcast + 6];
+    const bool publisher = blockIdx.x == 0 && y == 0 && tid == kCtlTid;
     if (flags & kStepSkip) {
         // a sampled-out replay: no record, no sequence number; the chain of head and tail
         // copies still has to reach the next launch
-        if (blockIdx.x == 0 && tid == kCtlTid) {
-            a.ctrl->head[par ^ 1u] = head;
+        if (publisher) {
+            a.ctrl->head[par ^ 1u] = head0;
             a.ctrl->tail_for[par ^ 1u] = tail_now > raw.tail_for ? tail_now : raw.tail_for;
         }
         return;
     }
-    bool dropped = false;
-    if (flags & kStepDropNewest) {
-        const uint64_t tail = (uint64_t)lds[m.bcast + 2] | ((uint64_t)lds[m.bcast + 3] << 32);
-        dropped = head - tail + record_bytes > a.cap;
-    }
+    const uint64_t tail = (uint64_t)lds[m.bcast + 2] | ((uint64_t)lds[m.bcast + 3] << 32);
+    const bool drop_newest = (flags & kStepDropNewest) != 0;
+    const bool dropped = drop_newest && head - tail + record_bytes > a.cap;
 
-    // ---- publish: workgroup 0 leaves head, tail and counters for the next launch and fills
-    //      this launch's commit slot, early, so that it overlaps the copy.  Everything here
-    //      is device memory; it becomes visible to the next launch and to the copy that
-    //      fetches the slot with the kernel-end release.
-    if (blockIdx.x == 0 && tid == kCtlTid) {
+    // ---- publish: one lane of the launch leaves head, tail and counters for the next launch and
+    //      fills the commit slot of the launch's last record, early, so that it overlaps the copy.
+    //      Everything here is device memory; it becomes visible to the next launch and to the copy
+    //      that fetches the slot with the kernel-end release.
+    if (publisher) {
         DevCtrl *c = a.ctrl;
-        const uint64_t new_head = dropped ? head : head + record_bytes;
-        if (dropped) {
-            cnt_drop[0] += 1; cnt_drop[1] += n_rows; cnt_drop[2] += record_bytes;
+        const uint64_t nb_rec = gridDim.y;
+        uint64_t n_fit = nb_rec;
+        if (drop_newest) {
+            const uint64_t used = head0 - tail;
+            n_fit = used < a.cap ? (a.cap - used) / record_bytes : 0u;
+            n_fit = n_fit < nb_rec ? n_fit : nb_rec;
+        }
+        const uint64_t n_drop = nb_rec - n_fit;
+        const uint64_t new_head = head0 + n_fit * record_bytes;
+        if (n_drop) {
+            cnt_drop[0] += n_drop; cnt_drop[1] += n_drop * n_rows; cnt_drop[2] += n_drop * record_bytes;
             c->dropped_records = cnt_drop[0]; c->dropped_rows = cnt_drop[1]; c->dropped_bytes = cnt_drop[2];
-            c->point_drops[a.point_id & 4095u] += 1;
-        } else {
-            cnt_cap[0] += 1; cnt_cap[1] += n_rows; cnt_cap[2] += record_bytes;
+        }
+        if (n_fit) {
+            cnt_cap[0] += n_fit; cnt_cap[1] += n_fit * n_rows; cnt_cap[2] += n_fit * record_bytes;
             c->captured_records = cnt_cap[0]; c->captured_rows = cnt_cap[1]; c->captured_bytes = cnt_cap[2];
         }
         c->head[par ^ 1u] = new_head;
         c->tail_for[par ^ 1u] = tail_now > raw.tail_for ? tail_now : raw.tail_for;
-        CommitSlot *h = a.step ? &c->slots[seq % kCommitSlots] : a.cslot;
+        const uint64_t last_seq = seq + nb_rec - 1u;
+        CommitSlot *h = a.step ? &c->slots[last_seq % kCommitSlots] : a.cslot;
         h->head = new_head;
         h->captured_records = cnt_cap[0];
         h->captured_rows = cnt_cap[1];
@@ -646,13 +661,18 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureKernelAr
         h->dropped_records = cnt_drop[0];
         h->dropped_rows = cnt_drop[1];
         h->dropped_bytes = cnt_drop[2];
-        h->seq_plus1 = seq + 1u;
+        h->seq_plus1 = last_seq + 1u;
     }
+    if (dropped && blockIdx.x == 0 && tid == kCtlTid)
+        atomicAdd(&a.ctrl->point_drops[point_id & 4095u], 1u);
 
+    // Whoever issued a launch of several records made sure they fit the ring together (or the
+    // ones that do not are dropped), so y records past the head are less than one lap away.
     RingW w;
     w.ring = a.ring;
     w.cap = a.cap;
-    w.base = (uint64_t)lds[m.bcast + 4] | ((uint64_t)lds[m.bcast + 5] << 32);
+    w.base = ((uint64_t)lds[m.bcast + 4] | ((uint64_t)lds[m.bcast + 5] << 32)) + (uint64_t)y * record_bytes;
+    if (w.base >= w.cap) w.base -= w.cap;
 
     // row g -> request r (largest r with pref[r] <= g; requests with no rows are skipped
     // because their successor shares the same prefix) -> source location
@@ -684,7 +704,7 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureKernelAr
                 if (j) row += (int64_t)j * (int64_t)a.req_table[r].z;
             }
             ref.ok = row >= 0 && row < a.n_src_rows;
-            ref.base = a.src + (ref.ok ? row : 0) * a.row_stride_b;
+            ref.base = src + (ref.ok ? row : 0) * a.row_stride_b;
         } else {
             uint32_t tok0, tstep, seq_row;
             if (a.table_in_lds) {
@@ -698,7 +718,7 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureKernelAr
             const uint32_t slot = t - lb * a.block_size;
             const int64_t blk = (int64_t)a.block_table[(int64_t)seq_row * a.bt_stride + (int64_t)lb];
             ref.ok = blk >= 0 && blk < a.n_src_rows;
-            ref.base = a.src + (ref.ok ? blk : 0) * a.block_stride_b + (int64_t)slot * a.slot_stride_b;
+            ref.base = src + (ref.ok ? blk : 0) * a.block_stride_b + (int64_t)slot * a.slot_stride_b;
         }
         return ref;
     };
@@ -730,9 +750,10 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureKernelAr
                 uint32_t *h = lds + m.hdr;
                 h[0] = 0x32494D44u;
                 h[1] = 1u | (64u << 16);
-                h[2] = lds[m.bcast + 8];         h[3] = lds[m.bcast + 9];       // seq
+                const uint64_t seq_y = ((uint64_t)lds[m.bcast + 8] | ((uint64_t)lds[m.bcast + 9] << 32)) + y;
+                h[2] = (uint32_t)seq_y;          h[3] = (uint32_t)(seq_y >> 32);
                 h[4] = lds[m.bcast + 10];        h[5] = lds[m.bcast + 11];      // step id
-                h[6] = a.point_id;
+                h[6] = point_id;
                 h[7] = a.src_dtype | (a.out_dtype << 8) | (a.summary_mask << 16) | (a.rec_flags << 24);
                 h[8] = n_reqs;  h[9] = n_rows;  h[10] = a.row_elems;  h[11] = a.rank_tag;
                 h[12] = (uint32_t)record_bytes;  h[13] = (uint32_t)(record_bytes >> 32);
@@ -1049,7 +1070,7 @@ extern "C" int dmi_trace_read(uint64_t *out)
 // workgroup needs in the third, and all three are fetched together at the top.
 struct DecodeArgs {
     // line 0
-    const uint8_t *src;
+    uint64_t spare0;
     int64_t row_stride_b;
     const int32_t *rows;            // row per request (int32 indices or uint32 first rows), unless consecutive
     uint8_t *ring;
@@ -1067,7 +1088,7 @@ struct DecodeArgs {
     const uint4 *req_table;
     CommitSlot *cslot;
     uint64_t payload_bytes;
-    uint32_t point_id, hdr7, rank_tag, pad;
+    uint32_t spare1, hdr7, rank_tag, pad;
     const uint64_t *tail_src;       // where the extra workgroup reads the drained-up-to mark (may be NULL)
     // line 3
     const uint8_t *keep_mask;       // keep vector (MASK variants): request r is captured iff keep_mask[r] != 0
@@ -1084,12 +1105,15 @@ constexpr uint32_t kDecDropNewest = 1u, kDecConsecutive = 2u, kDecIndexed = 4u, 
 // each workgroup derives from those the record's row count and its own row's place.  The
 // row itself is loaded before the vector is known and thrown away if the request is out.
 template <int OUT, bool SUMM, bool MASK>
-__global__ void __launch_bounds__(kThreads) capture_decode_kernel(const DecodeArgs a)
+__global__ void __launch_bounds__(kThreads) capture_decode_kernel(const DecodeArgs a, const BatchArgs b)
 {
     __shared__ uint32_t sh[32];
     __shared__ uint64_t kept_bits[16];      // MASK: bit i of word q = request 64 q + i is kept
     DMI_STAMP_D(0);
-    touch_argument_lines(a);
+    const uint32_t y = blockIdx.y;          // which tensor of the batch
+    const uint8_t *const src = b.src[y];
+    const uint32_t point_id = b.point[y];
+    touch_argument_lines(a, src, point_id);
     constexpr uint32_t U = 4;
     constexpr uint32_t NB_OUT = out_unit_bytes<2, 8, OUT>();
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
@@ -1119,7 +1143,7 @@ __global__ void __launch_bounds__(kThreads) capture_decode_kernel(const DecodeAr
                             : (a.flags & kDecIndexed) ? (int64_t)a.rows[g]
                                                       : (int64_t)reinterpret_cast<const uint32_t *>(a.rows)[g];
         ok = row >= 0 && row < (int64_t)a.n_src_rows;
-        const uint8_t *base = a.src + (ok ? row : 0) * a.row_stride_b;
+        const uint8_t *base = src + (ok ? row : 0) * a.row_stride_b;
 #pragma unroll
         for (uint32_t k = 0; k < U; k++) v[k] = u32x4{0u, 0u, 0u, 0u};
         if (ok) {
@@ -1143,7 +1167,7 @@ __global__ void __launch_bounds__(kThreads) capture_decode_kernel(const DecodeAr
     if (tid == kCtlTid) {
         // the drained-up-to mark for the next launch's drop decision, read where the host keeps
         // it by the extra workgroup's lane, after every other load of that lane
-        const uint64_t *ts = meta_wg && a.tail_src ? a.tail_src : &a.ctrl->tail;
+        const uint64_t *ts = meta_wg && y == 0 && a.tail_src ? a.tail_src : &a.ctrl->tail;
         tail_now = ld_system(ts);
         const Control ct = resolve_control(raw, a.step != nullptr, a.node, a.tail_floor, a.seq, a.step_id,
                                            a.flags & kDecDropNewest);
@@ -1182,12 +1206,13 @@ __global__ void __launch_bounds__(kThreads) capture_decode_kernel(const DecodeAr
     }
     lds_barrier();
     DMI_STAMP_D(2);
-    const uint64_t head = (uint64_t)sh[0] | ((uint64_t)sh[1] << 32);
+    const uint64_t head0 = (uint64_t)sh[0] | ((uint64_t)sh[1] << 32);
     const uint64_t tail = (uint64_t)sh[2] | ((uint64_t)sh[3] << 32);
     const uint32_t flags = sh[6];
+    const bool publisher = meta_wg && y == 0 && tid == kCtlTid;
     if (flags & kStepSkip) {    // sampled-out replay: pass head and tail on, capture nothing
-        if (meta_wg && tid == kCtlTid) {
-            a.ctrl->head[par ^ 1u] = head;
+        if (publisher) {
+            a.ctrl->head[par ^ 1u] = head0;
             a.ctrl->tail_for[par ^ 1u] = tail_now > raw.tail_for ? tail_now : raw.tail_for;
         }
         return;
@@ -1216,37 +1241,53 @@ __global__ void __launch_bounds__(kThreads) capture_decode_kernel(const DecodeAr
         sum_arr = ((uint64_t)n_rows * 4u + 63u) & ~63ull;
         record_bytes = off_sum + (uint64_t)__popc(a.summary_mask & 7u) * sum_arr;
     }
-    const bool dropped = (flags & kStepDropNewest) && head - tail + record_bytes > a.cap;
+    // record y of the launch lies y records behind the head the launch found (all records of a
+    // batch have one size: record y fits iff the y before it did, and then they were kept)
+    const bool drop_newest = (flags & kStepDropNewest) != 0;
+    const uint64_t head = head0 + (uint64_t)y * record_bytes;
+    const bool dropped = drop_newest && head - tail + record_bytes > a.cap;
     RingW w;
     w.ring = a.ring;
     w.cap = a.cap;
-    w.base = (uint64_t)sh[4] | ((uint64_t)sh[5] << 32);
+    w.base = ((uint64_t)sh[4] | ((uint64_t)sh[5] << 32)) + (uint64_t)y * record_bytes;
+    if (w.base >= w.cap) w.base -= w.cap;   // the issuer made sure a launch's records fit the ring together
 
     if (meta_wg) {
-        if (tid == kCtlTid) {
+        if (publisher) {
             DevCtrl *c = a.ctrl;
-            const uint64_t new_head = dropped ? head : head + record_bytes;
-            if (dropped) {
-                cnt_drop[0] += 1; cnt_drop[1] += n_rows; cnt_drop[2] += record_bytes;
+            const uint64_t nb_rec = gridDim.y;
+            uint64_t n_fit = nb_rec;
+            if (drop_newest) {
+                const uint64_t used = head0 - tail;
+                n_fit = used < a.cap ? (a.cap - used) / record_bytes : 0u;
+                n_fit = n_fit < nb_rec ? n_fit : nb_rec;
+            }
+            const uint64_t n_drop = nb_rec - n_fit;
+            const uint64_t new_head = head0 + n_fit * record_bytes;
+            if (n_drop) {
+                cnt_drop[0] += n_drop; cnt_drop[1] += n_drop * n_rows; cnt_drop[2] += n_drop * record_bytes;
                 c->dropped_records = cnt_drop[0]; c->dropped_rows = cnt_drop[1]; c->dropped_bytes = cnt_drop[2];
-                c->point_drops[a.point_id & 4095u] += 1;
-            } else {
-                cnt_cap[0] += 1; cnt_cap[1] += n_rows; cnt_cap[2] += record_bytes;
+            }
+            if (n_fit) {
+                cnt_cap[0] += n_fit; cnt_cap[1] += n_fit * n_rows; cnt_cap[2] += n_fit * record_bytes;
                 c->captured_records = cnt_cap[0]; c->captured_rows = cnt_cap[1]; c->captured_bytes = cnt_cap[2];
             }
             c->head[par ^ 1u] = new_head;
             c->tail_for[par ^ 1u] = tail_now > raw.tail_for ? tail_now : raw.tail_for;
-            CommitSlot *h = a.step ? &c->slots[seq % kCommitSlots] : a.cslot;
+            const uint64_t last_seq = seq + nb_rec - 1u;
+            CommitSlot *h = a.step ? &c->slots[last_seq % kCommitSlots] : a.cslot;
             h->head = new_head;
             h->captured_records = cnt_cap[0]; h->captured_rows = cnt_cap[1]; h->captured_bytes = cnt_cap[2];
             h->dropped_records = cnt_drop[0]; h->dropped_rows = cnt_drop[1]; h->dropped_bytes = cnt_drop[2];
-            h->seq_plus1 = seq + 1u;
+            h->seq_plus1 = last_seq + 1u;
         }
+        if (dropped && tid == kCtlTid) atomicAdd(&a.ctrl->point_drops[point_id & 4095u], 1u);
         if (dropped) return;
         if (tid < 4) {
             u32x4 hv;
-            if (tid == 0) hv = u32x4{0x32494D44u, 1u | (64u << 16), sh[24], sh[25]};
-            else if (tid == 1) hv = u32x4{sh[26], sh[27], a.point_id, a.hdr7};
+            const uint64_t seq_y = ((uint64_t)sh[24] | ((uint64_t)sh[25] << 32)) + y;
+            if (tid == 0) hv = u32x4{0x32494D44u, 1u | (64u << 16), (uint32_t)seq_y, (uint32_t)(seq_y >> 32)};
+            else if (tid == 1) hv = u32x4{sh[26], sh[27], point_id, a.hdr7};
             else if (tid == 2) hv = u32x4{a.n_reqs, n_rows, a.row_elems, a.rank_tag};
             else hv = u32x4{(uint32_t)record_bytes, (uint32_t)(record_bytes >> 32), (uint32_t)payload_bytes,
                             (uint32_t)(payload_bytes >> 32)};
@@ -1369,36 +1410,37 @@ __global__ void __launch_bounds__(kThreads) drain_kernel(const uint8_t *ring, ui
 
 // ---------------------------------------------------------------- launchers
 template <int ES_IN, int VEC, int OUT>
-static hipError_t launch_t(const CaptureArgs &a, uint32_t grid, hipStream_t s)
+static hipError_t launch_t(const CaptureArgs &a, const BatchArgs &b, uint32_t grid, hipStream_t s)
 {
+    const dim3 g(grid, a.n_batch);
     if (a.summary_mask)
-        hipLaunchKernelGGL((capture_kernel<ES_IN, VEC, OUT, true>), dim3(grid), dim3(kThreads), a.lds_bytes, s,
-                           static_cast<const CaptureKernelArgs &>(a));
+        hipLaunchKernelGGL((capture_kernel<ES_IN, VEC, OUT, true>), g, dim3(kThreads), a.lds_bytes, s,
+                           static_cast<const CaptureKernelArgs &>(a), b);
     else
-        hipLaunchKernelGGL((capture_kernel<ES_IN, VEC, OUT, false>), dim3(grid), dim3(kThreads), a.lds_bytes, s,
-                           static_cast<const CaptureKernelArgs &>(a));
+        hipLaunchKernelGGL((capture_kernel<ES_IN, VEC, OUT, false>), g, dim3(kThreads), a.lds_bytes, s,
+                           static_cast<const CaptureKernelArgs &>(a), b);
     return hipGetLastError();
 }
 
 template <int ES_IN, int VEC>
-static hipError_t launch_o(const CaptureArgs &a, uint32_t grid, hipStream_t s)
+static hipError_t launch_o(const CaptureArgs &a, const BatchArgs &b, uint32_t grid, hipStream_t s)
 {
     const bool raw = a.out_dtype == a.src_dtype;
-    if (a.out_dtype == 0) return launch_t<ES_IN, VEC, OUT_NONE>(a, grid, s);
-    if (raw) return launch_t<ES_IN, VEC, OUT_RAW>(a, grid, s);
+    if (a.out_dtype == 0) return launch_t<ES_IN, VEC, OUT_NONE>(a, b, grid, s);
+    if (raw) return launch_t<ES_IN, VEC, OUT_RAW>(a, b, grid, s);
     if constexpr (ES_IN == 2) {
-        if (a.out_dtype == 2) return launch_t<ES_IN, VEC, OUT_FP16>(a, grid, s);
-        if (a.out_dtype == 4) return launch_t<ES_IN, VEC, OUT_FP8>(a, grid, s);
+        if (a.out_dtype == 2) return launch_t<ES_IN, VEC, OUT_FP16>(a, b, grid, s);
+        if (a.out_dtype == 4) return launch_t<ES_IN, VEC, OUT_FP8>(a, b, grid, s);
     }
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_capture(const CaptureArgs &a, uint32_t grid, bool vec16, hipStream_t s)
+hipError_t launch_capture(const CaptureArgs &a, const BatchArgs &b, uint32_t grid, bool vec16, hipStream_t s)
 {
-    if (grid == 0 || grid > kMaxGrid) return hipErrorInvalidValue;
+    if (grid == 0 || grid > kMaxGrid || a.n_batch == 0 || a.n_batch > kMaxBatch) return hipErrorInvalidValue;
     const bool four = a.src_dtype == 3;
-    if (four) return vec16 ? launch_o<4, 4>(a, grid, s) : launch_o<4, 1>(a, grid, s);
-    return vec16 ? launch_o<2, 8>(a, grid, s) : launch_o<2, 1>(a, grid, s);
+    if (four) return vec16 ? launch_o<4, 4>(a, b, grid, s) : launch_o<4, 1>(a, b, grid, s);
+    return vec16 ? launch_o<2, 8>(a, b, grid, s) : launch_o<2, 1>(a, b, grid, s);
 }
 
 bool decode_kernel_applies(const CaptureArgs &a, bool vec16)
@@ -1413,29 +1455,30 @@ bool decode_kernel_applies(const CaptureArgs &a, bool vec16)
 }
 
 template <int OUT>
-static hipError_t launch_decode_t(const DecodeArgs &d, bool summaries, hipStream_t s)
+static hipError_t launch_decode_t(const DecodeArgs &d, const BatchArgs &b, uint32_t n_batch, bool summaries,
+                                  hipStream_t s)
 {
-    const dim3 grid(d.n_wg_rows + 1u);
+    const dim3 grid(d.n_wg_rows + 1u, n_batch);
     if (d.keep_mask) {
         if (summaries)
-            hipLaunchKernelGGL((capture_decode_kernel<OUT, true, true>), grid, dim3(kThreads), 0, s, d);
+            hipLaunchKernelGGL((capture_decode_kernel<OUT, true, true>), grid, dim3(kThreads), 0, s, d, b);
         else
-            hipLaunchKernelGGL((capture_decode_kernel<OUT, false, true>), grid, dim3(kThreads), 0, s, d);
+            hipLaunchKernelGGL((capture_decode_kernel<OUT, false, true>), grid, dim3(kThreads), 0, s, d, b);
     } else {
         if (summaries)
-            hipLaunchKernelGGL((capture_decode_kernel<OUT, true, false>), grid, dim3(kThreads), 0, s, d);
+            hipLaunchKernelGGL((capture_decode_kernel<OUT, true, false>), grid, dim3(kThreads), 0, s, d, b);
         else
-            hipLaunchKernelGGL((capture_decode_kernel<OUT, false, false>), grid, dim3(kThreads), 0, s, d);
+            hipLaunchKernelGGL((capture_decode_kernel<OUT, false, false>), grid, dim3(kThreads), 0, s, d, b);
     }
     return hipGetLastError();
 }
 
-hipError_t launch_capture_decode(const CaptureArgs &a, hipStream_t s)
+hipError_t launch_capture_decode(const CaptureArgs &a, const BatchArgs &b, hipStream_t s)
 {
     if (a.n_src_rows < 0 || a.n_src_rows > 0xFFFFFFFFll) return hipErrorInvalidValue;
+    if (a.n_batch == 0 || a.n_batch > kMaxBatch) return hipErrorInvalidValue;
     DecodeArgs d;
     std::memset(&d, 0, sizeof d);
-    d.src = a.src;
     d.row_stride_b = a.row_stride_b;
     d.rows = a.row_index ? a.row_index : reinterpret_cast<const int32_t *>(a.row_map ? a.row_map : a.row0);
     d.n_wg_rows = a.hdr[9];         // rows listed
@@ -1462,18 +1505,17 @@ hipError_t launch_capture_decode(const CaptureArgs &a, hipStream_t s)
     d.req_table = a.req_table;
     d.cslot = a.cslot;
     d.payload_bytes = a.payload_bytes;
-    d.point_id = a.point_id;
     d.hdr7 = a.hdr[7];
     d.rank_tag = a.rank_tag;
     d.tail_src = a.tail_src;
     d.keep_mask = a.keep_mask;
     if (a.keep_mask && a.n_reqs > 1024u) return hipErrorInvalidValue;
     const bool summ = a.summary_mask != 0;
-    if (a.out_dtype == a.src_dtype) return launch_decode_t<OUT_RAW>(d, summ, s);
+    if (a.out_dtype == a.src_dtype) return launch_decode_t<OUT_RAW>(d, b, a.n_batch, summ, s);
     switch (a.out_dtype) {
-    case 0: return launch_decode_t<OUT_NONE>(d, summ, s);
-    case 2: return launch_decode_t<OUT_FP16>(d, summ, s);
-    case 4: return launch_decode_t<OUT_FP8>(d, summ, s);
+    case 0: return launch_decode_t<OUT_NONE>(d, b, a.n_batch, summ, s);
+    case 2: return launch_decode_t<OUT_FP16>(d, b, a.n_batch, summ, s);
+    case 4: return launch_decode_t<OUT_FP8>(d, b, a.n_batch, summ, s);
     default: return hipErrorInvalidValue;
     }
 }

@@ -116,7 +116,12 @@ extern "C" dmi_status_t dmi_observe_into(uint32_t point_id, const dmi_tensor_t *
     a.par_in = 0;
     a.step = nullptr;
     a.node = 0;
-    const hipError_t e = pl.decode ? launch_capture_decode(a, s) : launch_capture(a, pl.grid, geo.vec16, s);
+    a.n_batch = 1;
+    BatchArgs b;
+    memset(&b, 0, sizeof b);
+    b.src[0] = a.src;
+    b.point[0] = point_id;
+    const hipError_t e = pl.decode ? launch_capture_decode(a, b, s) : launch_capture(a, b, pl.grid, geo.vec16, s);
     if (e != hipSuccess) return fail(DMI_ERR_HIP, "capture launch failed: %s", hipGetErrorString(e));
     if (record_bytes) *record_bytes = pl.ub;
     return DMI_OK;

@@ -167,6 +167,7 @@ struct dmi_ring {
     uint64_t inflight_sum = 0;
     uint64_t unprobed_launches = 0, unprobed_bytes = 0, probe_bytes = 8u << 20;
     uint32_t chain_par = 0;                                // which copy of head / tail_for the next launch reads
+    uint64_t launches = 0;                                 // capture launches issued by dmi_observe*
     bool step_open = false;                                // between dmi_step_begin and dmi_step_end
     std::atomic<int> quiet{0};                             // a capture is open: library threads make no HIP call
     std::atomic<bool> bg_parked{false};
@@ -229,9 +230,10 @@ struct StepTable {                  // one request table, shared by the nodes ca
     uint32_t slot = 0;
 };
 
-struct StepNode {
+struct StepNode {                   // one launch of the step: n_batch records from first_rec on
     CaptureArgs a;
-    Plan pl;
+    uint32_t first_rec = 0, n_batch = 1;
+    Plan pl;                        // per record
     Geometry geo;
     dmi_transform_t xf;
     uint32_t point_id = 0;
@@ -244,6 +246,7 @@ struct dmi_step {
     dmi_ring *r = nullptr;
     uint32_t max_nodes = 0;
     std::vector<StepNode> nodes;
+    std::vector<uint32_t> rec_launch;   // record of the step -> the launch that writes it
     std::vector<StepTable> tables;
     StepParams *dparams = nullptr;  // device
     uint32_t *slab = nullptr;       // device: max_nodes table slots
@@ -262,6 +265,9 @@ dmi_status_t wait_for_room(dmi_ring *r, uint64_t ub);
 dmi_status_t commit_slot_room(dmi_ring *r, uint32_t n);
 void selection_words(const dmi_req_sel_t *reqs, uint32_t n, bool paged, bool row_map, std::vector<uint32_t> &words);
 PlanEnv plan_env(const dmi_ring *r);
+uint32_t plan_grid(const CaptureArgs &a, uint32_t nb);
+bool batch_takes_decode_kernel(const CaptureArgs &a, uint32_t nb);
+dmi_status_t check_batch_sources(uint32_t n, const void *const *data, uint32_t es, bool *all16);
 dmi_status_t plan_capture(const PlanEnv &env, uint32_t point_id, const dmi_selection_t *sel, const dmi_transform_t *xf,
                           const Geometry &geo, CaptureArgs &a, Plan &pl, bool fixed_row_count_ok);
 dmi_status_t check_dense_rows(const dmi_req_sel_t *reqs, uint32_t n, int64_t T);

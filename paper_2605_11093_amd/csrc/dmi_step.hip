@@ -73,20 +73,22 @@ dmi_status_t dmi_step_capture_begin(dmi_step_t *st)
 
 namespace {
 
-// Add one launch to an open step and issue it on the capturing stream.  The only HIP
-// calls made here are the capture-status query and the kernel launch.
-dmi_status_t step_add(dmi_step *st, uint32_t point_id, const dmi_selection_t *sel, const dmi_transform_t *xf,
-                      const Geometry &geo, CaptureArgs &a, uint32_t n_seqs, void *hip_stream, uint32_t *node_out)
+// Add the captures of n tensors of one shape to an open step (n = 1: one observe) and issue
+// their launches, as few as kMaxBatch allows, on the capturing stream.  The only HIP calls made
+// here are the capture-status query and the kernel launches.
+dmi_status_t step_add(dmi_step *st, uint32_t n, const uint32_t *points, const uint8_t *const *srcs,
+                      const dmi_selection_t *sel, const dmi_transform_t *xf, const Geometry &geo, CaptureArgs &a,
+                      uint32_t n_seqs, void *hip_stream, uint32_t *node_out)
 {
     dmi_ring *r = st->r;
-    if (st->nodes.size() >= st->max_nodes)
-        return fail(DMI_ERR_INVALID_ARG, "the step holds max_observes (%u) launches already", st->max_nodes);
+    if (st->rec_launch.size() + n > st->max_nodes)
+        return fail(DMI_ERR_INVALID_ARG, "the step would hold more than max_observes (%u) records", st->max_nodes);
     // outside a capture the launch would run at once, with whatever the parameter block holds
     hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
     if (hipStreamIsCapturing((hipStream_t)hip_stream, &cs) != hipSuccess || cs != hipStreamCaptureStatusActive)
         return fail(DMI_ERR_INVALID_ARG, "hip_stream is not capturing");
     StepNode nd;
-    dmi_status_t rc = plan_capture(plan_env(r), point_id, sel, xf, geo, a, nd.pl, false);
+    dmi_status_t rc = plan_capture(plan_env(r), points[0], sel, xf, geo, a, nd.pl, false);
     if (rc != DMI_OK) return rc;
 
     // nodes captured with the same selection share one table (and are updated together)
@@ -105,54 +107,85 @@ dmi_status_t step_add(dmi_step *st, uint32_t point_id, const dmi_selection_t *se
         t.slot = ti;                // at most one table per node, so slots suffice
         st->tables.push_back(std::move(t));
     }
-    const uint32_t node = (uint32_t)st->nodes.size();
+    if (node_out) *node_out = (uint32_t)st->rec_launch.size();
     uint32_t *slot = st->slab + (size_t)st->tables[ti].slot * r->slab_slot_words;
-    a.req_table = reinterpret_cast<const uint4 *>(slot);
-    a.row0 = slot + 4u * (size_t)sel->n_reqs;
-    a.row_map = nd.pl.row_map ? a.row0 + sel->n_reqs : nullptr;
-    a.seq = 0;
-    a.step_id = 0;
-    a.cslot = nullptr;
-    a.tail_floor = 0;
-    a.drop_newest = 0;
-    a.tail_src = nullptr;           // the device copy that the step's begin launch refreshes
-    a.par_in = node & 1u;           // dmi_step_begin leaves head and tail in copy 0
-    a.step = st->dparams;
-    a.node = node;
-    const hipError_t e = nd.pl.decode ? launch_capture_decode(a, (hipStream_t)hip_stream)
-                                      : launch_capture(a, nd.pl.grid, geo.vec16, (hipStream_t)hip_stream);
-    if (e != hipSuccess) return fail(DMI_ERR_HIP, "capture launch failed: %s", hipGetErrorString(e));
-    nd.a = a;
-    nd.geo = geo;
-    nd.xf = *xf;
-    nd.point_id = point_id;
-    nd.table = ti;
-    nd.index_mode = sel->row_index_dev != nullptr;
-    nd.masked = sel->keep_mask_dev != nullptr;
-    nd.n_seqs = n_seqs;
-    st->nodes.push_back(nd);
-    if (node_out) *node_out = node;
+    BatchArgs b;
+    memset(&b, 0, sizeof b);
+    for (uint32_t done = 0; done < n;) {
+        const uint32_t nb = n - done < kMaxBatch ? n - done : kMaxBatch;
+        const uint32_t launch = (uint32_t)st->nodes.size(), first_rec = (uint32_t)st->rec_launch.size();
+        a.req_table = reinterpret_cast<const uint4 *>(slot);
+        a.row0 = slot + 4u * (size_t)sel->n_reqs;
+        a.row_map = nd.pl.row_map ? a.row0 + sel->n_reqs : nullptr;
+        a.seq = 0;
+        a.n_batch = nb;
+        a.step_id = 0;
+        a.cslot = nullptr;
+        a.tail_floor = 0;
+        a.drop_newest = 0;
+        a.tail_src = nullptr;           // the device copy that the step's begin launch refreshes
+        a.par_in = launch & 1u;         // dmi_step_begin leaves head and tail in copy 0
+        a.step = st->dparams;
+        a.node = first_rec;             // sequence number of the launch's first record, relative to the step's
+        for (uint32_t i = 0; i < nb; i++) { b.src[i] = srcs[done + i]; b.point[i] = points[done + i]; }
+        const bool decode = nd.pl.decode && batch_takes_decode_kernel(a, nb);
+        const hipError_t e = decode ? launch_capture_decode(a, b, (hipStream_t)hip_stream)
+                                    : launch_capture(a, b, plan_grid(a, nb), geo.vec16, (hipStream_t)hip_stream);
+        if (e != hipSuccess) return fail(DMI_ERR_HIP, "capture launch failed: %s", hipGetErrorString(e));
+        nd.a = a;
+        nd.first_rec = first_rec;
+        nd.n_batch = nb;
+        nd.geo = geo;
+        nd.xf = *xf;
+        nd.point_id = points[done];
+        nd.table = ti;
+        nd.index_mode = sel->row_index_dev != nullptr;
+        nd.masked = sel->keep_mask_dev != nullptr;
+        nd.n_seqs = n_seqs;
+        st->nodes.push_back(nd);
+        st->rec_launch.insert(st->rec_launch.end(), nb, launch);
+        done += nb;
+    }
     return DMI_OK;
 }
 
 // Front checks of dmi_step_observe*: state, arguments, hook filtering (a disabled point
 // adds no launch to the step: it is not in the graph at all).
-dmi_status_t step_gate(dmi_step *st, uint32_t point_id, const dmi_selection_t *sel, const dmi_transform_t *xf,
-                       uint32_t src_dtype)
+dmi_status_t step_gate(dmi_step *st, uint32_t n, const uint32_t *point_ids, const dmi_selection_t *sel,
+                       const dmi_transform_t *xf, uint32_t src_dtype, std::vector<uint32_t> &live)
 {
     if (!st) return fail(DMI_ERR_INVALID_ARG, "step is NULL");
     if (!st->open) return fail(DMI_ERR_INVALID_ARG, "call dmi_step_capture_begin first");
     dmi_ring *r = st->r;
     if (!sel || !xf) return fail(DMI_ERR_INVALID_ARG, "selection / transform is NULL");
-    if (point_id >= DMI_MAX_POINTS) return fail(DMI_ERR_INVALID_ARG, "point_id %u >= %u", point_id, DMI_MAX_POINTS);
+    if (n && !point_ids) return fail(DMI_ERR_INVALID_ARG, "point_ids is NULL");
+    for (uint32_t i = 0; i < n; i++)
+        if (point_ids[i] >= DMI_MAX_POINTS)
+            return fail(DMI_ERR_INVALID_ARG, "point_id %u >= %u", point_ids[i], DMI_MAX_POINTS);
     if (sel->n_reqs > r->max_reqs)
         return fail(DMI_ERR_INVALID_ARG, "n_reqs %u exceeds max_reqs_per_observe %u", sel->n_reqs, r->max_reqs);
     if (sel->n_reqs && !sel->reqs) return fail(DMI_ERR_INVALID_ARG, "reqs is NULL");
     if (!transform_ok(src_dtype, xf->out_dtype))
         return fail(DMI_ERR_INVALID_ARG, "unsupported dtype pair %u -> %u", src_dtype, xf->out_dtype);
     if (xf->summary_mask & ~7u) return fail(DMI_ERR_INVALID_ARG, "bad summary_mask %u", xf->summary_mask);
-    if (r->point_off[point_id]) return DMI_POINT_DISABLED;
-    return DMI_OK;
+    live.clear();
+    for (uint32_t i = 0; i < n; i++)
+        if (!r->point_off[point_ids[i]]) live.push_back(i);
+    return live.empty() ? DMI_POINT_DISABLED : DMI_OK;
+}
+
+// The tensors of a batch whose points are enabled, and their captures added to the step.
+dmi_status_t step_add_live(dmi_step *st, const std::vector<uint32_t> &live, const uint32_t *point_ids,
+                           const void *const *data, const dmi_selection_t *sel, const dmi_transform_t *xf,
+                           const Geometry &geo, CaptureArgs &a, uint32_t n_seqs, void *hip_stream, uint32_t *node)
+{
+    std::vector<uint32_t> pts(live.size());
+    std::vector<const uint8_t *> srcs(live.size());
+    for (size_t k = 0; k < live.size(); k++) {
+        pts[k] = point_ids[live[k]];
+        srcs[k] = static_cast<const uint8_t *>(data[live[k]]);
+    }
+    return step_add(st, (uint32_t)live.size(), pts.data(), srcs.data(), sel, xf, geo, a, n_seqs, hip_stream, node);
 }
 
 }  // namespace
@@ -163,12 +196,33 @@ dmi_status_t dmi_step_observe(dmi_step_t *st, uint32_t point_id, const dmi_tenso
                               const dmi_transform_t *xf, void *hip_stream, uint32_t *node)
 {
     if (!t) return fail(DMI_ERR_INVALID_ARG, "tensor is NULL");
-    dmi_status_t g = step_gate(st, point_id, sel, xf, t->dtype);
+    std::vector<uint32_t> live;
+    dmi_status_t g = step_gate(st, 1u, &point_id, sel, xf, t->dtype, live);
     if (g != DMI_OK) return g;
     Geometry geo;
     CaptureArgs a;
     if ((g = prep_dense(t, sel, geo, a)) != DMI_OK) return g;
-    return step_add(st, point_id, sel, xf, geo, a, 0u, hip_stream, node);
+    return step_add(st, 1u, &point_id, &a.src, sel, xf, geo, a, 0u, hip_stream, node);
+}
+
+dmi_status_t dmi_step_observe_batch(dmi_step_t *st, uint32_t n, const uint32_t *point_ids, const void *const *data,
+                                    const dmi_tensor_t *like, const dmi_selection_t *sel, const dmi_transform_t *xf,
+                                    void *hip_stream, uint32_t *node)
+{
+    if (!like) return fail(DMI_ERR_INVALID_ARG, "tensor description is NULL");
+    if (!n || !data) return fail(DMI_ERR_INVALID_ARG, "empty batch / data is NULL");
+    std::vector<uint32_t> live;
+    dmi_status_t g = step_gate(st, n, point_ids, sel, xf, like->dtype, live);
+    if (g != DMI_OK) return g;
+    dmi_tensor_t t = *like;
+    t.data = data[0];
+    Geometry geo;
+    CaptureArgs a;
+    if ((g = prep_dense(&t, sel, geo, a)) != DMI_OK) return g;
+    bool all16 = true;
+    if ((g = check_batch_sources(n, data, dtype_size(t.dtype), &all16)) != DMI_OK) return g;
+    geo.vec16 = geo.vec16 && all16;
+    return step_add_live(st, live, point_ids, data, sel, xf, geo, a, 0u, hip_stream, node);
 }
 
 dmi_status_t dmi_step_observe_paged(dmi_step_t *st, uint32_t point_id, const dmi_paged_kv_t *kv,
@@ -176,12 +230,34 @@ dmi_status_t dmi_step_observe_paged(dmi_step_t *st, uint32_t point_id, const dmi
                                     uint32_t *node)
 {
     if (!kv) return fail(DMI_ERR_INVALID_ARG, "kv is NULL");
-    dmi_status_t g = step_gate(st, point_id, sel, xf, kv->dtype);
+    std::vector<uint32_t> live;
+    dmi_status_t g = step_gate(st, 1u, &point_id, sel, xf, kv->dtype, live);
     if (g != DMI_OK) return g;
     Geometry geo;
     CaptureArgs a;
     if ((g = prep_paged(kv, sel, geo, a)) != DMI_OK) return g;
-    return step_add(st, point_id, sel, xf, geo, a, kv->n_seqs, hip_stream, node);
+    return step_add(st, 1u, &point_id, &a.src, sel, xf, geo, a, kv->n_seqs, hip_stream, node);
+}
+
+dmi_status_t dmi_step_observe_paged_batch(dmi_step_t *st, uint32_t n, const uint32_t *point_ids,
+                                          const void *const *bases, const dmi_paged_kv_t *like,
+                                          const dmi_selection_t *sel, const dmi_transform_t *xf, void *hip_stream,
+                                          uint32_t *node)
+{
+    if (!like) return fail(DMI_ERR_INVALID_ARG, "kv description is NULL");
+    if (!n || !bases) return fail(DMI_ERR_INVALID_ARG, "empty batch / bases is NULL");
+    std::vector<uint32_t> live;
+    dmi_status_t g = step_gate(st, n, point_ids, sel, xf, like->dtype, live);
+    if (g != DMI_OK) return g;
+    dmi_paged_kv_t kv = *like;
+    kv.base = bases[0];
+    Geometry geo;
+    CaptureArgs a;
+    if ((g = prep_paged(&kv, sel, geo, a)) != DMI_OK) return g;
+    bool all16 = true;
+    if ((g = check_batch_sources(n, bases, dtype_size(kv.dtype), &all16)) != DMI_OK) return g;
+    geo.vec16 = geo.vec16 && all16;
+    return step_add_live(st, live, point_ids, bases, sel, xf, geo, a, kv.n_seqs, hip_stream, node);
 }
 
 dmi_status_t dmi_step_seal(dmi_step_t *st)
@@ -191,7 +267,7 @@ dmi_status_t dmi_step_seal(dmi_step_t *st)
     st->open = false;
     st->sealed = true;
     st->sum_ub = st->sum_listed = 0;
-    for (auto &nd : st->nodes) { st->sum_ub += nd.pl.ub; st->sum_listed += nd.pl.listed; }
+    for (auto &nd : st->nodes) { st->sum_ub += nd.pl.ub * nd.n_batch; st->sum_listed += nd.pl.listed * nd.n_batch; }
     st->r->quiet.store(0, std::memory_order_release);
     return DMI_OK;
 }
@@ -201,9 +277,9 @@ dmi_status_t dmi_step_update(dmi_step_t *st, uint32_t node, const dmi_req_sel_t 
     if (!st || !reqs) return fail(DMI_ERR_INVALID_ARG, "NULL argument");
     if (!st->sealed) return fail(DMI_ERR_INVALID_ARG, "the step is not sealed");
     if (st->begun) return fail(DMI_ERR_INVALID_ARG, "between dmi_step_begin and dmi_step_end");
-    if (node >= st->nodes.size()) return fail(DMI_ERR_INVALID_ARG, "no node %u", node);
+    if (node >= st->rec_launch.size()) return fail(DMI_ERR_INVALID_ARG, "no node %u", node);
     dmi_ring *r = st->r;
-    const uint32_t ti = st->nodes[node].table;
+    const uint32_t ti = st->nodes[st->rec_launch[node]].table;
     StepTable &tab = st->tables[ti];
     if (n_reqs != tab.reqs.size())
         return fail(DMI_ERR_INVALID_ARG, "the node was captured with %zu requests, not %u", tab.reqs.size(), n_reqs);
@@ -237,8 +313,8 @@ dmi_status_t dmi_step_update(dmi_step_t *st, uint32_t node, const dmi_req_sel_t 
     size_t k = 0;
     for (auto &nd : st->nodes) {
         if (nd.table != ti) continue;
-        st->sum_ub += ubs[k] - nd.pl.ub;
-        st->sum_listed += listed - nd.pl.listed;
+        st->sum_ub += (ubs[k] - nd.pl.ub) * nd.n_batch;
+        st->sum_listed += (listed - nd.pl.listed) * nd.n_batch;
         nd.pl.ub = ubs[k++];
         nd.pl.listed = listed;
     }
@@ -256,7 +332,7 @@ dmi_status_t dmi_step_begin(dmi_step_t *st, uint64_t step_id, void *hip_stream)
     if (st->begun || r->step_open) return fail(DMI_ERR_INVALID_ARG, "a step is already between begin and end");
     (void)hipSetDevice(r->dev);
     hipStream_t s = (hipStream_t)hip_stream;
-    const uint32_t n = (uint32_t)st->nodes.size();
+    const uint32_t n = (uint32_t)st->rec_launch.size();
     const uint32_t mode = r->mode.load(std::memory_order_relaxed);
     const uint32_t k = r->sample_k.load(std::memory_order_relaxed);
     const bool skip = step_id % k != r->sample_phase.load(std::memory_order_relaxed);
@@ -311,23 +387,24 @@ dmi_status_t dmi_step_end(dmi_step_t *st, void *hip_stream)
     if (!st->begun) return fail(DMI_ERR_INVALID_ARG, "dmi_step_begin has not been called");
     dmi_ring *r = st->r;
     (void)hipSetDevice(r->dev);
-    const uint32_t n = (uint32_t)st->nodes.size();
+    const uint32_t n = (uint32_t)st->rec_launch.size();
     st->begun = false;
     r->step_open = false;
-    r->chain_par = n & 1u;
+    r->chain_par = (uint32_t)st->nodes.size() & 1u;
     r->last_launch_ns.store(now_ns(), std::memory_order_relaxed);
     r->last_stream.store(hip_stream, std::memory_order_release);
     if (st->skipped || !n) return DMI_OK;
-    for (uint32_t i = 0; i < n; i++) {
-        r->inflight.emplace_back(st->seq_base + i, st->nodes[i].pl.ub);
-        r->inflight_sum += st->nodes[i].pl.ub;
+    for (auto &nd : st->nodes) {
+        r->inflight.emplace_back(st->seq_base + nd.first_rec + nd.n_batch - 1u, nd.pl.ub * nd.n_batch);
+        r->inflight_sum += nd.pl.ub * nd.n_batch;
     }
     {
         std::lock_guard<std::mutex> lk(r->pmu);
         r->next_seq.store(st->seq_base + n, std::memory_order_release);
         for (auto &nd : st->nodes) {
             if (st->drop_newest || nd.masked) { r->window_exact = false; break; }
-            r->window.bytes += nd.pl.ub; r->window.records += 1; r->window.rows += nd.pl.listed;
+            r->window.bytes += nd.pl.ub * nd.n_batch; r->window.records += nd.n_batch;
+            r->window.rows += nd.pl.listed * nd.n_batch;
         }
     }
     r->unprobed_launches = 0;

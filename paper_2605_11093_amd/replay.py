@@ -52,6 +52,59 @@ def observe_call(ring: B.Ring, call, stream_handle: int, keep_alive: list, allow
                               keep_mask=km, allow=allow)
 
 
+def _same_arr(x, y) -> bool:
+    return (x is None and y is None) or (x is not None and y is not None and np.array_equal(x, y))
+
+
+def batchable(a, b) -> bool:
+    """Can call b ride in the same launch as call a?  Same layout, selection and transform."""
+    if (a.paged is None) != (b.paged is None):
+        return False
+    ta, tb = a.tensor, b.tensor
+    if ta.dtype != tb.dtype or tuple(ta.shape) != tuple(tb.shape) or tuple(ta.stride()) != tuple(tb.stride()):
+        return False
+    if a.out_dtype != b.out_dtype or a.summary_mask != b.summary_mask or a.step_id != b.step_id:
+        return False
+    if not (np.array_equal(a.reqs, b.reqs) and _same_arr(a.keep_mask, b.keep_mask)
+            and _same_arr(a.row_index, b.row_index)):
+        return False
+    if a.paged is not None:
+        pa, pb = a.paged, b.paged
+        if (pa.block_size, pa.n_heads, pa.head_dim, list(pa.heads_sel)) != (pb.block_size, pb.n_heads, pb.head_dim,
+                                                                            list(pb.heads_sel)):
+            return False
+        if pa.block_table is not pb.block_table and not torch.equal(pa.block_table, pb.block_table):
+            return False
+    return True
+
+
+def group_calls(calls, max_batch: int):
+    """Consecutive calls of a step that can share a launch, in hook order."""
+    groups: List[list] = []
+    for c in calls:
+        if groups and len(groups[-1]) < max_batch and batchable(groups[-1][0], c):
+            groups[-1].append(c)
+        else:
+            groups.append([c])
+    return groups
+
+
+def observe_group(ring: B.Ring, group, stream_handle: int, keep_alive: list, allow=()):
+    """One dmi_observe_batch / dmi_observe_paged_batch for a group of calls -> (status, n_done)."""
+    c = group[0]
+    dev = c.tensor.device
+    km = ri = None
+    if c.keep_mask is not None:
+        km = torch.from_numpy(np.ascontiguousarray(c.keep_mask, dtype=np.uint8)).to(dev)
+        keep_alive.append(km)
+    if c.row_index is not None:
+        ri = torch.from_numpy(np.ascontiguousarray(c.row_index, dtype=np.int32)).to(dev)
+        keep_alive.append(ri)
+    return ring.observe_batch([g.point_id for g in group], [g.tensor for g in group], c.reqs, step_id=c.step_id,
+                              stream=stream_handle, out_dtype=c.out_dtype, summary_mask=c.summary_mask,
+                              keep_mask=km, row_index=ri, paged=c.paged, allow=allow)
+
+
 def consume(ring: B.Ring, run: GpuRun, collect: bool, release: bool,
             on_record: Optional[Callable] = None):
     """Poll every complete record, hand it on, release it."""
@@ -77,11 +130,14 @@ def run_workload_gpu(wl, *, drain_every: int = 1, release: bool = True, collect:
                      max_steps=None, lockstep: bool = True, on_record=None,
                      block_timeout_ms: int = 1, poison: Optional[int] = None,
                      ring: Optional[B.Ring] = None, drain_flags: int = 0,
-                     bg_min_bytes: int = 0, before_observe: Optional[Callable] = None) -> GpuRun:
+                     bg_min_bytes: int = 0, before_observe: Optional[Callable] = None,
+                     batch: int = 0) -> GpuRun:
     """Lockstep schedule (the one the oracle's model follows): a step's observes,
     then every `drain_every` steps a flush-drain followed by poll + release.
     With lockstep=False the drain after a step moves only what has committed by
-    then, without waiting for the step's kernels."""
+    then, without waiting for the step's kernels.  batch > 0: consecutive calls of
+    a step that share layout, selection and transform go out together through
+    dmi_observe_batch, at most `batch` per call."""
     own = ring is None
     if own:
         ring = B.Ring(device_ring_bytes or wl.device_ring_bytes, host_ring_bytes or wl.host_ring_bytes,
@@ -97,7 +153,23 @@ def run_workload_gpu(wl, *, drain_every: int = 1, release: bool = True, collect:
         for step, calls in wl.steps():
             if max_steps is not None and step >= max_steps:
                 break
-            for c in calls:
+            for group in (group_calls(calls, batch) if batch else ()):
+                if before_observe is not None:
+                    for c in group:
+                        before_observe(c, s.cuda_stream)
+                tries = 0
+                while group:
+                    rc, done = observe_group(ring, group, s.cuda_stream, keep_alive,
+                                             allow=(B.ERR_AGAIN,) if tries < 200000 else ())
+                    if rc == B.OK:
+                        # disabled points are skipped inside the call; the oracle's driver lists what ran
+                        run.launched.extend(c for c in group[:done])
+                    group = group[done:]
+                    if rc == B.ERR_AGAIN:
+                        # completeness policy, no room: this thread is also the consumer
+                        consume(ring, run, collect, release, on_record)
+                        tries += 1
+            for c in (() if batch else calls):
                 if before_observe is not None:
                     before_observe(c, s.cuda_stream)       # e.g. the model compute that produces the tensor
                 rc = observe_call(ring, c, s.cuda_stream, keep_alive, allow=(B.ERR_AGAIN,))
@@ -140,7 +212,8 @@ def run_workload_gpu(wl, *, drain_every: int = 1, release: bool = True, collect:
 
 def run_workload_graph(wl, *, n_graph: Optional[int] = None, drain_every: int = 1, release: bool = True,
                        flags: int = 0, device_ring_bytes=None, host_ring_bytes=None, lockstep: bool = True,
-                       block_timeout_ms: int = 1, bg_min_bytes: int = 0, replays_per_capture: int = 0) -> GpuRun:
+                       block_timeout_ms: int = 1, bg_min_bytes: int = 0, replays_per_capture: int = 0,
+                       batch: int = 0) -> GpuRun:
     """Feed a host-side workload whose steps repeat a fixed list of observes through
     a captured graph: the first `n_graph` calls of step 0 are captured once
     (torch.cuda.graph over dmi_step_observe launches on static device buffers); every
@@ -148,7 +221,10 @@ def run_workload_graph(wl, *, n_graph: Optional[int] = None, drain_every: int = 
     those buffers, hands changed request tables to dmi_step_update, and replays the
     graph between dmi_step_begin and dmi_step_end.  Calls beyond the first n_graph of
     a step go through dmi_observe.  replays_per_capture > 0 re-captures the graph
-    (a new step object) after that many replays."""
+    (a new step object) after that many replays.  batch > 0: consecutive fixed calls that
+    share layout, selection and transform are captured as one dmi_step_observe_batch
+    launch (at most `batch` of them); their keep vector, row indices and block table are
+    then the first one's static buffers."""
     dev = "cuda:0"
     n_graph = wl.notes["n_graph"] if n_graph is None else n_graph
     ring = B.Ring(device_ring_bytes or wl.device_ring_bytes, host_ring_bytes or wl.host_ring_bytes,
@@ -177,6 +253,7 @@ def run_workload_graph(wl, *, n_graph: Optional[int] = None, drain_every: int = 
                 self.table.copy_(c.paged.block_table)
 
     statics = [Static(c) for c in calls0]
+    groups0 = group_calls(calls0, batch) if batch else [[c] for c in calls0]
 
     def capture():
         step = B.Step(ring, max(1, n_graph))
@@ -184,7 +261,23 @@ def run_workload_graph(wl, *, n_graph: Optional[int] = None, drain_every: int = 
         step.capture_begin()
         with torch.cuda.graph(graph):
             h = torch.cuda.current_stream().cuda_stream
-            for c, st in zip(calls0, statics):
+            pos = 0
+            for grp in groups0:
+                sts = statics[pos: pos + len(grp)]
+                pos += len(grp)
+                c, st = grp[0], sts[0]
+                if len(grp) > 1:
+                    spec = None
+                    if c.paged is not None:
+                        p = c.paged
+                        spec = type(p)(p.block_size, p.n_heads, p.head_dim, p.heads_sel, st.table)
+                    first = step.observe_batch([g.point_id for g in grp], [x.tensor for x in sts], c.reqs, stream=h,
+                                               out_dtype=c.out_dtype, summary_mask=c.summary_mask, keep_mask=st.keep,
+                                               row_index=st.rows, paged=spec)
+                    for i, x in enumerate(sts):
+                        x.node = first + i if first >= 0 else -1
+                        x.reqs = np.array(c.reqs, copy=True)
+                    continue
                 if c.paged is None:
                     node = step.observe_tensor(c.point_id, st.tensor, c.reqs, stream=h, out_dtype=c.out_dtype,
                                                summary_mask=c.summary_mask, keep_mask=st.keep, row_index=st.rows)

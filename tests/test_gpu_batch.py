@@ -1,0 +1,341 @@
+"""Batched captures (dmi_observe_batch, dmi_observe_paged_batch, dmi_step_observe_batch):
+several observation points in one launch must give exactly the stream of the same observes
+issued one by one.  The oracle knows nothing of batches: it builds the records of the single
+calls, in hook order, and the batched HIP path is compared with that."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as orc
+from oracle.replay import run_workload
+from workloads import configs, prng
+from _util import compare_record, compare_streams
+
+pytestmark = pytest.mark.gpu
+
+DT_NONE, DT_BF16, DT_FP16, DT_FP32, DT_FP8 = 0, 1, 2, 3, 4
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def B():
+    assert torch.cuda.is_available()
+    from paper_2605_11093_amd import binding
+    binding.lib()
+    return binding
+
+
+@pytest.fixture(scope="module")
+def run_gpu(B):
+    from paper_2605_11093_amd.replay import run_workload_gpu
+    return run_workload_gpu
+
+
+def _batch(B, tensors, reqs, *, points=None, out_dtype=None, summary_mask=0, keep_mask=None, row_index=None,
+           paged=None, ring_bytes=1 << 23, poison=0xA5, policy=None):
+    """One batched observe on a fresh, poisoned ring -> list of (gpu record, oracle record)."""
+    reqs = np.asarray(reqs, dtype=np.uint32).reshape(-1, 5)
+    n = len(tensors)
+    points = list(range(10, 10 + n)) if points is None else points
+    src_dt = {torch.bfloat16: 1, torch.float16: 2, torch.float32: 3}[tensors[0].dtype]
+    od = src_dt if out_dtype is None else out_dtype
+    with B.Ring(ring_bytes, ring_bytes, max_reqs_per_observe=2048) as ring:
+        ring.debug_fill_rings(poison)
+        if policy is not None:
+            ring.set_policy(policy)
+        s = torch.cuda.current_stream()
+        km = None if keep_mask is None else torch.tensor(keep_mask, dtype=torch.uint8, device=DEV)
+        ri = None if row_index is None else torch.tensor(row_index, dtype=torch.int32, device=DEV)
+        rc, done = ring.observe_batch(points, tensors, reqs, step_id=21, stream=s.cuda_stream, out_dtype=od,
+                                      summary_mask=summary_mask, keep_mask=km, row_index=ri, paged=paged)
+        assert rc == B.OK and done == n
+        ring.drain(B.DRAIN_FLUSH)
+        views = ring.poll_host(256)
+        assert [v.seq for v in views] == list(range(n))
+        got = [v.bytes() for v in views]
+        st = ring.get_stats()
+        assert st.captured_records == n and st.launched_records == n and st.observed_calls == n
+        s.synchronize()
+    cpu_paged = None
+    if paged is not None:
+        cpu_paged = configs.PagedSpec(paged.block_size, paged.n_heads, paged.head_dim, paged.heads_sel,
+                                      paged.block_table.cpu())
+    out = []
+    for i, t in enumerate(tensors):
+        ref = orc.build_record(t.cpu(), reqs, seq=i, step_id=21, point_id=points[i], out_dtype=od,
+                               summary_mask=summary_mask, keep_mask=keep_mask, row_index=row_index, paged=cpu_paged)
+        out.append((got[i], ref))
+    return out
+
+
+def _tensors(seed, n, T, E, pitch=None, dtype=torch.bfloat16):
+    pitch = pitch or E
+    out = []
+    for i in range(n):
+        t = prng.randn_bf16(prng.sub_seed(seed, i), T * pitch, DEV).view(T, pitch)[:, :E]
+        out.append(t.to(dtype) if dtype != torch.bfloat16 else t)
+    return out
+
+
+# ------------------------------------------------------------------ one batched call, every kernel path
+@pytest.mark.parametrize("n", [1, 2, 7, 128])
+def test_decode_shaped_batch(B, n):
+    ts = _tensors(31, n, 16, 512)
+    reqs = [(100 + r, r, 0, 1, 1) for r in range(16)]
+    for got, ref in _batch(B, ts, reqs, summary_mask=5):
+        compare_record(got, ref)
+    for got, ref in _batch(B, ts, reqs):
+        assert np.array_equal(got, ref)
+
+
+def test_decode_shaped_batch_with_keep_vector_and_fp8(B):
+    ts = _tensors(32, 9, 70, 1024)
+    reqs = [(r, 69 - r, 0, 1, 1) for r in range(70)]
+    mask = (np.arange(70) % 3 != 1).astype(np.uint8)
+    for got, ref in _batch(B, ts, reqs, keep_mask=mask, out_dtype=DT_FP8, summary_mask=7):
+        compare_record(got, ref)
+
+
+@pytest.mark.parametrize("n,T,E", [(33, 256, 8192), (70, 128, 16384), (40, 230, 4096)])
+def test_large_decode_shaped_batch_takes_the_general_kernel(B, n, T, E):
+    """Beyond some eight thousand rows a decode-shaped batch goes through the general kernel, a
+    workgroup per work item (rows of 1024 units, rows of two items, two rows per item)."""
+    ts = _tensors(43, n, T, E)
+    reqs = [(7000 + r, T - 1 - r, 0, 1, 1) for r in range(T)]
+    res = _batch(B, ts, reqs, ring_bytes=(n + 2) * orc.record_bytes(T, T, E, 1, 0) // 64 * 64)
+    for got, ref in res:
+        assert np.array_equal(got, ref)
+
+
+@pytest.mark.parametrize("E,T", [(4096, 300), (256, 3000), (14336, 40), (8192, 256)])
+@pytest.mark.parametrize("out_dtype", [DT_BF16, DT_FP8])
+def test_general_kernel_batch_long_rows(B, E, T, out_dtype):
+    ts = _tensors(33, 3, T, E)
+    reqs = [(1, 0, 0, T // 3, 2), (2, 2 * (T // 3), 1, T // 4, 1), (3, T - 1, 0, 1, 1)]
+    # a keep vector with several rows per request keeps the launch on the general kernel
+    for got, ref in _batch(B, ts, reqs, out_dtype=out_dtype, keep_mask=[1, 1, 1], ring_bytes=1 << 25):
+        assert np.array_equal(got, ref)
+    # without one, selections of up to 1024 rows take the decode-shaped kernel (a row map behind the table)
+    for got, ref in _batch(B, ts, reqs, out_dtype=out_dtype, ring_bytes=1 << 25):
+        assert np.array_equal(got, ref)
+
+
+def test_general_kernel_batch_with_summaries_masks_and_indices(B):
+    ts = _tensors(34, 5, 300, 512)
+    reqs = [(10 + i, 20 * i, 0, 3 + i, 2) for i in range(9)]
+    mask = [1, 0, 1, 1, 0, 0, 1, 0, 1]
+    n = sum(r[3] for r in reqs)
+    idx = (np.arange(n) * 37 + 11) % 300
+    for got, ref in _batch(B, ts, reqs, keep_mask=mask, summary_mask=7):
+        compare_record(got, ref)
+    for got, ref in _batch(B, ts, reqs, row_index=idx, keep_mask=mask, out_dtype=DT_FP16):
+        assert np.array_equal(got, ref)
+    for got, ref in _batch(B, ts, reqs, keep_mask=[0] * 9):
+        assert np.array_equal(got, ref) and got.size == 64 + 192
+
+
+@pytest.mark.parametrize("E", [3, 250, 2056])
+def test_batch_of_rows_that_are_not_16_byte_movable(B, E):
+    ts = _tensors(35, 4, 37, E, pitch=E + 24)
+    # one of the tensors sits at an odd element offset: the whole batch takes the element-wise kernel
+    buf = prng.randn_bf16(36, 37 * (E + 24) + 8, DEV)
+    ts[2] = buf[1: 1 + 37 * (E + 24)].view(37, E + 24)[:, :E]
+    reqs = [(1, 0, 2, 3, 1), (2, 10, 0, 6, 4), (3, 36, 0, 1, 1), (4, 5, 0, 0, 1)]
+    for got, ref in _batch(B, ts, reqs, summary_mask=2):
+        compare_record(got, ref)
+
+
+def test_fp32_batch(B):
+    ts = _tensors(37, 3, 40, 512, dtype=torch.float32)
+    for got, ref in _batch(B, ts, [(1, 3, 1, 9, 2), (2, 30, 0, 10, 1)], summary_mask=7):
+        compare_record(got, ref)
+
+
+def test_paged_batch(B):
+    NB, BS, NH, HD = 64, 16, 8, 128
+    caches = [prng.randn_bf16(prng.sub_seed(38, i), NB * BS * NH * HD, DEV).view(NB, BS, NH, HD) for i in range(4)]
+    table = torch.from_numpy(prng.permutation(3, NB).astype(np.int32).reshape(4, 16)).to(DEV)
+    spec = configs.PagedSpec(BS, NH, HD, [1, 5], table)
+    reqs = [(1, 2, 0, 200, 1), (2, 0, 5, 40, 3), (3, 3, 255, 1, 1)]
+    for got, ref in _batch(B, caches, reqs, paged=spec):
+        assert np.array_equal(got, ref)
+    for got, ref in _batch(B, caches, reqs, paged=spec, keep_mask=[0, 1, 1], summary_mask=5, out_dtype=DT_FP8):
+        compare_record(got, ref)
+
+
+def test_batch_larger_than_one_launch_and_mixed_layout_is_refused(B):
+    ts = _tensors(39, 131, 4, 64)                     # 131 tensors: two launches (128 + 3)
+    reqs = [(1, 0, 0, 2, 1), (2, 3, 0, 1, 1)]
+    res = _batch(B, ts, reqs, points=[p % 4096 for p in range(500, 631)])
+    assert len(res) == 131
+    for got, ref in res:
+        assert np.array_equal(got, ref)
+    with pytest.raises(ValueError):
+        with B.Ring(1 << 20, 1 << 20) as ring:
+            ring.observe_batch([1, 2], [ts[0], _tensors(40, 1, 4, 128)[0]], reqs, step_id=0)
+
+
+# ------------------------------------------------------------------ policy inside a batch
+def test_disabled_points_and_sampling_inside_a_batch(B):
+    ts = _tensors(41, 6, 8, 256)
+    reqs = np.array([(r, r, 0, 1, 1) for r in range(8)], dtype=np.uint32)
+    pts = [3, 4, 5, 6, 7, 8]
+    with B.Ring(1 << 20, 1 << 20) as ring:
+        s = torch.cuda.current_stream().cuda_stream
+        ring.point_enable(4, False)
+        ring.point_enable(8, False)
+        rc, done = ring.observe_batch(pts, ts, reqs, step_id=0, stream=s)
+        assert rc == B.OK and done == 6
+        ring.set_policy(B.POLICY_BLOCK, 2, 0)
+        rc, done = ring.observe_batch(pts, ts, reqs, step_id=1, stream=s)     # sampled out
+        assert rc == B.SAMPLED_OUT and done == 6
+        for p in (3, 5, 6, 7):
+            ring.point_enable(p, False)
+        rc, done = ring.observe_batch(pts, ts, reqs, step_id=2, stream=s)     # nothing enabled
+        assert rc == B.POINT_DISABLED and done == 6
+        ring.drain(B.DRAIN_FLUSH)
+        views = ring.poll_host()
+        assert [v.seq for v in views] == [0, 1, 2, 3]
+        for v, i in zip(views, (0, 2, 3, 4)):
+            ref = orc.build_record(ts[i].cpu(), reqs, seq=v.seq, step_id=0, point_id=pts[i], out_dtype=1)
+            assert np.array_equal(v.bytes(), ref)
+        st = ring.get_stats()
+        assert st.observed_calls == 18 and st.launched_records == 4 and st.captured_records == 4
+        assert st.disabled_calls == 2 + 2 + 6 and st.sampled_out_calls == 4 and st.sampled_out_rows == 32
+
+
+def test_drop_newest_in_the_middle_of_a_batch(B):
+    """Ring of 5.5 records, batch of 8: records 0..4 stay, 5..7 are dropped and counted per point;
+    a second batch with the ring still full drops everything; after a drain it is admitted again."""
+    ts = _tensors(42, 8, 16, 512)
+    reqs = np.array([(r, r, 0, 1, 1) for r in range(16)], dtype=np.uint32)
+    rb = orc.record_bytes(16, 16, 512, 1, 0)
+    pts = [20, 21, 22, 23, 24, 25, 26, 25]
+    with B.Ring(rb * 5 + rb // 2 // 64 * 64, 1 << 22) as ring:
+        ring.set_policy(B.POLICY_DROP_NEWEST)
+        s = torch.cuda.current_stream()
+        ring.observe_batch(pts, ts, reqs, step_id=0, stream=s.cuda_stream)
+        ring.observe_batch(pts, ts, reqs, step_id=1, stream=s.cuda_stream)
+        s.synchronize()
+        ring.drain(B.DRAIN_FLUSH)
+        views = ring.poll_host()
+        assert [v.seq for v in views] == [0, 1, 2, 3, 4]
+        ring.release_host(4)
+        ring.observe_batch(pts[:3], ts[:3], reqs, step_id=2, stream=s.cuda_stream)
+        s.synchronize()
+        ring.drain(B.DRAIN_FLUSH)
+        more = ring.poll_host()
+        assert [v.seq for v in more] == [16, 17, 18]
+        for v in views:
+            ref = orc.build_record(ts[v.seq].cpu(), reqs, seq=v.seq, step_id=0, point_id=pts[v.seq], out_dtype=1)
+            assert np.array_equal(v.bytes(), ref)
+        for v in more:
+            i = v.seq - 16
+            ref = orc.build_record(ts[i].cpu(), reqs, seq=v.seq, step_id=2, point_id=pts[i], out_dtype=1)
+            assert np.array_equal(v.bytes(), ref)
+        st = ring.get_stats()
+        assert (st.captured_records, st.dropped_records) == (8, 11)
+        assert (st.dropped_rows, st.dropped_bytes) == (11 * 16, 11 * rb)
+        drops = {p: ring.get_point_drops(p) for p in set(pts)}
+        assert drops == {20: 1, 21: 1, 22: 1, 23: 1, 24: 1, 25: 4, 26: 2}
+
+
+def test_block_policy_splits_a_batch_that_exceeds_the_ring(B, run_gpu):
+    """Device ring of 2 records, batches of 8 under the completeness policy: the library issues
+    the batch in pieces and waits for the drain in between; nothing is lost."""
+    wl = configs.config1_tiny(device=DEV)
+    got = run_gpu(wl, device_ring_bytes=4352, host_ring_bytes=8192, poison=0x5A, batch=128)
+    assert np.array_equal(got.stream, run_workload(wl).stream())
+    assert got.stats.dev_ring_high_water <= 4352
+
+
+# ------------------------------------------------------------------ whole workloads, batched
+def test_config1_batched_equals_oracle_stream(run_gpu):
+    wl = configs.config1_tiny(device=DEV)
+    got = run_gpu(wl, poison=0xA5, batch=128)
+    assert np.array_equal(got.stream, run_workload(wl).stream())
+    got = run_gpu(wl, device_ring_bytes=8192, host_ring_bytes=16384, poison=0xA5, batch=3)
+    assert np.array_equal(got.stream, run_workload(wl).stream())
+
+
+def test_config2_batched_with_summaries(run_gpu):
+    wl = configs.config2_decode8b(device=DEV, n_points=6, n_steps=5,
+                                  device_ring_bytes=4 << 20, host_ring_bytes=8 << 20)
+    got = run_gpu(wl, poison=0xA5, batch=128)
+    assert got.stats.captured_records == 30
+    compare_streams(got.stream, run_workload(wl).stream())
+
+
+def test_config3_batched_fp8(run_gpu):
+    wl = configs.config3_prefill(device=DEV, n_reqs=5, len_lo=30, len_hi=300, n_steps=2, hidden=4096,
+                                 inter=14336, n_resid=3, n_mlp=2, device_ring_bytes=64 << 20,
+                                 host_ring_bytes=64 << 20)
+    got = run_gpu(wl, poison=0xA5, batch=128)
+    ref = run_workload(wl)
+    assert ref.stats.dropped_records == 0
+    assert np.array_equal(got.stream, ref.stream())
+
+
+def test_config4_batched_paged_kv(run_gpu):
+    wl = configs.config4_paged_kv(device=DEV, n_layers_cap=2, n_blocks=1024, n_reqs=12, ctx_lo=20,
+                                  ctx_hi=700, reqs_per_step=4, n_steps=3,
+                                  device_ring_bytes=16 << 20, host_ring_bytes=32 << 20)
+    got = run_gpu(wl, poison=0xA5, batch=128)
+    assert np.array_equal(got.stream, run_workload(wl).stream())
+    assert got.stats.captured_records == 2 * 2 * 3
+
+
+@pytest.mark.parametrize("k", [1, 2])
+def test_config5_batched_lockstep_drops_and_sampling(run_gpu, k):
+    # device ring holds 3 records of 4,198,464 bytes; drain only every 2nd step; 5 points per batch
+    wl = configs.config5_saturation(device=DEV, n_points=5, n_steps=8, sample_k=k,
+                                    device_ring_bytes=13 << 20, host_ring_bytes=64 << 20)
+    got = run_gpu(wl, drain_every=2, batch=128)
+    ref = run_workload(wl, drain_every=2)
+    assert np.array_equal(got.stream, ref.stream())
+    a, b = got.stats, ref.stats
+    assert (a.dropped_records, a.dropped_rows, a.dropped_bytes) == (b.dropped_records, b.dropped_rows, b.dropped_bytes)
+    assert (a.sampled_out_calls, a.sampled_out_rows) == (b.sampled_out_calls, b.sampled_out_rows)
+    assert a.captured_records == b.captured_records and a.launched_records == ref.next_seq
+    if k == 1:
+        assert b.dropped_records > 0
+
+
+# ------------------------------------------------------------------ batched launches inside replayed steps
+def _check_stats(run, ref):
+    for k in ("observed_calls", "captured_records", "captured_rows", "captured_bytes", "dropped_records",
+              "dropped_rows", "dropped_bytes", "sampled_out_calls", "sampled_out_rows"):
+        assert getattr(run.stats, k) == getattr(ref.stats, k), k
+
+
+@pytest.mark.parametrize("batch,extra", [(128, 0), (128, 2), (2, 3)])
+def test_replayed_step_with_batched_launches(B, batch, extra):
+    """11 hooks per step captured as 4 launches (5 + 3 + 2 + 1 records), or, with at most two per
+    launch, as 7: an odd and an even number of launches per step, with ordinary observes between
+    replays, exercise the hand-over of head and tail between the two copies of the control words."""
+    from oracle import replay as oreplay
+    from paper_2605_11093_amd import replay as G
+    wl = configs.replayed_batches(n_steps=5, eager_extra_every=extra)
+    ref = oreplay.run_workload(wl)
+    run = G.run_workload_graph(wl, batch=batch)
+    compare_streams(run.stream, ref.stream())
+    _check_stats(run, ref)
+    assert run.stats.bad_rows == 0
+
+
+def test_replayed_batches_sampled_out_and_drop_newest(B):
+    from oracle import replay as oreplay
+    from oracle.stream import POLICY_DROP_NEWEST
+    from paper_2605_11093_amd import replay as G
+    wl = configs.replayed_batches(n_steps=6, sample_k=2, eager_extra_every=2)
+    ref = oreplay.run_workload(wl)
+    run = G.run_workload_graph(wl, batch=128)
+    compare_streams(run.stream, ref.stream())
+    _check_stats(run, ref)
+    # device ring holds about one and a half steps (a step is ~0.9 MB); drains every second step
+    wl = configs.replayed_batches(n_steps=6, policy_mode=POLICY_DROP_NEWEST, device_ring_bytes=1344 << 10)
+    ref = oreplay.run_workload(wl, drain_every=2)
+    assert ref.stats.dropped_records > 0 and ref.stats.captured_records > 0
+    run = G.run_workload_graph(wl, drain_every=2, batch=128)
+    compare_streams(run.stream, ref.stream())
+    _check_stats(run, ref)

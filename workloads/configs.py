@@ -280,3 +280,50 @@ def replayed_step(n_steps=6, n_graph=6, eager_extra_every=0, policy_mode=POLICY_
 
     return Workload("replayed_step", device_ring_bytes, host_ring_bytes, policy_mode, sample_k, n_steps,
                     step_calls, max_reqs=64, notes={"n_graph": n_graph})
+
+
+def replayed_batches(n_steps=5, policy_mode=POLICY_BLOCK, sample_k=1, device_ring_bytes=8 << 20,
+                     host_ring_bytes=32 << 20, eager_extra_every=0) -> Workload:
+    """Host-side workload for replayed steps whose hooks can share launches: every step lists,
+    in hook order,
+      0-4   five bf16 [64, 1024] tensors, one row per request (ids and rows change per step), raw + L2
+      5-7   three bf16 [300, 256] tensors, ragged token ranges + one keep vector, fp8 out, absmax
+      8-9   K and V of a paged cache [48, 16, 4, 64], heads {1, 3}, contexts that grow, raw
+      10    one more bf16 [64, 1024] tensor with the selection of 0-4 but fp16 out (its own launch)
+    Consecutive calls of a group have the same layout, selection and transform."""
+    n_r = 64
+    block_size, n_heads, head_dim, n_blocks, n_seqs, max_blocks = 16, 4, 64, 48, 6, 8
+
+    def t_bf16(tag, step, shape):
+        return prng.randn_bf16(prng.sub_seed(19, tag, step), int(np.prod(shape))).view(*shape)
+
+    def step_calls(step):
+        calls = []
+        perm = prng.permutation(prng.sub_seed(19, 50, step), n_r)
+        reqs_a = make_reqs((100 * step + r, int(perm[r]), 0, 1, 1) for r in range(n_r))
+        for i in range(5):
+            calls.append(ObserveCall(point_id=i, step_id=step, tensor=t_bf16(i, step, (n_r, 1024)), reqs=reqs_a,
+                                     out_dtype=DT_BF16, summary_mask=SUM_L2))
+        lens = prng.randint(prng.sub_seed(19, 20, step), 5, 0, 12)
+        starts = prng.randint(prng.sub_seed(19, 21, step), 5, 0, 20)
+        reqs_b = make_reqs((7 * step + r, 60 * r, int(starts[r]), int(lens[r]), 1 + (r + step) % 3) for r in range(5))
+        keep_b = (prng.randint(prng.sub_seed(19, 22, step), 5, 0, 3) > 0).astype(np.uint8)
+        for i in range(5, 8):
+            calls.append(ObserveCall(point_id=i, step_id=step, tensor=t_bf16(i, step, (300, 256)), reqs=reqs_b,
+                                     out_dtype=DT_FP8, summary_mask=SUM_ABSMAX, keep_mask=keep_b))
+        table = prng.permutation(prng.sub_seed(19, 40, step), n_blocks).astype(np.int32).reshape(n_seqs, max_blocks)
+        spec = PagedSpec(block_size, n_heads, head_dim, [1, 3], torch.from_numpy(np.ascontiguousarray(table)))
+        reqs_c = make_reqs((900 + r, r + 1, 0, 20 + 9 * r + step, 1) for r in range(4))
+        for i in range(8, 10):
+            calls.append(ObserveCall(point_id=i, step_id=step,
+                                     tensor=t_bf16(i, step, (n_blocks, block_size, n_heads, head_dim)),
+                                     reqs=reqs_c, out_dtype=DT_BF16, paged=spec))
+        calls.append(ObserveCall(point_id=10, step_id=step, tensor=t_bf16(10, step, (n_r, 1024)), reqs=reqs_a,
+                                 out_dtype=DT_FP16))
+        if eager_extra_every and step % eager_extra_every == eager_extra_every - 1:
+            calls.append(ObserveCall(point_id=11, step_id=step, tensor=calls[0].tensor,
+                                     reqs=make_reqs([(1, 2, 0, 3, 1)]), out_dtype=DT_BF16))
+        return calls
+
+    return Workload("replayed_batches", device_ring_bytes, host_ring_bytes, policy_mode, sample_k, n_steps,
+                    step_calls, max_reqs=64, notes={"n_graph": 11})
