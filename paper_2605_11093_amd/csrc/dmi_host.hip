@@ -58,7 +58,7 @@ dmi_status_t record_probe(dmi_ring *r)
         HIP_TRY(launch_fetch_slot(&r->dctrl->slots[slot], r->hslots_dev + slot, us));
     }
     HIP_TRY(hipEventRecord(ev, us));
-    r->probes.push_back({ev, launched, fetch, r->window});
+    r->probes.push_back({ev, launched, r->launches.load(std::memory_order_relaxed), fetch, r->window});
     r->window = Delta();
     r->window_exact = true;
     r->probed_upto = launched;
@@ -88,10 +88,12 @@ dmi_status_t advance_commits(dmi_ring *r, bool block)
         } else {
             // state after the previous probe is exact, and so is what came since
             r->snap[0] += p.delta.records; r->snap[1] += p.delta.rows; r->snap[2] += p.delta.bytes;
+            r->snap[3] += p.delta.drop_records; r->snap[4] += p.delta.drop_rows; r->snap[5] += p.delta.drop_bytes;
             r->committed.store(r->committed.load(std::memory_order_relaxed) + p.delta.bytes,
                                std::memory_order_release);
         }
         r->confirmed.store(p.covers, std::memory_order_release);
+        r->confirmed_launches.store(p.launches, std::memory_order_release);
         r->probe_pool.push_back(p.ev);
         r->probes.pop_front();
     }
@@ -314,7 +316,12 @@ uint32_t plan_grid(const CaptureArgs &a, uint32_t nb)
     } else if (upr >= kThreads && upr < 4u * kThreads && (4u * kThreads) % upr == 0) {
         groups = balanced((listed + 4u * kThreads / upr - 1u) / (4u * kThreads / upr));      // 2 or 4 rows per work item
     } else if (upr >= kThreads) {
-        groups = balanced(listed * ((upr + 4u * kThreads - 1u) / (4u * kThreads)));
+        // a row's last item is shorter than its others: a grid size that shares a factor with the
+        // items per row would give some workgroups only long items and others only short ones
+        const uint64_t cpr = (upr + 4u * kThreads - 1u) / (4u * kThreads);
+        groups = balanced(listed * cpr);
+        auto gcd = [](uint64_t x, uint64_t y) { while (y) { const uint64_t t = x % y; x = y; y = t; } return x; };
+        while (!flat && groups > 1u && gcd(groups, cpr) != 1u) groups++;
     } else {
         // short rows: slices of 256 units; a workgroup takes 4 per round once there are enough
         const uint64_t slices = (listed * upr + kThreads - 1u) / kThreads;
@@ -327,10 +334,14 @@ uint32_t plan_grid(const CaptureArgs &a, uint32_t nb)
 // quickest way through a small launch, where every dependent trip to memory counts; from
 // some eight thousand rows on the general kernel's one-item workgroups are as quick or quicker
 // (measured on 256 x 8192 bf16 tensors: 13.3 against 15.2 us for 8 tensors, 44 us either way for
-// 32, 116 against 113 us for 80).
+// 32, 116 against 113 us for 80).  The caller has set a.drop_newest and a.step.
 bool batch_takes_decode_kernel(const CaptureArgs &a, uint32_t nb)
 {
     if (nb == 1u) return true;
+    // the decode-shaped kernel loads its row before it knows whether the record is dropped: fine for
+    // one record, wasted reads for the dropped part of a batch under best effort (a replayable
+    // step's policy is not known when it is captured)
+    if (a.drop_newest || a.step) return false;
     return (uint64_t)nb * (a.listed_rows + 1u) <= 8192u;
 }
 
@@ -472,20 +483,17 @@ dmi_status_t observe_common(dmi_ring *r, uint32_t n, const uint32_t *points, con
     // that does not is issued in pieces, each waiting for its room as single observes would
     const uint64_t fit = r->dev_cap / ub < kMaxBatch ? r->dev_cap / ub : kMaxBatch;
     uint32_t slot = 0;
-    bool staged = false;
+    bool staged = false, host_decides = false;
     BatchArgs b;
     memset(&b, 0, sizeof b);
-    for (uint32_t done = 0; done < n;) {
-        uint32_t nb = n - done < kMaxBatch ? n - done : kMaxBatch;
-        if (mode == DMI_POLICY_BLOCK) {
-            if (nb > fit) nb = (uint32_t)fit;
-            if ((st = wait_for_room(r, ub * nb)) != DMI_OK) return st;
-        } else {
-            head_upper_bound(r);    // keeps the in-flight list short
-        }
-        if ((st = commit_slot_room(r, nb)) != DMI_OK) return st;
+
+    // one launch: records [first, first + cnt) of the caller's list; force_drop: records the host
+    // already knows cannot fit, launched with one workgroup each only to be counted
+    auto issue = [&](uint32_t first, uint32_t cnt, uint64_t floor, bool force_drop) -> dmi_status_t {
+        dmi_status_t rc;
+        if ((rc = commit_slot_room(r, cnt)) != DMI_OK) return rc;
         if (!staged) {
-            if ((st = stage_selection(r, sel, a.paged != 0, pl.row_map, s, &slot)) != DMI_OK) return st;
+            if ((rc = stage_selection(r, sel, a.paged != 0, pl.row_map, s, &slot)) != DMI_OK) return rc;
             staged = true;
         }
         const uint64_t seq = r->next_seq.load(std::memory_order_relaxed);
@@ -493,39 +501,93 @@ dmi_status_t observe_common(dmi_ring *r, uint32_t n, const uint32_t *points, con
         a.row0 = r->slab + (size_t)slot * r->slab_slot_words + 4u * (size_t)sel->n_reqs;
         a.row_map = pl.row_map ? a.row0 + sel->n_reqs : nullptr;
         a.seq = seq;
-        a.n_batch = nb;
+        a.n_batch = cnt;
         a.step_id = step_id;
-        a.cslot = &r->dctrl->slots[(seq + nb - 1u) % kCommitSlots];
-        a.tail_floor = r->drain_done.load(std::memory_order_acquire);
+        a.cslot = &r->dctrl->slots[(seq + cnt - 1u) % kCommitSlots];
+        a.tail_floor = floor;
         a.drop_newest = mode == DMI_POLICY_DROP_NEWEST ? 1u : 0u;
+        a.force_drop = force_drop ? 1u : 0u;
         // best effort: every fourth launch refreshes the drained-up-to mark from the host's word
         // (a read across the host link by one lane); in between, the launch-time floor stands
-        a.tail_src = (a.drop_newest && (r->launches & 3u) == 0) ? r->htail_dev : nullptr;
+        a.tail_src = (a.drop_newest && (r->launches.load(std::memory_order_relaxed) & 3u) == 0) ? r->htail_dev : nullptr;
         a.par_in = r->chain_par;
         a.step = nullptr;
         a.node = 0;
-        for (uint32_t i = 0; i < nb; i++) { b.src[i] = srcs[done + i]; b.point[i] = points[done + i]; }
+        for (uint32_t i = 0; i < cnt; i++) { b.src[i] = srcs[first + i]; b.point[i] = points[first + i]; }
 
-        const bool decode = pl.decode && batch_takes_decode_kernel(a, nb);
-        const hipError_t e = decode ? launch_capture_decode(a, b, s)
-                                    : launch_capture(a, b, nb == 1u ? pl.grid : plan_grid(a, nb), geo.vec16, s);
+        const bool decode = !force_drop && pl.decode && batch_takes_decode_kernel(a, cnt);
+        const uint32_t grid = force_drop ? 1u : cnt == 1u ? pl.grid : plan_grid(a, cnt);
+        const hipError_t e = decode ? launch_capture_decode(a, b, s) : launch_capture(a, b, grid, geo.vec16, s);
         if (e != hipSuccess) return fail(DMI_ERR_HIP, "capture launch failed: %s", hipGetErrorString(e));
+        const uint64_t bytes = force_drop ? 0u : ub * cnt;      // what the launch may add to the ring
+        // can the host tell what this launch does?  Under the completeness policy nothing is dropped;
+        // under best effort the caller of this function has decided (host_decides) which records fit
+        const bool exact = pl.size_known && (mode == DMI_POLICY_BLOCK || host_decides);
         r->chain_par ^= 1u;
-        r->launches += 1;
         r->last_launch_ns.store(now_ns(), std::memory_order_relaxed);
         {
             std::lock_guard<std::mutex> lk(r->pmu);
-            r->next_seq.store(seq + nb, std::memory_order_release);
-            if (mode == DMI_POLICY_BLOCK && pl.size_known) {
-                r->window.bytes += ub * nb; r->window.records += nb; r->window.rows += pl.rows_known * nb;
+            r->launches.fetch_add(1, std::memory_order_relaxed);
+            r->next_seq.store(seq + cnt, std::memory_order_release);
+            if (exact && !force_drop) {
+                r->window.bytes += bytes; r->window.records += cnt; r->window.rows += pl.rows_known * cnt;
+            } else if (exact) {
+                r->window.drop_bytes += ub * cnt; r->window.drop_records += cnt;
+                r->window.drop_rows += pl.rows_known * cnt;
             } else {
                 r->window_exact = false;
             }
         }
-        r->inflight.emplace_back(seq + nb - 1u, ub * nb);   // confirmed launch by launch: the last record stands for all
-        r->inflight_sum += ub * nb;
+        if (exact && r->head_exact) r->exact_head += bytes;
+        else r->head_exact = false;
+        r->inflight.emplace_back(seq + cnt - 1u, bytes);    // confirmed launch by launch: the last record stands for all
+        r->inflight_sum += bytes;
         r->unprobed_launches += 1;
-        r->unprobed_bytes += ub * nb;
+        r->unprobed_bytes += bytes;
+        return DMI_OK;
+    };
+
+    for (uint32_t done = 0; done < n;) {
+        uint32_t nb = n - done < kMaxBatch ? n - done : kMaxBatch;
+        uint32_t n_keep = nb;
+        if (mode == DMI_POLICY_BLOCK) {
+            if (nb > fit) nb = (uint32_t)fit;
+            n_keep = nb;
+            if ((st = wait_for_room(r, ub * nb)) != DMI_OK) return st;
+        } else {
+            head_upper_bound(r);    // keeps the in-flight list short
+        }
+        const uint64_t floor = r->drain_done.load(std::memory_order_acquire);
+        host_decides = false;
+        if (mode == DMI_POLICY_DROP_NEWEST && pl.size_known) {
+            // Best effort: while the host knows where the head will stand when this launch runs, it
+            // knows which records fit, because the kernel decides on this very drained mark or a newer
+            // one (a newer one only makes more room).  It then launches the records that fit as
+            // usual and the ones that do not apart, with a single workgroup each, only to be counted:
+            // under sustained overload those are a third or more of all records, and a full grid of
+            // workgroups for each of them, all finding out that they have nothing to do, costs a
+            // quarter of what copying the record would.  And since the outcome is known, the host
+            // needs no commit slot fetched to follow the head (an event behind the launches will do).
+            // Not while the host runs far ahead of the GPU, though: the drained mark it decides on is
+            // the one of this moment, the kernel's is at most a launch or so older than its own start.
+            if ((st = advance_commits(r, false)) != DMI_OK) return st;
+            if (!r->head_exact &&
+                r->confirmed.load(std::memory_order_acquire) == r->next_seq.load(std::memory_order_relaxed)) {
+                r->head_exact = true;
+                r->exact_head = r->committed.load(std::memory_order_acquire);
+            }
+            constexpr uint64_t kTightLaunches = 4;
+            const bool tight = r->launches.load(std::memory_order_relaxed) -
+                               r->confirmed_launches.load(std::memory_order_acquire) <= kTightLaunches;
+            if (r->head_exact && tight) {
+                host_decides = true;
+                const uint64_t used = r->exact_head - floor;
+                const uint64_t room = used < r->dev_cap ? (r->dev_cap - used) / ub : 0u;
+                if (room < nb) n_keep = (uint32_t)room;
+            }
+        }
+        if (n_keep && (st = issue(done, n_keep, floor, false)) != DMI_OK) return st;
+        if (n_keep < nb && (st = issue(done + n_keep, nb - n_keep, floor, true)) != DMI_OK) return st;
         done += nb;
         *n_launched = done;
         if (r->unprobed_launches >= 16u || r->unprobed_bytes >= r->probe_bytes) {

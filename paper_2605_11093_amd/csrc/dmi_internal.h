@@ -108,6 +108,7 @@ struct CaptureKernelArgs {
     uint32_t upr_shift;             // log2(units_per_row) if that is a power of two, else 32
     uint32_t bs_shift, seg_shift;   // same for block_size and seg_units
     uint32_t drop_newest;
+    uint32_t force_drop;            // every record of this launch is dropped (the host knows none can fit)
     uint32_t table_in_lds;
     // launch chain: which copy of head / tail_for this launch reads (it writes the other)
     uint32_t par_in;

@@ -567,7 +567,11 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureKernelAr
     RowRef pre_ref = {nullptr, 0};
     bool pre = false;
     const bool multi_row_items = a.units_per_row < CH && CH % a.units_per_row == 0u;
-    if (simple && !a.paged && (SUMM || (OUT != OUT_NONE && a.units_per_row >= kThreads && !multi_row_items))) {
+    // (not in a launch of several records some of which may turn out to be dropped: a dropped
+    // record's rows would have been read for nothing)
+    const bool may_drop_some = a.n_batch > 1u && (a.drop_newest != 0u || a.step != nullptr);
+    if (simple && !a.paged && !may_drop_some &&
+        (SUMM || (OUT != OUT_NONE && a.units_per_row >= kThreads && !multi_row_items))) {
         uint32_t g, c_begin, stride;
         if constexpr (SUMM) { g = blockIdx.x * rpw + sub; c_begin = l; stride = gsz; }
         else { g = blockIdx.x / cpr; c_begin = (blockIdx.x - g * cpr) * CH + tid; stride = kThreads; }
@@ -625,7 +629,7 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureKernelAr
     }
     const uint64_t tail = (uint64_t)lds[m.bcast + 2] | ((uint64_t)lds[m.bcast + 3] << 32);
     const bool drop_newest = (flags & kStepDropNewest) != 0;
-    const bool dropped = drop_newest && head - tail + record_bytes > a.cap;
+    const bool dropped = a.force_drop != 0u || (drop_newest && head - tail + record_bytes > a.cap);
 
     // ---- publish: one lane of the launch leaves head, tail and counters for the next launch and
     //      fills the commit slot of the launch's last record, early, so that it overlaps the copy.
@@ -640,6 +644,7 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureKernelAr
             n_fit = used < a.cap ? (a.cap - used) / record_bytes : 0u;
             n_fit = n_fit < nb_rec ? n_fit : nb_rec;
         }
+        if (a.force_drop) n_fit = 0;
         const uint64_t n_drop = nb_rec - n_fit;
         const uint64_t new_head = head0 + n_fit * record_bytes;
         if (n_drop) {

@@ -115,15 +115,18 @@ struct PlanEnv {
 };
 
 // What the launches between two probes add when the host can tell without asking the
-// device: completeness policy and no keep vector, so each record has its listed size and
-// none is dropped.
+// device: records whose size the host knows (no keep vector, or one it has a copy of), under
+// the completeness policy, where none is dropped, or under best effort while the host knows
+// where the head stands and decides itself which records fit.
 struct Delta {
-    uint64_t bytes = 0, records = 0, rows = 0;
+    uint64_t bytes = 0, records = 0, rows = 0;              // captured
+    uint64_t drop_bytes = 0, drop_records = 0, drop_rows = 0;   // dropped, by the host's own decision
 };
 
 struct Probe {
     hipEvent_t ev;          // recorded on the producer's stream behind the launches (and the slot fetch)
     uint64_t covers;        // every launch with seq < covers was enqueued before ev
+    uint64_t launches;      // how many capture launches that is
     bool fetched;           // the commit slot of launch covers-1 was copied to the host mirror
     Delta delta;            // else: what the launches since the previous probe added
 };
@@ -167,7 +170,15 @@ struct dmi_ring {
     uint64_t inflight_sum = 0;
     uint64_t unprobed_launches = 0, unprobed_bytes = 0, probe_bytes = 8u << 20;
     uint32_t chain_par = 0;                                // which copy of head / tail_for the next launch reads
-    uint64_t launches = 0;                                 // capture launches issued by dmi_observe*
+    std::atomic<uint64_t> launches{0};                     // capture launches issued so far
+    std::atomic<uint64_t> confirmed_launches{0};           // ... and how many of them are known to have finished
+    // Does the host know where the device head will stand once everything launched so far has run?
+    // It does while every launch since the last confirmed state had an outcome the host could tell
+    // in advance; it then decides best-effort drops itself instead of leaving them to the kernel,
+    // provided it is not running far ahead of the GPU (the drained mark it would decide on ages
+    // while the launch waits in the queue; the kernel decides on a fresher one).
+    bool head_exact = true;
+    uint64_t exact_head = 0;
     bool step_open = false;                                // between dmi_step_begin and dmi_step_end
     std::atomic<int> quiet{0};                             // a capture is open: library threads make no HIP call
     std::atomic<bool> bg_parked{false};

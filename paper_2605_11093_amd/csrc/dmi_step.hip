@@ -398,8 +398,14 @@ dmi_status_t dmi_step_end(dmi_step_t *st, void *hip_stream)
         r->inflight.emplace_back(st->seq_base + nd.first_rec + nd.n_batch - 1u, nd.pl.ub * nd.n_batch);
         r->inflight_sum += nd.pl.ub * nd.n_batch;
     }
+    // the step's launches decide drops and read keep vectors on the device
+    bool host_knows = !st->drop_newest;
+    for (auto &nd : st->nodes) host_knows = host_knows && !nd.masked;
+    if (host_knows && r->head_exact) r->exact_head += st->sum_ub;
+    else r->head_exact = false;
     {
         std::lock_guard<std::mutex> lk(r->pmu);
+        r->launches.fetch_add(st->nodes.size(), std::memory_order_relaxed);
         r->next_seq.store(st->seq_base + n, std::memory_order_release);
         for (auto &nd : st->nodes) {
             if (st->drop_newest || nd.masked) { r->window_exact = false; break; }
