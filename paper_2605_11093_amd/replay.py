@@ -131,13 +131,14 @@ def run_workload_gpu(wl, *, drain_every: int = 1, release: bool = True, collect:
                      block_timeout_ms: int = 1, poison: Optional[int] = None,
                      ring: Optional[B.Ring] = None, drain_flags: int = 0,
                      bg_min_bytes: int = 0, before_observe: Optional[Callable] = None,
-                     batch: int = 0) -> GpuRun:
+                     batch: int = 0, run: Optional[GpuRun] = None) -> GpuRun:
     """Lockstep schedule (the one the oracle's model follows): a step's observes,
     then every `drain_every` steps a flush-drain followed by poll + release.
     With lockstep=False the drain after a step moves only what has committed by
     then, without waiting for the step's kernels.  batch > 0: consecutive calls of
     a step that share layout, selection and transform go out together through
-    dmi_observe_batch, at most `batch` per call."""
+    dmi_observe_batch, at most `batch` per call.  run: a GpuRun to fill in (so that an
+    on_record callback can look at run.launched while the workload is still running)."""
     own = ring is None
     if own:
         ring = B.Ring(device_ring_bytes or wl.device_ring_bytes, host_ring_bytes or wl.host_ring_bytes,
@@ -146,7 +147,7 @@ def run_workload_gpu(wl, *, drain_every: int = 1, release: bool = True, collect:
         ring.set_policy(wl.policy_mode, wl.sample_k, 0)
     if poison is not None:
         ring.debug_fill_rings(poison)
-    run = GpuRun()
+    run = GpuRun() if run is None else run
     s = torch.cuda.current_stream()
     keep_alive: list = []
     try:
