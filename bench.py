@@ -112,7 +112,7 @@ def time_launches(ctx, make_call, n_launch, ring_bytes, alg_bytes, reps=3, max_r
     B = ctx.B
     per = []
     for rep in range(reps + 1):
-        ring = B.Ring(ring_bytes, 1 << 26, max_reqs_per_observe=max_reqs)
+        ring = B.Ring(ring_bytes, max(1 << 26, (alg_bytes + 63) // 64 * 64), max_reqs_per_observe=max_reqs)
         ring.set_policy(B.POLICY_BLOCK if policy is None else policy)
         po = make_call(ring)
         if rep == 0:                                    # warm-up: code objects, allocator
@@ -227,7 +227,7 @@ def run_kernel_table(ctx, only=None, profile=False):
             if only is not None and name not in only:
                 continue
             if profile:
-                ring = ctx.B.Ring(ring_bytes, 1 << 26, max_reqs_per_observe=256)
+                ring = ctx.B.Ring(ring_bytes, max(1 << 26, (alg + 63) // 64 * 64), max_reqs_per_observe=256)
                 ring.set_policy(policy)
                 po = make(ring)
                 for i in range(n_launch):

@@ -62,7 +62,7 @@ enum {
     DMI_POINT_DISABLED = 2,     /* point switched off: nothing captured */
     DMI_ERR_INVALID_ARG = -1,
     DMI_ERR_NOMEM = -2,
-    DMI_ERR_TOO_LARGE = -3,     /* the record can never fit the device ring */
+    DMI_ERR_TOO_LARGE = -3,     /* the record can never fit the device ring (or the host ring) */
     DMI_ERR_HIP = -4,           /* a HIP call failed (also: no GPU present) */
     DMI_ERR_AGAIN = -5,         /* would block: no room and nothing more can be drained */
     DMI_ERR_CLOSED = -6
@@ -168,7 +168,12 @@ typedef struct {
 /* What is stored per row.  out_dtype: NONE (summaries only), the source dtype
  * (raw copy), or, from a BF16 source, FP16 or FP8_E4M3FN (round to nearest even;
  * FP8 saturates to +-448, NaN stays NaN).  summary_mask: DMI_SUM_* bits, fp32
- * reductions over the source row. */
+ * reductions over the source row: L2 = sqrt(sum x^2), mean = sum x / row length,
+ * absmax = max |x|; a row holding a NaN gives NaN for all three.
+ * Limit of L2: the squares are summed in fp32, so a row whose sum of squares leaves
+ * fp32's range gives +inf (some |x| beyond 1.8e19 / sqrt(how many such elements))
+ * or 0 (every |x| below about 1e-22) although the norm itself is representable;
+ * mean and absmax are exact in those cases. */
 typedef struct {
     uint32_t out_dtype;
     uint32_t summary_mask;
@@ -178,7 +183,7 @@ typedef struct {
  * Capture one tensor (paper section 4.2 step 1-2, section 4.4 gather-compact).
  * Launches one kernel on hip_stream [hipStream_t, 0 = null stream] and returns.
  * Policy: disabled point -> DMI_POINT_DISABLED; step_id % sample_k != sample_phase
- * -> DMI_SAMPLED_OUT; record larger than the device ring -> DMI_ERR_TOO_LARGE;
+ * -> DMI_SAMPLED_OUT; record larger than the device ring or the host ring -> DMI_ERR_TOO_LARGE;
  * DMI_POLICY_BLOCK with no room -> drains, waiting on the host up to
  * block_timeout_ms, then DMI_ERR_AGAIN; DMI_POLICY_DROP_NEWEST never waits: the
  * kernel discards the record if it does not fit when it runs, and counts it.

@@ -9,9 +9,9 @@ prioritised; when capacity is insufficient the others are dropped first.
 Written out as the definition: rank the requests, keep the longest prefix of the
 ranking whose cost fits the budget.
 
-Pins (tests/test_policy_select.py): drop-recent keeps the oldest requests, keep-by-pattern
-drops non-matching requests first, the kept set is a maximal prefix of the ranking (adding
-the next request would exceed the budget).  Parity unpinned: tie-breaking and "prefix, not
+Pins (tests/test_policy_select.py, applied to this function directly): drop-recent keeps the
+oldest requests, keep-by-pattern drops non-matching requests first, the kept set is a maximal
+prefix of the ranking (adding the next request would exceed the budget).  Parity unpinned: tie-breaking and "prefix, not
 best fit" are this build's readings of a strategy the paper describes in a sentence each.
 """
 from __future__ import annotations

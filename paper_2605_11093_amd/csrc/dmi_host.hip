@@ -115,9 +115,10 @@ dmi_status_t reap(dmi_ring *r, bool wait)
 }
 
 // Issue copies for what is committed and fits the host ring.  Caller holds r->mu.
-dmi_status_t drain_issue_locked(dmi_ring *r, uint64_t *moved)
+dmi_status_t drain_issue_locked(dmi_ring *r, uint64_t *moved, bool *host_full)
 {
     if (moved) *moved = 0;
+    if (host_full) *host_full = false;
     dmi_status_t st = reap(r, false);
     if (st != DMI_OK) return st;
     const uint64_t committed = read_committed(r);
@@ -125,6 +126,7 @@ dmi_status_t drain_issue_locked(dmi_ring *r, uint64_t *moved)
     const uint64_t avail = committed - r->drain_issued;
     const uint64_t host_free = r->host_cap - (r->drain_issued - r->released);
     uint64_t n = avail < host_free ? avail : host_free;
+    if (host_full) *host_full = avail > 0 && host_free == 0;
     // bounded batches: the device tail (what drop-newest decides on) moves once per batch
     const uint64_t batch = (r->dev_cap / 8u > (64u << 20) ? r->dev_cap / 8u : (64u << 20)) & ~63ull;
     if (n > batch) n = batch;
@@ -161,12 +163,12 @@ dmi_status_t drain_issue_locked(dmi_ring *r, uint64_t *moved)
 // Issue the copies and, if asked, wait for them.  The ring's lock is held only while the
 // bookkeeping is touched, never across the wait: the consumer polls and releases, and the
 // producer asks for room, while a copy is in flight.
-dmi_status_t drain(dmi_ring *r, bool wait, uint64_t *moved)
+dmi_status_t drain(dmi_ring *r, bool wait, uint64_t *moved, bool *host_full)
 {
     uint64_t mark;
     {
         std::lock_guard<std::mutex> lk(r->mu);
-        dmi_status_t st = drain_issue_locked(r, moved);
+        dmi_status_t st = drain_issue_locked(r, moved, host_full);
         if (st != DMI_OK) return st;
         mark = r->drain_issued;
         if (!wait || r->drain_done.load(std::memory_order_relaxed) == mark) return DMI_OK;
@@ -357,7 +359,7 @@ dmi_status_t check_batch_sources(uint32_t n, const void *const *data, uint32_t e
     return DMI_OK;
 }
 
-PlanEnv plan_env(const dmi_ring *r) { return PlanEnv{r->dev_ring, r->dev_cap, r->dctrl, r->cfg.rank_tag, r}; }
+PlanEnv plan_env(const dmi_ring *r) { return PlanEnv{r->dev_ring, r->dev_cap, r->host_cap, r->dctrl, r->cfg.rank_tag, r}; }
 
 dmi_status_t plan_capture(const PlanEnv &env, uint32_t point_id, const dmi_selection_t *sel, const dmi_transform_t *xf,
                           const Geometry &geo, CaptureArgs &a, Plan &pl, bool fixed_row_count_ok)
@@ -375,6 +377,9 @@ dmi_status_t plan_capture(const PlanEnv &env, uint32_t point_id, const dmi_selec
     if (ub > env.cap)
         return fail(DMI_ERR_TOO_LARGE, "record of %llu bytes exceeds the device ring (%llu)",
                     (unsigned long long)ub, (unsigned long long)env.cap);
+    if (env.host_cap && ub > env.host_cap)      // such a record could be drained but never polled whole
+        return fail(DMI_ERR_TOO_LARGE, "record of %llu bytes exceeds the host ring (%llu)",
+                    (unsigned long long)ub, (unsigned long long)env.host_cap);
     pl.listed = listed;
     pl.ub = ub;
     pl.rows_known = listed;
@@ -691,6 +696,9 @@ void bg_loop(dmi_ring *r)
         uint64_t pending_bytes;
         {
             std::lock_guard<std::mutex> lk(r->mu);
+            // copies issued by somebody's non-blocking dmi_drain are noted here as they finish: with
+            // this thread running, nobody else looks at the drain stream
+            (void)reap(r, false);
             pending_bytes = read_committed(r) - r->drain_issued;
         }
         const uint64_t t = now_ns();
@@ -1082,29 +1090,28 @@ dmi_status_t dmi_drain(dmi_ring_t *r, uint32_t flags, uint64_t *bytes_moved)
     const uint64_t want_seq = r->next_seq.load(std::memory_order_acquire);
     if ((st = record_probe(r)) != DMI_OK) return st;
     const uint64_t t0 = now_ns();
-    uint64_t total = 0;
+    uint64_t total = 0, target = UINT64_MAX;
     for (;;) {
         if ((st = advance_commits(r, false)) != DMI_OK) return st;
-        const uint64_t done = r->confirmed.load(std::memory_order_acquire);
-        uint64_t moved = 0, left, in_flight;
-        if ((st = drain(r, true, &moved)) != DMI_OK) return st;
-        {
-            std::lock_guard<std::mutex> lk(r->mu);
-            left = read_committed(r) - r->drain_issued;
-            // the drain thread may have issued a batch after the wait above began
-            in_flight = r->drain_issued - r->drain_done.load(std::memory_order_relaxed);
-        }
+        // once the launches issued before the call are known to have finished, their records lie
+        // below the head committed at that moment: the call is done when the drain has passed it,
+        // whatever a producer thread commits behind it in the meantime
+        if (target == UINT64_MAX && r->confirmed.load(std::memory_order_acquire) >= want_seq)
+            target = read_committed(r);
+        uint64_t moved = 0;
+        bool host_full = false;
+        if ((st = drain(r, true, &moved, &host_full)) != DMI_OK) return st;
         total += moved;
         if (bytes_moved) *bytes_moved = total;
-        if (done >= want_seq && left == 0 && in_flight == 0) return DMI_OK;
-        if (done >= want_seq && left == 0) continue;        // wait for that batch too
-        if (done >= want_seq && moved == 0)
+        if (target != UINT64_MAX && r->drain_done.load(std::memory_order_acquire) >= target) return DMI_OK;
+        if (moved) continue;
+        if (target != UINT64_MAX && host_full)
             return fail(DMI_ERR_AGAIN, "host ring is full: release records and drain again");
-        if (moved == 0) {
-            if (now_ns() - t0 > (uint64_t)r->block_timeout_ms * 1000000ull)
-                return fail(DMI_ERR_AGAIN, "observes did not finish within %u ms", r->block_timeout_ms);
-            std::this_thread::sleep_for(std::chrono::microseconds(10));
-        }
+        if (now_ns() - t0 > (uint64_t)r->block_timeout_ms * 1000000ull)
+            return fail(DMI_ERR_AGAIN, target == UINT64_MAX ? "observes did not finish within %u ms"
+                                                            : "the drain did not finish within %u ms",
+                        r->block_timeout_ms);
+        std::this_thread::sleep_for(std::chrono::microseconds(10));
     }
 }
 

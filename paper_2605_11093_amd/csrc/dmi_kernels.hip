@@ -987,6 +987,8 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureKernelAr
                     ref = pre_ref;
 #pragma unroll
                     for (uint32_t k = 0; k < U; k++) v[k] = pre_v[k];
+                    // (fetch() counts the rows it locates; this one was located up front)
+                    if (!ref.ok && l == 0 && cur_g0 + sub < n_rows) atomicAdd((unsigned long long *)&a.ctrl->bad_rows, 1ull);
                 } else {
                     fetch(cur_g0, cur_pass, ref, v);
                 }

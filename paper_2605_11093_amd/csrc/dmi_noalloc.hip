@@ -91,7 +91,7 @@ extern "C" dmi_status_t dmi_observe_into(uint32_t point_id, const dmi_tensor_t *
         return fail(DMI_ERR_TOO_LARGE, "the record may take %llu bytes, out_bytes is %llu", (unsigned long long)ub,
                     (unsigned long long)out_bytes);
     Plan pl;
-    const PlanEnv env{static_cast<uint8_t *>(out), out_bytes, &S->ctrl, rank_tag, nullptr};
+    const PlanEnv env{static_cast<uint8_t *>(out), out_bytes, 0u, &S->ctrl, rank_tag, nullptr};
     if ((st = plan_capture(env, point_id, sel, xf, geo, a, pl, true)) != DMI_OK) return st;
 
     std::vector<uint32_t> words;

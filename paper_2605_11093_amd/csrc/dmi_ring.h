@@ -109,6 +109,7 @@ struct Plan {
 struct PlanEnv {
     uint8_t *ring;
     uint64_t cap;
+    uint64_t host_cap;      // 0: the records do not travel on to a host ring
     DevCtrl *ctrl;
     uint32_t rank_tag;
     const dmi_ring *masks;
@@ -273,6 +274,7 @@ dmi_status_t record_probe(dmi_ring *r);
 dmi_status_t advance_commits(dmi_ring *r, bool block);
 uint64_t head_upper_bound(dmi_ring *r);
 dmi_status_t wait_for_room(dmi_ring *r, uint64_t ub);
+dmi_status_t drain(dmi_ring *r, bool wait, uint64_t *moved, bool *host_full = nullptr);
 dmi_status_t commit_slot_room(dmi_ring *r, uint32_t n);
 void selection_words(const dmi_req_sel_t *reqs, uint32_t n, bool paged, bool row_map, std::vector<uint32_t> &words);
 PlanEnv plan_env(const dmi_ring *r);

@@ -285,6 +285,40 @@ def test_summaries_closed_forms_and_non_finite(B):
     assert abs(g.summaries[2][3] - v.mean()) <= 1e-3 * abs(v.mean()) + 1e-5 * np.abs(v).mean()
 
 
+@pytest.mark.parametrize("rows_per_request", [1, 3])
+def test_l2_limit_of_the_fp32_sum_of_squares(B, rows_per_request):
+    """The documented limit of the L2 summary (include/dmi.h, dmi_transform_t): the kernels sum
+    squares in fp32, the oracle in float64 rounded once.  Where the fp32 sum overflows although the
+    norm itself is representable the stored L2 is +inf; where every square underflows it is 0.
+    Mean and absmax are not affected, and just inside the limits the L2 is within tolerance.
+    (Activations are nowhere near either end: |x| > 1.8e19 / sqrt(E) or |x| < 1e-22.)
+    One row per request takes the decode-shaped kernel, three per request with a keep vector the
+    general one."""
+    from oracle.decode import decode_record
+    E = 4096
+    x = torch.zeros(6, E, dtype=torch.bfloat16, device=DEV)
+    x[0, :] = 2.0 ** 70                      # sum of squares 2^152: beyond fp32; L2 = 2^76 is not
+    x[1, 9] = torch.tensor([0x7F7F], dtype=torch.int16).view(torch.bfloat16)[0]     # largest finite bf16
+    x[2, :] = 2.0 ** -80                     # squares underflow; L2 = 2^-74 is representable
+    x[3, :] = 2.0 ** 57                      # sum of squares 2^126: still fine
+    x[4, :] = -(2.0 ** -60)                  # squares 2^-120: still fine
+    x[5] = prng.randn_bf16(77, E, DEV)
+    if rows_per_request == 1:
+        reqs, keep = [(i, i, 0, 1, 1) for i in range(6)], None
+    else:
+        reqs, keep = [(1, 0, 0, 3, 1), (2, 3, 0, 3, 1)], [1, 1]
+    got, ref = _one(B, x, reqs, out_dtype=DT_NONE, summary_mask=7, keep_mask=keep)
+    g, r = decode_record(got), decode_record(ref)
+    assert np.array_equal(g.summaries[4], r.summaries[4])                                  # absmax exact
+    assert g.summaries[4][1] == np.float32(3.3895313892515355e38)
+    assert np.allclose(g.summaries[2], r.summaries[2], rtol=1e-3, atol=0)                  # means
+    l2g, l2r = g.summaries[1], r.summaries[1]
+    assert np.isfinite(l2r).all() and l2r[0] == np.float32(2.0 ** 76) and l2r[2] == np.float32(2.0 ** -74)
+    assert np.isposinf(l2g[0]) and np.isposinf(l2g[1]) and l2g[2] == 0.0                   # the limit
+    for i in (3, 4, 5):
+        assert abs(float(l2g[i]) - float(l2r[i])) <= 1e-3 * float(l2r[i])
+
+
 @pytest.mark.parametrize("E", [64, 257, 1024, 14336])
 @pytest.mark.parametrize("out_dtype", [DT_BF16, DT_FP8])
 def test_summaries_with_payload_across_row_lengths(B, E, out_dtype):

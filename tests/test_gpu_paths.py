@@ -192,6 +192,25 @@ def test_out_of_range_device_indices_give_zero_rows_and_are_counted(B):
             else:
                 assert not r.payload[g].any() and r.summaries[1][g] == 0 and r.summaries[4][g] == 0
         assert ring.get_stats().bad_rows == 3
+    # the general kernel's summary pass (an fp32 source keeps the launch off the decode-shaped kernel),
+    # a workgroup per row (E = 8200) and a wavefront per row (E = 96)
+    for E in (8200, 96):
+        t32 = prng.randn_bf16(prng.sub_seed(34, 3, E), 50 * E, DEV).view(50, E).float()
+        with B.Ring(1 << 22, 1 << 22) as ring:
+            s = torch.cuda.current_stream()
+            ri = torch.from_numpy(idx).to(DEV)
+            ring.observe_tensor(0, t32, reqs, step_id=0, stream=s.cuda_stream, row_index=ri, summary_mask=7)
+            ring.drain(B.DRAIN_FLUSH)
+            r = decode_record(ring.poll_host()[0].bytes())
+            src32 = t32.cpu().numpy()
+            for g, src in enumerate(idx):
+                if 0 <= src < 50:
+                    assert (r.payload[g] == src32[src]).all()
+                    assert r.summaries[4][g] == np.abs(src32[src]).max()
+                    assert abs(r.summaries[1][g] - np.sqrt((src32[src].astype(np.float64) ** 2).sum())) <= 1e-3 * r.summaries[1][g]
+                else:
+                    assert not r.payload[g].any() and r.summaries[1][g] == 0 and r.summaries[4][g] == 0
+            assert ring.get_stats().bad_rows == 3, E
     # a block-table entry beyond the cache
     NB, BS, NH, HD = 8, 16, 2, 128
     cache = prng.randn_bf16(prng.sub_seed(34, 2), NB * BS * NH * HD, DEV).view(NB, BS, NH, HD)

@@ -9,6 +9,15 @@ from oracle import policy as opol
 from paper_2605_11093_amd import binding as B
 
 
+def _lib_select(strategy, reqs, bpr, budget):
+    return B.policy_select(strategy, reqs, bpr, budget).tolist()
+
+
+# the properties the paper states are held against the oracle's definition and against the
+# library's host function alike
+IMPLS = [pytest.param(opol.select, id="oracle"), pytest.param(_lib_select, id="library")]
+
+
 def _random_batch(rng, n):
     return [(1000 + i, int(rng.integers(0, 9)), int(rng.integers(0, 50)), int(rng.random() < 0.3))
             for i in range(n)]
@@ -25,32 +34,34 @@ def test_select_matches_the_oracle_on_random_batches(strategy):
         assert got.tolist() == opol.select(strategy, reqs, bpr, budget)
 
 
-def test_drop_recent_keeps_the_oldest_requests():
+@pytest.mark.parametrize("select", IMPLS)
+def test_drop_recent_keeps_the_oldest_requests(select):
     # admit order 0..7, one row each, 100 bytes per row, room for 5
     reqs = [(i, 1, 7 - i, 0) for i in range(8)]             # position 0 is the most recent
-    keep = B.policy_select(B.SELECT_DROP_RECENT, reqs, 100, 599)
-    assert keep.tolist() == [0, 0, 0, 1, 1, 1, 1, 1]
-    assert B.policy_select(B.SELECT_DROP_RECENT, reqs, 100, 10 ** 9).all()
-    assert not B.policy_select(B.SELECT_DROP_RECENT, reqs, 100, 99).any()
+    assert select(B.SELECT_DROP_RECENT, reqs, 100, 599) == [0, 0, 0, 1, 1, 1, 1, 1]
+    assert all(select(B.SELECT_DROP_RECENT, reqs, 100, 10 ** 9))
+    assert not any(select(B.SELECT_DROP_RECENT, reqs, 100, 99))
 
 
-def test_keep_by_pattern_drops_non_matching_first():
+@pytest.mark.parametrize("select", IMPLS)
+def test_keep_by_pattern_drops_non_matching_first(select):
     reqs = [(0, 2, 0, 0), (1, 2, 1, 1), (2, 2, 2, 0), (3, 2, 3, 1), (4, 2, 4, 0)]
     # budget for three requests: both matching ones, then the oldest of the others
-    assert B.policy_select(B.SELECT_KEEP_BY_PATTERN, reqs, 10, 60).tolist() == [1, 1, 0, 1, 0]
+    assert select(B.SELECT_KEEP_BY_PATTERN, reqs, 10, 60) == [1, 1, 0, 1, 0]
     # budget for one: the older matching request
-    assert B.policy_select(B.SELECT_KEEP_BY_PATTERN, reqs, 10, 25).tolist() == [0, 1, 0, 0, 0]
+    assert select(B.SELECT_KEEP_BY_PATTERN, reqs, 10, 25) == [0, 1, 0, 0, 0]
     # same data under drop-recent ignores the predicate
-    assert B.policy_select(B.SELECT_DROP_RECENT, reqs, 10, 60).tolist() == [1, 1, 1, 0, 0]
+    assert select(B.SELECT_DROP_RECENT, reqs, 10, 60) == [1, 1, 1, 0, 0]
 
 
-def test_kept_set_is_a_maximal_prefix_of_the_ranking():
+@pytest.mark.parametrize("select", IMPLS)
+def test_kept_set_is_a_maximal_prefix_of_the_ranking(select):
     rng = np.random.default_rng(3)
     for _ in range(200):
         reqs = _random_batch(rng, 12)
         bpr, budget = 64, int(rng.integers(0, 12 * 8 * 64))
         for strategy in (0, 1):
-            keep = B.policy_select(strategy, reqs, bpr, budget)
+            keep = select(strategy, reqs, bpr, budget)
             order = sorted(range(12), key=lambda i: ((0 if (strategy and reqs[i][3]) else strategy), reqs[i][2], i))
             flags = [int(keep[i]) for i in order]
             k = sum(flags)
