@@ -33,10 +33,11 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0           # MI355X published HBM3E bandwidth
 SEED_NOTE = "synthetic (seeded ~N(0,1) bf16, shapes of the paper's LLM workloads)"
-# HBM bytes per launch of the batched config-5 capture kernel (80 records), from the two
-# rocprofv3 --pmc runs summarised in profiles/capture_batched_config5.md (FETCH_SIZE and
-# WRITE_SIZE, each scaled by what the same counter reads for a plain copy of known size).
-TRAFFIC_CONFIG5_BATCH80_BYTES = None
+# HBM bytes per launch of the batched config-5 capture kernel when it keeps all 80 records, from
+# the two rocprofv3 --pmc runs summarised in profiles/hbm_traffic_counters.md (FETCH_SIZE and
+# WRITE_SIZE, each scaled by what the same counter reads for a plain copy of known size):
+# 335.77 MB read + 339.66 MB written, against 671.83 MB algorithmic.
+TRAFFIC_CONFIG5_BATCH80_BYTES = 675428850
 
 
 def log(*a):
@@ -930,7 +931,10 @@ def main():
                 "us_per_launch_min": round(head["launch_us_min"], 3), "launches": n_launch,
                 "algorithmic_bytes_per_launch": round(alg_total / n_launch),
                 "records_kept_per_launch": round(head["captured_records"] / n_launch, 2),
-                "traffic": TRAFFIC_CONFIG5_BATCH80_BYTES}
+                # the profiled launch keeps all 80 records; a launch of this run kept this share of them
+                "traffic": round(TRAFFIC_CONFIG5_BATCH80_BYTES * head["captured_records"] / n_launch / 80),
+                "traffic_of_a_launch_that_keeps_all_80_records": TRAFFIC_CONFIG5_BATCH80_BYTES,
+                "traffic_source": "profiles/hbm_traffic_counters.md"}
     log(f"roofline: {roofline}")
     sat = {}
     if not args.skip_extra:

@@ -303,3 +303,45 @@ def test_flush_waits_for_batches_the_drain_thread_issued(B):
                     break
             st = ring.get_stats()
             assert st.released_bytes == st.captured_bytes == st.drained_bytes, (trial, st)
+
+
+def test_nonblocking_drain_on_a_ring_with_a_drain_thread_becomes_visible(B):
+    """A caller's non-blocking drain on a ring whose drain thread is running: nothing else is
+    pending afterwards, and still the copies it issued must be noted as finished (by the drain
+    thread) so that the records can be polled."""
+    import time
+    t = prng.randn_bf16(61, 64 * 1024, DEV).view(64, 1024)
+    reqs = np.array([(i, i, 0, 1, 1) for i in range(64)], dtype=np.uint32)
+    # thresholds the drain thread will not reach by itself for a long time
+    with B.Ring(1 << 22, 1 << 22, flags=B.BG_THREAD, bg_min_bytes=1 << 21, bg_timeout_us=5_000_000) as ring:
+        s = torch.cuda.current_stream()
+        ring.observe_tensor(0, t, reqs, step_id=0, stream=s.cuda_stream)
+        s.synchronize()
+        moved = 0
+        for _ in range(2000):                      # the commit has to be noticed first
+            moved += ring.drain(B.DRAIN_NONBLOCK)
+            if moved:
+                break
+            time.sleep(0.001)
+        assert moved == orc.record_bytes(64, 64, 1024, 1, 0)
+        views = []
+        for _ in range(2000):
+            views = ring.poll_host()
+            if views:
+                break
+            time.sleep(0.001)
+        assert len(views) == 1 and views[0].seq == 0
+        ref = orc.build_record(t.cpu(), reqs, seq=0, step_id=0, point_id=0, out_dtype=1)
+        assert np.array_equal(views[0].bytes(), ref)
+
+
+def test_a_record_larger_than_the_host_ring_is_refused(B):
+    t = prng.randn_bf16(62, 64 * 1024, DEV).view(64, 1024)
+    reqs = np.array([(0, 0, 0, 64, 1)], dtype=np.uint32)          # 128 KiB of payload
+    with B.Ring(1 << 20, 1 << 16) as ring:                        # device ring 1 MiB, host ring 64 KiB
+        rc = ring.observe_tensor(0, t, reqs, step_id=0, allow=(B.ERR_TOO_LARGE,))
+        assert rc == B.ERR_TOO_LARGE
+        assert ring.get_stats().launched_records == 0
+        ring.observe_tensor(0, t, np.array([(0, 0, 0, 16, 1)], dtype=np.uint32), step_id=0)   # 32 KiB fits
+        ring.drain(B.DRAIN_FLUSH)
+        assert len(ring.poll_host()) == 1
