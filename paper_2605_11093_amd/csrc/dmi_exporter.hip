@@ -7,6 +7,15 @@ using namespace dmi::host;
 
 namespace {
 
+// Wait for `pred` under `lk` for at most timeout_ms.  Against the system clock on purpose: that wait
+// is pthread_cond_timedwait, which ThreadSanitizer follows; this libstdc++'s steady-clock wait is
+// pthread_cond_clockwait, which it does not (it then believes the mutex held throughout the wait).
+template <typename Pred>
+bool wait_ms(std::condition_variable &cv, std::unique_lock<std::mutex> &lk, uint32_t timeout_ms, Pred pred)
+{
+    return cv.wait_until(lk, std::chrono::system_clock::now() + std::chrono::milliseconds(timeout_ms), pred);
+}
+
 // Exporter stage 3 for one record copy: shape / dtype from the header, one slice per request with rows.
 void slice_record(RecordCopy *rc, std::vector<dmi_slice_t> &made)
 {
@@ -158,7 +167,7 @@ dmi_status_t dmi_exporter_next(dmi_ring_t *r, dmi_slice_t *out, uint32_t timeout
 {
     if (!r || !out) return fail(DMI_ERR_INVALID_ARG, "NULL argument");
     std::unique_lock<std::mutex> lk(r->emu);
-    if (!r->ecv_data.wait_for(lk, std::chrono::milliseconds(timeout_ms), [&] { return !r->slices.empty(); }))
+    if (!wait_ms(r->ecv_data, lk, timeout_ms, [&] { return !r->slices.empty(); }))
         return fail(DMI_ERR_AGAIN, "no slice within %u ms", timeout_ms);
     *out = r->slices.front();
     r->slices.pop_front();
@@ -170,7 +179,7 @@ dmi_status_t dmi_exporter_next_many(dmi_ring_t *r, dmi_slice_t *out, uint32_t ma
     if (!r || !n || (max && !out)) return fail(DMI_ERR_INVALID_ARG, "NULL argument");
     *n = 0;
     std::unique_lock<std::mutex> lk(r->emu);
-    if (!r->ecv_data.wait_for(lk, std::chrono::milliseconds(timeout_ms), [&] { return !r->slices.empty(); }))
+    if (!wait_ms(r->ecv_data, lk, timeout_ms, [&] { return !r->slices.empty(); }))
         return fail(DMI_ERR_AGAIN, "no slice within %u ms", timeout_ms);
     while (*n < max && !r->slices.empty()) {
         out[(*n)++] = r->slices.front();

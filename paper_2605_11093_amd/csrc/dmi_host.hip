@@ -102,6 +102,13 @@ dmi_status_t advance_commits(dmi_ring *r, bool block)
 
 uint64_t read_committed(const dmi_ring *r) { return r->committed.load(std::memory_order_acquire); }
 
+// The drained-up-to mark, where the kernels read it: one pinned word, written here and read by a
+// lane of a running kernel across the host link at any time, so the store is an atomic one.
+static void publish_tail(dmi_ring *r, uint64_t mark)
+{
+    __atomic_store_n(const_cast<uint64_t *>(r->htail), mark, __ATOMIC_RELEASE);
+}
+
 // Retire finished copies (all of them at once: the drain stream is idle).  Caller holds r->mu.
 dmi_status_t reap(dmi_ring *r, bool wait)
 {
@@ -110,7 +117,7 @@ dmi_status_t reap(dmi_ring *r, bool wait)
     if (e == hipErrorNotReady) return DMI_OK;
     if (e != hipSuccess) return fail(DMI_ERR_HIP, "drain stream: %s", hipGetErrorString(e));
     r->drain_done.store(r->drain_issued, std::memory_order_release);
-    *r->htail = r->drain_issued;
+    publish_tail(r, r->drain_issued);
     return DMI_OK;
 }
 
@@ -179,7 +186,7 @@ dmi_status_t drain(dmi_ring *r, bool wait, uint64_t *moved, bool *host_full)
     std::lock_guard<std::mutex> lk(r->mu);
     if (r->drain_done.load(std::memory_order_relaxed) < mark) {
         r->drain_done.store(mark, std::memory_order_release);
-        *r->htail = mark;       // the span may be reused only now that its copies have run
+        publish_tail(r, mark);  // the span may be reused only now that its copies have run
     }
     return DMI_OK;
 }
@@ -331,6 +338,22 @@ uint32_t plan_grid(const CaptureArgs &a, uint32_t nb)
     }
     return groups < 1u ? 1u : groups > kMaxGrid ? kMaxGrid : (uint32_t)groups;
 }
+
+} }  // namespace dmi::host
+namespace dmi {
+// Which launches the decode-shaped kernel can take (see capture_decode_kernel).
+bool decode_kernel_applies(const CaptureArgs &a, bool vec16)
+{
+    // one row per request (with a keep vector: up to 1024 requests), or, without a keep vector, any
+    // selection of at most 1024 rows (the host then lists the source row of every output row)
+    const bool shape = a.simple || (a.one_row_each && a.keep_mask && a.n_reqs <= 1024u) ||
+                       (!a.keep_mask && a.listed_rows >= 1u && a.listed_rows <= kDecodeMaxListed);
+    // 16-bit sources: bf16 with any supported output, fp16 as it is (or summaries only)
+    const bool types = a.src_dtype == 1u || (a.src_dtype == 2u && (a.out_dtype == 2u || a.out_dtype == 0u));
+    return shape && !a.paged && vec16 && types && a.units_per_row <= 4u * kThreads && a.n_reqs >= 1u;
+}
+}  // namespace dmi
+namespace dmi { namespace host {
 
 // Which kernel a launch of `nb` decode-shaped tensors takes.  The decode-shaped kernel is the
 // quickest way through a small launch, where every dependent trip to memory counts; from

@@ -1450,17 +1450,6 @@ hipError_t launch_capture(const CaptureArgs &a, const BatchArgs &b, uint32_t gri
     return vec16 ? launch_o<2, 8>(a, b, grid, s) : launch_o<2, 1>(a, b, grid, s);
 }
 
-bool decode_kernel_applies(const CaptureArgs &a, bool vec16)
-{
-    // one row per request (with a keep vector: up to 1024 requests), or, without a keep vector, any
-    // selection of at most 1024 rows (the host then lists the source row of every output row)
-    const bool shape = a.simple || (a.one_row_each && a.keep_mask && a.n_reqs <= 1024u) ||
-                       (!a.keep_mask && a.listed_rows >= 1u && a.listed_rows <= kDecodeMaxListed);
-    // 16-bit sources: bf16 with any supported output, fp16 as it is (or summaries only)
-    const bool types = a.src_dtype == 1u || (a.src_dtype == 2u && (a.out_dtype == 2u || a.out_dtype == 0u));
-    return shape && !a.paged && vec16 && types && a.units_per_row <= 4u * kThreads && a.n_reqs >= 1u;
-}
-
 template <int OUT>
 static hipError_t launch_decode_t(const DecodeArgs &d, const BatchArgs &b, uint32_t n_batch, bool summaries,
                                   hipStream_t s)
