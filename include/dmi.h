@@ -99,10 +99,14 @@ enum {
  *             the per-request prefix sums live in LDS).
  *   rank_tag: written into every header (section 4.5: records carry the
  *             producer's parallel coordinates).
- *   bg_min_bytes / bg_timeout_us: the background drain thread issues a copy
- *             once this many committed bytes are waiting or the oldest has
- *             waited this long (section 4.3: byte-count and timeout thresholds);
- *             0 = 1 MiB / 200 us.
+ *   bg_min_bytes, bg_min_records, bg_occupancy_pct, bg_timeout_us: when the library's drain
+ *             thread issues a batch of copies (section 4.3: batched to avoid fragmented
+ *             transfers, "once enough ready entries accumulate, or configurable occupancy,
+ *             byte-count, or timeout thresholds are reached"): as soon as this many committed
+ *             bytes are waiting, or this many committed records, or the device ring is this
+ *             full (per cent of its capacity, undrained bytes), or the oldest waiting byte has
+ *             waited this long.  0 = 1 MiB / 64 records / 50 % / 200 us.  A trigger is switched
+ *             off by a value it cannot reach (UINT64_MAX, UINT32_MAX, more than 100, UINT32_MAX).
  *   block_timeout_ms: how long a blocking call waits for room before returning
  *             DMI_ERR_AGAIN (0 = 2000 ms).
  * Returns DMI_ERR_HIP if the device or a HIP allocation is not available,
@@ -118,6 +122,8 @@ typedef struct {
     uint64_t bg_min_bytes;
     uint32_t bg_timeout_us;
     uint32_t block_timeout_ms;
+    uint32_t bg_min_records;
+    uint32_t bg_occupancy_pct;
 } dmi_ring_config_t;
 
 /* The environment variable DMI_DRAIN_MODE ("copy" or "kernel") overrides the drain engine chosen in flags. */

@@ -36,7 +36,8 @@ class RingConfig(C.Structure):
                 ("device_id", C.c_int32), ("flags", C.c_uint32),
                 ("max_reqs_per_observe", C.c_uint32), ("rank_tag", C.c_uint32),
                 ("bg_min_bytes", C.c_uint64), ("bg_timeout_us", C.c_uint32),
-                ("block_timeout_ms", C.c_uint32)]
+                ("block_timeout_ms", C.c_uint32), ("bg_min_records", C.c_uint32),
+                ("bg_occupancy_pct", C.c_uint32)]
 
 
 class Tensor(C.Structure):
@@ -464,9 +465,11 @@ class Ring:
 
     def __init__(self, device_ring_bytes: int, host_ring_bytes: int, *, device_id: int = 0,
                  flags: int = 0, max_reqs_per_observe: int = 0, rank_tag: int = 0,
-                 bg_min_bytes: int = 0, bg_timeout_us: int = 0, block_timeout_ms: int = 0):
+                 bg_min_bytes: int = 0, bg_timeout_us: int = 0, block_timeout_ms: int = 0,
+                 bg_min_records: int = 0, bg_occupancy_pct: int = 0):
         cfg = RingConfig(device_ring_bytes, host_ring_bytes, device_id, flags, max_reqs_per_observe,
-                         rank_tag, bg_min_bytes, bg_timeout_us, block_timeout_ms)
+                         rank_tag, bg_min_bytes, bg_timeout_us, block_timeout_ms, bg_min_records,
+                         bg_occupancy_pct)
         h = C.c_void_p()
         _check(lib().dmi_ring_create(C.byref(cfg), C.byref(h)))
         self._h = h

@@ -128,7 +128,12 @@ dmi_status_t drain_issue_locked(dmi_ring *r, uint64_t *moved, bool *host_full)
     if (host_full) *host_full = false;
     dmi_status_t st = reap(r, false);
     if (st != DMI_OK) return st;
-    const uint64_t committed = read_committed(r);
+    uint64_t committed, committed_records;
+    {   // the head and the record count that belong to it
+        std::lock_guard<std::mutex> pk(r->pmu);
+        committed = read_committed(r);
+        committed_records = r->snap[0];
+    }
     atomic_max(r->dev_high, committed - r->drain_done.load(std::memory_order_relaxed));
     const uint64_t avail = committed - r->drain_issued;
     const uint64_t host_free = r->host_cap - (r->drain_issued - r->released);
@@ -159,6 +164,7 @@ dmi_status_t drain_issue_locked(dmi_ring *r, uint64_t *moved, bool *host_full)
             }
         }
         r->drain_issued = from + n;
+        if (r->drain_issued == committed) r->drain_issued_records = committed_records;
         r->drained_bytes += n;
         r->drain_batches += 1;
         atomic_max(r->host_high, r->drain_issued - r->released);
@@ -689,11 +695,19 @@ dmi_status_t gate_batch(dmi_ring *r, uint32_t n, const uint32_t *point_ids, cons
     return DMI_OK;
 }
 
+// The library's drain thread (section 4.3): follows the commits and issues a batch of copies once
+// enough has accumulated by any of four measures: committed bytes, committed records, how full the
+// device ring is, how long the oldest waiting byte has waited.
 void bg_loop(dmi_ring *r)
 {
     (void)hipSetDevice(r->dev);
     const uint64_t min_bytes = r->cfg.bg_min_bytes ? r->cfg.bg_min_bytes : (1u << 20);
+    const uint64_t min_records = r->cfg.bg_min_records ? r->cfg.bg_min_records : 64u;
+    const uint64_t occupancy_pct = r->cfg.bg_occupancy_pct ? r->cfg.bg_occupancy_pct : 50u;
     const uint64_t timeout_ns = (uint64_t)(r->cfg.bg_timeout_us ? r->cfg.bg_timeout_us : 200u) * 1000ull;
+    // how long the producer must have paused before this thread puts a probe of its own behind
+    // its launches (while it keeps launching it probes by itself)
+    const uint64_t quiet_ns = timeout_ns < 200000ull ? timeout_ns : 200000ull;
     uint64_t waiting_since = 0, last_probe = 0;
     while (!r->stop.load(std::memory_order_acquire)) {
         if (r->quiet.load(std::memory_order_acquire)) {
@@ -708,26 +722,37 @@ void bg_loop(dmi_ring *r)
             std::lock_guard<std::mutex> lk(r->pmu);
             idle_probes = r->probes.empty();
         }
-        // cover launches the producer left unprobed once it has paused (while it keeps launching it
-        // probes by itself): every probe is a barrier, or a small launch, in the inference queue
-        if (idle_probes && now_ns() - last_probe >= timeout_ns &&
-            now_ns() - r->last_launch_ns.load(std::memory_order_relaxed) >= timeout_ns) {
+        // every probe is a barrier, or a small launch, in the inference queue
+        if (idle_probes && now_ns() - last_probe >= quiet_ns &&
+            now_ns() - r->last_launch_ns.load(std::memory_order_relaxed) >= quiet_ns) {
             (void)record_probe(r);
             last_probe = now_ns();
         }
         (void)advance_commits(r, false);
-        uint64_t pending_bytes;
+        uint64_t pending_bytes, pending_records, undrained;
         {
             std::lock_guard<std::mutex> lk(r->mu);
             // copies issued by somebody's non-blocking dmi_drain are noted here as they finish: with
             // this thread running, nobody else looks at the drain stream
             (void)reap(r, false);
-            pending_bytes = read_committed(r) - r->drain_issued;
+            uint64_t committed, committed_records;
+            {
+                std::lock_guard<std::mutex> pk(r->pmu);
+                committed = read_committed(r);
+                committed_records = r->snap[0];
+            }
+            pending_bytes = committed - r->drain_issued;
+            pending_records = pending_bytes ? committed_records - r->drain_issued_records : 0u;
+            undrained = committed - r->drain_done.load(std::memory_order_relaxed);
         }
         const uint64_t t = now_ns();
         if (pending_bytes == 0) waiting_since = 0;
         else if (!waiting_since) waiting_since = t;
-        if (pending_bytes >= min_bytes || (pending_bytes && t - waiting_since >= timeout_ns)) {
+        const bool by_bytes = pending_bytes >= min_bytes;
+        const bool by_records = pending_records >= min_records;
+        const bool by_occupancy = pending_bytes && undrained * 100u >= occupancy_pct * r->dev_cap;
+        const bool by_timeout = pending_bytes && t - waiting_since >= timeout_ns;
+        if (by_bytes || by_records || by_occupancy || by_timeout) {
             uint64_t moved = 0;
             (void)drain(r, true, &moved);
             waiting_since = 0;

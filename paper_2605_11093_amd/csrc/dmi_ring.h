@@ -198,6 +198,8 @@ struct dmi_ring {
     // drain / host ring state
     std::mutex mu;
     uint64_t drain_issued = 0;
+    uint64_t drain_issued_records = 0;                     // captured records below drain_issued (a lower bound
+                                                           // while a batch stops short of the committed head)
     std::atomic<uint64_t> drain_done{0};
     // The drain stream carries the batch copies only (no launch, no event, no small copy: any
     // of these is a packet on a second compute queue that waits for the copy in front of it, and

@@ -44,7 +44,7 @@ def test_record_bytes_matches_oracle(oracle):
 
 
 def test_struct_sizes_match_the_header_layout():
-    assert ctypes.sizeof(B.RingConfig) == 48
+    assert ctypes.sizeof(B.RingConfig) == 56
     assert ctypes.sizeof(B.ReqSel) == 20
     assert ctypes.sizeof(B.Tensor) == 48
     assert ctypes.sizeof(B.Selection) == 32

@@ -345,3 +345,61 @@ def test_a_record_larger_than_the_host_ring_is_refused(B):
         ring.observe_tensor(0, t, np.array([(0, 0, 0, 16, 1)], dtype=np.uint32), step_id=0)   # 32 KiB fits
         ring.drain(B.DRAIN_FLUSH)
         assert len(ring.poll_host()) == 1
+
+
+OFF64, OFF32 = (1 << 64) - 1, (1 << 32) - 1
+
+
+@pytest.mark.parametrize("trigger", ["bytes", "records", "occupancy", "timeout"])
+def test_each_drain_threshold_alone_starts_a_batch(B, trigger):
+    """The drain thread's four batching thresholds (ready entries, occupancy, byte count, timeout):
+    with three of them switched off, the fourth alone must start a batch once it is reached, and
+    nothing may be drained before."""
+    import time
+    t = prng.randn_bf16(63, 64 * 1024, DEV).view(64, 1024)
+    one = np.array([(0, 0, 0, 1, 1)], dtype=np.uint32)             # 64 + 64 + 2048 = 2176 bytes
+    many = np.array([(0, 0, 0, 40, 1)], dtype=np.uint32)           # 64 + 64 + 81920 = 82048 bytes
+    kw = dict(bg_min_bytes=OFF64, bg_min_records=OFF32, bg_occupancy_pct=101, bg_timeout_us=OFF32)
+    if trigger == "bytes":
+        kw["bg_min_bytes"], below, reach = 100_000, (many, 1), (many, 1)        # 82 KB, then 164 KB
+    elif trigger == "records":
+        kw["bg_min_records"], below, reach = 5, (one, 4), (one, 1)
+    elif trigger == "occupancy":
+        kw["bg_occupancy_pct"], below, reach = 25, (many, 3), (many, 1)          # 1 MiB ring: 246 KB, then 328 KB
+    else:
+        kw["bg_timeout_us"], below, reach = 30_000, None, (one, 1)
+    with B.Ring(1 << 20, 1 << 22, flags=B.BG_THREAD, **kw) as ring:
+        s = torch.cuda.current_stream()
+
+        def settle_commits():
+            s.synchronize()
+            time.sleep(0.02)            # the drain thread notices the commits (its probe comes after 200 us of quiet)
+
+        n_rec = 0
+        if below is not None:
+            for _ in range(below[1]):
+                ring.observe_tensor(0, t, below[0], step_id=0, stream=s.cuda_stream)
+                n_rec += 1
+            settle_commits()
+            st = ring.get_stats()
+            assert st.captured_records == n_rec and st.drain_batches == 0 and st.drained_bytes == 0
+        t0 = time.monotonic()
+        for _ in range(reach[1]):
+            ring.observe_tensor(0, t, reach[0], step_id=0, stream=s.cuda_stream)
+            n_rec += 1
+        s.synchronize()
+        if trigger == "timeout":
+            time.sleep(0.005)
+            assert ring.get_stats().drain_batches == 0              # 5 ms in: not yet
+        for _ in range(2000):
+            st = ring.get_stats()
+            if st.drain_batches:
+                break
+            time.sleep(0.001)
+        assert st.drain_batches >= 1 and st.drained_bytes == st.captured_bytes and st.captured_records == n_rec
+        if trigger == "timeout":
+            assert time.monotonic() - t0 >= 0.030
+        for _ in range(200):
+            if len(ring.poll_host()) or ring.get_stats().released_bytes:
+                break
+            time.sleep(0.001)
