@@ -129,9 +129,10 @@ typedef struct {
 /* The environment variable DMI_DRAIN_MODE ("copy" or "kernel") overrides the drain engine chosen in flags. */
 dmi_status_t dmi_ring_create(const dmi_ring_config_t *cfg /*[host]*/, dmi_ring_t **out /*[host]*/);
 
-/* Stops the drain thread, waits for the library's own streams, frees both
- * rings.  Undrained data is discarded.  The caller must have synchronised the
- * streams it passed to dmi_observe. */
+/* End of the staging rings' life (section 4.2: allocated once, for the whole run): stops the
+ * drain thread and the exporter, waits for the library's own streams, frees both rings and the
+ * control memory.  Undrained data is discarded.  The caller must have synchronised the streams
+ * it passed to dmi_observe, and destroyed the ring's replayable steps. */
 dmi_status_t dmi_ring_destroy(dmi_ring_t *ring);
 
 /* Observed tensor: a row-major matrix [shape[0], shape[1]] of `dtype`
@@ -307,11 +308,16 @@ typedef struct {
     uint64_t seq;
 } dmi_record_view_t;
 
-/* Return up to max complete, not yet polled records in sequence order. */
+/* The consumer's side of the pinned host buffer (section 4.3: the stage behind the drain takes
+ * payloads out of pinned staging): up to max complete, not yet polled records, in sequence
+ * order (section 4.2: ring order is hook order).  *n [host] = how many.  A record is complete
+ * once the copy that carries its last byte has finished.  Views stay valid until released. */
 dmi_status_t dmi_poll_host(dmi_ring_t *ring, dmi_record_view_t *out /*[host]*/, uint32_t max,
                            uint32_t *n /*[host]*/);
 
-/* Give back every polled record with seq <= upto_seq_inclusive. */
+/* Give back the pinned space of every polled record with seq <= upto_seq_inclusive (section 4.3:
+ * pinned memory is limited and is released as soon as the consumer has taken the payload; the
+ * drain, and through it the backpressure policy, sees the space at once). */
 dmi_status_t dmi_release_host(dmi_ring_t *ring, uint64_t upto_seq_inclusive);
 
 /*
@@ -499,16 +505,16 @@ typedef struct {
                                    stored as zeros (read from the device, synchronises the library's
                                    own stream only) */
 } dmi_stats_t;
-/* Device-side counters (captured_*, dropped_*) cover the launches whose completion the
- * library has observed: after dmi_drain(DMI_DRAIN_FLUSH) that is all of them. */
+/* Counters of the observation path (section 4.4: what was dropped under best effort is counted,
+ * section 6 reports overhead and volume from such counters).  Device-side counters (captured_*,
+ * dropped_*) cover the launches whose completion the library has observed: after
+ * dmi_drain(DMI_DRAIN_FLUSH) that is all of them.  May be called from any thread; each value is
+ * read atomically, the set of values is not one consistent snapshot while other threads run. */
 dmi_status_t dmi_get_stats(dmi_ring_t *ring, dmi_stats_t *out /*[host]*/);
-/* Records of one point discarded by drop-newest (synchronises the library's
- * own stream only). */
+/* Records of one observation point discarded under best effort (section 4.4: drops are made
+ * visible per hook, so that a consumer knows which points have gaps).  Reads the device's
+ * counter: synchronises the library's own stream only. */
 dmi_status_t dmi_get_point_drops(dmi_ring_t *ring, uint32_t point_id, uint64_t *n /*[host]*/);
-
-/* Test hook: fill both rings with one byte value (synchronous).  Lets a test see
- * that every byte of every record, pads included, is written by the capture. */
-dmi_status_t dmi_debug_fill_rings(dmi_ring_t *ring, uint8_t value);
 
 /* Pure host helpers (no GPU needed). */
 uint64_t dmi_record_bytes(uint32_t n_reqs, uint64_t n_rows, uint32_t row_elems, uint32_t out_dtype,

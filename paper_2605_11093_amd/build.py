@@ -11,7 +11,7 @@ SO = os.path.join(HERE, "libdmi.so")
 SOURCES = [os.path.join(HERE, "csrc", f) for f in ("dmi_kernels.hip", "dmi_host.hip", "dmi_step.hip",
                                                      "dmi_exporter.hip", "dmi_noalloc.hip")]
 HEADERS = [os.path.join(HERE, "csrc", "dmi_internal.h"), os.path.join(HERE, "csrc", "dmi_ring.h"),
-           os.path.join(ROOT, "include", "dmi.h")]
+           os.path.join(ROOT, "include", "dmi.h"), os.path.join(ROOT, "include", "dmi_debug.h")]
 
 
 def hipcc() -> str:

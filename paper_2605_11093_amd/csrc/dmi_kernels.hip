@@ -368,18 +368,6 @@ struct RowRef {
                             // is copied around and should stay in registers)
 };
 
-// Optional phase timestamps (development builds with -DDMI_TRACE only).
-#ifdef DMI_TRACE
-__device__ uint64_t g_trace[256 * 8];
-#define DMI_STAMP(k) do { if (tid == 0 && blockIdx.x < 256) g_trace[blockIdx.x * 8 + (k)] = wall_clock64(); } while (0)
-// decode-shaped kernel: first row workgroup and the extra workgroup of the last 32 launches
-#define DMI_STAMP_D(k) do { if (threadIdx.x == 0 && (blockIdx.x == 0 || blockIdx.x == a.n_wg_rows)) \
-        g_trace[(a.seq & 31u) * 16u + (blockIdx.x == 0 ? 0u : 8u) + (k)] = wall_clock64(); } while (0)
-#else
-#define DMI_STAMP(k) do { } while (0)
-#define DMI_STAMP_D(k) do { } while (0)
-#endif
-
 // Control words of one launch, fetched by one lane per workgroup.  Every load is issued
 // before any result is used, whether or not this launch needs it: loads issued together
 // cost one trip to memory, loads issued as their conditions become known cost one each.
@@ -460,7 +448,6 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureKernelAr
     const uint32_t nb = (n_reqs + 63u) / 64u;
     const uint32_t par = a.par_in;
 
-    DMI_STAMP(0);
     // -- control words: lane 0 of the last wavefront fetches head, tail copy, running counters
     //    and (for a replayable step) the step's parameters, all at once and whether or not this
     //    workgroup will need them, while the first wavefronts start on the request table.
@@ -492,7 +479,6 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureKernelAr
         lds[m.bcast + 11] = (uint32_t)(ct.step_id >> 32);
     };
     if (tid < 8) lds[m.heads + tid] = a.heads_sel[tid];
-    DMI_STAMP(1);
 
     if (!simple) {
         // -- per-request kept row counts -> exclusive prefix sums (wavefront shuffle scans)
@@ -600,7 +586,6 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureKernelAr
     }
     lds_barrier();
 
-    DMI_STAMP(2);
     // -- record geometry
     const uint32_t n_rows = simple ? n_reqs : pref[n_reqs];
     const uint32_t es_out = OUT == OUT_NONE ? 0u : OUT == OUT_FP8 ? 1u : (uint32_t)ES_IN;
@@ -792,7 +777,6 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureKernelAr
             }
         }
 
-        DMI_STAMP(3);
         if constexpr (!SUMM) {
             if constexpr (OUT != OUT_NONE) {
                 Accum dummy = {0.f, 0.f, 0u};
@@ -1014,11 +998,9 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureKernelAr
                         }
                     }
                     if (cur_pass == spr - 1u) {     // the row is complete: reduce and store its summaries
-                        DMI_STAMP(5);
                         acc.ss = wave_sum(acc.ss);
                         acc.s = wave_sum(acc.s);
                         uint32_t am = wave_max_u32(fold_am<ES_IN, VEC>(acc.am));
-                        DMI_STAMP(6);
                         if (rpw == 1u) {
                             lds_barrier();        // the previous row's readers are done with red[]
                             if (lane == 0) {
@@ -1033,7 +1015,6 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureKernelAr
                             const uint32_t m01 = ra[0] > ra[1] ? ra[0] : ra[1], m23 = ra[2] > ra[3] ? ra[2] : ra[3];
                             am = m01 > m23 ? m01 : m23;
                         }
-                        DMI_STAMP(7);
                         if (active && l == 0) {
                             uint64_t o = off_sum + g * 4u;
                             if (a.summary_mask & 1u) { ring_store<float>(w, o, sqrtf(acc.ss)); o += sum_arr; }
@@ -1052,15 +1033,8 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureKernelAr
             }
         }
     }
-    DMI_STAMP(4);
 }
 
-#ifdef DMI_TRACE
-extern "C" int dmi_trace_read(uint64_t *out)
-{
-    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_trace), sizeof(uint64_t) * 256 * 8);
-}
-#endif
 
 // ---------------------------------------------------------------- decode-shaped capture
 // The common case of the paper's workloads (every layer's hidden state at a decode step):
@@ -1116,7 +1090,6 @@ __global__ void __launch_bounds__(kThreads) capture_decode_kernel(const DecodeAr
 {
     __shared__ uint32_t sh[32];
     __shared__ uint64_t kept_bits[16];      // MASK: bit i of word q = request 64 q + i is kept
-    DMI_STAMP_D(0);
     const uint32_t y = blockIdx.y;          // which tensor of the batch
     const uint8_t *const src = b.src[y];
     const uint32_t point_id = b.point[y];
@@ -1127,7 +1100,6 @@ __global__ void __launch_bounds__(kThreads) capture_decode_kernel(const DecodeAr
     const uint32_t par = (a.flags & kDecParIn) ? 1u : 0u;
     const bool meta_wg = blockIdx.x == a.n_wg_rows;
     constexpr uint32_t kCtlTid = kThreads - 64u;
-    DMI_STAMP_D(1);
 
     // control words first (they depend on nothing but the arguments), then the row
     uint64_t cnt_cap[3] = {0, 0, 0}, cnt_drop[3] = {0, 0, 0}, tail_now = 0, seq = a.seq;
@@ -1212,7 +1184,6 @@ __global__ void __launch_bounds__(kThreads) capture_decode_kernel(const DecodeAr
         }
     }
     lds_barrier();
-    DMI_STAMP_D(2);
     const uint64_t head0 = (uint64_t)sh[0] | ((uint64_t)sh[1] << 32);
     const uint64_t tail = (uint64_t)sh[2] | ((uint64_t)sh[3] << 32);
     const uint32_t flags = sh[6];
@@ -1318,7 +1289,6 @@ __global__ void __launch_bounds__(kThreads) capture_decode_kernel(const DecodeAr
             const uint32_t arr = k / spad, i = k - arr * spad;
             ring_store<uint32_t>(w, off_sum + arr * sum_arr + (uint64_t)n_rows * 4u + 4ull * i, 0u);
         }
-        DMI_STAMP_D(4);
         return;
     }
 
@@ -1333,7 +1303,6 @@ __global__ void __launch_bounds__(kThreads) capture_decode_kernel(const DecodeAr
         if (c < a.units_per_row)
             emit_unit<2, 8, OUT, false>(w, row_off + (uint64_t)c * NB_OUT, v[k], a.hdr7 & 0xFFu, acc);
     }
-    DMI_STAMP_D(3);
     if constexpr (SUMM) {
         if (tid == 0) {
             const float *red = reinterpret_cast<const float *>(sh + 8);
@@ -1347,7 +1316,6 @@ __global__ void __launch_bounds__(kThreads) capture_decode_kernel(const DecodeAr
             if (a.summary_mask & 4u) { ring_store<float>(w, o, am_value(am, a.hdr7 & 0xFFu)); }
         }
     }
-    DMI_STAMP_D(5);
 }
 
 // ---------------------------------------------------------------- small kernels

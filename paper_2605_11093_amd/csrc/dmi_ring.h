@@ -3,6 +3,7 @@
 // exporter stages 2-3).  Not part of the public ABI.
 #pragma once
 #include "dmi.h"
+#include "dmi_debug.h"
 #include "dmi_internal.h"
 
 #include <algorithm>
