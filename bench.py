@@ -878,6 +878,7 @@ def main():
                          "the reference the profiler's HBM byte counters are scaled by; 'list' names the shapes")
     ap.add_argument("--kernels", default=None,
                     help="time just these kernel shapes (comma-separated names, see --profile-shape list) and exit")
+    ap.add_argument("--hook-cost", action="store_true", help="measure just the host cost per hook and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build is a one-GPU path (each rank runs a private ring with no "
@@ -910,6 +911,10 @@ def main():
         return
 
     extra = {}
+    if args.hook_cost:
+        run_hook_cost(ctx, extra)
+        print(json.dumps(extra), flush=True)
+        return
     run_probes(ctx, extra)
 
     # ------------------------------------------------------------------ headline: config 5, k = 1, batched

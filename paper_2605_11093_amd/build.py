@@ -45,6 +45,30 @@ def build(force: bool = True) -> str:
     return SO
 
 
+TORCH_SO = os.path.join(HERE, "libdmi_torch.so")
+TORCH_SRC = os.path.join(HERE, "csrc", "dmi_torch_op.cpp")
+
+
+def build_torch_op() -> str:
+    """The HookPoint operator as a native PyTorch operator (host code only: g++ against libtorch and
+    libdmi.so, which must be built first)."""
+    import torch
+    from torch.utils import cpp_extension as ce
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    tlib = os.path.join(os.path.dirname(torch.__file__), "lib")
+    cmd = ["g++", "-std=c++17", "-O2", "-fPIC", "-shared", "-Wall", "-Wno-unused-function",
+           "-D__HIP_PLATFORM_AMD__=1", "-DUSE_ROCM=1",
+           f"-D_GLIBCXX_USE_CXX11_ABI={int(torch._C._GLIBCXX_USE_CXX11_ABI)}",
+           "-I", os.path.join(ROOT, "include")]
+    for inc in ce.include_paths("cuda"):
+        cmd += ["-isystem", inc]
+    cmd += [TORCH_SRC, "-o", TORCH_SO, "-L", HERE, "-ldmi", "-L", tlib, "-ltorch", "-ltorch_cpu", "-lc10", "-lc10_hip",
+            "-L", os.path.join(rocm, "lib"), "-lamdhip64",
+            "-Wl,-rpath,$ORIGIN", "-Wl,-rpath," + tlib, "-Wl,-rpath," + os.path.join(rocm, "lib")]
+    subprocess.check_call(cmd)
+    return TORCH_SO
+
+
 C_CLIENT_SRC = os.path.join(ROOT, "examples", "c_client.c")
 C_CLIENT = os.path.join(ROOT, "examples", "c_client")
 
@@ -63,4 +87,5 @@ def build_c_client() -> str:
 if __name__ == "__main__":
     print(build())
     print(build_bench())
+    print(build_torch_op())
     print(build_c_client())

@@ -3,9 +3,12 @@ in a model's forward; reaching it launches one capture on the current stream and
 returns the tensor itself.  No Python callback runs on the GPU's time line, no host
 synchronisation happens, the tensor is neither modified nor retained.
 
-The work is the C ABI's dmi_observe; this file only finds the arguments: the ring, the
-point id, and the step context (request selection, step id) that the serving loop sets
-once per forward step (the paper's prepare_step).
+Reaching a HookPoint is one call of the operator dmi::observe(x, hook), which is native code
+(csrc/dmi_torch_op.cpp, built into libdmi_torch.so): it reads the tensor's address, layout and
+current stream and calls the C ABI's dmi_observe.  This file only keeps the handles: the ring,
+the point id, and the step context (request selection, step id) that the serving loop sets once
+per forward step (the paper's prepare_step).  There is no Python implementation of the operator:
+without the built library, making a HookPoint raises.
 
 Under graph capture (StepContext.capture) a HookPoint adds its launch to a replayable
 step (dmi_step_observe) instead, so the captures sit in the same graph as the model's own
@@ -13,6 +16,8 @@ kernels; StepContext.begin_replay / end_replay bracket each replay of that graph
 """
 from __future__ import annotations
 
+import ctypes as C
+import os
 import weakref
 from typing import Dict, Iterable, Optional
 
@@ -22,24 +27,77 @@ from torch import nn
 
 from . import binding as B
 
+_TORCH_SO = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libdmi_torch.so")
+_native = None
+
+
+def native():
+    """Load libdmi_torch.so: registers the operator dmi::observe with PyTorch and gives the handle
+    functions.  Raises if it has not been built."""
+    global _native
+    if _native is not None:
+        return _native
+    B.lib()                                     # libdmi.so first: the operator library links against it
+    if not os.path.exists(_TORCH_SO):
+        raise ImportError(f"{_TORCH_SO} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
+    torch.ops.load_library(_TORCH_SO)
+    L = C.CDLL(_TORCH_SO)
+    L.dmi_torch_ctx_create.restype = C.c_int32
+    L.dmi_torch_ctx_set.argtypes = [C.c_int32, C.c_uint64, C.c_void_p, C.c_uint32, C.c_void_p]
+    L.dmi_torch_ctx_capture.argtypes = [C.c_int32, C.c_void_p]
+    L.dmi_torch_ctx_nodes.argtypes = [C.c_int32, C.POINTER(C.c_uint32), C.c_uint32]
+    L.dmi_torch_ctx_nodes.restype = C.c_uint32
+    L.dmi_torch_hook_create.argtypes = [C.c_void_p, C.c_uint32, C.c_int32, C.c_uint32, C.c_int32]
+    L.dmi_torch_hook_create.restype = C.c_int32
+    L.dmi_torch_hook_destroy.argtypes = [C.c_int32]
+
+    @torch.library.register_fake("dmi::observe")
+    def _observe_fake(x, hook):                 # shape propagation for tracing: no result
+        return None
+
+    _native = L
+    return L
+
 
 class StepContext:
     """What every HookPoint of a forward step shares: which rows belong to which
-    request, the step id, an optional keep vector (device address)."""
+    request, the step id, an optional keep vector (device address).  The values live in the
+    operator library, where the hooks read them; this object is the handle."""
 
     def __init__(self):
-        self.reqs: Optional[np.ndarray] = None
+        self._id = native().dmi_torch_ctx_create()
+        self._reqs: Optional[np.ndarray] = None
         self.step_id = 0
         self.keep_mask_dev = 0
         self.step: Optional[B.Step] = None          # set while / after a graph capture
-        self._capturing = False
-        self._nodes: list = []
         self._keep_tensor = None
 
+    def _push(self):
+        r = self._reqs
+        B._check(native().dmi_torch_ctx_set(self._id, self.step_id, None if r is None else r.ctypes.data,
+                                            0 if r is None else r.shape[0], self.keep_mask_dev or None))
+
+    @property
+    def reqs(self) -> Optional[np.ndarray]:
+        return self._reqs
+
+    @reqs.setter
+    def reqs(self, value):
+        """None: no step prepared, hooks launch nothing."""
+        self._reqs = None if value is None else np.ascontiguousarray(np.asarray(value, dtype=np.uint32).reshape(-1, 5))
+        self._push()
+
     def prepare_step(self, step_id: int, reqs, keep_mask_dev: int = 0):
-        self.reqs = np.ascontiguousarray(np.asarray(reqs, dtype=np.uint32).reshape(-1, 5))
         self.step_id = int(step_id)
         self.keep_mask_dev = int(keep_mask_dev)
+        self.reqs = reqs
+
+    @property
+    def _nodes(self):
+        n = native().dmi_torch_ctx_nodes(self._id, None, 0)
+        out = (C.c_uint32 * max(n, 1))()
+        native().dmi_torch_ctx_nodes(self._id, out, n)
+        return list(out[:n])
 
     # -- graph capture and replay ------------------------------------------
     def capture(self, ring: B.Ring, reqs, *, max_observes: int = 64, keep_mask=None):
@@ -57,16 +115,14 @@ class StepContext:
         class _Capture:
             def __enter__(self_inner):
                 ctx.step = B.Step(ring, max_observes)
-                ctx.reqs = np.ascontiguousarray(np.asarray(reqs, dtype=np.uint32).reshape(-1, 5))
-                ctx.keep_mask_dev = 0 if keep_mask is None else keep_mask.data_ptr()
                 ctx._keep_tensor = keep_mask
-                ctx._nodes = []
+                ctx.prepare_step(ctx.step_id, reqs, 0 if keep_mask is None else keep_mask.data_ptr())
                 ctx.step.capture_begin()
-                ctx._capturing = True
+                B._check(native().dmi_torch_ctx_capture(ctx._id, ctx.step._h))
                 return ctx.step
 
             def __exit__(self_inner, *exc):
-                ctx._capturing = False
+                B._check(native().dmi_torch_ctx_capture(ctx._id, None))
                 ctx.step.seal()
                 return False
 
@@ -77,9 +133,10 @@ class StepContext:
         (same number of requests), then the step's policy gate and parameter upload."""
         if reqs is not None:
             ra = np.ascontiguousarray(np.asarray(reqs, dtype=np.uint32).reshape(-1, 5))
-            if not np.array_equal(ra, self.reqs):
-                if self._nodes:
-                    self.step.update(self._nodes[0], ra)    # all hook points share the step's one table
+            if not np.array_equal(ra, self._reqs):
+                nodes = self._nodes
+                if nodes:
+                    self.step.update(nodes[0], ra)          # all hook points share the step's one table
                 self.reqs = ra
         return self.step.begin(step_id, stream, allow=allow)
 
@@ -87,68 +144,28 @@ class StepContext:
         self.step.end(stream)
 
 
-# The custom-operator layer (paper section 4.1): reaching a HookPoint is one call of the
-# operator dmi::observe(x, hook), so a traced / compiled model carries the capture as an
-# ordinary node of its graph instead of breaking at a Python callback.  The operator is
-# declared as writing its input (it writes nothing): that keeps compilers from dropping a
-# call whose result nobody uses, and from moving it across other uses of the tensor.
-_HOOKS: "weakref.WeakValueDictionary[int, HookPoint]" = weakref.WeakValueDictionary()
-_next_hook_id = 0
-_op_registered = False
-
-
-def _register_op():
-    global _op_registered
-    if _op_registered:
-        return
-    _op_registered = True
-
-    @torch.library.custom_op("dmi::observe", mutates_args=("x",))
-    def _observe(x: torch.Tensor, hook: int) -> None:
-        _HOOKS[hook]._launch(x)
-
-
 class HookPoint(nn.Module):
     """Identity module that observes its input.  `enabled=False` makes it a plain
-    identity: nothing is launched (hook filtering)."""
+    identity: nothing is launched (hook filtering).  out_dtype None = store the source dtype."""
 
     def __init__(self, ring: B.Ring, point_id: int, ctx: StepContext, *, out_dtype: Optional[int] = None,
                  summary_mask: int = 0, enabled: bool = True, name: str = ""):
         super().__init__()
         self.ring, self.point_id, self.ctx = ring, int(point_id), ctx
         self.out_dtype, self.summary_mask, self.enabled, self.hook_name = out_dtype, summary_mask, enabled, name
-        _register_op()
-        global _next_hook_id
-        _next_hook_id += 1
-        self._hook_id = _next_hook_id
-        _HOOKS[self._hook_id] = self
+        hid = native().dmi_torch_hook_create(ring._h, self.point_id, -1 if out_dtype is None else int(out_dtype),
+                                             int(summary_mask), ctx._id)
+        B._check(hid)
+        self._hook_id = hid
+        weakref.finalize(self, native().dmi_torch_hook_destroy, hid)
 
     def forward(self, x: torch.Tensor) -> torch.Tensor:
         if not self.enabled:            # hook filtering: a disabled hook is not in the graph at all
             return x
+        if self.ring._h is None:
+            raise B.DmiError(B.ERR_CLOSED, "HookPoint reached after its ring was destroyed")
         torch.ops.dmi.observe(x, self._hook_id)
         return x
-
-    def _launch(self, x: torch.Tensor) -> None:
-        if self.ctx.reqs is None:
-            return
-        t = x if x.dim() == 2 else x.reshape(-1, x.shape[-1])      # [tokens, features] view, no copy
-        if t.stride(-1) != 1 or t.data_ptr() != x.data_ptr():
-            raise ValueError("HookPoint needs a tensor whose rows are contiguous in memory")
-        dt = B._torch_dtype_code(t)
-        if self.ctx._capturing:
-            node = self.ctx.step.observe_tensor(self.point_id, t, self.ctx.reqs,
-                                                stream=torch.cuda.current_stream(x.device).cuda_stream,
-                                                out_dtype=dt if self.out_dtype is None else self.out_dtype,
-                                                summary_mask=self.summary_mask, keep_mask=self.ctx._keep_tensor)
-            if node >= 0:
-                self.ctx._nodes.append(node)
-            return
-        self.ring.observe(self.point_id, t.data_ptr(), dt, tuple(t.shape), tuple(t.stride()), self.ctx.reqs,
-                          step_id=self.ctx.step_id, stream=torch.cuda.current_stream(x.device).cuda_stream,
-                          out_dtype=dt if self.out_dtype is None else self.out_dtype,
-                          summary_mask=self.summary_mask, keep_mask_dev=self.ctx.keep_mask_dev,
-                          allow=())
 
 
 def install_hookpoints(model: nn.Module, ring: B.Ring, ctx: StepContext, where: Dict[str, int],

@@ -66,3 +66,18 @@ def test_bad_arguments_are_rejected_before_any_gpu_work():
     L = dmi.lib()
     assert L.dmi_drain(None, 0, None) == B.ERR_INVALID_ARG
     assert b"NULL" in L.dmi_last_error()
+
+
+def test_hookpoint_operator_library_loads_and_has_no_cpu_path():
+    """libdmi_torch.so registers dmi::observe as a native operator for GPU tensors only: on a CPU
+    tensor the dispatcher refuses it (nothing silently falls back), and the handle functions work."""
+    from paper_2605_11093_amd import hookpoint as hp
+    L = hp.native()
+    assert "observe" in str(torch.ops.dmi.observe)
+    ctx = hp.StepContext()
+    ctx.prepare_step(3, [(1, 0, 0, 2, 1)])
+    assert ctx.reqs.tolist() == [[1, 0, 0, 2, 1]] and ctx._nodes == []
+    assert L.dmi_torch_ctx_set(10 ** 6, 0, None, 0, None) == B.ERR_INVALID_ARG
+    assert L.dmi_torch_hook_create(None, 0, -1, 0, ctx._id) == B.ERR_INVALID_ARG
+    with pytest.raises((NotImplementedError, RuntimeError)):
+        torch.ops.dmi.observe(torch.zeros(2, 2), 0)
