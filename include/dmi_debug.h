@@ -14,6 +14,10 @@ extern "C" {
  * (dmi.h) says that every pad byte is zero. */
 dmi_status_t dmi_debug_fill_rings(dmi_ring_t *ring, uint8_t value);
 
+/* How many pageable buffers the exporter's copy stage has taken from the allocator, and how many
+ * records found an idle buffer instead, since the ring was created [both host]. */
+dmi_status_t dmi_debug_exporter_allocs(dmi_ring_t *ring, uint64_t *allocated, uint64_t *reused);
+
 #ifdef __cplusplus
 }
 #endif

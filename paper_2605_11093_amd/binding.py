@@ -189,6 +189,8 @@ def lib():
     L.dmi_get_stats.argtypes = [C.c_void_p, P(StatsC)]
     L.dmi_get_point_drops.argtypes = [C.c_void_p, C.c_uint32, P(C.c_uint64)]
     L.dmi_debug_fill_rings.argtypes = [C.c_void_p, C.c_uint8]
+    L.dmi_debug_exporter_allocs.argtypes = [C.c_void_p, P(C.c_uint64), P(C.c_uint64)]
+    L.dmi_debug_exporter_allocs.restype = C.c_int32
     L.dmi_exporter_start.argtypes = [C.c_void_p, C.c_uint64, C.c_uint32]
     L.dmi_exporter_next.argtypes = [C.c_void_p, P(SliceC), C.c_uint32]
     L.dmi_exporter_release.argtypes = [C.c_void_p, P(SliceC)]
@@ -625,3 +627,9 @@ class Ring:
 
     def debug_fill_rings(self, value: int):
         _check(lib().dmi_debug_fill_rings(self._h, value))
+
+    def debug_exporter_allocs(self):
+        """(buffers taken from the allocator, records that reused an idle buffer) of the exporter's copy stage."""
+        a, b = C.c_uint64(0), C.c_uint64(0)
+        _check(lib().dmi_debug_exporter_allocs(self._h, C.byref(a), C.byref(b)))
+        return a.value, b.value

@@ -16,6 +16,63 @@ bool wait_ms(std::condition_variable &cv, std::unique_lock<std::mutex> &lk, uint
     return cv.wait_until(lk, std::chrono::system_clock::now() + std::chrono::milliseconds(timeout_ms), pred);
 }
 
+// Pageable buffers are reused instead of allocated per record (section 4.3: the copy stage must keep
+// up with the drain; a workload has few distinct record sizes, so nearly every record finds a buffer).
+// A buffer serves a record of size s if s <= cap <= s + s/8.  Idle buffers count against the budget:
+// in use + idle <= max_pageable_bytes (+ the 1/8 slack), the oldest idle ones are freed first.
+// Both functions need emu held.
+uint8_t *pool_take_locked(dmi_ring *r, uint64_t size, uint64_t *cap)
+{
+    for (size_t i = r->exp_pool.size(); i-- > 0;) {         // newest first: most likely still in cache
+        const PoolBuf b = r->exp_pool[i];
+        if (b.cap >= size && b.cap <= size + size / 8) {
+            r->exp_pool.erase(r->exp_pool.begin() + (ptrdiff_t)i);
+            r->exp_pool_bytes -= b.cap;
+            *cap = b.cap;
+            return b.p;
+        }
+    }
+    return nullptr;
+}
+
+void pool_trim_locked(dmi_ring *r, uint64_t keep_bytes)
+{
+    while (!r->exp_pool.empty() && r->exp_pool_bytes > keep_bytes) {
+        r->exp_pool_bytes -= r->exp_pool.front().cap;
+        free(r->exp_pool.front().p);
+        r->exp_pool.erase(r->exp_pool.begin());
+    }
+}
+
+// A record copy is done with: its budget share is free again, its buffer goes to the pool.
+void retire_locked(dmi_ring *r, RecordCopy *rc)
+{
+    r->exp_bytes -= rc->size;
+    r->exp_pool.push_back(PoolBuf{rc->bytes, rc->cap});
+    r->exp_pool_bytes += rc->cap;
+    // a stopped exporter keeps nothing: slices given back after dmi_exporter_stop free their memory
+    const bool keep = !r->exp_stop.load() && r->exp_max_bytes > r->exp_bytes;
+    pool_trim_locked(r, keep ? r->exp_max_bytes - r->exp_bytes : 0);
+    delete rc;
+}
+
+// A buffer for a record of `size` bytes: from the pool, else from the allocator.  If memory is short the
+// idle buffers go first; after that the budget is the caller's promise that the record fits, so wait for
+// the consumer to give copies back.
+uint8_t *buffer_for(dmi_ring *r, uint64_t size, uint64_t *cap)
+{
+    std::unique_lock<std::mutex> lk(r->emu);
+    for (;;) {
+        if (uint8_t *p = pool_take_locked(r, size, cap)) { r->exp_reuses++; return p; }
+        lk.unlock();
+        uint8_t *p = static_cast<uint8_t *>(malloc(size));
+        lk.lock();
+        if (p) { r->exp_mallocs++; *cap = size; return p; }
+        if (!r->exp_pool.empty()) { pool_trim_locked(r, 0); continue; }
+        wait_ms(r->ecv_space, lk, 1, [] { return false; });
+    }
+}
+
 // Exporter stage 3 for one record copy: shape / dtype from the header, one slice per request with rows.
 void slice_record(RecordCopy *rc, std::vector<dmi_slice_t> &made)
 {
@@ -79,11 +136,7 @@ void exporter_worker(dmi_ring *r)
         }
         RecordCopy *rc = new RecordCopy;
         rc->size = job.view.n0 + job.view.n1;
-        rc->bytes = static_cast<uint8_t *>(malloc(rc->size));
-        while (!rc->bytes) {        // the budget is the caller's promise that this fits; wait for memory
-            std::this_thread::sleep_for(std::chrono::milliseconds(1));
-            rc->bytes = static_cast<uint8_t *>(malloc(rc->size));
-        }
+        rc->bytes = buffer_for(r, rc->size, &rc->cap);
         memcpy(rc->bytes, job.view.p0, job.view.n0);
         if (job.view.n1) memcpy(rc->bytes + job.view.n0, job.view.p1, job.view.n1);
         std::vector<dmi_slice_t> made;
@@ -99,9 +152,7 @@ void exporter_worker(dmi_ring *r)
             ExportDone &d = r->done_jobs.begin()->second;
             (void)release_host_impl(r, d.seq);      // pinned space is free again, in ring order
             if (d.slices.empty()) {                 // nothing to hand out: the copy goes at once
-                r->exp_bytes -= d.rc->size;
-                free(d.rc->bytes);
-                delete d.rc;
+                retire_locked(r, d.rc);
                 r->ecv_space.notify_all();
             } else {
                 for (auto &sl : d.slices) r->slices.push_back(sl);
@@ -205,12 +256,18 @@ dmi_status_t dmi_exporter_release(dmi_ring_t *r, const dmi_slice_t *sl)
     if (rc->refs.fetch_sub(1) == 1) {
         {
             std::lock_guard<std::mutex> lk(r->emu);
-            r->exp_bytes -= rc->size;
+            retire_locked(r, rc);
         }
         r->ecv_space.notify_all();
-        free(rc->bytes);
-        delete rc;
     }
+    return DMI_OK;
+}
+
+dmi_status_t dmi_debug_exporter_allocs(dmi_ring_t *r, uint64_t *allocated, uint64_t *reused)
+{
+    if (!r || !allocated || !reused) return fail(DMI_ERR_INVALID_ARG, "NULL argument");
+    *allocated = r->exp_mallocs.load();
+    *reused = r->exp_reuses.load();
     return DMI_OK;
 }
 
@@ -238,9 +295,7 @@ dmi_status_t dmi_exporter_stop(dmi_ring_t *r)
         r->exp_bytes -= dropped;
         for (auto &kv : r->done_jobs) {
             if (kv.second.slices.empty()) {
-                r->exp_bytes -= kv.second.rc->size;
-                free(kv.second.rc->bytes);
-                delete kv.second.rc;
+                retire_locked(r, kv.second.rc);
             } else {
                 for (auto &sl : kv.second.slices) r->slices.push_back(sl);
             }
@@ -248,9 +303,10 @@ dmi_status_t dmi_exporter_stop(dmi_ring_t *r)
         r->done_jobs.clear();
         for (auto &sl : r->slices) {
             RecordCopy *rc = static_cast<RecordCopy *>(sl.owner);
-            if (rc->refs.fetch_sub(1) == 1) { r->exp_bytes -= rc->size; free(rc->bytes); delete rc; }
+            if (rc->refs.fetch_sub(1) == 1) retire_locked(r, rc);
         }
         r->slices.clear();
+        pool_trim_locked(r, 0);
     }
     r->exp_running.store(false);
     return DMI_OK;

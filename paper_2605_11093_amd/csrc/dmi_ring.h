@@ -74,8 +74,15 @@ struct SelCache {
 // One record copied out of the pinned ring (exporter stage 2) and shared by its slices.
 struct RecordCopy {
     uint8_t *bytes;
-    uint64_t size;
+    uint64_t size;              // the record's bytes
+    uint64_t cap;               // the buffer's bytes (>= size: buffers are reused, see PoolBuf)
     std::atomic<uint32_t> refs;
+};
+
+// An idle pageable buffer of the exporter, kept for the next record of about this size.
+struct PoolBuf {
+    uint8_t *p;
+    uint64_t cap;
 };
 
 struct ExportJob {
@@ -232,6 +239,9 @@ struct dmi_ring {
     std::deque<ExportJob> jobs;
     std::map<uint64_t, ExportDone> done_jobs;
     std::atomic<uint64_t> exp_records{0}, exp_copied_bytes{0};
+    std::vector<PoolBuf> exp_pool;          // idle buffers, oldest first (guarded by emu)
+    uint64_t exp_pool_bytes = 0;
+    std::atomic<uint64_t> exp_mallocs{0}, exp_reuses{0};
 };
 
 // A replayable step (section 4.4, policy manager): a fixed list of capture launches that

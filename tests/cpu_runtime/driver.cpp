@@ -18,6 +18,7 @@
 #include <vector>
 
 #include "dmi.h"
+#include "dmi_debug.h"
 
 #define CHECK(cond)                                                                          \
     do {                                                                                     \
@@ -250,6 +251,15 @@ void scenario(const char *name, uint32_t policy, bool use_exporter, bool with_st
             (void)dmi_drain(ring, DMI_DRAIN_NONBLOCK, nullptr);
         }
         CHECK(dmi_exporter_stop(ring) == DMI_OK);
+        // the copy stage reuses its pageable buffers: far fewer allocations than records
+        uint64_t allocated = 0, reused = 0;
+        CHECK(dmi_debug_exporter_allocs(ring, &allocated, &reused) == DMI_OK);
+        dmi_stats_t e;
+        CHECK(dmi_get_stats(ring, &e) == DMI_OK);
+        fprintf(stderr, "  exporter buffers: %llu allocated, %llu reused\n", (unsigned long long)allocated,
+                (unsigned long long)reused);
+        CHECK(allocated + reused == e.captured_records);
+        if (e.captured_records > 64) CHECK(allocated * 4 < e.captured_records);
     }
     dmi_stats_t s;
     CHECK(dmi_get_stats(ring, &s) == DMI_OK);

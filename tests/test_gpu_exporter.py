@@ -74,6 +74,8 @@ def test_slices_equal_the_decoders(which):
         s.synchronize()
         st = ring.get_stats()
         assert st.dropped_records == 0 and st.released_bytes == st.captured_bytes
+        allocated, reused = ring.debug_exporter_allocs()       # pageable buffers are pooled, not allocated per record
+        assert allocated + reused == st.captured_records       # (the reuse rate itself is checked on the CPU build)
     assert len(got) == len(expect)
     for g, (seq, q, rec, off, n) in zip(got, expect):
         assert (g["seq"], g["q"], g["step"], g["point"]) == (seq, q, rec.step_id, rec.point_id)
