@@ -184,6 +184,14 @@ def shape_table(ctx):
             g0 = grp[0]
             yield (f"config3_{nm}_fp8", lambda r, g0=g0: dmi.PreparedObserve(r, g0.point_id, g0.tensor, g0.reqs, out_dtype=B.DT_FP8),
                    alg, 8, rb * 10)
+            if nm == "resid":
+                # the same rows' worth of bytes from consecutive tokens instead of every fourth: does the
+                # stride through the source cost anything?
+                dense = g0.reqs.copy()
+                dense[:, 4] = 1
+                yield ("config3_resid_fp8_consecutive_tokens",
+                       lambda r, g0=g0, dense=dense: dmi.PreparedObserve(r, g0.point_id, g0.tensor, dense, out_dtype=B.DT_FP8),
+                       alg, 8, rb * 10)
             yield (f"config3_{nm}_fp8_batch{len(grp)}",
                    lambda r, grp=grp, g0=g0: dmi.PreparedBatch(r, [x.point_id for x in grp], [x.tensor for x in grp], g0.reqs,
                                                                out_dtype=B.DT_FP8), alg * len(grp), 4, rb * len(grp) * 6)

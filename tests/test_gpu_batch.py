@@ -120,6 +120,89 @@ def test_general_kernel_batch_long_rows(B, E, T, out_dtype):
         assert np.array_equal(got, ref)
 
 
+# A batch of long rows with more work items than fit the GPU at once: workgroups of a few items
+# each, many more of them than are resident, tensor after tensor.
+@pytest.mark.parametrize("E,T,n", [(4096, 3000, 4), (14336, 420, 3), (2048, 2600, 3), (5000, 700, 5), (4096, 1500, 128)])
+@pytest.mark.parametrize("out_dtype", [DT_BF16, DT_FP8])
+def test_long_batch_of_long_rows(B, E, T, n, out_dtype):
+    if n == 128:
+        T, per = 40, 11             # many small tensors: 128 x 40 rows of 512 units = 2,560 items
+        ts = _tensors(35, n, T, E)
+        reqs = [(1, 0, 0, per, 2), (2, 20, 1, 9, 2), (3, T - 1, 0, 1, 1)]
+    else:
+        ts = _tensors(35, n, T, E)
+        q = T // 4
+        reqs = [(1, 0, 0, q // 2, 2), (2, q, 3, q - 5, 1), (3, 2 * q, 0, q, 1), (4, 3 * q, 1, q // 3, 3), (5, T - 1, 0, 1, 1)]
+    rows = sum(r[3] for r in reqs)
+    es = 1 if out_dtype == DT_FP8 else 2
+    ring = 1 << max(23, int(np.ceil(np.log2(n * (rows * E * es + 4096)))) + 1)
+    for got, ref in _batch(B, ts, reqs, out_dtype=out_dtype, keep_mask=[1] * len(reqs), ring_bytes=ring):
+        assert np.array_equal(got, ref)
+    keep = [1, 0, 1, 1, 0][:len(reqs)]
+    for got, ref in _batch(B, ts, reqs, out_dtype=out_dtype, keep_mask=keep, ring_bytes=ring):
+        assert np.array_equal(got, ref)
+
+
+def test_long_batch_of_long_rows_wraps_and_drops_mid_batch(B):
+    """The same with the ring's end inside the batch, and under best effort with room for two and a
+    half of four records: records 0 and 1 stay, 2 and 3 are dropped and counted."""
+    E, T, n = 4096, 1600, 4
+    ts = _tensors(36, n, T, E)
+    reqs = np.array([(1, 0, 0, 700, 2), (2, 1400, 0, 200, 1), (3, 3, 0, 1, 1)], dtype=np.uint32)
+    rb = orc.record_bytes(3, 901, E, DT_FP8, 0)
+    km = torch.ones(3, dtype=torch.uint8, device=DEV)
+    refs = [orc.build_record(t.cpu(), reqs, seq=0, step_id=0, point_id=0, out_dtype=DT_FP8, keep_mask=[1, 1, 1]) for t in ts]
+
+    def same(v, i, seq, step, point):
+        got, ref = v.bytes(), refs[i].copy()
+        ref[8:16] = np.frombuffer(np.uint64(seq).tobytes(), dtype=np.uint8)
+        ref[16:24] = np.frombuffer(np.uint64(step).tobytes(), dtype=np.uint8)
+        ref[24:28] = np.frombuffer(np.uint32(point).tobytes(), dtype=np.uint8)
+        assert np.array_equal(got, ref), (seq, i)
+
+    s = torch.cuda.current_stream()
+    # (a) completeness policy, ring of 4.6 records: the second batch starts at 4 records and wraps
+    with B.Ring((rb * 46 // 10) // 64 * 64, 1 << 25) as ring:
+        for step in range(3):
+            rc, done = ring.observe_batch([5, 6, 7, 8], ts, reqs, step_id=step, stream=s.cuda_stream, out_dtype=DT_FP8,
+                                          keep_mask=km)
+            assert rc == B.OK and done == 4
+            ring.drain(B.DRAIN_FLUSH)
+            views = ring.poll_host()
+            assert [v.seq for v in views] == [4 * step + i for i in range(4)]
+            for i, v in enumerate(views):
+                same(v, i, 4 * step + i, step, 5 + i)
+            ring.release_host(views[-1].seq)
+        assert ring.get_stats().dropped_records == 0
+    # (b) best effort, ring of 2.5 records
+    with B.Ring((rb * 5 // 2) // 64 * 64, 1 << 25) as ring:
+        ring.set_policy(B.POLICY_DROP_NEWEST)
+        for step in range(2):
+            ring.observe_batch([5, 6, 7, 6], ts, reqs, step_id=step, stream=s.cuda_stream, out_dtype=DT_FP8, keep_mask=km)
+            s.synchronize()
+            ring.drain(B.DRAIN_FLUSH)
+            views = ring.poll_host()
+            assert [v.seq for v in views] == [4 * step, 4 * step + 1]
+            for i, v in enumerate(views):
+                same(v, i, 4 * step + i, step, 5 + i)
+            ring.release_host(views[-1].seq)
+        st = ring.get_stats()
+        assert (st.captured_records, st.dropped_records, st.dropped_rows, st.dropped_bytes) == (4, 4, 4 * 901, 4 * rb)
+        assert {p: ring.get_point_drops(p) for p in (5, 6, 7)} == {5: 0, 6: 2, 7: 2}
+
+
+def test_long_paged_batch_of_long_rows(B):
+    NB, BS, NH, HD = 80, 16, 8, 256              # rows of 8 heads x 256 = 2048 elements
+    caches = [prng.randn_bf16(prng.sub_seed(39, i), NB * BS * NH * HD, DEV).view(NB, BS, NH, HD) for i in range(6)]
+    table = torch.from_numpy(prng.permutation(4, NB).astype(np.int32).reshape(5, 16)).to(DEV)
+    spec = configs.PagedSpec(BS, NH, HD, [7, 0, 3, 1, 2, 6, 5, 4], table)
+    reqs = [(1, 2, 0, 256, 1), (2, 0, 5, 80, 3), (3, 3, 255, 1, 1), (4, 1, 0, 250, 1), (5, 4, 1, 255, 1), (6, 0, 0, 256, 1)]
+    for got, ref in _batch(B, caches, reqs, paged=spec, ring_bytes=1 << 26):
+        assert np.array_equal(got, ref)
+    for got, ref in _batch(B, caches, reqs, paged=spec, keep_mask=[1, 1, 0, 1, 1, 1], out_dtype=DT_FP8, ring_bytes=1 << 26):
+        assert np.array_equal(got, ref)
+
+
 def test_general_kernel_batch_with_summaries_masks_and_indices(B):
     ts = _tensors(34, 5, 300, 512)
     reqs = [(10 + i, 20 * i, 0, 3 + i, 2) for i in range(9)]
@@ -321,6 +404,27 @@ def test_replayed_step_with_batched_launches(B, batch, extra):
     compare_streams(run.stream, ref.stream())
     _check_stats(run, ref)
     assert run.stats.bad_rows == 0
+
+
+def test_replayed_step_with_a_long_batch_of_long_rows(B):
+    """A replayed step whose last group (3 tensors, ~2,000 ragged rows of 4 KiB each, fp8) is one launch with
+    more work than fits the GPU at once; the row counts change from replay to replay.  Then the same
+    under best effort with a device ring of about one and a half steps, drained every second step."""
+    from oracle import replay as oreplay
+    from oracle.stream import POLICY_DROP_NEWEST
+    from paper_2605_11093_amd import replay as G
+    wl = configs.replayed_batches(n_steps=4, long_rows=3, device_ring_bytes=64 << 20, host_ring_bytes=128 << 20)
+    ref = oreplay.run_workload(wl)
+    run = G.run_workload_graph(wl, batch=128)
+    compare_streams(run.stream, ref.stream())
+    _check_stats(run, ref)
+    wl = configs.replayed_batches(n_steps=4, long_rows=3, policy_mode=POLICY_DROP_NEWEST, device_ring_bytes=19 << 20,
+                                  host_ring_bytes=128 << 20)
+    ref = oreplay.run_workload(wl, drain_every=2)
+    assert ref.stats.dropped_records > 0 and ref.stats.captured_records > 0
+    run = G.run_workload_graph(wl, drain_every=2, batch=128)
+    compare_streams(run.stream, ref.stream())
+    _check_stats(run, ref)
 
 
 def test_replayed_batches_sampled_out_and_drop_newest(B):

@@ -283,14 +283,17 @@ def replayed_step(n_steps=6, n_graph=6, eager_extra_every=0, policy_mode=POLICY_
 
 
 def replayed_batches(n_steps=5, policy_mode=POLICY_BLOCK, sample_k=1, device_ring_bytes=8 << 20,
-                     host_ring_bytes=32 << 20, eager_extra_every=0) -> Workload:
+                     host_ring_bytes=32 << 20, eager_extra_every=0, long_rows=0) -> Workload:
     """Host-side workload for replayed steps whose hooks can share launches: every step lists,
     in hook order,
       0-4   five bf16 [64, 1024] tensors, one row per request (ids and rows change per step), raw + L2
       5-7   three bf16 [300, 256] tensors, ragged token ranges + one keep vector, fp8 out, absmax
       8-9   K and V of a paged cache [48, 16, 4, 64], heads {1, 3}, contexts that grow, raw
       10    one more bf16 [64, 1024] tensor with the selection of 0-4 but fp16 out (its own launch)
-    Consecutive calls of a group have the same layout, selection and transform."""
+    Consecutive calls of a group have the same layout, selection and transform.
+    long_rows = n > 0 adds, as points 12..12+n-1, n bf16 [2400, 2048] tensors with ragged token ranges of
+    some 2,000 rows, fp8 out: rows of 4 KiB, enough of them that one launch for the group has more
+    work than fits the GPU at once."""
     n_r = 64
     block_size, n_heads, head_dim, n_blocks, n_seqs, max_blocks = 16, 4, 64, 48, 6, 8
 
@@ -320,10 +323,16 @@ def replayed_batches(n_steps=5, policy_mode=POLICY_BLOCK, sample_k=1, device_rin
                                      reqs=reqs_c, out_dtype=DT_BF16, paged=spec))
         calls.append(ObserveCall(point_id=10, step_id=step, tensor=t_bf16(10, step, (n_r, 1024)), reqs=reqs_a,
                                  out_dtype=DT_FP16))
+        if long_rows:
+            lens_d = prng.randint(prng.sub_seed(19, 60, step), 6, 300, 400)
+            reqs_d = make_reqs((40 * step + r, 400 * r, int(step % 3), int(lens_d[r]), 1) for r in range(6))
+            for i in range(long_rows):
+                calls.append(ObserveCall(point_id=12 + i, step_id=step, tensor=t_bf16(12 + i, step, (2400, 2048)),
+                                         reqs=reqs_d, out_dtype=DT_FP8))
         if eager_extra_every and step % eager_extra_every == eager_extra_every - 1:
             calls.append(ObserveCall(point_id=11, step_id=step, tensor=calls[0].tensor,
                                      reqs=make_reqs([(1, 2, 0, 3, 1)]), out_dtype=DT_BF16))
         return calls
 
     return Workload("replayed_batches", device_ring_bytes, host_ring_bytes, policy_mode, sample_k, n_steps,
-                    step_calls, max_reqs=64, notes={"n_graph": 11})
+                    step_calls, max_reqs=64, notes={"n_graph": 11 + long_rows})
