@@ -686,7 +686,7 @@ def run_config2(ctx, extra, skip_overhead):
     # -- exporter stages 2-3
     r6 = B.Ring(wl.device_ring_bytes, wl.host_ring_bytes, flags=B.BG_THREAD, max_reqs_per_observe=256)
     p6 = prepared_batch(r6)
-    r6.exporter_start(1 << 30, 4)
+    r6.exporter_start(1 << 30, 8)
     buf = (B.SliceC * 4096)()
     n_exp_steps, got_slices = 64, 0
     want_slices = n_exp_steps * n_points * n_reqs
@@ -706,7 +706,7 @@ def run_config2(ctx, extra, skip_overhead):
     stream.synchronize()
     r6.destroy()
     extra["exporter"] = {"GBs": round(n_exp_steps * step_bytes / dt / 1e9, 2), "slices_per_s": round(got_slices / dt),
-                         "what": "config 2 stream through capture, drain thread, pageable copy (4 workers), "
+                         "what": "config 2 stream through capture, drain thread, pageable copy (8 workers), "
                                  "slice by request; Python consumer releasing in batches"}
     log(f"exporter: {extra['exporter']}")
     extra["config2_decode8b"] = out

@@ -20,7 +20,8 @@ bool wait_ms(std::condition_variable &cv, std::unique_lock<std::mutex> &lk, uint
 // up with the drain; a workload has few distinct record sizes, so nearly every record finds a buffer).
 // A buffer serves a record of size s if s <= cap <= s + s/8.  Idle buffers count against the budget:
 // in use + idle <= max_pageable_bytes (+ the 1/8 slack), the oldest idle ones are freed first.
-// Both functions need emu held.
+// The pool has a lock of its own (pool_mu), taken last: the copy workers get their buffers without
+// touching the lock that the consumer's queue is under.  The *_locked functions need pool_mu held.
 uint8_t *pool_take_locked(dmi_ring *r, uint64_t size, uint64_t *cap)
 {
     for (size_t i = r->exp_pool.size(); i-- > 0;) {         // newest first: most likely still in cache
@@ -44,10 +45,11 @@ void pool_trim_locked(dmi_ring *r, uint64_t keep_bytes)
     }
 }
 
-// A record copy is done with: its budget share is free again, its buffer goes to the pool.
+// A record copy is done with: its budget share is free again, its buffer goes to the pool (emu held).
 void retire_locked(dmi_ring *r, RecordCopy *rc)
 {
     r->exp_bytes -= rc->size;
+    std::lock_guard<std::mutex> pk(r->pool_mu);
     r->exp_pool.push_back(PoolBuf{rc->bytes, rc->cap});
     r->exp_pool_bytes += rc->cap;
     // a stopped exporter keeps nothing: slices given back after dmi_exporter_stop free their memory
@@ -61,14 +63,17 @@ void retire_locked(dmi_ring *r, RecordCopy *rc)
 // the consumer to give copies back.
 uint8_t *buffer_for(dmi_ring *r, uint64_t size, uint64_t *cap)
 {
-    std::unique_lock<std::mutex> lk(r->emu);
     for (;;) {
-        if (uint8_t *p = pool_take_locked(r, size, cap)) { r->exp_reuses++; return p; }
-        lk.unlock();
-        uint8_t *p = static_cast<uint8_t *>(malloc(size));
-        lk.lock();
-        if (p) { r->exp_mallocs++; *cap = size; return p; }
-        if (!r->exp_pool.empty()) { pool_trim_locked(r, 0); continue; }
+        {
+            std::lock_guard<std::mutex> pk(r->pool_mu);
+            if (uint8_t *p = pool_take_locked(r, size, cap)) { r->exp_reuses++; return p; }
+        }
+        if (uint8_t *p = static_cast<uint8_t *>(malloc(size))) { r->exp_mallocs++; *cap = size; return p; }
+        {
+            std::lock_guard<std::mutex> pk(r->pool_mu);
+            if (!r->exp_pool.empty()) { pool_trim_locked(r, 0); continue; }
+        }
+        std::unique_lock<std::mutex> lk(r->emu);
         wait_ms(r->ecv_space, lk, 1, [] { return false; });
     }
 }
@@ -306,6 +311,7 @@ dmi_status_t dmi_exporter_stop(dmi_ring_t *r)
             if (rc->refs.fetch_sub(1) == 1) retire_locked(r, rc);
         }
         r->slices.clear();
+        std::lock_guard<std::mutex> pk(r->pool_mu);
         pool_trim_locked(r, 0);
     }
     r->exp_running.store(false);

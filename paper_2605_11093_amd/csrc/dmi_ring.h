@@ -239,7 +239,8 @@ struct dmi_ring {
     std::deque<ExportJob> jobs;
     std::map<uint64_t, ExportDone> done_jobs;
     std::atomic<uint64_t> exp_records{0}, exp_copied_bytes{0};
-    std::vector<PoolBuf> exp_pool;          // idle buffers, oldest first (guarded by emu)
+    std::mutex pool_mu;                     // guards exp_pool and exp_pool_bytes; taken after emu, never before it
+    std::vector<PoolBuf> exp_pool;          // idle buffers, oldest first
     uint64_t exp_pool_bytes = 0;
     std::atomic<uint64_t> exp_mallocs{0}, exp_reuses{0};
 };
