@@ -534,10 +534,12 @@ dmi_status_t observe_common(dmi_ring *r, uint32_t n, const uint32_t *points, con
     memset(&b, 0, sizeof b);
 
     // one launch: records [first, first + cnt) of the caller's list; force_drop: records the host
-    // already knows cannot fit, launched with one workgroup each only to be counted
-    auto issue = [&](uint32_t first, uint32_t cnt, uint64_t floor, bool force_drop) -> dmi_status_t {
+    // already knows cannot fit, launched with one workgroup each only to be counted; tail: as many
+    // records behind the cnt launched ones that the host knows cannot fit either, counted by the
+    // same launch without any workgroup of their own
+    auto issue = [&](uint32_t first, uint32_t cnt, uint64_t floor, bool force_drop, uint32_t tail) -> dmi_status_t {
         dmi_status_t rc;
-        if ((rc = commit_slot_room(r, cnt)) != DMI_OK) return rc;
+        if ((rc = commit_slot_room(r, cnt + tail)) != DMI_OK) return rc;
         if (!staged) {
             if ((rc = stage_selection(r, sel, a.paged != 0, pl.row_map, s, &slot)) != DMI_OK) return rc;
             staged = true;
@@ -549,19 +551,22 @@ dmi_status_t observe_common(dmi_ring *r, uint32_t n, const uint32_t *points, con
         a.seq = seq;
         a.n_batch = cnt;
         a.step_id = step_id;
-        a.cslot = &r->dctrl->slots[(seq + cnt - 1u) % kCommitSlots];
+        a.cslot = &r->dctrl->slots[(seq + cnt + tail - 1u) % kCommitSlots];
         a.tail_floor = floor;
         a.drop_newest = mode == DMI_POLICY_DROP_NEWEST ? 1u : 0u;
         a.force_drop = force_drop ? 1u : 0u;
+        a.n_tail_drop = tail;
         // best effort: every fourth launch refreshes the drained-up-to mark from the host's word
         // (a read across the host link by one lane); in between, the launch-time floor stands
         a.tail_src = (a.drop_newest && (r->launches.load(std::memory_order_relaxed) & 3u) == 0) ? r->htail_dev : nullptr;
         a.par_in = r->chain_par;
         a.step = nullptr;
         a.node = 0;
-        for (uint32_t i = 0; i < cnt; i++) { b.src[i] = srcs[first + i]; b.point[i] = points[first + i]; }
+        for (uint32_t i = 0; i < cnt; i++) b.src[i] = srcs[first + i];
+        for (uint32_t i = 0; i < cnt + tail; i++) b.point[i] = points[first + i];
 
-        const bool decode = !force_drop && pl.decode && batch_takes_decode_kernel(a, cnt);
+        // (only the general kernel counts a tail)
+        const bool decode = !force_drop && !tail && pl.decode && batch_takes_decode_kernel(a, cnt);
         const uint32_t grid = force_drop ? 1u : cnt == 1u ? pl.grid : plan_grid(a, cnt);
         const hipError_t e = decode ? launch_capture_decode(a, b, s) : launch_capture(a, b, grid, geo.vec16, s);
         if (e != hipSuccess) return fail(DMI_ERR_HIP, "capture launch failed: %s", hipGetErrorString(e));
@@ -574,19 +579,21 @@ dmi_status_t observe_common(dmi_ring *r, uint32_t n, const uint32_t *points, con
         {
             std::lock_guard<std::mutex> lk(r->pmu);
             r->launches.fetch_add(1, std::memory_order_relaxed);
-            r->next_seq.store(seq + cnt, std::memory_order_release);
+            r->next_seq.store(seq + cnt + tail, std::memory_order_release);
             if (exact && !force_drop) {
                 r->window.bytes += bytes; r->window.records += cnt; r->window.rows += pl.rows_known * cnt;
+                r->window.drop_bytes += ub * tail; r->window.drop_records += tail;
+                r->window.drop_rows += pl.rows_known * tail;
             } else if (exact) {
-                r->window.drop_bytes += ub * cnt; r->window.drop_records += cnt;
-                r->window.drop_rows += pl.rows_known * cnt;
+                r->window.drop_bytes += ub * (cnt + tail); r->window.drop_records += cnt + tail;
+                r->window.drop_rows += pl.rows_known * (cnt + tail);
             } else {
                 r->window_exact = false;
             }
         }
         if (exact && r->head_exact) r->exact_head += bytes;
         else r->head_exact = false;
-        r->inflight.emplace_back(seq + cnt - 1u, bytes);    // confirmed launch by launch: the last record stands for all
+        r->inflight.emplace_back(seq + cnt + tail - 1u, bytes);    // confirmed launch by launch: the last record stands for all
         r->inflight_sum += bytes;
         r->unprobed_launches += 1;
         r->unprobed_bytes += bytes;
@@ -632,8 +639,11 @@ dmi_status_t observe_common(dmi_ring *r, uint32_t n, const uint32_t *points, con
                 if (room < nb) n_keep = (uint32_t)room;
             }
         }
-        if (n_keep && (st = issue(done, n_keep, floor, false)) != DMI_OK) return st;
-        if (n_keep < nb && (st = issue(done + n_keep, nb - n_keep, floor, true)) != DMI_OK) return st;
+        // (a tail is only ever the host's own decision: sizes known, so the launch's outcome is exact)
+        // (nothing fits: one workgroup counts them all)
+        if (n_keep) st = issue(done, n_keep, floor, false, nb - n_keep);
+        else st = issue(done, 1u, floor, true, nb - 1u);
+        if (st != DMI_OK) return st;
         done += nb;
         *n_launched = done;
         if (r->unprobed_launches >= 16u || r->unprobed_bytes >= r->probe_bytes) {

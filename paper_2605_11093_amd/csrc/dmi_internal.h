@@ -109,6 +109,9 @@ struct CaptureKernelArgs {
     uint32_t bs_shift, seg_shift;   // same for block_size and seg_units
     uint32_t drop_newest;
     uint32_t force_drop;            // every record of this launch is dropped (the host knows none can fit)
+    uint32_t n_tail_drop;           // records of the caller's list behind the n_batch launched ones that the host
+                                    // knows cannot fit: this launch only counts them (BatchArgs::point has their
+                                    // points behind the launched ones'); they take the sequence numbers that follow
     uint32_t table_in_lds;
     // launch chain: which copy of head / tail_for this launch reads (it writes the other)
     uint32_t par_in;

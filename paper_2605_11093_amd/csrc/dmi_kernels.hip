@@ -630,7 +630,7 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureKernelAr
             n_fit = n_fit < nb_rec ? n_fit : nb_rec;
         }
         if (a.force_drop) n_fit = 0;
-        const uint64_t n_drop = nb_rec - n_fit;
+        const uint64_t n_drop = nb_rec - n_fit + a.n_tail_drop;
         const uint64_t new_head = head0 + n_fit * record_bytes;
         if (n_drop) {
             cnt_drop[0] += n_drop; cnt_drop[1] += n_drop * n_rows; cnt_drop[2] += n_drop * record_bytes;
@@ -642,7 +642,10 @@ __global__ void __launch_bounds__(kThreads) capture_kernel(const CaptureKernelAr
         }
         c->head[par ^ 1u] = new_head;
         c->tail_for[par ^ 1u] = tail_now > raw.tail_for ? tail_now : raw.tail_for;
-        const uint64_t last_seq = seq + nb_rec - 1u;
+        const uint64_t last_seq = seq + nb_rec + a.n_tail_drop - 1u;
+        // (a loop of one lane over a uniform index: the points come straight out of the argument block)
+        for (uint32_t i = 0; i < a.n_tail_drop; i++)
+            atomicAdd(&c->point_drops[b.point[nb_rec + i] & 4095u], 1u);
         CommitSlot *h = a.step ? &c->slots[last_seq % kCommitSlots] : a.cslot;
         h->head = new_head;
         h->captured_records = cnt_cap[0];
