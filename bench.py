@@ -366,6 +366,10 @@ class Config5:
                 ctx.check(self.batched[s % 4](s, ctx.sh))
                 if events is not None:
                     e1.record(ctx.stream)
+            elif mode is None and events is not None:   # what the bracket itself measures, with nothing in it
+                e0, e1 = events[s - first]
+                e0.record(ctx.stream)
+                e1.record(ctx.stream)
             self.step_done[slot].record(ctx.stream)
             if mode:
                 ctx.consume(self.ring)
@@ -378,6 +382,10 @@ class Config5:
         self.steps(0, 20, None)
         torch.cuda.synchronize()
         self.base_s = (time.perf_counter() - t) / 20
+        evs = [self.ctx.ev_pair() for _ in range(20)]
+        self.steps(0, 20, None, evs)
+        torch.cuda.synchronize()
+        self.empty_bracket_us = sum(e0.elapsed_time(e1) * 1e3 for e0, e1 in evs) / len(evs)
         return self.base_s
 
     def run(self, k, mode, n_steps, warmup=0, events=False, first_step=0):
@@ -944,6 +952,8 @@ def main():
                 "us_per_launch_min": round(head["launch_us_min"], 3), "launches": n_launch,
                 "algorithmic_bytes_per_launch": round(alg_total / n_launch),
                 "records_kept_per_launch": round(head["captured_records"] / n_launch, 2),
+                # the same pair of events at the same place in a step with nothing between them
+                "us_between_the_events_with_nothing_between": round(c5.empty_bracket_us, 3),
                 # the profiled launch keeps all 80 records; a launch of this run kept this share of them
                 "traffic": round(TRAFFIC_CONFIG5_BATCH80_BYTES * head["captured_records"] / n_launch / 80),
                 "traffic_of_a_launch_that_keeps_all_80_records": TRAFFIC_CONFIG5_BATCH80_BYTES,
