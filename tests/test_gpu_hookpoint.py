@@ -146,3 +146,55 @@ def test_hookpoints_survive_compilation_as_graph_nodes():
                 compare_record(v.bytes(), orc.build_record(t, reqs, seq=v.seq, step_id=step, point_id=pid, out_dtype=1))
             ring.release_host(views[-1].seq)
             seq += 2
+
+
+def test_hookpoint_operator_reads_layouts_and_refuses_what_it_cannot_view():
+    """The native operator sees a tensor of any rank as [tokens, features] without a copy: leading
+    dimensions that collapse into evenly spaced rows are fine (a batch dimension, a step through the
+    tokens, a row pitch wider than the features); rows that are not evenly spaced, or whose elements
+    are not contiguous, are refused; so is a hook whose ring is gone."""
+    from paper_2605_11093_amd import binding as B
+    from paper_2605_11093_amd.hookpoint import HookPoint, StepContext
+    from workloads import prng
+    Bt, T, E = 3, 10, 512
+    x = prng.randn_bf16(77, Bt * T * E, DEV).view(Bt, T, E)
+    cases = [
+        ("batch of sequences", x, x.reshape(-1, E)),
+        ("every second token", x[:, ::2, :], x[:, ::2, :].reshape(-1, E)),
+        ("half of the features", x[0, :, :E // 2], x[0, :, :E // 2]),
+        ("one sequence, kept 3-d", x[1:2], x[1]),
+        ("a vector", x[2, 3], x[2, 3].reshape(1, E)),
+    ]
+    ring = B.Ring(1 << 22, 1 << 22)
+    ctx = StepContext()
+    hook = HookPoint(ring, 9, ctx, summary_mask=4)
+    seq = 0
+    with torch.no_grad():
+        for what, view, rows in cases:
+            n = rows.shape[0]
+            reqs = [(1, 0, 0, n, 1)] if n < 4 else [(1, 0, 1, n // 2, 2), (2, 0, n - 1, 1, 1)]
+            ctx.prepare_step(seq, reqs)
+            y = hook(view)
+            assert y is view
+            ring.drain(B.DRAIN_FLUSH)
+            (v,) = ring.poll_host()
+            ref = orc.build_record(rows.contiguous().cpu(), reqs, seq=seq, step_id=seq, point_id=9, out_dtype=1,
+                                   summary_mask=4)
+            assert np.array_equal(v.bytes(), ref), what
+            ring.release_host(v.seq)
+            seq += 1
+        ctx.prepare_step(seq, [(1, 0, 0, 2, 1)])
+        for bad in (x[:, :T - 1, :], x.transpose(1, 2), x[0].t()):
+            with pytest.raises(RuntimeError):
+                hook(bad)
+        with pytest.raises(RuntimeError):
+            hook(x.to(torch.float64))
+        assert ring.get_stats().launched_records == seq          # the refused calls launched nothing
+        ctx.reqs = None
+        hook(x)                                                   # no step prepared: a plain identity
+        assert ring.get_stats().observed_calls == seq
+        torch.cuda.synchronize()
+        ring.destroy()
+        ctx.prepare_step(seq, [(1, 0, 0, 2, 1)])
+        with pytest.raises(B.DmiError):
+            hook(x)
