@@ -46,7 +46,9 @@ struct Hook {
 
 // Hooks fire from whichever threads run forward passes; the tables change only when models are
 // built or torn down.  Entries are never moved once made (unique_ptr), so a reader needs the
-// lock only to find its entry.
+// lock only to find its entry.  An entry's contents have no lock: a step context belongs to the
+// thread that drives its model (it sets the step, then runs the forward whose hooks read it), as
+// a ring belongs to one producer thread.
 std::shared_mutex g_mu;
 std::vector<std::unique_ptr<StepCtx>> g_ctx;
 std::vector<std::unique_ptr<Hook>> g_hooks;

@@ -323,6 +323,34 @@ def test_drop_newest_in_the_middle_of_a_batch(B):
         assert drops == {20: 1, 21: 1, 22: 1, 23: 1, 24: 1, 25: 4, 26: 2}
 
 
+@pytest.mark.parametrize("room", [1, 2, 7])
+def test_drop_newest_keeps_a_prefix_of_any_length(B, room):
+    """Room for `room` and a half records, batches of 8 decode-shaped tensors: exactly the first `room`
+    stay (one kept record is a launch of its own kind: it would take the decode-shaped kernel if it
+    did not also have to count the seven behind it)."""
+    ts = _tensors(43, 8, 16, 1024)
+    reqs = np.array([(r, 15 - r, 0, 1, 1) for r in range(16)], dtype=np.uint32)
+    rb = orc.record_bytes(16, 16, 1024, 1, 0)
+    pts = list(range(30, 38))
+    with B.Ring(rb * room + rb // 2 // 64 * 64, 1 << 22) as ring:
+        ring.set_policy(B.POLICY_DROP_NEWEST)
+        s = torch.cuda.current_stream()
+        for step in range(3):
+            ring.observe_batch(pts, ts, reqs, step_id=step, stream=s.cuda_stream)
+            s.synchronize()
+            ring.drain(B.DRAIN_FLUSH)
+            views = ring.poll_host()
+            assert [v.seq for v in views] == [8 * step + i for i in range(room)]
+            for i, v in enumerate(views):
+                ref = orc.build_record(ts[i].cpu(), reqs, seq=v.seq, step_id=step, point_id=pts[i], out_dtype=1)
+                assert np.array_equal(v.bytes(), ref)
+            ring.release_host(views[-1].seq)
+        st = ring.get_stats()
+        assert (st.captured_records, st.dropped_records, st.launched_records) == (3 * room, 3 * (8 - room), 24)
+        assert st.dropped_bytes == 3 * (8 - room) * rb and st.dropped_rows == 3 * (8 - room) * 16
+        assert [ring.get_point_drops(p) for p in pts] == [0] * room + [3] * (8 - room)
+
+
 def test_block_policy_splits_a_batch_that_exceeds_the_ring(B, run_gpu):
     """Device ring of 2 records, batches of 8 under the completeness policy: the library issues
     the batch in pieces and waits for the drain in between; nothing is lost."""
