@@ -533,10 +533,10 @@ dmi_status_t observe_common(dmi_ring *r, uint32_t n, const uint32_t *points, con
     BatchArgs b;
     memset(&b, 0, sizeof b);
 
-    // one launch: records [first, first + cnt) of the caller's list; force_drop: records the host
-    // already knows cannot fit, launched with one workgroup each only to be counted; tail: as many
-    // records behind the cnt launched ones that the host knows cannot fit either, counted by the
-    // same launch without any workgroup of their own
+    // one launch: records [first, first + cnt) of the caller's list; force_drop: they are records
+    // the host already knows cannot fit, launched with one workgroup each only to be counted; tail:
+    // as many records behind the cnt launched ones that the host knows cannot fit either, counted
+    // by the same launch without any workgroup of their own
     auto issue = [&](uint32_t first, uint32_t cnt, uint64_t floor, bool force_drop, uint32_t tail) -> dmi_status_t {
         dmi_status_t rc;
         if ((rc = commit_slot_room(r, cnt + tail)) != DMI_OK) return rc;
