@@ -2,13 +2,15 @@
  * A plain C client of the C ABI (include/dmi.h): no Python, no torch.  Reads a bf16
  * matrix from a file, puts it into device memory with the HIP runtime, captures three
  * selections of its rows through dmi_observe (raw with summaries, fp8, with a keep
- * vector), drains, polls the pinned host ring and writes the records, in order, to a file.
+ * vector) and, through dmi_observe_batch, the two halves of the matrix as two observation points in
+ * one launch; drains, polls the pinned host ring and writes the records, in order, to a file.
  *
  *   c_client <in.bin> <rows> <elems> <out.bin>
  *
  * Selection used (the test that runs this builds the same one for the oracle):
  *   request i of 6: req_id 100+i, rows i*7 .. i*7+(i%3), step 1      (6 requests, 1-3 rows each)
  *   keep vector for the third observe: requests 1 and 4 are out.
+ *   batch: rows 2, 5, 8 and the last row of each half, as fp16 with the mean.
  */
 #include <hip/hip_runtime_api.h>
 #include <stdint.h>
@@ -71,6 +73,19 @@ int main(int argc, char **argv)
     CHECK_DMI(dmi_observe(ring, 2, &t, &sel, &fp8, 40, NULL));
     sel.keep_mask_dev = keep_dev;
     CHECK_DMI(dmi_observe(ring, 3, &t, &sel, &raw_sum, 41, NULL));
+    /* two observation points in one launch: the two halves of the tensor as two tensors of one
+     * shape, one selection (rows 2, 5, 8 and the last row of each half), stored as fp16 */
+    dmi_req_sel_t reqs2[2] = {{200, 2, 0, 3, 3}, {201, (uint32_t)(rows / 2 - 1), 0, 1, 1}};
+    dmi_selection_t sel2 = {2, reqs2, NULL, NULL};
+    dmi_tensor_t half = t;
+    half.data = NULL;                   /* ignored: the addresses travel in data[] */
+    half.shape[0] = rows / 2;
+    const uint32_t points[2] = {4, 5};
+    const void *data[2] = {dev, (const char *)dev + (size_t)(rows / 2) * elems * 2u};
+    dmi_transform_t fp16 = {DMI_DTYPE_FP16, DMI_SUM_MEAN};
+    uint32_t n_done = 0;
+    CHECK_DMI(dmi_observe_batch(ring, 2, points, data, &half, &sel2, &fp16, 42, NULL, &n_done));
+    if (n_done != 2) { fprintf(stderr, "batch stopped after %u of 2\n", n_done); return 5; }
     uint64_t moved = 0;
     CHECK_DMI(dmi_drain(ring, DMI_DRAIN_FLUSH, &moved));
 
@@ -93,5 +108,5 @@ int main(int argc, char **argv)
     CHECK_HIP(hipFree(keep_dev));
     CHECK_HIP(hipFree(dev));
     free(host);
-    return n == 3 ? 0 : 4;
+    return n == 5 ? 0 : 4;
 }

@@ -35,8 +35,12 @@ def test_plain_c_client_writes_the_oracles_records(tmp_path):
             orc.build_record(t, reqs, seq=1, step_id=40, point_id=2, out_dtype=4, rank_tag=7),
             orc.build_record(t, reqs, seq=2, step_id=41, point_id=3, out_dtype=1, summary_mask=5, keep_mask=keep,
                              rank_tag=7)]
+    # dmi_observe_batch on the two halves of the tensor: the records of two single observes
+    reqs2 = np.array([(200, 2, 0, 3, 3), (201, rows // 2 - 1, 0, 1, 1)], dtype=np.uint32)
+    want += [orc.build_record(t[:rows // 2], reqs2, seq=3, step_id=42, point_id=4, out_dtype=2, summary_mask=2, rank_tag=7),
+             orc.build_record(t[rows // 2:], reqs2, seq=4, step_id=42, point_id=5, out_dtype=2, summary_mask=2, rank_tag=7)]
     offs = record_offsets(got)
-    assert [s for s, _, _ in offs] == [0, 1, 2]
+    assert [s for s, _, _ in offs] == [0, 1, 2, 3, 4]
     for (seq, off, n), w in zip(offs, want):
         compare_record(got[off:off + n], w, what=f"seq {seq}")
-    assert "3 records" in r.stdout and "rows captured" in r.stdout
+    assert "5 records" in r.stdout and "rows captured" in r.stdout
