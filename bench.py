@@ -67,6 +67,11 @@ class Ctx:
         bl.dmi_bench_stream_gemv.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p]
         bl.dmi_bench_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]
         self.bl = bl
+        hip = C.CDLL("libamdhip64.so")
+        hip.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+        hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        hip.hipEventSynchronize.argtypes = [C.c_void_p]
+        self.hip = hip
         self.stream = torch.cuda.current_stream()
         self.sh = self.stream.cuda_stream
         self.d2h_peak = None
@@ -74,6 +79,22 @@ class Ctx:
     def ev_pair(self):
         t = self.torch
         return t.cuda.Event(enable_timing=True), t.cuda.Event(enable_timing=True)
+
+    def hw_ev_pair(self):
+        """Two raw hipEvent_t handles for dmi_debug_time_next_launch (the kernel's own start and end)."""
+        out = []
+        for _ in range(2):
+            e = C.c_void_p()
+            assert self.hip.hipEventCreate(C.byref(e)) == 0
+            out.append(e)
+        return tuple(out)
+
+    def hw_elapsed_us(self, k0, k1):
+        assert self.hip.hipEventSynchronize(k1) == 0
+        ms = C.c_float()
+        rc = self.hip.hipEventElapsedTime(C.byref(ms), k0, k1)
+        assert rc == 0, f"hipEventElapsedTime: {rc}"
+        return ms.value * 1e3
 
     def consume(self, ring):
         n = 0
@@ -361,13 +382,14 @@ class Config5:
                     ctx.check(self.single[s % 4][l](s, ctx.sh))
             if mode == "batched":
                 if events is not None:
-                    e0, e1 = events[s - first]
+                    e0, e1, k0, k1 = events[s - first]
                     e0.record(ctx.stream)
+                    ctx.B.time_next_launch(k0, k1)      # the launch's own start and end, by the hardware
                 ctx.check(self.batched[s % 4](s, ctx.sh))
                 if events is not None:
                     e1.record(ctx.stream)
             elif mode is None and events is not None:   # what the bracket itself measures, with nothing in it
-                e0, e1 = events[s - first]
+                e0, e1 = events[s - first][:2]
                 e0.record(ctx.stream)
                 e1.record(ctx.stream)
             self.step_done[slot].record(ctx.stream)
@@ -397,7 +419,7 @@ class Config5:
             self.steps(first_step, warmup, mode)
         ctx.settle(ring)
         a0 = ring.get_stats()
-        evs = [ctx.ev_pair() for _ in range(n_steps)] if events else None
+        evs = [ctx.ev_pair() + ctx.hw_ev_pair() for _ in range(n_steps)] if events else None
         ctx.torch.cuda.synchronize()
         t = time.perf_counter()
         self.steps(first_step + warmup, n_steps, mode, evs)
@@ -420,9 +442,12 @@ class Config5:
         if self.base_s:
             res["overhead_pct"] = round((t_stream / n_steps - self.base_s) / self.base_s * 100, 2)
         if evs:
-            us = [e0.elapsed_time(e1) * 1e3 for e0, e1 in evs]
-            res["launch_us_mean"] = sum(us) / len(us)
-            res["launch_us_min"] = min(us)
+            us = [e0.elapsed_time(e1) * 1e3 for e0, e1, _, _ in evs]
+            hw = [ctx.hw_elapsed_us(k0, k1) for _, _, k0, k1 in evs]
+            res["launch_us_mean"] = sum(hw) / len(hw)
+            res["launch_us_min"] = min(hw)
+            res["launch_us_max"] = max(hw)
+            res["launch_us_between_events_mean"] = sum(us) / len(us)
             res["launches"] = len(us)
         return res
 
@@ -946,13 +971,18 @@ def main():
     cap_gbs = alg_total / n_launch / cap_us / 1e3
     roofline = {"bound": "hbm",
                 "kernel": "capture_kernel<bf16, 16-byte units, raw, no summaries>, one launch for the step's 80 "
-                          "tensors (config 5), as timed inside the headline run",
+                          "tensors (config 5), every launch of the headline's timed region",
+                "timing": "HIP events that take the launch's own start and end time stamps from the hardware "
+                          "(hipExtLaunchKernelGGL on the launch stream): the kernel's duration as a profiler reports it",
                 "achieved": round(cap_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(cap_gbs / HBM_PEAK_GBS, 4), "us_per_launch": round(cap_us, 3),
-                "us_per_launch_min": round(head["launch_us_min"], 3), "launches": n_launch,
+                "us_per_launch_min": round(head["launch_us_min"], 3),
+                "us_per_launch_max": round(head["launch_us_max"], 3), "launches": n_launch,
                 "algorithmic_bytes_per_launch": round(alg_total / n_launch),
                 "records_kept_per_launch": round(head["captured_records"] / n_launch, 2),
-                # the same pair of events at the same place in a step with nothing between them
+                # for comparison, markers recorded on the stream before and after the call, and the same
+                # pair at the same place in a step with nothing between them
+                "us_per_launch_between_events": round(head["launch_us_between_events_mean"], 3),
                 "us_between_the_events_with_nothing_between": round(c5.empty_bracket_us, 3),
                 # the profiled launch keeps all 80 records; a launch of this run kept this share of them
                 "traffic": round(TRAFFIC_CONFIG5_BATCH80_BYTES * head["captured_records"] / n_launch / 80),

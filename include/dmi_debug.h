@@ -18,6 +18,13 @@ dmi_status_t dmi_debug_fill_rings(dmi_ring_t *ring, uint8_t value);
  * records found an idle buffer instead, since the ring was created [both host]. */
 dmi_status_t dmi_debug_exporter_allocs(dmi_ring_t *ring, uint64_t *allocated, uint64_t *reused);
 
+/* The next capture launch issued by the calling thread is timed by the hardware: start_event and
+ * stop_event [hipEvent_t, created with timing enabled] take the time stamps at which that kernel
+ * began to execute and ended, so that hipEventElapsedTime between them is the kernel's own
+ * duration (what a profiler reports), without what two markers recorded around the call add.
+ * One launch only; NULL, NULL cancels.  For benchmarks; thread local. */
+dmi_status_t dmi_debug_time_next_launch(void *start_event, void *stop_event);
+
 #ifdef __cplusplus
 }
 #endif

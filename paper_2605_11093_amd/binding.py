@@ -191,6 +191,8 @@ def lib():
     L.dmi_debug_fill_rings.argtypes = [C.c_void_p, C.c_uint8]
     L.dmi_debug_exporter_allocs.argtypes = [C.c_void_p, P(C.c_uint64), P(C.c_uint64)]
     L.dmi_debug_exporter_allocs.restype = C.c_int32
+    L.dmi_debug_time_next_launch.argtypes = [C.c_void_p, C.c_void_p]
+    L.dmi_debug_time_next_launch.restype = C.c_int32
     L.dmi_exporter_start.argtypes = [C.c_void_p, C.c_uint64, C.c_uint32]
     L.dmi_exporter_next.argtypes = [C.c_void_p, P(SliceC), C.c_uint32]
     L.dmi_exporter_release.argtypes = [C.c_void_p, P(SliceC)]
@@ -264,6 +266,11 @@ def _torch_dtype_code(t) -> int:
         import torch
         _TORCH_DT = {torch.bfloat16: DT_BF16, torch.float16: DT_FP16, torch.float32: DT_FP32}
     return _TORCH_DT[t.dtype]
+
+
+def time_next_launch(start_event: int, stop_event: int) -> None:
+    """The calling thread's next capture launch records its own start and end into the two hipEvent_t handles."""
+    _check(lib().dmi_debug_time_next_launch(start_event or None, stop_event or None))
 
 
 def _reqs_buffer(reqs):

@@ -30,7 +30,9 @@
 //     lds_barrier), and the common small shapes have a short straight-line kernel of
 //     their own (capture_decode_kernel).
 #include "dmi_internal.h"
+#include "dmi_debug.h"
 
+#include <hip/hip_ext.h>
 #include <hip/hip_fp16.h>
 
 #include <cstring>
@@ -1387,15 +1389,37 @@ __global__ void __launch_bounds__(kThreads) drain_kernel(const uint8_t *ring, ui
 }
 
 // ---------------------------------------------------------------- launchers
+// A benchmark may ask for the next capture launch of its thread to be timed by the hardware itself:
+// the two events then take the dispatch's own start and end time stamps (what a profiler reports
+// as the kernel's duration), not the times at which markers around the launch were reached.
+static thread_local hipEvent_t t_time_start = nullptr, t_time_stop = nullptr;
+
+extern "C" dmi_status_t dmi_debug_time_next_launch(void *start_event, void *stop_event)
+{
+    t_time_start = static_cast<hipEvent_t>(start_event);
+    t_time_stop = static_cast<hipEvent_t>(stop_event);
+    return DMI_OK;
+}
+
+#define DMI_LAUNCH_CAPTURE(kernel, grid, lds, stream, ...)                                                            \
+    do {                                                                                                              \
+        if (t_time_start && t_time_stop) {                                                                            \
+            hipExtLaunchKernelGGL(kernel, grid, dim3(kThreads), lds, stream, t_time_start, t_time_stop, 0, __VA_ARGS__); \
+            t_time_start = t_time_stop = nullptr;                                                                     \
+        } else {                                                                                                      \
+            hipLaunchKernelGGL(kernel, grid, dim3(kThreads), lds, stream, __VA_ARGS__);                                \
+        }                                                                                                             \
+    } while (0)
+
 template <int ES_IN, int VEC, int OUT>
 static hipError_t launch_t(const CaptureArgs &a, const BatchArgs &b, uint32_t grid, hipStream_t s)
 {
     const dim3 g(grid, a.n_batch);
     if (a.summary_mask)
-        hipLaunchKernelGGL((capture_kernel<ES_IN, VEC, OUT, true>), g, dim3(kThreads), a.lds_bytes, s,
+        DMI_LAUNCH_CAPTURE((capture_kernel<ES_IN, VEC, OUT, true>), g, a.lds_bytes, s,
                            static_cast<const CaptureKernelArgs &>(a), b);
     else
-        hipLaunchKernelGGL((capture_kernel<ES_IN, VEC, OUT, false>), g, dim3(kThreads), a.lds_bytes, s,
+        DMI_LAUNCH_CAPTURE((capture_kernel<ES_IN, VEC, OUT, false>), g, a.lds_bytes, s,
                            static_cast<const CaptureKernelArgs &>(a), b);
     return hipGetLastError();
 }
@@ -1428,14 +1452,14 @@ static hipError_t launch_decode_t(const DecodeArgs &d, const BatchArgs &b, uint3
     const dim3 grid(d.n_wg_rows + 1u, n_batch);
     if (d.keep_mask) {
         if (summaries)
-            hipLaunchKernelGGL((capture_decode_kernel<OUT, true, true>), grid, dim3(kThreads), 0, s, d, b);
+            DMI_LAUNCH_CAPTURE((capture_decode_kernel<OUT, true, true>), grid, 0, s, d, b);
         else
-            hipLaunchKernelGGL((capture_decode_kernel<OUT, false, true>), grid, dim3(kThreads), 0, s, d, b);
+            DMI_LAUNCH_CAPTURE((capture_decode_kernel<OUT, false, true>), grid, 0, s, d, b);
     } else {
         if (summaries)
-            hipLaunchKernelGGL((capture_decode_kernel<OUT, true, false>), grid, dim3(kThreads), 0, s, d, b);
+            DMI_LAUNCH_CAPTURE((capture_decode_kernel<OUT, true, false>), grid, 0, s, d, b);
         else
-            hipLaunchKernelGGL((capture_decode_kernel<OUT, false, false>), grid, dim3(kThreads), 0, s, d, b);
+            DMI_LAUNCH_CAPTURE((capture_decode_kernel<OUT, false, false>), grid, 0, s, d, b);
     }
     return hipGetLastError();
 }
