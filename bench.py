@@ -71,6 +71,7 @@ class Ctx:
         hip.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
         hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
         hip.hipEventSynchronize.argtypes = [C.c_void_p]
+        hip.hipEventDestroy.argtypes = [C.c_void_p]
         self.hip = hip
         self.stream = torch.cuda.current_stream()
         self.sh = self.stream.cuda_stream
@@ -130,7 +131,8 @@ def time_launches(ctx, make_call, n_launch, ring_bytes, alg_bytes, reps=3, max_r
     """n_launch captures queued behind a sleeping stream so that they run back to back; HIP
     events on the same stream bracket them.  The ring holds every launch, so the completeness
     policy never waits and its commit probes are events only.  Returns the mean over `reps`
-    repetitions (and the best) of microseconds per launch."""
+    repetitions (and the best) of microseconds per launch, and (us_kernel) the mean duration of the
+    kernels themselves in one more repetition, first launch left out."""
     B = ctx.B
     per = []
     for rep in range(reps + 1):
@@ -155,9 +157,27 @@ def time_launches(ctx, make_call, n_launch, ring_bytes, alg_bytes, reps=3, max_r
         assert st.dropped_records == 0, st
         ring.destroy()
     mean = sum(per) / len(per)
+    # once more with every launch timed by the hardware itself (its own start and end stamps):
+    # the kernel's duration without the gap to the next dispatch
+    ring = B.Ring(ring_bytes, max(1 << 26, (alg_bytes + 63) // 64 * 64), max_reqs_per_observe=max_reqs)
+    ring.set_policy(B.POLICY_BLOCK if policy is None else policy)
+    po = make_call(ring)
+    pairs = [ctx.hw_ev_pair() for _ in range(n_launch)]
+    ctx.bl.dmi_bench_sleep(ctx.sh, 300 + 20 * n_launch)
+    for i in range(n_launch):
+        B.time_next_launch(*pairs[i])
+        ctx.check(po(i, ctx.sh))
+    ctx.stream.synchronize()
+    own = [ctx.hw_elapsed_us(k0, k1) for k0, k1 in pairs]
+    for k0, k1 in pairs:
+        ctx.hip.hipEventDestroy(k0)
+        ctx.hip.hipEventDestroy(k1)
+    ring.destroy()
+    kern = sum(own[1:]) / len(own[1:]) if len(own) > 1 else own[0]
     return {"us_per_launch": round(mean, 3), "us_per_launch_best": round(min(per), 3),
             "algorithmic_bytes": alg_bytes, "GBs": round(alg_bytes / mean / 1e3, 1),
-            "frac_hbm_peak": round(alg_bytes / mean / 1e3 / HBM_PEAK_GBS, 4)}
+            "frac_hbm_peak": round(alg_bytes / mean / 1e3 / HBM_PEAK_GBS, 4),
+            "us_kernel": round(kern, 3), "frac_hbm_peak_kernel": round(alg_bytes / kern / 1e3 / HBM_PEAK_GBS, 4)}
 
 
 def shape_table(ctx):
