@@ -203,6 +203,29 @@ def test_long_paged_batch_of_long_rows(B):
         assert np.array_equal(got, ref)
 
 
+def test_empty_and_degenerate_batches(B):
+    """Nothing to capture is still a well-formed answer: a batch of no tensors does nothing; a batch whose
+    selection lists no request, or only requests without rows, or whose keep vector keeps nobody, gives
+    one record per tensor with a header, a table and no rows, as the single observes do."""
+    ts = _tensors(44, 3, 40, 256)
+    with B.Ring(1 << 20, 1 << 20) as ring:
+        s = torch.cuda.current_stream()
+        import ctypes as C
+        ra = np.array([(1, 0, 0, 1, 1)], dtype=np.uint32)
+        like = B.Tensor(None, 1, (C.c_int64 * 2)(40, 256), (C.c_int64 * 2)(256, 1))
+        sel, xf, done = B.Selection(1, ra.ctypes.data, None, None), B.Transform(1, 0), C.c_uint32(7)
+        rc = B.lib().dmi_observe_batch(ring._h, 0, None, None, C.byref(like), C.byref(sel), C.byref(xf), 0,
+                                       s.cuda_stream, C.byref(done))
+        assert (rc, done.value) == (B.OK, 0) and ring.get_stats().launched_records == 0
+    for reqs, km, sm in [(np.zeros((0, 5), np.uint32), None, 0),
+                         ([(5, 3, 0, 0, 1), (6, 9, 2, 0, 4)], None, 7),
+                         ([(1, 0, 0, 2, 1), (2, 7, 0, 3, 1)], [0, 0], 5)]:
+        for got, ref in _batch(B, ts, reqs, keep_mask=km, summary_mask=sm):
+            assert np.array_equal(got, ref)
+        for got, ref in _batch(B, ts, reqs, keep_mask=km, out_dtype=DT_FP8):
+            assert np.array_equal(got, ref)
+
+
 def test_general_kernel_batch_with_summaries_masks_and_indices(B):
     ts = _tensors(34, 5, 300, 512)
     reqs = [(10 + i, 20 * i, 0, 3 + i, 2) for i in range(9)]
