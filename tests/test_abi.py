@@ -1,4 +1,4 @@
-"""The C-ABI library loads and exports every symbol include/dmi.h declares; the
+"""The C-ABI library loads and exports every symbol include/*.h declares; the
 pure-host helpers agree with the oracle; without a GPU the product path fails
 loudly instead of falling back to anything."""
 import ctypes
@@ -14,8 +14,8 @@ from paper_2605_11093_amd import binding as B
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def _declared_symbols():
-    src = open(os.path.join(ROOT, "include", "dmi.h")).read()
+def _declared_symbols(header="dmi.h"):
+    src = open(os.path.join(ROOT, "include", header)).read()
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
     return sorted(set(re.findall(r"\b(dmi_[a-z_0-9]+)\s*\(", src)))
 
@@ -28,6 +28,18 @@ def test_library_exports_every_declared_symbol():
     for n in names:
         assert hasattr(L, n), n
     assert "gfx950" in dmi.version()
+    # the test hooks live in the same library; the benchmark's harness kernels in one of their own
+    hooks = _declared_symbols("dmi_debug.h")
+    assert {"dmi_debug_fill_rings", "dmi_debug_exporter_allocs", "dmi_debug_time_next_launch"} <= set(hooks)
+    for n in hooks:
+        assert hasattr(L, n), n
+    bench_so = os.path.join(ROOT, "paper_2605_11093_amd", "libdmi_bench.so")
+    assert os.path.exists(bench_so), "run __graft_entry__.build()"
+    Lb = ctypes.CDLL(bench_so)
+    harness = _declared_symbols("dmi_bench.h")
+    assert harness
+    for n in harness:
+        assert hasattr(Lb, n), n
 
 
 def test_record_bytes_matches_oracle(oracle):
