@@ -92,10 +92,13 @@ void model_capture(const CaptureArgs &a, const BatchArgs &b)
             ring_put(a.ring, a.cap, at + 64 + 16ull * r, e, 16);
         }
     }
-    const uint64_t n_drop = nb - n_fit;
+    // records behind the launched ones that the host has already decided to drop: counted here
+    for (uint32_t i = 0; i < a.n_tail_drop; i++)
+        __atomic_fetch_add(&c->point_drops[b.point[nb + i] & 4095u], 1u, __ATOMIC_RELAXED);
+    const uint64_t n_drop = nb - n_fit + a.n_tail_drop;
     c->dropped_records += n_drop; c->dropped_rows += n_drop * n_rows; c->dropped_bytes += n_drop * rb;
     c->captured_records += n_fit; c->captured_rows += n_fit * n_rows; c->captured_bytes += n_fit * rb;
-    const uint64_t new_head = head0 + n_fit * rb, last = seq + nb - 1u;
+    const uint64_t new_head = head0 + n_fit * rb, last = seq + nb + a.n_tail_drop - 1u;
     c->head[par ^ 1u] = new_head;
     c->tail_for[par ^ 1u] = next_tail_for;
     CommitSlot *s = a.step ? &c->slots[last % kCommitSlots] : a.cslot;
