@@ -279,6 +279,60 @@ void scenario(const char *name, uint32_t policy, bool use_exporter, bool with_st
     CHECK(hipStreamDestroy(stream) == hipSuccess);
 }
 
+// Best effort with the host knowing exactly where the head stands (everything flushed, nothing in
+// flight): of a batch of six records into a ring that holds two and a half, the host launches the two
+// that fit and has that launch count the four behind them; with the ring still full, the next batch
+// is counted by a launch of one workgroup.  Single-threaded: what is checked is the bookkeeping.
+void scenario_host_decided_drops()
+{
+    fprintf(stderr, "scenario drop-newest, the host decides\n");
+    Source src(64, 512);
+    std::vector<dmi_req_sel_t> decode(16);
+    for (uint32_t i = 0; i < 16; i++) decode[i] = {100 + i, i, 0, 1, 1};
+    const dmi_selection_t sel = {16, decode.data(), nullptr, nullptr};
+    const dmi_transform_t raw = {DMI_DTYPE_BF16, 0};
+    const uint64_t rb = dmi_record_bytes(16, 16, 512, DMI_DTYPE_BF16, 0);
+    dmi_ring_config_t cfg;
+    memset(&cfg, 0, sizeof cfg);
+    cfg.device_ring_bytes = (2 * rb + rb / 2) / 64 * 64;
+    cfg.host_ring_bytes = 1u << 20;
+    cfg.max_reqs_per_observe = 64;
+    dmi_ring_t *ring = nullptr;
+    CHECK(dmi_ring_create(&cfg, &ring) == DMI_OK);
+    dmi_policy_t pol = {DMI_POLICY_DROP_NEWEST, 1, 0};
+    CHECK(dmi_set_policy(ring, &pol) == DMI_OK);
+    hipStream_t stream;
+    CHECK(hipStreamCreate(&stream) == hipSuccess);
+    const uint32_t points[6] = {1, 2, 3, 4, 3, 2};
+    const void *datas[6] = {src.data.data(), src.data.data(), src.data.data(), src.data.data(), src.data.data(), src.data.data()};
+    uint32_t done = 0;
+    CHECK(dmi_observe_batch(ring, 6, points, datas, &src.t, &sel, &raw, 0, stream, &done) == DMI_OK && done == 6);
+    CHECK(dmi_observe_batch(ring, 6, points, datas, &src.t, &sel, &raw, 1, stream, &done) == DMI_OK && done == 6);
+    CHECK(hipStreamSynchronize(stream) == hipSuccess);
+    flush_all(ring);
+    dmi_stats_t s;
+    CHECK(dmi_get_stats(ring, &s) == DMI_OK);
+    CHECK(s.launched_records == 12 && s.captured_records == 2 && s.dropped_records == 10);
+    CHECK(s.captured_bytes == 2 * rb && s.dropped_bytes == 10 * rb && s.dropped_rows == 160);
+    dmi_record_view_t v[4];
+    uint32_t n = 0;
+    CHECK(dmi_poll_host(ring, v, 4, &n) == DMI_OK && n == 2 && v[0].seq == 0 && v[1].seq == 1);
+    CHECK(dmi_release_host(ring, 1) == DMI_OK);
+    // first batch: points 1, 2 kept, then 3, 4, 3, 2 dropped; second batch: all of 1, 2, 3, 4, 3, 2 dropped
+    const uint64_t want[5] = {0, 1, 3, 4, 2};
+    for (uint32_t p = 0; p < 5; p++) {
+        uint64_t d = 0;
+        CHECK(dmi_get_point_drops(ring, p, &d) == DMI_OK && d == want[p]);
+    }
+    // room again: the next batch's first two are sequence numbers 12 and 13
+    CHECK(dmi_observe_batch(ring, 6, points, datas, &src.t, &sel, &raw, 2, stream, &done) == DMI_OK && done == 6);
+    CHECK(hipStreamSynchronize(stream) == hipSuccess);
+    flush_all(ring);
+    CHECK(dmi_poll_host(ring, v, 4, &n) == DMI_OK && n == 2 && v[0].seq == 12 && v[1].seq == 13);
+    CHECK(dmi_ring_destroy(ring) == DMI_OK);
+    CHECK(hipStreamDestroy(stream) == hipSuccess);
+}
+
 }  // namespace
 
 int main(int argc, char **argv)
@@ -289,6 +343,7 @@ int main(int argc, char **argv)
     scenario("drop-newest, poll/release consumer, steps", DMI_POLICY_DROP_NEWEST, false, true, n_iter);
     scenario("block, exporter as the consumer", DMI_POLICY_BLOCK, true, false, n_iter / 2);
     scenario("drop-newest, exporter as the consumer", DMI_POLICY_DROP_NEWEST, true, false, n_iter / 2);
+    scenario_host_decided_drops();
     fprintf(stderr, "all scenarios passed\n");
     return 0;
 }
