@@ -12,7 +12,7 @@ and compare whole streams and counters with the oracle's ring model.
 Coverage of each configuration's stream (the oracle builds 0.3 to 3 GB of records per second
 on one core, and a GPU test has about two minutes):
   config 2   all 256 steps, all 8,192 records (4.3 GB)
-  config 3   all 8 steps, all 80 records (4.3 GB), asynchronous; plus 4 steps in lockstep with
+  config 3   all 8 steps, all 80 records (4.3 GB), asynchronous, singly and batched; plus 4 steps in lockstep with
              the drain withheld every other step, and 4 steps with a 256 MiB device ring
   config 4   all 128 steps, all 1,024 records (37 GB) batched; 40 steps (320 records) singly
   config 5   k = 1: all 200 steps, every record that was not dropped, batched; k = 4: all 200
@@ -136,9 +136,12 @@ def _dropped_accounting(run, missing):
     assert by == run.stats.dropped_bytes
 
 
-def test_config3_full_ragged_prefill_fp8_every_record(B):
+@pytest.mark.parametrize("batch", [0, 8])
+def test_config3_full_ragged_prefill_fp8_every_record(B, batch):
+    """batch = 8: a step's eight residual points in one launch and its two MLP points in another, the
+    launches bench.py times as config3_*_batch*."""
     wl = configs.config3_prefill(device=DEV)                          # all 8 steps, 512 MiB ring, drop-newest
-    run, chk = _run(B, wl, flags=B.BG_THREAD)
+    run, chk = _run(B, wl, flags=B.BG_THREAD, batch=batch)
     missing = _check(run, chk, expect_drops=True)
     _dropped_accounting(run, missing)
     assert run.stats.launched_records == 80
