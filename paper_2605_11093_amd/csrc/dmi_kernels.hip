@@ -3,7 +3,10 @@
 // capture_kernel is the producer of the paper's Ring^2 (section 4.2, steps 1-2;
 // section 5 "Device-to-device kernel"; section 4.4 gather-compact): it copies the
 // selected rows of one observed tensor into the device byte ring and publishes the
-// record.  The paper's kernel (1-64 blocks, grid-stride 16-byte copies, last block
+// record; or, in one launch, the rows of up to kMaxBatch tensors of one layout that share a
+// selection, one record each, laid down as single launches in the same order would (a
+// launch costs microseconds whatever it moves, and only more bytes per launch amortise
+// that).  The paper's kernel (1-64 blocks, grid-stride 16-byte copies, last block
 // publishes) is prior art for other hardware; here
 //   * every workgroup rebuilds the per-request prefix sums in LDS with wavefront
 //     shuffle scans, so row -> (request, token) needs no pre-pass launch;
