@@ -795,12 +795,23 @@ def run_configs34(ctx, extra):
         stt = run.stats
         rr.destroy()
         tot = stt.captured_bytes + stt.dropped_bytes
+        base = None
+        if compute:     # the same stand-in alone: one 2 ms sleep per observe
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            for _ in range(stt.observed_calls):
+                bl.dmi_bench_sleep(sh, 2000)
+            stream.synchronize()
+            base = time.perf_counter() - t
         e2e[name] = {"drained_GBs": round(stt.drained_bytes / dt / 1e9, 2),
                      "frac_of_d2h_peak": round(stt.drained_bytes / dt / 1e9 / ctx.d2h_peak, 3),
                      "dropped_fraction": round(stt.dropped_bytes / tot, 4) if tot else 0.0,
                      "records": stt.launched_records, "seconds": round(dt, 3),
                      "model_compute_stand_in": "2 ms sleep kernel before every observe" if compute
                      else "none: captures issued back to back, the host link is the limit"}
+        if base:
+            e2e[name]["no_capture_seconds"] = round(base, 3)
+            e2e[name]["overhead_pct"] = round((dt - base) / base * 100, 2)
         log(f"end to end {name}: {e2e[name]}")
 
     w3e = configs.config3_prefill(device=dev, n_steps=4)
@@ -928,6 +939,42 @@ def run_cpu_baseline(ctx, budget_s=25.0):
     log(f"cpu oracle: {cpu}")
     del w, calls
     ctx.free()
+    # the other configurations' records, a few seconds each (record bytes built per second, one core)
+    others = {}
+    for name, make in (("config1", lambda: ctx.configs.config1_tiny(device=ctx.dev)),
+                       ("config2", lambda: ctx.configs.config2_decode8b(device=ctx.dev, n_steps=4)),
+                       ("config3", lambda: ctx.configs.config3_prefill(device=ctx.dev, n_steps=1)),
+                       ("config4", lambda: ctx.configs.config4_paged_kv(device=ctx.dev, n_steps=1, n_layers_cap=1))):
+        w = make()
+        view = CpuView()
+        n_steps = w.n_steps
+        pre = [w.step_calls(s) for s in range(min(n_steps, 4))]
+        for cs in pre:                               # device -> host copies of the inputs are not the oracle's work
+            for c in cs:
+                view.tensor(c.tensor)
+                view.paged(c.paged)
+        t = time.perf_counter()
+        nbytes = seq = 0
+        rounds = 0
+        while time.perf_counter() - t < 3.0 and rounds < 64:
+            for cs in pre:
+                for c in cs:
+                    rec = oracle.build_record(view.tensor(c.tensor), c.reqs, seq=seq, step_id=0, point_id=c.point_id,
+                                              out_dtype=c.out_dtype, summary_mask=c.summary_mask, keep_mask=c.keep_mask,
+                                              row_index=c.row_index, paged=view.paged(c.paged))
+                    nbytes += rec.size
+                    seq += 1
+                    if time.perf_counter() - t > 3.0:
+                        break
+                if time.perf_counter() - t > 3.0:
+                    break
+            rounds += 1
+        dt = time.perf_counter() - t
+        others[name] = {"GBs": round(nbytes / dt / 1e9, 4), "records": seq, "seconds": round(dt, 2)}
+        del w, pre, view
+        ctx.free()
+    cpu["other_configs_record_GBs"] = others
+    log(f"cpu oracle, other configurations: {others}")
     return cpu
 
 
