@@ -226,6 +226,95 @@ def test_empty_and_degenerate_batches(B):
             assert np.array_equal(got, ref)
 
 
+@pytest.mark.parametrize("seed", range(48))
+def test_random_batches_equal_the_oracles_single_records(B, seed):
+    """A seeded sweep over what a batched call can be given: row widths on both sides of every path's
+    limits (16-byte movable or not), tensor counts, ragged selections with empty requests, repeated and
+    strided tokens, keep vectors, every transform, row pitches wider than the rows."""
+    rng = np.random.RandomState(1000 + seed)
+    E = int(rng.choice([8, 56, 64, 250, 256, 264, 512, 1000, 1024, 2048, 2056, 4096, 5000, 8192, 9000]))
+    T = int(rng.randint(1, 260)) if E <= 4096 else int(rng.randint(1, 60))
+    n = int(rng.choice([1, 2, 3, 5, 9, 17]))
+    pitch = E + int(rng.choice([0, 0, 8, 24])) if E % 8 == 0 else E
+    ts = _tensors(500 + seed, n, T, E, pitch=pitch)
+    n_reqs = int(rng.randint(1, 24))
+    reqs = []
+    for q in range(n_reqs):
+        step = int(rng.choice([0, 1, 1, 1, 2, 3, 7]))
+        count = int(rng.choice([0, 1, 1, 2, 5, 30]))
+        base = int(rng.randint(0, T))
+        start = int(rng.randint(0, T - base))
+        if count > 1 and step > 0:
+            count = min(count, (T - 1 - base - start) // step + 1)
+        reqs.append((1000 + q, base, start, max(count, 0), step))
+    keep = None
+    if rng.rand() < 0.5:
+        keep = [int(x) for x in (rng.rand(n_reqs) < 0.7)]
+    out_dtype = int(rng.choice([DT_BF16, DT_BF16, DT_FP8, DT_FP16, DT_NONE]))
+    sm = int(rng.randint(0, 8))
+    if out_dtype == DT_NONE and sm == 0:
+        sm = 5
+    if out_dtype == DT_NONE and (sm & 2):
+        sm |= 1                 # the mean's tolerance is scaled by the row's L2 when there is no payload
+    rows = sum(r[3] for r in reqs)
+    ring = 1 << max(22, int(np.ceil(np.log2(n * (rows * E * 2 + 64 * n_reqs + 8192)))) + 1)
+    for got, ref in _batch(B, ts, reqs, out_dtype=out_dtype, summary_mask=sm, keep_mask=keep, ring_bytes=ring):
+        compare_record(got, ref, what=f"seed {seed}: E={E} T={T} n={n} reqs={n_reqs} out={out_dtype} sm={sm}")
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_indexed_batches(B, seed):
+    """The same sweep with an explicit row for every listed row (row_index_dev)."""
+    rng = np.random.RandomState(3000 + seed)
+    E = int(rng.choice([64, 256, 512, 1024, 4096, 8192]))
+    T = int(rng.randint(4, 200))
+    n = int(rng.choice([1, 2, 4, 9]))
+    ts = _tensors(700 + seed, n, T, E)
+    n_reqs = int(rng.randint(1, 20))
+    reqs = [(50 + q, 0, int(rng.randint(0, 5)), int(rng.choice([0, 1, 1, 2, 6])), 1) for q in range(n_reqs)]
+    listed = sum(r[3] for r in reqs)
+    idx = rng.randint(0, T, size=max(listed, 1))[:listed]
+    keep = [int(x) for x in (rng.rand(n_reqs) < 0.7)] if rng.rand() < 0.5 else None
+    out_dtype = int(rng.choice([DT_BF16, DT_FP8, DT_FP16]))
+    sm = int(rng.choice([0, 0, 1, 4, 5, 7]))
+    for got, ref in _batch(B, ts, reqs, out_dtype=out_dtype, summary_mask=sm, keep_mask=keep, row_index=idx,
+                           ring_bytes=1 << 24):
+        compare_record(got, ref, what=f"seed {seed}: E={E} T={T} n={n} reqs={n_reqs} out={out_dtype} sm={sm}")
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_paged_batches(B, seed):
+    """A seeded sweep over paged caches: block sizes, head counts and widths (rows of 64 bytes to 4 KiB), head
+    subsets in any order, shuffled block tables, contexts that end anywhere in a block."""
+    rng = np.random.RandomState(5000 + seed)
+    BS = int(rng.choice([4, 8, 16, 32]))
+    NH = int(rng.choice([1, 2, 4, 8]))
+    HD = int(rng.choice([32, 64, 128, 256]))
+    n_seqs, max_blocks = int(rng.randint(1, 6)), int(rng.randint(1, 9))
+    NBLK = n_seqs * max_blocks + int(rng.randint(0, 8))
+    n = int(rng.choice([1, 2, 4, 6]))
+    caches = [prng.randn_bf16(prng.sub_seed(900 + seed, i), NBLK * BS * NH * HD, DEV).view(NBLK, BS, NH, HD) for i in range(n)]
+    table = rng.permutation(NBLK)[:n_seqs * max_blocks].astype(np.int32).reshape(n_seqs, max_blocks)
+    k = int(rng.randint(1, NH + 1))
+    heads = [int(h) for h in rng.permutation(NH)[:k]]
+    spec = configs.PagedSpec(BS, NH, HD, heads, torch.from_numpy(table).to(DEV))
+    ctx_len = BS * max_blocks
+    reqs = []
+    for q in range(int(rng.randint(1, 12))):
+        step = int(rng.choice([1, 1, 2, 5]))
+        start = int(rng.randint(0, ctx_len))
+        count = int(rng.choice([0, 1, 3, 40, 400]))
+        if count:
+            count = min(count, (ctx_len - 1 - start) // step + 1)
+        reqs.append((70 + q, int(rng.randint(0, n_seqs)), start, count, step))
+    keep = [int(x) for x in (rng.rand(len(reqs)) < 0.7)] if rng.rand() < 0.4 else None
+    out_dtype = int(rng.choice([DT_BF16, DT_BF16, DT_FP8, DT_FP16]))
+    sm = int(rng.choice([0, 0, 0, 1, 5, 7]))
+    for got, ref in _batch(B, caches, reqs, paged=spec, out_dtype=out_dtype, summary_mask=sm, keep_mask=keep,
+                           ring_bytes=1 << 25):
+        compare_record(got, ref, what=f"seed {seed}: BS={BS} NH={NH} HD={HD} heads={heads} n={n} out={out_dtype} sm={sm}")
+
+
 def test_general_kernel_batch_with_summaries_masks_and_indices(B):
     ts = _tensors(34, 5, 300, 512)
     reqs = [(10 + i, 20 * i, 0, 3 + i, 2) for i in range(9)]
