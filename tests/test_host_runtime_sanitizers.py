@@ -28,7 +28,7 @@ def _build(tmp_path, sanitizer):
 
 
 @pytest.mark.skipif(shutil.which("g++") is None, reason="needs g++")
-@pytest.mark.parametrize("sanitizer,iters", [("thread", 600), ("address", 1500)])
+@pytest.mark.parametrize("sanitizer,iters", [("thread", 3000), ("address", 3000)])
 def test_host_runtime_is_clean_under(tmp_path, sanitizer, iters):
     exe = _build(tmp_path, sanitizer)
     env = dict(os.environ, TSAN_OPTIONS="halt_on_error=1 exitcode=66 second_deadlock_stack=1",
