@@ -37,7 +37,7 @@ SEED_NOTE = "synthetic (seeded ~N(0,1) bf16, shapes of the paper's LLM workloads
 # the two rocprofv3 --pmc runs summarised in profiles/hbm_traffic_counters.md (FETCH_SIZE and
 # WRITE_SIZE, each scaled by what the same counter reads for a plain copy of known size):
 # 335.77 MB read + 339.66 MB written, against 671.83 MB algorithmic.
-TRAFFIC_CONFIG5_BATCH80_BYTES = 675428850
+TRAFFIC_CONFIG5_BATCH80_BYTES = 675418753
 
 
 def log(*a):
