@@ -36,7 +36,7 @@ SEED_NOTE = "synthetic (seeded ~N(0,1) bf16, shapes of the paper's LLM workloads
 # HBM bytes per launch of the batched config-5 capture kernel when it keeps all 80 records, from
 # the two rocprofv3 --pmc runs summarised in profiles/hbm_traffic_counters.md (FETCH_SIZE and
 # WRITE_SIZE, each scaled by what the same counter reads for a plain copy of known size):
-# 335.77 MB read + 339.66 MB written, against 671.83 MB algorithmic.
+# 335.79 MB read + 339.63 MB written, against 671.83 MB algorithmic.
 TRAFFIC_CONFIG5_BATCH80_BYTES = 675418753
 
 
