@@ -22,7 +22,8 @@ dmi_status_t dmi_debug_exporter_allocs(dmi_ring_t *ring, uint64_t *allocated, ui
  * stop_event [hipEvent_t, created with timing enabled] take the time stamps at which that kernel
  * began to execute and ended, so that hipEventElapsedTime between them is the kernel's own
  * duration (what a profiler reports), without what two markers recorded around the call add.
- * One launch only; NULL, NULL cancels.  For benchmarks; thread local. */
+ * One launch only; NULL, NULL cancels.  For benchmarks; thread local; not for launches of a
+ * replayable step (a stream that is being captured records no events of this kind). */
 dmi_status_t dmi_debug_time_next_launch(void *start_event, void *stop_event);
 
 #ifdef __cplusplus
