@@ -1404,9 +1404,9 @@ extern "C" dmi_status_t dmi_debug_time_next_launch(void *start_event, void *stop
     return DMI_OK;
 }
 
-#define DMI_LAUNCH_CAPTURE(kernel, grid, lds, stream, ...)                                                            \
+#define DMI_LAUNCH_CAPTURE(in_step, kernel, grid, lds, stream, ...)                                                   \
     do {                                                                                                              \
-        if (t_time_start && t_time_stop) {                                                                            \
+        if (t_time_start && t_time_stop && !(in_step)) {                                                              \
             hipExtLaunchKernelGGL(kernel, grid, dim3(kThreads), lds, stream, t_time_start, t_time_stop, 0, __VA_ARGS__); \
             t_time_start = t_time_stop = nullptr;                                                                     \
         } else {                                                                                                      \
@@ -1419,10 +1419,10 @@ static hipError_t launch_t(const CaptureArgs &a, const BatchArgs &b, uint32_t gr
 {
     const dim3 g(grid, a.n_batch);
     if (a.summary_mask)
-        DMI_LAUNCH_CAPTURE((capture_kernel<ES_IN, VEC, OUT, true>), g, a.lds_bytes, s,
+        DMI_LAUNCH_CAPTURE(a.step != nullptr, (capture_kernel<ES_IN, VEC, OUT, true>), g, a.lds_bytes, s,
                            static_cast<const CaptureKernelArgs &>(a), b);
     else
-        DMI_LAUNCH_CAPTURE((capture_kernel<ES_IN, VEC, OUT, false>), g, a.lds_bytes, s,
+        DMI_LAUNCH_CAPTURE(a.step != nullptr, (capture_kernel<ES_IN, VEC, OUT, false>), g, a.lds_bytes, s,
                            static_cast<const CaptureKernelArgs &>(a), b);
     return hipGetLastError();
 }
@@ -1455,14 +1455,14 @@ static hipError_t launch_decode_t(const DecodeArgs &d, const BatchArgs &b, uint3
     const dim3 grid(d.n_wg_rows + 1u, n_batch);
     if (d.keep_mask) {
         if (summaries)
-            DMI_LAUNCH_CAPTURE((capture_decode_kernel<OUT, true, true>), grid, 0, s, d, b);
+            DMI_LAUNCH_CAPTURE(d.step != nullptr, (capture_decode_kernel<OUT, true, true>), grid, 0, s, d, b);
         else
-            DMI_LAUNCH_CAPTURE((capture_decode_kernel<OUT, false, true>), grid, 0, s, d, b);
+            DMI_LAUNCH_CAPTURE(d.step != nullptr, (capture_decode_kernel<OUT, false, true>), grid, 0, s, d, b);
     } else {
         if (summaries)
-            DMI_LAUNCH_CAPTURE((capture_decode_kernel<OUT, true, false>), grid, 0, s, d, b);
+            DMI_LAUNCH_CAPTURE(d.step != nullptr, (capture_decode_kernel<OUT, true, false>), grid, 0, s, d, b);
         else
-            DMI_LAUNCH_CAPTURE((capture_decode_kernel<OUT, false, false>), grid, 0, s, d, b);
+            DMI_LAUNCH_CAPTURE(d.step != nullptr, (capture_decode_kernel<OUT, false, false>), grid, 0, s, d, b);
     }
     return hipGetLastError();
 }
